@@ -1,0 +1,142 @@
+/*
+ * mx.h -- C ABI of the MI355X (gfx950) microscaling library.
+ *
+ * The library implements, as hand-written HIP kernels, the data-parallel hot path of
+ * multi-format QAT with anchor storage:
+ *   - block-wise MX quantization of fp32 / bf16 tensors (Eq. (1), Eq. (2)),
+ *   - Slice-and-Scale conversion of an 8-bit anchor (MXINT8 / MXFP8 E4M3) to a lower MXINT /
+ *     MXFP format without going back to fp32 weights (Eq. (4), Eq. (6)),
+ *   - the fused quantize-dequantize ("fake-quant") of the training forward pass (Sec. 3.2,
+ *     Eq. (7)) and the reconstruction V^ = X * P (Sec. 3.3 notation).
+ *
+ * Conventions common to every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller (borrowed for the call); the
+ *     descriptor structs themselves and the format structs are HOST memory.
+ *   - Nothing is allocated, freed or synchronized by the library.  Work is enqueued on the HIP
+ *     stream passed as `stream` (a hipStream_t cast to void*; NULL = the default stream) and is
+ *     complete when that stream reaches the end of the enqueued work.
+ *   - All arguments are validated on the host before anything is launched: a call that returns
+ *     an error has had no effect on device memory.  Errors are reported by return code only.
+ *   - Dense tensors are row-major [rows, cols] with leading dimension `ld` (elements, >= cols).
+ *   - Packed tensors are block-contiguous: codes[outer][nblocks][block * bits / 8] bytes and
+ *     scales[outer][nblocks] bytes, the block axis innermost.  For axis = 1 (blocks run along a
+ *     row) outer = rows, nblocks = cols / block.  For axis = 0 (blocks run down a column) the
+ *     packed tensor is stored transposed: outer = cols, nblocks = rows / block.
+ *   - Inside one block, element i occupies bits [i * w, (i + 1) * w) of the block's
+ *     little-endian bit string (w = element width).  MXINT codes are two's complement in w bits,
+ *     MXFP codes are sign | exponent | mantissa.
+ *   - A scale is one E8M0 byte: X = 2^(byte - 127); byte 255 marks a block that held NaN / Inf.
+ *   - MXINT uses the integer view of the paper's Eq. (4): e_max(b) = b - 2, symmetric clip
+ *     +-(2^(b-1) - 1).  Rounding: MX_ROUND_DEFAULT is half-away-from-zero for MXINT and
+ *     half-to-even for MXFP.
+ *   - Pointers must be 16-byte aligned (MX_ERR_ALIGN otherwise), `ld` a multiple of 8 elements.
+ */
+#ifndef MX_H_
+#define MX_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MX_OK = 0,
+  MX_ERR_NULL = 1,        /* a required pointer is NULL                                        */
+  MX_ERR_FORMAT = 2,      /* unknown element / scale / rounding, or anchor -> target is not a  */
+                          /* down-conversion inside one family                                 */
+  MX_ERR_SHAPE = 3,       /* negative size, blocked extent not a multiple of block, ld < cols  */
+  MX_ERR_ALIGN = 4,       /* pointer not 16-byte aligned, or ld not a multiple of 8            */
+  MX_ERR_UNSUPPORTED = 5, /* valid request this build has no kernel for                        */
+  MX_ERR_LAUNCH = 6,      /* the HIP runtime refused the launch                                */
+  MX_ERR_WORKSPACE = 7    /* workspace too small                                               */
+} mx_status_t;
+
+/* Element formats.  Sec. 3.2 "Evaluation" lists MXINT b = 2..8 and MXFP E2M1, E2M2, E3M2, E3M3,
+ * E4M3; E2M3 is the OCP FP6 variant added by the benchmark definition. */
+typedef enum {
+  MX_INT8 = 0, MX_INT7, MX_INT6, MX_INT5, MX_INT4, MX_INT3, MX_INT2,
+  MX_FP8_E4M3, MX_FP7_E3M3, MX_FP6_E3M2, MX_FP6_E2M3, MX_FP5_E2M2, MX_FP4_E2M1,
+  MX_ELEM_COUNT
+} mx_elem_t;
+
+typedef enum { MX_SCALE_E8M0 = 0 } mx_scale_t;
+typedef enum { MX_F32 = 0, MX_BF16 = 1 } mx_dtype_t;
+typedef enum { MX_ROUND_DEFAULT = 0, MX_ROUND_HALF_AWAY = 1, MX_ROUND_HALF_EVEN = 2 } mx_round_t;
+
+/* An MX format: element type, scale type, block size k and the axis the blocks run along
+ * (Sec. 2 "Microscaling formats"; Sec. 3.3 notation). */
+typedef struct {
+  mx_elem_t elem;
+  mx_scale_t scale;
+  int32_t block;   /* k: 32 (the only size the kernels are built for) */
+  int32_t axis;    /* 1: along rows (last axis); 0: down columns */
+  mx_round_t round;
+} mx_format_t;
+
+/* Dense matrix in device memory. */
+typedef struct {
+  void* data;
+  mx_dtype_t dtype;
+  int64_t rows, cols, ld;
+} mx_dense_t;
+
+/* Packed MX tensor in device memory: outer * nblocks blocks. */
+typedef struct {
+  void* codes;
+  uint8_t* scales;
+  int64_t outer, nblocks;
+} mx_packed_t;
+
+/* Element width in bits, e_max (Sec. 3.3 notation), or -1 for an unknown element. */
+int mx_elem_bits(mx_elem_t elem);
+int mx_elem_emax(mx_elem_t elem);
+
+/* Bytes needed for the codes and the scales of a [rows, cols] tensor in format f. */
+mx_status_t mx_packed_bytes(const mx_format_t* f, int64_t rows, int64_t cols, size_t* code_bytes,
+                            size_t* scale_bytes);
+
+/* Q_f, Eq. (1) and Eq. (2): per block, shared_exp = floor(log2 max|V_i|) - e_max(f), clamped to
+ * [-127, 127]; P_i = quantize_f(V_i / 2^shared_exp).  src: dense, read-only.  dst: packed with
+ * outer / nblocks matching src and f->axis; dst must not overlap src.  An all-zero block gets
+ * scale byte 0; a block holding NaN / Inf gets scale byte 255 and zero codes. */
+mx_status_t mx_quantize(const mx_format_t* f, const mx_dense_t* src, const mx_packed_t* dst, void* stream);
+
+/* Q_{A->t}, Eq. (4) (SSMXINT) and Eq. (6) (SSMXFP): P_l = quantize_t(P_h / 2^De),
+ * X_l = X_h * 2^De, De = e_max(anchor) - e_max(target).  The anchor must be an 8-bit format
+ * (MX_INT8 or MX_FP8_E4M3) and the target a narrower format of the same family with the same
+ * block size; the axis is irrelevant (a flat run of blocks).  The scale byte saturates at 254;
+ * 255 stays 255.  target->outer * target->nblocks must equal the anchor's block count.
+ * The target must not overlap the anchor. */
+mx_status_t mx_slice_and_scale(const mx_format_t* fa, const mx_packed_t* anchor, const mx_format_t* ft,
+                               const mx_packed_t* target, void* stream);
+
+/* The same conversion for n tensors in ONE kernel launch (a whole checkpoint, Sec. 3.5
+ * "Inference").  anchors / targets: host arrays of n descriptors.  workspace: device memory of
+ * at least mx_slice_and_scale_batched_workspace(n) bytes, 16-byte aligned; the descriptor table
+ * is copied there with hipMemcpyAsync on `stream`, so the host arrays may be reused as soon as
+ * the call returns only if they are in pageable memory (the runtime stages those). */
+size_t mx_slice_and_scale_batched_workspace(int32_t n);
+mx_status_t mx_slice_and_scale_batched(const mx_format_t* fa, const mx_format_t* ft, int32_t n,
+                                       const mx_packed_t* anchors, const mx_packed_t* targets,
+                                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* Fake-quant of the QAT forward pass.  anchor == NULL: dst = DQ(Q_target(src)) (Sec. 3.2).
+ * anchor != NULL: dst = DQ(Q_{A->t}(Q_A(src))) (Eq. (7)).  src and dst have the same shape;
+ * dst may be src itself (in place) but must not partially overlap it.  Nothing but dst is
+ * written.  The backward pass of the straight-through estimator is the identity and needs no
+ * kernel. */
+mx_status_t mx_fake_quant(const mx_format_t* target, const mx_format_t* anchor, const mx_dense_t* src,
+                          const mx_dense_t* dst, void* stream);
+
+/* V^ = X * P (Sec. 3.3 notation) into a dense matrix; scale byte 255 gives NaN.  Results that
+ * are not representable in dst->dtype round to nearest even (overflow gives +-Inf). */
+mx_status_t mx_dequant(const mx_format_t* f, const mx_packed_t* src, const mx_dense_t* dst, void* stream);
+
+const char* mx_status_str(mx_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MX_H_ */

@@ -1,1 +1,184 @@
-"""MI355X-native MX quantization, Slice-and-Scale, fake-quant and dequantization."""
+"""MI355X-native MX quantization, Slice-and-Scale, fake-quant and dequantization.
+
+Thin Python front end over the C-ABI library libmx.so (hand-written HIP kernels for gfx950).
+The functions here have the names of the C entry points and only marshal arguments: torch
+supplies device memory and the current stream.  bfloat16 / float32 CUDA(HIP) tensors in,
+uint8 CUDA tensors for codes and scales.
+"""
+import ctypes
+
+from . import binding
+from .binding import ELEMS, MxError, make_format
+
+__all__ = ["mx_quantize", "mx_slice_and_scale", "mx_slice_and_scale_batched", "mx_fake_quant", "mx_dequant",
+           "mx_packed_bytes", "mx_elem_bits", "mx_elem_emax", "MxFakeQuantSTE", "ELEMS", "MxError", "make_format",
+           "packed_shape"]
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _stream(t):
+    torch = _torch()
+    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def _dense(t):
+    torch = _torch()
+    if t.dim() != 2:
+        raise ValueError("dense tensors are 2-D [rows, cols]")
+    if not t.is_cuda:
+        raise ValueError("tensors must live on the GPU")
+    if t.dtype == torch.float32:
+        dt = binding.MX_F32
+    elif t.dtype == torch.bfloat16:
+        dt = binding.MX_BF16
+    else:
+        raise TypeError("dense tensors are float32 or bfloat16")
+    if t.stride(1) != 1 and t.shape[1] > 1:
+        raise ValueError("dense tensors must be row-major (unit stride along columns)")
+    ld = t.stride(0) if t.shape[0] > 1 else t.shape[1]
+    return binding.MxDense(t.data_ptr(), dt, t.shape[0], t.shape[1], ld)
+
+
+def _packed(codes, scales, outer, nblocks):
+    torch = _torch()
+    for x in (codes, scales):
+        if x.dtype != torch.uint8 or not x.is_cuda or not x.is_contiguous():
+            raise TypeError("codes and scales are contiguous uint8 GPU tensors")
+    return binding.MxPacked(codes.data_ptr(), scales.data_ptr(), outer, nblocks)
+
+
+def mx_elem_bits(elem):
+    return binding.lib().mx_elem_bits(ELEMS[elem])
+
+
+def mx_elem_emax(elem):
+    return binding.lib().mx_elem_emax(ELEMS[elem])
+
+
+def mx_packed_bytes(fmt, rows, cols):
+    cb, sb = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    binding.check(binding.lib().mx_packed_bytes(ctypes.byref(fmt), rows, cols, ctypes.byref(cb), ctypes.byref(sb)),
+                  "mx_packed_bytes")
+    return cb.value, sb.value
+
+
+def packed_shape(fmt, rows, cols):
+    """(outer, nblocks, bytes_per_block) of a [rows, cols] tensor in format fmt."""
+    outer, ext = (rows, cols) if fmt.axis == 1 else (cols, rows)
+    return outer, ext // fmt.block, fmt.block * binding.lib().mx_elem_bits(fmt.elem) // 8
+
+
+def _alloc_packed(fmt, rows, cols, device):
+    torch = _torch()
+    outer, nblocks, bb = packed_shape(fmt, rows, cols)
+    codes = torch.empty((outer, nblocks, bb), dtype=torch.uint8, device=device)
+    scales = torch.empty((outer, nblocks), dtype=torch.uint8, device=device)
+    return codes, scales
+
+
+def mx_quantize(src, fmt, codes=None, scales=None):
+    """Q_f (Eq. (1), (2)): dense [rows, cols] -> (codes[outer, nblocks, bytes], scales[outer, nblocks])."""
+    rows, cols = src.shape
+    if codes is None:
+        codes, scales = _alloc_packed(fmt, rows, cols, src.device)
+    outer, nblocks, _ = packed_shape(fmt, rows, cols)
+    d = _dense(src)
+    p = _packed(codes, scales, outer, nblocks)
+    binding.check(binding.lib().mx_quantize(ctypes.byref(fmt), ctypes.byref(d), ctypes.byref(p), _stream(src)), "mx_quantize")
+    return codes, scales
+
+
+def mx_slice_and_scale(codes, scales, fa, ft, out_codes=None, out_scales=None):
+    """Q_{A->t} (Eq. (4), (6)) on a packed anchor; returns (codes, scales) of the target format."""
+    torch = _torch()
+    nb = scales.numel()
+    bb = ft.block * binding.lib().mx_elem_bits(ft.elem) // 8
+    if out_codes is None:
+        out_codes = torch.empty(tuple(scales.shape) + (bb,), dtype=torch.uint8, device=codes.device)
+        out_scales = torch.empty_like(scales)
+    a = _packed(codes, scales, 1, nb)
+    t = _packed(out_codes, out_scales, 1, nb)
+    binding.check(binding.lib().mx_slice_and_scale(ctypes.byref(fa), ctypes.byref(a), ctypes.byref(ft), ctypes.byref(t),
+                                                   _stream(codes)), "mx_slice_and_scale")
+    return out_codes, out_scales
+
+
+def mx_slice_and_scale_batched(anchors, fa, ft, targets=None, workspace=None):
+    """One launch over a list of (codes, scales) anchors (a checkpoint).  Returns the target list."""
+    torch = _torch()
+    n = len(anchors)
+    L = binding.lib()
+    bb = ft.block * L.mx_elem_bits(ft.elem) // 8
+    if targets is None:
+        targets = [(torch.empty(tuple(s.shape) + (bb,), dtype=torch.uint8, device=c.device), torch.empty_like(s))
+                   for c, s in anchors]
+    if n == 0:
+        return targets
+    dev = anchors[0][0].device
+    need = L.mx_slice_and_scale_batched_workspace(n)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    A = (binding.MxPacked * n)(*[_packed(c, s, 1, s.numel()) for c, s in anchors])
+    T = (binding.MxPacked * n)(*[_packed(c, s, 1, s.numel()) for c, s in targets])
+    binding.check(L.mx_slice_and_scale_batched(ctypes.byref(fa), ctypes.byref(ft), n, A, T,
+                                               ctypes.c_void_p(workspace.data_ptr()), workspace.numel(),
+                                               _stream(anchors[0][0])), "mx_slice_and_scale_batched")
+    return targets
+
+
+def mx_fake_quant(src, target, anchor=None, out=None):
+    """DQ(Q_t(src)), or DQ(Q_{A->t}(Q_A(src))) when an anchor format is given (Eq. (7))."""
+    torch = _torch()
+    if out is None:
+        out = torch.empty_like(src)
+    s, d = _dense(src), _dense(out)
+    a = ctypes.byref(anchor) if anchor is not None else None
+    binding.check(binding.lib().mx_fake_quant(ctypes.byref(target), a, ctypes.byref(s), ctypes.byref(d), _stream(src)),
+                  "mx_fake_quant")
+    return out
+
+
+def mx_dequant(codes, scales, fmt, rows, cols, dtype=None, out=None):
+    """V^ = X * P into a dense [rows, cols] tensor."""
+    torch = _torch()
+    if out is None:
+        out = torch.empty((rows, cols), dtype=dtype or torch.float32, device=codes.device)
+    outer, nblocks, _ = packed_shape(fmt, rows, cols)
+    p = _packed(codes, scales, outer, nblocks)
+    d = _dense(out)
+    binding.check(binding.lib().mx_dequant(ctypes.byref(fmt), ctypes.byref(p), ctypes.byref(d), _stream(codes)), "mx_dequant")
+    return out
+
+
+def _ste_class():
+    torch = _torch()
+
+    class _MxFakeQuantSTE(torch.autograd.Function):
+        """Fake-quant forward; the backward pass is the straight-through estimator of Sec. 3.5:
+        the gradient goes through both quantizers unchanged (the same tensor is returned)."""
+
+        @staticmethod
+        def forward(ctx, w, target, anchor):
+            return mx_fake_quant(w, target, anchor)
+
+        @staticmethod
+        def backward(ctx, grad_out):
+            return grad_out, None, None
+
+    return _MxFakeQuantSTE
+
+
+class _Lazy:
+    _cls = None
+
+    def apply(self, w, target, anchor=None):
+        if _Lazy._cls is None:
+            _Lazy._cls = _ste_class()
+        return _Lazy._cls.apply(w, target, anchor)
+
+
+MxFakeQuantSTE = _Lazy()

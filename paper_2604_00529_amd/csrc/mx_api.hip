@@ -1,0 +1,220 @@
+// C-ABI layer: argument validation on the host, then dispatch to the kernel launchers.
+// Nothing here allocates, frees or synchronizes; a call that fails validation launches nothing.
+#include "mx_device.h"
+#include "mx_launch.h"
+
+namespace {
+
+struct ElemInfo {
+  int bits, emax, family;  // family 0 = MXINT, 1 = MXFP
+};
+
+bool elem_info(int e, ElemInfo* out) {
+  switch (e) {
+#define MX_CASE(ID) \
+  case ID:          \
+    *out = ElemInfo{mx::Elem<ID>::bits, mx::Elem<ID>::emax, mx::Elem<ID>::is_int ? 0 : 1}; \
+    return true;
+    MX_CASE(MX_INT8) MX_CASE(MX_INT7) MX_CASE(MX_INT6) MX_CASE(MX_INT5) MX_CASE(MX_INT4) MX_CASE(MX_INT3) MX_CASE(MX_INT2)
+    MX_CASE(MX_FP8_E4M3) MX_CASE(MX_FP7_E3M3) MX_CASE(MX_FP6_E3M2) MX_CASE(MX_FP6_E2M3) MX_CASE(MX_FP5_E2M2)
+    MX_CASE(MX_FP4_E2M1)
+#undef MX_CASE
+    default:
+      return false;
+  }
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+mx_status_t check_format(const mx_format_t* f, ElemInfo* info) {
+  if (!f) return MX_ERR_NULL;
+  if (!elem_info((int)f->elem, info)) return MX_ERR_FORMAT;
+  if (f->scale != MX_SCALE_E8M0) return MX_ERR_FORMAT;
+  if ((int)f->round < MX_ROUND_DEFAULT || (int)f->round > MX_ROUND_HALF_EVEN) return MX_ERR_FORMAT;
+  if (f->axis != 0 && f->axis != 1) return MX_ERR_SHAPE;
+  if (f->block <= 0) return MX_ERR_SHAPE;
+  if (f->block != 32) return MX_ERR_UNSUPPORTED;
+  return MX_OK;
+}
+
+// outer / nblocks of a [rows, cols] tensor blocked along f->axis
+mx_status_t blocked_shape(const mx_format_t* f, int64_t rows, int64_t cols, int64_t* outer, int64_t* nblocks) {
+  if (rows < 0 || cols < 0) return MX_ERR_SHAPE;
+  int64_t ext = f->axis == 1 ? cols : rows;
+  if (ext % f->block) return MX_ERR_SHAPE;
+  *outer = f->axis == 1 ? rows : cols;
+  *nblocks = ext / f->block;
+  return MX_OK;
+}
+
+mx_status_t check_dense(const mx_dense_t* d) {
+  if (!d) return MX_ERR_NULL;
+  if (d->dtype != MX_F32 && d->dtype != MX_BF16) return MX_ERR_FORMAT;
+  if (d->rows < 0 || d->cols < 0 || d->ld < d->cols) return MX_ERR_SHAPE;
+  if (d->rows > 0 && d->cols > 0 && !d->data) return MX_ERR_NULL;
+  if (!aligned16(d->data) || (d->ld % 8)) return MX_ERR_ALIGN;
+  return MX_OK;
+}
+
+mx_status_t check_packed(const mx_packed_t* p) {
+  if (!p) return MX_ERR_NULL;
+  if (p->outer < 0 || p->nblocks < 0) return MX_ERR_SHAPE;
+  if (p->outer > 0 && p->nblocks > 0 && (!p->codes || !p->scales)) return MX_ERR_NULL;
+  if (!aligned16(p->codes) || !aligned16(p->scales)) return MX_ERR_ALIGN;
+  if (p->outer > 0 && p->nblocks > ((int64_t)1 << 40) / p->outer) return MX_ERR_UNSUPPORTED;
+  return MX_OK;
+}
+
+// The tie rule the kernels implement in hardware conversions: ties to even on an MXFP target.
+bool hw_tie(const ElemInfo& info, mx_round_t r) {
+  return info.family == 1 && (r == MX_ROUND_DEFAULT || r == MX_ROUND_HALF_EVEN);
+}
+
+mx_status_t check_ss_pair(const mx_format_t* fa, const mx_format_t* ft, ElemInfo* ia, ElemInfo* it) {
+  mx_status_t st = check_format(fa, ia);
+  if (st != MX_OK) return st;
+  st = check_format(ft, it);
+  if (st != MX_OK) return st;
+  if (ia->family != it->family || it->bits >= ia->bits) return MX_ERR_FORMAT;  // not a down-conversion
+  if (fa->block != ft->block) return MX_ERR_FORMAT;
+  if (fa->round != ft->round) return MX_ERR_FORMAT;
+  if (fa->elem != MX_INT8 && fa->elem != MX_FP8_E4M3) return MX_ERR_UNSUPPORTED;
+  return MX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mx_elem_bits(mx_elem_t elem) {
+  ElemInfo i;
+  return elem_info((int)elem, &i) ? i.bits : -1;
+}
+
+int mx_elem_emax(mx_elem_t elem) {
+  ElemInfo i;
+  return elem_info((int)elem, &i) ? i.emax : -1;
+}
+
+mx_status_t mx_packed_bytes(const mx_format_t* f, int64_t rows, int64_t cols, size_t* code_bytes, size_t* scale_bytes) {
+  ElemInfo info;
+  mx_status_t st = check_format(f, &info);
+  if (st != MX_OK) return st;
+  if (!code_bytes || !scale_bytes) return MX_ERR_NULL;
+  int64_t outer, nblocks;
+  st = blocked_shape(f, rows, cols, &outer, &nblocks);
+  if (st != MX_OK) return st;
+  *scale_bytes = (size_t)(outer * nblocks);
+  *code_bytes = (size_t)(outer * nblocks) * (size_t)(f->block * info.bits / 8);
+  return MX_OK;
+}
+
+mx_status_t mx_quantize(const mx_format_t* f, const mx_dense_t* src, const mx_packed_t* dst, void* stream) {
+  ElemInfo info;
+  mx_status_t st = check_format(f, &info);
+  if (st != MX_OK) return st;
+  if ((st = check_dense(src)) != MX_OK) return st;
+  if ((st = check_packed(dst)) != MX_OK) return st;
+  int64_t outer, nblocks;
+  if ((st = blocked_shape(f, src->rows, src->cols, &outer, &nblocks)) != MX_OK) return st;
+  if (outer != dst->outer || nblocks != dst->nblocks) return MX_ERR_SHAPE;
+  if (outer == 0 || nblocks == 0) return MX_OK;
+  mx::DenseArg s{src->data, (int)src->dtype, src->rows, src->cols, src->ld};
+  return mx::quantize_launch((int)f->elem, f->axis, (int)f->round, s, dst->codes, dst->scales, static_cast<hipStream_t>(stream));
+}
+
+mx_status_t mx_slice_and_scale(const mx_format_t* fa, const mx_packed_t* anchor, const mx_format_t* ft,
+                               const mx_packed_t* target, void* stream) {
+  ElemInfo ia, it;
+  mx_status_t st = check_ss_pair(fa, ft, &ia, &it);
+  if (st != MX_OK) return st;
+  if ((st = check_packed(anchor)) != MX_OK) return st;
+  if ((st = check_packed(target)) != MX_OK) return st;
+  int64_t nb = anchor->outer * anchor->nblocks;
+  if (nb != target->outer * target->nblocks) return MX_ERR_SHAPE;
+  if (nb == 0) return MX_OK;
+  mx::SsTensor t{anchor->codes, anchor->scales, target->codes, target->scales, nb, 0, 0};
+  return mx::ss_launch_one((int)fa->elem, (int)ft->elem, hw_tie(it, ft->round), t, (int)ft->round,
+                           static_cast<hipStream_t>(stream));
+}
+
+size_t mx_slice_and_scale_batched_workspace(int32_t n) { return n > 0 ? sizeof(mx::SsTensor) * (size_t)n : 0; }
+
+mx_status_t mx_slice_and_scale_batched(const mx_format_t* fa, const mx_format_t* ft, int32_t n, const mx_packed_t* anchors,
+                                       const mx_packed_t* targets, void* workspace, size_t workspace_bytes, void* stream) {
+  ElemInfo ia, it;
+  mx_status_t st = check_ss_pair(fa, ft, &ia, &it);
+  if (st != MX_OK) return st;
+  if (n < 0) return MX_ERR_SHAPE;
+  if (n == 0) return MX_OK;
+  if (!anchors || !targets || !workspace) return MX_ERR_NULL;
+  if (!aligned16(workspace)) return MX_ERR_ALIGN;
+  if (workspace_bytes < mx_slice_and_scale_batched_workspace(n)) return MX_ERR_WORKSPACE;
+  std::vector<mx::SsTensor> t((size_t)n);
+  for (int32_t i = 0; i < n; ++i) {
+    if ((st = check_packed(&anchors[i])) != MX_OK) return st;
+    if ((st = check_packed(&targets[i])) != MX_OK) return st;
+    int64_t nb = anchors[i].outer * anchors[i].nblocks;
+    if (nb != targets[i].outer * targets[i].nblocks) return MX_ERR_SHAPE;
+    t[(size_t)i] = mx::SsTensor{anchors[i].codes, anchors[i].scales, targets[i].codes, targets[i].scales, nb, 0, 0};
+  }
+  return mx::ss_launch_many((int)fa->elem, (int)ft->elem, hw_tie(it, ft->round), n, t.data(), workspace, (int)ft->round,
+                            static_cast<hipStream_t>(stream));
+}
+
+mx_status_t mx_fake_quant(const mx_format_t* target, const mx_format_t* anchor, const mx_dense_t* src, const mx_dense_t* dst,
+                          void* stream) {
+  ElemInfo it, ia;
+  mx_status_t st = check_format(target, &it);
+  if (st != MX_OK) return st;
+  int anchor_elem = -1;
+  if (anchor) {
+    if ((st = check_format(anchor, &ia)) != MX_OK) return st;
+    if (ia.family != it.family || it.bits >= ia.bits) return MX_ERR_FORMAT;
+    if (anchor->block != target->block || anchor->axis != target->axis || anchor->round != target->round) return MX_ERR_FORMAT;
+    if (anchor->elem != MX_INT8 && anchor->elem != MX_FP8_E4M3) return MX_ERR_UNSUPPORTED;
+    anchor_elem = (int)anchor->elem;
+  }
+  if ((st = check_dense(src)) != MX_OK) return st;
+  if ((st = check_dense(dst)) != MX_OK) return st;
+  if (src->rows != dst->rows || src->cols != dst->cols) return MX_ERR_SHAPE;
+  if (src->dtype != dst->dtype) return MX_ERR_UNSUPPORTED;
+  if (src->data == dst->data && src->ld != dst->ld) return MX_ERR_SHAPE;
+  int64_t outer, nblocks;
+  if ((st = blocked_shape(target, src->rows, src->cols, &outer, &nblocks)) != MX_OK) return st;
+  if (outer == 0 || nblocks == 0) return MX_OK;
+  mx::DenseArg s{src->data, (int)src->dtype, src->rows, src->cols, src->ld};
+  mx::DenseArg d{dst->data, (int)dst->dtype, dst->rows, dst->cols, dst->ld};
+  return mx::fake_quant_launch((int)target->elem, anchor_elem, target->axis, (int)target->round, s, d,
+                               static_cast<hipStream_t>(stream));
+}
+
+mx_status_t mx_dequant(const mx_format_t* f, const mx_packed_t* src, const mx_dense_t* dst, void* stream) {
+  ElemInfo info;
+  mx_status_t st = check_format(f, &info);
+  if (st != MX_OK) return st;
+  if ((st = check_packed(src)) != MX_OK) return st;
+  if ((st = check_dense(dst)) != MX_OK) return st;
+  int64_t outer, nblocks;
+  if ((st = blocked_shape(f, dst->rows, dst->cols, &outer, &nblocks)) != MX_OK) return st;
+  if (outer != src->outer || nblocks != src->nblocks) return MX_ERR_SHAPE;
+  if (outer == 0 || nblocks == 0) return MX_OK;
+  mx::DenseArg d{dst->data, (int)dst->dtype, dst->rows, dst->cols, dst->ld};
+  return mx::dequant_launch((int)f->elem, f->axis, src->codes, src->scales, d, static_cast<hipStream_t>(stream));
+}
+
+const char* mx_status_str(mx_status_t status) {
+  switch (status) {
+    case MX_OK: return "ok";
+    case MX_ERR_NULL: return "null pointer";
+    case MX_ERR_FORMAT: return "bad format";
+    case MX_ERR_SHAPE: return "bad shape";
+    case MX_ERR_ALIGN: return "bad alignment";
+    case MX_ERR_UNSUPPORTED: return "unsupported";
+    case MX_ERR_LAUNCH: return "launch failed";
+    case MX_ERR_WORKSPACE: return "workspace too small";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,592 @@
+// Dense <-> packed kernels: MX quantization (Eq. (1), (2)), dequantization (V^ = X * P) and the
+// fused quantize-dequantize of the QAT forward pass (Sec. 3.2; Eq. (7) when an anchor is given).
+//
+// Blocks along a row (axis 1): one lane owns one 16-byte chunk of the dense tensor (4 fp32 or
+// 8 bf16), a block is 8 or 4 adjacent lanes.  The block maximum is reduced with DPP lane
+// permutes (no LDS), every lane converts its own elements, and sub-dword code pieces are merged
+// across neighbouring lanes with DPP so that the stores are whole dwords.
+// Blocks down a column (axis 0): one lane owns 4 adjacent columns over the 32 rows of a block
+// (32 coalesced row loads held in registers); no cross-lane step at all.
+#include "mx_device.h"
+#include "mx_launch.h"
+
+namespace mx {
+
+// ------------------------------------------------------------------ dense chunks
+template <int DT> struct Dense;
+template <> struct Dense<MX_F32> { static constexpr int N = 4, ESZ = 4; };
+template <> struct Dense<MX_BF16> { static constexpr int N = 8, ESZ = 2; };
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  bf16x2 p = {(__bf16)a, (__bf16)b};  // round to nearest even
+  return __builtin_bit_cast(uint32_t, p);
+}
+
+// 16-byte chunk at element offset `off` -> N floats
+template <int DT>
+__device__ __forceinline__ void load_chunk(const void* base, int64_t off, float (&v)[Dense<DT>::N]) {
+  u32x4 t = *reinterpret_cast<const u32x4*>(static_cast<const char*>(base) + off * Dense<DT>::ESZ);
+  if constexpr (DT == MX_F32) {
+    v[0] = __uint_as_float(t.x); v[1] = __uint_as_float(t.y); v[2] = __uint_as_float(t.z); v[3] = __uint_as_float(t.w);
+  } else {
+    v[0] = bf16_lo(t.x); v[1] = bf16_hi(t.x); v[2] = bf16_lo(t.y); v[3] = bf16_hi(t.y);
+    v[4] = bf16_lo(t.z); v[5] = bf16_hi(t.z); v[6] = bf16_lo(t.w); v[7] = bf16_hi(t.w);
+  }
+}
+
+template <int DT>
+__device__ __forceinline__ void store_chunk(void* base, int64_t off, const float (&v)[Dense<DT>::N]) {
+  u32x4 t;
+  if constexpr (DT == MX_F32) {
+    t = u32x4{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
+  } else {
+    t = u32x4{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
+  }
+  *reinterpret_cast<u32x4*>(static_cast<char*>(base) + off * Dense<DT>::ESZ) = t;
+}
+
+// 4 elements (one lane's columns of one row) for the column-axis kernels: 16 B fp32 / 8 B bf16
+template <int DT>
+__device__ __forceinline__ void load_quad(const void* base, int64_t off, float (&v)[4]) {
+  if constexpr (DT == MX_F32) {
+    u32x4 t = *reinterpret_cast<const u32x4*>(static_cast<const char*>(base) + off * 4);
+    v[0] = __uint_as_float(t.x); v[1] = __uint_as_float(t.y); v[2] = __uint_as_float(t.z); v[3] = __uint_as_float(t.w);
+  } else {
+    u32x2 t = *reinterpret_cast<const u32x2*>(static_cast<const char*>(base) + off * 2);
+    v[0] = bf16_lo(t.x); v[1] = bf16_hi(t.x); v[2] = bf16_lo(t.y); v[3] = bf16_hi(t.y);
+  }
+}
+
+template <int DT>
+__device__ __forceinline__ void store_quad(void* base, int64_t off, const float (&v)[4]) {
+  if constexpr (DT == MX_F32) {
+    *reinterpret_cast<u32x4*>(static_cast<char*>(base) + off * 4) =
+        u32x4{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
+  } else {
+    *reinterpret_cast<u32x2*>(static_cast<char*>(base) + off * 2) = u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+  }
+}
+
+// ------------------------------------------------------------------ cross-lane helpers (DPP, no LDS)
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+constexpr int DPP_XOR1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int DPP_XOR2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int DPP_HALF_MIRROR = 0x141; // lane i <-> 7 - i inside each group of 8
+constexpr int DPP_ROW_SHL1 = 0x101;    // lane i reads lane i + 1 (inside a row of 16)
+
+// maximum over the G (4 or 8) adjacent lanes that share a block; every lane gets the result
+template <int G>
+__device__ __forceinline__ uint32_t group_max(uint32_t m) {
+  uint32_t o = dpp<DPP_XOR1>(m); m = m > o ? m : o;
+  o = dpp<DPP_XOR2>(m); m = m > o ? m : o;
+  if constexpr (G == 8) { o = dpp<DPP_HALF_MIRROR>(m); m = m > o ? m : o; }
+  return m;
+}
+
+template <int N>
+__device__ __forceinline__ uint32_t chunk_amax_bits(const float (&v)[N]) {
+  uint32_t m = 0;
+#pragma unroll
+  for (int i = 0; i < N; ++i) { uint32_t a = abs_bits(v[i]); m = m > a ? m : a; }
+  return m;
+}
+
+// ------------------------------------------------------------------ chunk index -> element offset
+// Chunk q of a [rows, cols] matrix (cols / N chunks per row).  flat: ld == cols.
+template <int N>
+__device__ __forceinline__ int64_t chunk_offset(int64_t q, uint32_t chunks_per_row, int64_t ld, bool flat) {
+  if (flat) return q * N;
+  uint32_t row = (uint32_t)((uint64_t)q / chunks_per_row);
+  uint32_t c = (uint32_t)((uint64_t)q - (uint64_t)row * chunks_per_row);
+  return (int64_t)row * ld + (int64_t)c * N;
+}
+
+// ------------------------------------------------------------------ axis 1: quantize
+// Store the N * W code bits of this lane's chunk.  `lig` = lane index inside the block's group.
+template <int W, int N>
+__device__ __forceinline__ void store_chunk_codes(uint32_t* block_words, uint64_t bits, int lig) {
+  constexpr int NB = N * W;  // bits per lane
+  if constexpr (NB == 64) {
+    *reinterpret_cast<u32x2*>(block_words + 2 * lig) = u32x2{(uint32_t)bits, (uint32_t)(bits >> 32)};
+  } else if constexpr (NB == 32) {
+    block_words[lig] = (uint32_t)bits;
+  } else if constexpr (NB == 16) {
+    // pairs of lanes make one dword; the even lane stores
+    uint32_t nxt = dpp<DPP_ROW_SHL1>((uint32_t)bits);
+    if ((lig & 1) == 0) block_words[lig >> 1] = (uint32_t)bits | (nxt << 16);
+  } else if constexpr (NB == 24) {
+    // 4 lanes make 3 dwords: lane j < 3 of the quad stores (p_j >> 8j) | (p_{j+1} << (24 - 8j))
+    uint32_t nxt = dpp<DPP_ROW_SHL1>((uint32_t)bits);
+    int j = lig & 3;
+    uint32_t d = ((uint32_t)bits >> (8 * j)) | (nxt << (24 - 8 * j));
+    if (j < 3) block_words[(lig >> 2) * 3 + j] = d;
+  } else if constexpr (NB == 48) {
+    // 2 lanes make 3 dwords: even lane stores dwords 0 and 1, odd lane dword 2
+    uint32_t nxt = dpp<DPP_ROW_SHL1>((uint32_t)bits);
+    uint32_t* p = block_words + (lig >> 1) * 3;
+    if ((lig & 1) == 0) {
+      p[0] = (uint32_t)bits;
+      p[1] = (uint32_t)(bits >> 32) | (nxt << 16);
+    } else {
+      p[2] = (uint32_t)(bits >> 16);
+    }
+  } else {
+    static_assert(NB == 64, "odd element widths take the byte-staged path");
+  }
+}
+
+constexpr bool direct_code_store(int nb) { return nb == 64 || nb == 32 || nb == 16 || nb == 24 || nb == 48; }
+
+template <int ELEM, bool HW, int DT, int U>
+__global__ __launch_bounds__(256) void quantize_rows_kernel(const void* __restrict__ src, uint32_t* __restrict__ codes,
+                                                            uint8_t* __restrict__ scales, int64_t nchunks,
+                                                            uint32_t chunks_per_row, int64_t ld, int flat, int tie) {
+  using E = Elem<ELEM>;
+  constexpr int N = Dense<DT>::N, G = 32 / N, W = E::bits;
+  __shared__ uint32_t stage[direct_code_store(N * W) ? 1 : 256 * U * (N / 4)];
+  int tid = threadIdx.x;
+  if constexpr (HW && E::hw == HW_FP8) tid = set_fp8_saturation(tid);
+  int64_t q0 = (int64_t)blockIdx.x * (256 * U) + tid;
+  float v[U][N];
+  bool live[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    int64_t q = q0 + 256 * u;
+    live[u] = q < nchunks;
+    if (live[u]) load_chunk<DT>(src, chunk_offset<N>(q, chunks_per_row, ld, flat), v[u]);
+    else {
+#pragma unroll
+      for (int i = 0; i < N; ++i) v[u][i] = 0.0f;
+    }
+  }
+  const int lig = tid & (G - 1);
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    int64_t q = q0 + 256 * u;
+    uint32_t byte = scale_byte_from_amax<E::emax>(group_max<G>(chunk_amax_bits(v[u])));
+    uint64_t bits = byte == 255u ? 0ull : encode_chunk<ELEM, HW, N>(v[u], byte, tie);
+    int64_t blk = q / G;  // blocks are numbered like the chunks: row-major
+    if constexpr (direct_code_store(N * W)) {
+      // a block's lanes are all live or all not (chunks per row is a multiple of the group size)
+      if (live[u]) store_chunk_codes<W, N>(codes + blk * W, bits, lig);
+    } else {
+      // odd widths: stage one byte per code, repack one block per lane below
+      uint32_t b4[N / 4];
+#pragma unroll
+      for (int i = 0; i < N / 4; ++i) {
+        uint32_t r = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) r |= (uint32_t)((bits >> ((4 * i + k) * W)) & ((1u << W) - 1u)) << (8 * k);
+        b4[i] = r;
+      }
+#pragma unroll
+      for (int i = 0; i < N / 4; ++i) stage[(u * 256 + tid) * (N / 4) + i] = b4[i];
+    }
+    if (live[u] && lig == 0) scales[blk] = (uint8_t)byte;
+  }
+  if constexpr (!direct_code_store(N * W)) {
+    __syncthreads();
+    // 256 * U chunks = 256 * U / G blocks staged as 32 bytes each, in chunk order
+    constexpr int BLOCKS = 256 * U / G;
+    for (int b = tid; b < BLOCKS; b += 256) {
+      // chunk order inside the stage: u-major, then lane; block b of slab u' covers lanes [G*b', G*b'+G)
+      int u2 = b / (256 / G), bl = b % (256 / G);
+      int64_t blk = ((int64_t)blockIdx.x * (256 * U) + 256 * u2) / G + bl;
+      if (blk * G < nchunks) {
+        uint32_t in[8], out[W];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) in[i] = stage[(u2 * 256 + bl * G) * (N / 4) + i];
+        pack_block_bytes<W>(in, out);
+        store_dwords<W>(codes + blk * W, out);
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ axis 1: dequantize
+// N * W code bits of this lane's chunk out of the block's W dwords.
+template <int W, int N>
+__device__ __forceinline__ uint64_t load_chunk_codes(const uint32_t* block_words, int lig) {
+  constexpr int NB = N * W;
+  int o = lig * NB, d = o >> 5, sh = o & 31;
+  uint32_t w0 = block_words[d];
+  uint32_t w1 = block_words[d + 1 < W ? d + 1 : W - 1];
+  uint64_t lohi = (uint64_t)w0 | ((uint64_t)w1 << 32);
+  uint64_t r = lohi >> sh;
+  if constexpr (NB > 33) {  // may straddle three dwords
+    uint32_t w2 = block_words[d + 2 < W ? d + 2 : W - 1];
+    if (sh) r |= (uint64_t)w2 << (64 - sh);
+  }
+  if constexpr (NB < 64) r &= (1ull << NB) - 1ull;
+  return r;
+}
+
+template <int ELEM, int DT, int U>
+__global__ __launch_bounds__(256) void dequant_rows_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restrict__ scales,
+                                                           void* __restrict__ dst, int64_t nchunks, uint32_t chunks_per_row,
+                                                           int64_t ld, int flat) {
+  using E = Elem<ELEM>;
+  constexpr int N = Dense<DT>::N, G = 32 / N, W = E::bits;
+  constexpr bool HW = E::hw != HW_NONE;
+  int tid = threadIdx.x;
+  int64_t q0 = (int64_t)blockIdx.x * (256 * U) + tid;
+  const int lig = tid & (G - 1);
+  uint64_t bits[U];
+  uint32_t byte[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    int64_t q = q0 + 256 * u;
+    bits[u] = 0; byte[u] = 0;
+    if (q < nchunks) {
+      int64_t blk = q / G;
+      bits[u] = load_chunk_codes<W, N>(codes + blk * W, lig);
+      byte[u] = scales[blk];
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    int64_t q = q0 + 256 * u;
+    if (q < nchunks) {
+      float v[N];
+      decode_chunk<ELEM, HW, N>(bits[u], byte[u], v);
+      if (byte[u] == 255u) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] = __uint_as_float(0x7FC00000u);
+      }
+      store_chunk<DT>(dst, chunk_offset<N>(q, chunks_per_row, ld, flat), v);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ fake-quant of one chunk / column piece
+// v (N elements of a block whose scale byte(s) are given) -> DQ(Q(v)) in place.
+template <int TARGET, int ANCHOR, bool HW, int N>
+__device__ __forceinline__ void fake_quant_chunk(float (&v)[N], uint32_t byte_first, int tie) {
+  // byte_first: scale byte of the format quantized first (the anchor if there is one)
+  if (byte_first == 255u) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = __uint_as_float(0x7FC00000u);
+    return;
+  }
+  if constexpr (ANCHOR < 0) {
+    uint64_t c = encode_chunk<TARGET, HW, N>(v, byte_first, tie);
+    decode_chunk<TARGET, HW, N>(c, byte_first, v);
+  } else {
+    // Eq. (7): W_A = Q_A(W); W_t = Q_{A->t}(W_A) = quantize_t(P_h / 2^De) with X_l = X_h 2^De
+    constexpr int DE = Elem<ANCHOR>::emax - Elem<TARGET>::emax;
+    uint64_t ch = encode_chunk<ANCHOR, HW, N>(v, byte_first, tie);
+    float ph[N];
+    decode_chunk<ANCHOR, HW, N>(ch, 127u, ph);               // the anchor elements P_h as numbers
+    uint64_t cl = encode_chunk<TARGET, HW, N>(ph, 127u + DE, tie);
+    uint32_t byte_l = byte_first + DE > 254u ? 254u : byte_first + DE;
+    decode_chunk<TARGET, HW, N>(cl, byte_l, v);
+  }
+}
+
+template <int TARGET, int ANCHOR>
+struct FirstFormat { static constexpr int elem = ANCHOR < 0 ? TARGET : ANCHOR; };
+
+template <int TARGET, int ANCHOR, bool HW, int DT, int U>
+__global__ __launch_bounds__(256) void fake_quant_rows_kernel(const void* __restrict__ src, void* __restrict__ dst,
+                                                              int64_t nchunks, uint32_t chunks_per_row, int64_t ld_src,
+                                                              int64_t ld_dst, int flat_src, int flat_dst, int tie) {
+  constexpr int FIRST = FirstFormat<TARGET, ANCHOR>::elem;
+  constexpr int N = Dense<DT>::N, G = 32 / N;
+  int tid = threadIdx.x;
+  if constexpr (HW && Elem<FIRST>::hw == HW_FP8) tid = set_fp8_saturation(tid);
+  int64_t q0 = (int64_t)blockIdx.x * (256 * U) + tid;
+  float v[U][N];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    int64_t q = q0 + 256 * u;
+    if (q < nchunks) load_chunk<DT>(src, chunk_offset<N>(q, chunks_per_row, ld_src, flat_src), v[u]);
+    else {
+#pragma unroll
+      for (int i = 0; i < N; ++i) v[u][i] = 0.0f;
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    int64_t q = q0 + 256 * u;
+    uint32_t byte = scale_byte_from_amax<Elem<FIRST>::emax>(group_max<G>(chunk_amax_bits(v[u])));
+    fake_quant_chunk<TARGET, ANCHOR, HW, N>(v[u], byte, tie);
+    if (q < nchunks) store_chunk<DT>(dst, chunk_offset<N>(q, chunks_per_row, ld_dst, flat_dst), v[u]);
+  }
+}
+
+// ------------------------------------------------------------------ axis 0 (blocks down a column)
+// Work item = (row block rb, column quad cq): 4 adjacent columns x 32 rows in registers.
+struct ColItem { int64_t rb; uint32_t cq; };
+__device__ __forceinline__ ColItem col_item(int64_t item, uint32_t quads_per_row) {
+  uint32_t rb = (uint32_t)((uint64_t)item / quads_per_row);
+  return ColItem{(int64_t)rb, (uint32_t)((uint64_t)item - (uint64_t)rb * quads_per_row)};
+}
+
+template <int FIRST_EMAX>
+__device__ __forceinline__ void column_bytes(const float (&v)[32][4], uint32_t (&byte)[4]) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    uint32_t m = 0;
+#pragma unroll
+    for (int r = 0; r < 32; ++r) { uint32_t a = abs_bits(v[r][j]); m = m > a ? m : a; }
+    byte[j] = scale_byte_from_amax<FIRST_EMAX>(m);
+  }
+}
+
+// insert `nbits` bits at bit position `pos` (compile-time) of a W-dword string
+template <int W, int POS, int NBITS>
+__device__ __forceinline__ void insert_bits(uint32_t (&out)[W], uint64_t bits) {
+  constexpr int d = POS >> 5, s = POS & 31;
+  out[d] |= (uint32_t)(bits << s);
+  if constexpr (s + NBITS > 32) out[d + 1] |= (uint32_t)(bits >> (32 - s));
+  if constexpr (s + NBITS > 64) out[d + 2] |= (uint32_t)(bits >> (64 - s));
+}
+template <int W, int POS, int NBITS>
+__device__ __forceinline__ uint64_t extract_bits(const uint32_t (&in)[W]) {
+  constexpr int d = POS >> 5, s = POS & 31;
+  uint64_t r = (uint64_t)in[d] >> s;
+  if constexpr (s + NBITS > 32) r |= (uint64_t)in[d + 1] << (32 - s);
+  if constexpr (s + NBITS > 64) r |= (uint64_t)in[d + 2] << (64 - s);
+  if constexpr (NBITS < 64) r &= (1ull << NBITS) - 1ull;
+  return r;
+}
+
+template <int ELEM, bool HW, int DT>
+__global__ __launch_bounds__(256) void quantize_cols_kernel(const void* __restrict__ src, uint32_t* __restrict__ codes,
+                                                            uint8_t* __restrict__ scales, int64_t nitems,
+                                                            uint32_t quads_per_row, int64_t ld, int64_t nrb, int tie) {
+  using E = Elem<ELEM>;
+  constexpr int W = E::bits;
+  int tid = threadIdx.x;
+  if constexpr (HW && E::hw == HW_FP8) tid = set_fp8_saturation(tid);
+  int64_t item = (int64_t)blockIdx.x * 256 + tid;
+  if (item >= nitems) return;
+  ColItem it = col_item(item, quads_per_row);
+  float v[32][4];
+  int64_t off = it.rb * 32 * ld + (int64_t)it.cq * 4;
+#pragma unroll
+  for (int r = 0; r < 32; ++r) load_quad<DT>(src, off + r * ld, v[r]);
+  uint32_t byte[4];
+  column_bytes<E::emax>(v, byte);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    uint32_t out[W];
+#pragma unroll
+    for (int i = 0; i < W; ++i) out[i] = 0;
+    static_for<0, 4>([&](auto cc) {
+      constexpr int C = decltype(cc)::value;
+      float x[8];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) x[r] = v[8 * C + r][j];
+      uint64_t bits = byte[j] == 255u ? 0ull : encode_chunk<ELEM, HW, 8>(x, byte[j], tie);
+      insert_bits<W, C * 8 * W, 8 * W>(out, bits);
+    });
+    int64_t blk = ((int64_t)it.cq * 4 + j) * nrb + it.rb;  // packed tensor is [cols][row blocks]
+    store_dwords<W>(codes + blk * W, out);
+    scales[blk] = (uint8_t)byte[j];
+  }
+}
+
+template <int ELEM, int DT>
+__global__ __launch_bounds__(256) void dequant_cols_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restrict__ scales,
+                                                           void* __restrict__ dst, int64_t nitems, uint32_t quads_per_row,
+                                                           int64_t ld, int64_t nrb) {
+  using E = Elem<ELEM>;
+  constexpr int W = E::bits;
+  constexpr bool HW = E::hw != HW_NONE;
+  int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (item >= nitems) return;
+  ColItem it = col_item(item, quads_per_row);
+  float v[32][4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    int64_t blk = ((int64_t)it.cq * 4 + j) * nrb + it.rb;
+    uint32_t in[W];
+    load_dwords<W>(codes + blk * W, in);
+    uint32_t byte = scales[blk];
+    static_for<0, 4>([&](auto cc) {
+      constexpr int C = decltype(cc)::value;
+      float x[8];
+      decode_chunk<ELEM, HW, 8>(extract_bits<W, C * 8 * W, 8 * W>(in), byte, x);
+#pragma unroll
+      for (int r = 0; r < 8; ++r) v[8 * C + r][j] = byte == 255u ? __uint_as_float(0x7FC00000u) : x[r];
+    });
+  }
+  int64_t off = it.rb * 32 * ld + (int64_t)it.cq * 4;
+#pragma unroll
+  for (int r = 0; r < 32; ++r) store_quad<DT>(dst, off + r * ld, v[r]);
+}
+
+template <int TARGET, int ANCHOR, bool HW, int DT>
+__global__ __launch_bounds__(256) void fake_quant_cols_kernel(const void* __restrict__ src, void* __restrict__ dst,
+                                                              int64_t nitems, uint32_t quads_per_row, int64_t ld_src,
+                                                              int64_t ld_dst, int tie) {
+  constexpr int FIRST = FirstFormat<TARGET, ANCHOR>::elem;
+  int tid = threadIdx.x;
+  if constexpr (HW && Elem<FIRST>::hw == HW_FP8) tid = set_fp8_saturation(tid);
+  int64_t item = (int64_t)blockIdx.x * 256 + tid;
+  if (item >= nitems) return;
+  ColItem it = col_item(item, quads_per_row);
+  float v[32][4];
+  int64_t off = it.rb * 32 * ld_src + (int64_t)it.cq * 4;
+#pragma unroll
+  for (int r = 0; r < 32; ++r) load_quad<DT>(src, off + r * ld_src, v[r]);
+  uint32_t byte[4];
+  column_bytes<Elem<FIRST>::emax>(v, byte);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      float x[8];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) x[r] = v[8 * c + r][j];
+      fake_quant_chunk<TARGET, ANCHOR, HW, 8>(x, byte[j], tie);
+#pragma unroll
+      for (int r = 0; r < 8; ++r) v[8 * c + r][j] = x[r];
+    }
+  }
+  int64_t offd = it.rb * 32 * ld_dst + (int64_t)it.cq * 4;
+#pragma unroll
+  for (int r = 0; r < 32; ++r) store_quad<DT>(dst, offd + r * ld_dst, v[r]);
+}
+
+// ------------------------------------------------------------------ host launchers
+constexpr int kRowsUnroll = 4;
+
+static inline bool launch_ok() { return hipGetLastError() == hipSuccess; }
+
+template <int ELEM, bool HW, int DT>
+static mx_status_t run_quantize(int axis, int tie, const DenseArg& s, void* codes, uint8_t* scales, hipStream_t st) {
+  if (axis == 1) {
+    constexpr int N = Dense<DT>::N;
+    int64_t cpr = s.cols / N, nchunks = s.rows * cpr;
+    if (cpr > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;
+    int64_t wgs = (nchunks + 256 * kRowsUnroll - 1) / (256 * kRowsUnroll);
+    if (wgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((quantize_rows_kernel<ELEM, HW, DT, kRowsUnroll>), dim3((unsigned)wgs), dim3(256), 0, st, s.data,
+                       static_cast<uint32_t*>(codes), scales, nchunks, (uint32_t)cpr, s.ld, (int)(s.ld == s.cols), tie);
+  } else {
+    if (s.cols % 4) return MX_ERR_UNSUPPORTED;
+    int64_t qpr = s.cols / 4, nrb = s.rows / 32, nitems = qpr * nrb;
+    if (qpr > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;
+    int64_t wgs = (nitems + 255) / 256;
+    if (wgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((quantize_cols_kernel<ELEM, HW, DT>), dim3((unsigned)wgs), dim3(256), 0, st, s.data,
+                       static_cast<uint32_t*>(codes), scales, nitems, (uint32_t)qpr, s.ld, nrb, tie);
+  }
+  return launch_ok() ? MX_OK : MX_ERR_LAUNCH;
+}
+
+template <int ELEM, int DT>
+static mx_status_t run_dequant(int axis, const void* codes, const uint8_t* scales, const DenseArg& d, hipStream_t st) {
+  if (axis == 1) {
+    constexpr int N = Dense<DT>::N;
+    int64_t cpr = d.cols / N, nchunks = d.rows * cpr;
+    if (cpr > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;
+    int64_t wgs = (nchunks + 256 * kRowsUnroll - 1) / (256 * kRowsUnroll);
+    if (wgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((dequant_rows_kernel<ELEM, DT, kRowsUnroll>), dim3((unsigned)wgs), dim3(256), 0, st,
+                       static_cast<const uint32_t*>(codes), scales, d.data, nchunks, (uint32_t)cpr, d.ld, (int)(d.ld == d.cols));
+  } else {
+    if (d.cols % 4) return MX_ERR_UNSUPPORTED;
+    int64_t qpr = d.cols / 4, nrb = d.rows / 32, nitems = qpr * nrb;
+    if (qpr > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;
+    int64_t wgs = (nitems + 255) / 256;
+    if (wgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((dequant_cols_kernel<ELEM, DT>), dim3((unsigned)wgs), dim3(256), 0, st,
+                       static_cast<const uint32_t*>(codes), scales, d.data, nitems, (uint32_t)qpr, d.ld, nrb);
+  }
+  return launch_ok() ? MX_OK : MX_ERR_LAUNCH;
+}
+
+template <int TARGET, int ANCHOR, bool HW, int DT>
+static mx_status_t run_fake_quant(int axis, int tie, const DenseArg& s, const DenseArg& d, hipStream_t st) {
+  if (axis == 1) {
+    constexpr int N = Dense<DT>::N;
+    int64_t cpr = s.cols / N, nchunks = s.rows * cpr;
+    if (cpr > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;
+    int64_t wgs = (nchunks + 256 * kRowsUnroll - 1) / (256 * kRowsUnroll);
+    if (wgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((fake_quant_rows_kernel<TARGET, ANCHOR, HW, DT, kRowsUnroll>), dim3((unsigned)wgs), dim3(256), 0, st,
+                       s.data, d.data, nchunks, (uint32_t)cpr, s.ld, d.ld, (int)(s.ld == s.cols), (int)(d.ld == d.cols), tie);
+  } else {
+    if (s.cols % 4) return MX_ERR_UNSUPPORTED;
+    int64_t qpr = s.cols / 4, nrb = s.rows / 32, nitems = qpr * nrb;
+    if (qpr > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;
+    int64_t wgs = (nitems + 255) / 256;
+    if (wgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((fake_quant_cols_kernel<TARGET, ANCHOR, HW, DT>), dim3((unsigned)wgs), dim3(256), 0, st, s.data, d.data,
+                       nitems, (uint32_t)qpr, s.ld, d.ld, tie);
+  }
+  return launch_ok() ? MX_OK : MX_ERR_LAUNCH;
+}
+
+// ---- runtime -> template dispatch
+#define MX_FOR_EACH_ELEM(X)                                                                                   \
+  X(MX_INT8) X(MX_INT7) X(MX_INT6) X(MX_INT5) X(MX_INT4) X(MX_INT3) X(MX_INT2) X(MX_FP8_E4M3) X(MX_FP7_E3M3) \
+  X(MX_FP6_E3M2) X(MX_FP6_E2M3) X(MX_FP5_E2M2) X(MX_FP4_E2M1)
+
+static inline bool use_hw(int elem_is_fp, int tie) { return elem_is_fp && (tie == MX_ROUND_DEFAULT || tie == MX_ROUND_HALF_EVEN); }
+
+mx_status_t quantize_launch(int elem, int axis, int tie, const DenseArg& src, void* codes, uint8_t* scales, hipStream_t stream) {
+#define X(ID)                                                                                              \
+  if (elem == ID) {                                                                                        \
+    constexpr bool CAN = Elem<ID>::hw != HW_NONE;                                                          \
+    bool hw = CAN && use_hw(!Elem<ID>::is_int, tie);                                                       \
+    if (src.dtype == MX_F32)                                                                               \
+      return hw ? run_quantize<ID, CAN, MX_F32>(axis, tie, src, codes, scales, stream)                     \
+                : run_quantize<ID, false, MX_F32>(axis, tie, src, codes, scales, stream);                  \
+    return hw ? run_quantize<ID, CAN, MX_BF16>(axis, tie, src, codes, scales, stream)                      \
+              : run_quantize<ID, false, MX_BF16>(axis, tie, src, codes, scales, stream);                   \
+  }
+  MX_FOR_EACH_ELEM(X)
+#undef X
+  return MX_ERR_FORMAT;
+}
+
+mx_status_t dequant_launch(int elem, int axis, const void* codes, const uint8_t* scales, const DenseArg& dst, hipStream_t stream) {
+#define X(ID)                                                                               \
+  if (elem == ID) {                                                                         \
+    if (dst.dtype == MX_F32) return run_dequant<ID, MX_F32>(axis, codes, scales, dst, stream); \
+    return run_dequant<ID, MX_BF16>(axis, codes, scales, dst, stream);                      \
+  }
+  MX_FOR_EACH_ELEM(X)
+#undef X
+  return MX_ERR_FORMAT;
+}
+
+template <int TARGET, int ANCHOR>
+static mx_status_t fake_quant_pick(int axis, int tie, const DenseArg& s, const DenseArg& d, hipStream_t stream) {
+  constexpr bool CAN = Elem<TARGET>::hw != HW_NONE;  // the 8-bit FP anchor always has a hardware path
+  bool hw = CAN && use_hw(!Elem<TARGET>::is_int, tie);
+  if (s.dtype == MX_F32)
+    return hw ? run_fake_quant<TARGET, ANCHOR, CAN, MX_F32>(axis, tie, s, d, stream)
+              : run_fake_quant<TARGET, ANCHOR, false, MX_F32>(axis, tie, s, d, stream);
+  return hw ? run_fake_quant<TARGET, ANCHOR, CAN, MX_BF16>(axis, tie, s, d, stream)
+            : run_fake_quant<TARGET, ANCHOR, false, MX_BF16>(axis, tie, s, d, stream);
+}
+
+mx_status_t fake_quant_launch(int target, int anchor, int axis, int tie, const DenseArg& src, const DenseArg& dst,
+                              hipStream_t stream) {
+#define X(ID)                                                                                             \
+  if (target == ID) {                                                                                     \
+    if (anchor < 0) return fake_quant_pick<ID, -1>(axis, tie, src, dst, stream);                          \
+    if constexpr (Elem<ID>::is_int && Elem<ID>::bits < 8) {                                               \
+      if (anchor == MX_INT8) return fake_quant_pick<ID, MX_INT8>(axis, tie, src, dst, stream);            \
+    }                                                                                                     \
+    if constexpr (!Elem<ID>::is_int && Elem<ID>::bits < 8) {                                              \
+      if (anchor == MX_FP8_E4M3) return fake_quant_pick<ID, MX_FP8_E4M3>(axis, tie, src, dst, stream);    \
+    }                                                                                                     \
+    return MX_ERR_FORMAT;                                                                                 \
+  }
+  MX_FOR_EACH_ELEM(X)
+#undef X
+  return MX_ERR_FORMAT;
+}
+
+}  // namespace mx

@@ -1,0 +1,45 @@
+// Host-side declarations shared by the C-ABI layer (mx_api.hip) and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "mx.h"
+
+namespace mx {
+
+// One tensor of a Slice-and-Scale launch (device pointers).  wg_begin / wg_scale are filled in
+// by the batched launcher: first workgroup of the tensor's code part and of its scale part.
+struct SsTensor {
+  const void* codes_h;
+  const uint8_t* scales_h;
+  void* codes_l;
+  uint8_t* scales_l;
+  int64_t nblocks;
+  int64_t wg_begin;
+  int64_t wg_scale;
+};
+
+constexpr int kSsTableChunk = 64;  // descriptors per table-writer launch (kernel arguments stay under 4 KiB)
+struct SsTableChunk {
+  SsTensor t[kSsTableChunk];
+  int base, count;
+};
+
+mx_status_t ss_launch_one(int anchor, int target, bool hw, const SsTensor& t, int tie, hipStream_t stream);
+mx_status_t ss_launch_many(int anchor, int target, bool hw, int n, const SsTensor* h_tensors, void* workspace, int tie,
+                           hipStream_t stream);
+
+// Dense <-> packed kernels.  `dense` / `ld` in elements of dtype; outer / nblocks as in mx.h.
+struct DenseArg {
+  void* data;
+  int dtype;
+  int64_t rows, cols, ld;
+};
+mx_status_t quantize_launch(int elem, int axis, int tie, const DenseArg& src, void* codes, uint8_t* scales, hipStream_t stream);
+mx_status_t dequant_launch(int elem, int axis, const void* codes, const uint8_t* scales, const DenseArg& dst, hipStream_t stream);
+mx_status_t fake_quant_launch(int target, int anchor /* -1: none */, int axis, int tie, const DenseArg& src,
+                              const DenseArg& dst, hipStream_t stream);
+
+}  // namespace mx

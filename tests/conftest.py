@@ -16,4 +16,5 @@ def pytest_configure(config):
 def oracle():
     import oracle as _oracle
     _oracle.build()
+    _oracle.set_threads(min(8, os.cpu_count() or 1))
     return _oracle
