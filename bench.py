@@ -1,0 +1,269 @@
+#!/usr/bin/env python3
+"""Benchmark of the MX hot path on one MI355X.
+
+Headline (the benchmark's metric): Slice-and-Scale MXFP8 (E4M3) -> MXFP4 (E2M1) over a
+Llama-8B-shaped decoder checkpoint (224 linear weights, 6 979 321 856 elements, block 32), as
+GB/s of algorithmic traffic (anchor codes + anchor scales read, target codes + target scales
+written) and as a fraction of the 8 TB/s HBM peak.  One step = one such pass over the whole
+checkpoint in one batched launch, the anchor already resident in HBM.  The other rows of the
+hot path (quantize, dequantize, fake-quant, the other conversions) are timed in the same run
+and reported under "rows".  The CPU oracle is timed beside it on a bounded sample.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers L] [--no-rows] [--no-cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+HBM_PEAK_GBS = 8000.0
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_region(torch, fn, steps, warmup):
+    """Average milliseconds per call: events on the current stream, bracketed by synchronize."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    t0 = time.perf_counter()
+    ev[0].record()
+    for i in range(steps):
+        fn()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    per = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
+    return sum(per) / steps, min(per), wall_ms / steps
+
+
+def build_checkpoint(torch, mx, synth, layers, anchor_elem):
+    """Quantize the synthetic decoder weights to one packed anchor arena; returns per-tensor views."""
+    tensors = synth.llama8b_tensor_list(layers)
+    total_blocks = sum(r * c // 32 for _, r, c in tensors)
+    codes = torch.empty((total_blocks, 32), dtype=torch.uint8, device="cuda")
+    scales = torch.empty((total_blocks,), dtype=torch.uint8, device="cuda")
+    fmt = mx.make_format(anchor_elem)
+    views, b0 = [], 0
+    for i, (_, r, c) in enumerate(tensors):
+        w = synth.torch_config3_weight(i, r, c)
+        nb = r * c // 32
+        cv = codes[b0:b0 + nb].view(r, c // 32, 32)
+        sv = scales[b0:b0 + nb].view(r, c // 32)
+        mx.mx_quantize(w, fmt, cv, sv)
+        views.append((cv, sv))
+        b0 += nb
+        del w
+    torch.cuda.synchronize()
+    return tensors, codes, scales, views
+
+
+def alloc_targets(torch, mx, views, target_elem):
+    bb = 32 * mx.mx_elem_bits(target_elem) // 8
+    total = sum(s.numel() for _, s in views)
+    codes = torch.empty((total, bb), dtype=torch.uint8, device="cuda")
+    scales = torch.empty((total,), dtype=torch.uint8, device="cuda")
+    out, b0 = [], 0
+    for _, s in views:
+        nb = s.numel()
+        out.append((codes[b0:b0 + nb].view(tuple(s.shape) + (bb,)), scales[b0:b0 + nb].view(s.shape)))
+        b0 += nb
+    return codes, scales, out
+
+
+def ss_bytes(nblocks, anchor_bits, target_bits):
+    return nblocks * (4 * anchor_bits + 4 * target_bits + 2)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=32, help="decoder layers of the synthetic checkpoint (32 = the 8B shape)")
+    ap.add_argument("--no-rows", action="store_true", help="skip the secondary rows")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no collectives exist in this path); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2604_00529_amd as mx
+    from paper_2604_00529_amd import synth
+    mx.binding.lib()
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+
+    # ---------------------------------------------------------------- headline: SS E4M3 -> E2M1, whole checkpoint
+    log("[bench] building the MXFP8 anchor checkpoint (%d layers)" % args.layers)
+    tensors, a_codes, a_scales, a_views = build_checkpoint(torch, mx, synth, args.layers, "e4m3")
+    nblocks = a_scales.numel()
+    n_elem = nblocks * 32
+    fa, ft = mx.make_format("e4m3"), mx.make_format("e2m1")
+    t_codes, t_scales, t_views = alloc_targets(torch, mx, a_views, "e2m1")
+    ws = torch.empty(mx.binding.lib().mx_slice_and_scale_batched_workspace(len(a_views)), dtype=torch.uint8, device="cuda")
+
+    batch = mx.SsBatch(a_views, fa, ft, t_views, ws)      # descriptors marshalled once; run() is one C call
+
+    def step():
+        batch.run()
+
+    log("[bench] timing Slice-and-Scale E4M3 -> E2M1: %d tensors, %d elements" % (len(a_views), n_elem))
+    ms, ms_min, wall_ms = time_region(torch, step, args.steps, args.warmup)
+    nbytes = ss_bytes(nblocks, 8, 4)
+    value = nbytes / (wall_ms * 1e-3) / 1e9
+    achieved = nbytes / (ms * 1e-3) / 1e9
+    log("[bench] %.3f ms/step (events avg %.3f, min %.3f): %.1f GB/s, %.1f %% of HBM peak"
+        % (wall_ms, ms, ms_min, value, 100 * achieved / HBM_PEAK_GBS))
+
+    result = {
+        "metric": "Slice-and-Scale GB/s and % of HBM peak, 8B-shaped checkpoint MXFP8->MXFP4",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "configs[2]: Llama-8B-shaped decoder checkpoint, %d layers, %d linear weights, "
+                               "%d elements, MXFP8 E4M3 anchor -> MXFP4 E2M1, block 32, one batched launch"
+                               % (args.layers, len(a_views), n_elem),
+                   "bytes_per_step": nbytes, "pct_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2)},
+        "roofline": {"bound": "hbm", "kernel": "ss_batched_kernel<E4M3,E2M1>", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC.get("ss_e4m3_e2m1")},
+    }
+
+    # ---------------------------------------------------------------- CPU oracle beside it (bounded sample)
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(torch, a_views, tensors)
+
+    # ---------------------------------------------------------------- the other rows of the hot path
+    if not args.no_rows:
+        rows = {}
+        steps2 = max(3, min(args.steps, 10))
+        for tgt in ("e3m2", "e2m3"):
+            c2, s2, v2 = alloc_targets(torch, mx, a_views, tgt)
+            f2 = mx.make_format(tgt)
+            m, _, _ = time_region(torch, mx.SsBatch(a_views, fa, f2, v2, ws).run, steps2, 2)
+            rows["ss_e4m3_%s" % tgt] = row(ss_bytes(nblocks, 8, 6), m)
+            del c2, s2, v2
+        del t_codes, t_scales, t_views, batch
+        torch.cuda.empty_cache()
+        # MXINT8 anchor -> MXINT6 / MXINT4: the anchor arena is re-quantized in place of the FP8 one
+        del a_codes, a_scales, a_views
+        torch.cuda.empty_cache()
+        tensors, a_codes, a_scales, a_views = build_checkpoint(torch, mx, synth, args.layers, "int8")
+        fi = mx.make_format("int8")
+        for tgt, bits in (("int4", 4), ("int6", 6)):
+            c2, s2, v2 = alloc_targets(torch, mx, a_views, tgt)
+            f2 = mx.make_format(tgt)
+            m, _, _ = time_region(torch, mx.SsBatch(a_views, fi, f2, v2, ws).run, steps2, 2)
+            rows["ss_int8_%s" % tgt] = row(ss_bytes(nblocks, 8, bits), m)
+            del c2, s2, v2
+        del a_codes, a_scales, a_views
+        torch.cuda.empty_cache()
+        # quantize / dequantize on the largest decoder weight (gate_proj, 14336 x 4096 bf16, 58.7 M elements):
+        # 8 distinct copies are rotated so that the 256 MB last-level cache cannot hold the working set
+        r, c = 14336, 4096
+        ws_list = [synth.torch_config3_weight(1000 + i, r, c) for i in range(8)]
+        state = {"i": 0}
+        for elem, bits in (("e4m3", 8), ("int8", 8), ("e2m1", 4)):
+            f = mx.make_format(elem)
+            outs = [mx.mx_quantize(w, f) for w in ws_list]
+
+            def q():
+                i = state["i"] = (state["i"] + 1) % 8
+                mx.mx_quantize(ws_list[i], f, *outs[i])
+            m, _, _ = time_region(torch, q, 16, 8)
+            rows["quantize_bf16_%s" % elem] = row(r * c * 2 + r * c // 32 * (4 * bits + 1), m)
+            deq = [torch.empty((r, c), dtype=torch.bfloat16, device="cuda") for _ in range(8)]
+
+            def dq():
+                i = state["i"] = (state["i"] + 1) % 8
+                mx.mx_dequant(outs[i][0], outs[i][1], f, r, c, out=deq[i])
+            m, _, _ = time_region(torch, dq, 16, 8)
+            rows["dequant_%s_bf16" % elem] = row(r * c * 2 + r * c // 32 * (4 * bits + 1), m)
+            del outs, deq
+        del ws_list
+        torch.cuda.empty_cache()
+        # fake-quant step of multi-format QAT (configs[3]): bf16 activations 32768 x 4096, blocks along the
+        # reduction axis, one sampled format per step, direct and through the 8-bit anchor
+        act = synth.torch_config4_activations()
+        out = torch.empty_like(act)
+        sched = synth.config4_format_schedule(steps=64)
+        nby = act.numel() * 4
+        for via in (False, True):
+            st = {"k": 0}
+
+            def fq():
+                elem = sched[st["k"] % len(sched)]
+                st["k"] += 1
+                anchor = None
+                if via and elem not in ("int8", "e4m3"):
+                    anchor = mx.make_format("int8" if elem.startswith("int") else "e4m3")
+                mx.mx_fake_quant(act, mx.make_format(elem), anchor, out)
+            m, _, _ = time_region(torch, fq, 64, 6)
+            rows["fake_quant_bf16_mixed_formats" + ("_via_anchor" if via else "")] = row(nby, m)
+        for elem in ("int8", "int4", "e4m3", "e3m2", "e2m1"):
+            f = mx.make_format(elem)
+            m, _, _ = time_region(torch, lambda: mx.mx_fake_quant(act, f, None, out), 10, 3)
+            rows["fake_quant_bf16_%s" % elem] = row(nby, m)
+        wt = synth.torch_config3_weight(2000, 4096, 14336)       # [K, N] weight, blocks down the columns (axis 0)
+        wo = torch.empty_like(wt)
+        for elem in ("int4", "e2m1"):
+            f0 = mx.make_format(elem, axis=0)
+            m, _, _ = time_region(torch, lambda: mx.mx_fake_quant(wt, f0, None, wo), 10, 3)
+            rows["fake_quant_bf16_%s_axis0_cache_resident" % elem] = row(wt.numel() * 4, m)
+        result["rows"] = rows
+
+    print(json.dumps(result), flush=True)
+
+
+def row(nbytes, ms):
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    return {"ms": round(ms, 4), "GB/s": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+
+
+# HBM bytes per launch of the headline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
+# scaled by the same counters on a plain copy of known size (see profiles/); None until measured.
+MEASURED_TRAFFIC = {}
+
+
+def cpu_baseline(torch, a_views, tensors):
+    """The CPU oracle on a bounded sample of the same anchor: whole tensors from layer 0 on."""
+    import numpy as np
+    import oracle
+    oracle.build()
+    threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
+    oracle.set_threads(threads)
+    # calibrate on the smallest tensor (k_proj), then take whole tensors worth roughly 15 s
+    c0 = a_views[1][0].cpu().numpy()
+    s0 = a_views[1][1].cpu().numpy()
+    t0 = time.perf_counter()
+    oracle.slice_and_scale(c0, s0, "e4m3", "e2m1")
+    rate = s0.size / (time.perf_counter() - t0)           # blocks per second
+    budget_blocks = rate * 15.0
+    sample, used = [], 0
+    for (cv, sv), (name, r, c) in zip(a_views, tensors):
+        if used and used + sv.numel() > budget_blocks:
+            break
+        sample.append((cv.cpu().numpy(), sv.cpu().numpy(), name))
+        used += sv.numel()
+    log("[bench] CPU oracle on %d tensors (%d elements), %d threads" % (len(sample), used * 32, threads))
+    t0 = time.perf_counter()
+    for cv, sv, _ in sample:
+        oracle.slice_and_scale(cv, sv, "e4m3", "e2m1")
+    dt = time.perf_counter() - t0
+    gbs = ss_bytes(used, 8, 4) / dt / 1e9
+    return {"value": round(gbs, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": "Slice-and-Scale E4M3->E2M1 of the first %d tensors of the same anchor (%s..%s), %d elements, %.1f s"
+                      % (len(sample), sample[0][2], sample[-1][2], used * 32, dt)}
+
+
+if __name__ == "__main__":
+    main()

@@ -12,7 +12,7 @@ from .binding import ELEMS, MxError, make_format
 
 __all__ = ["mx_quantize", "mx_slice_and_scale", "mx_slice_and_scale_batched", "mx_fake_quant", "mx_dequant",
            "mx_packed_bytes", "mx_elem_bits", "mx_elem_emax", "MxFakeQuantSTE", "ELEMS", "MxError", "make_format",
-           "packed_shape"]
+           "packed_shape", "SsBatch"]
 
 
 def _torch():
@@ -128,6 +128,36 @@ def mx_slice_and_scale_batched(anchors, fa, ft, targets=None, workspace=None):
                                                ctypes.c_void_p(workspace.data_ptr()), workspace.numel(),
                                                _stream(anchors[0][0])), "mx_slice_and_scale_batched")
     return targets
+
+
+class SsBatch:
+    """A batched Slice-and-Scale call with its descriptor arrays marshalled once (a checkpoint's
+    layout is static): `run()` is then a single C call."""
+
+    def __init__(self, anchors, fa, ft, targets=None, workspace=None):
+        torch = _torch()
+        L = binding.lib()
+        n = len(anchors)
+        bb = ft.block * L.mx_elem_bits(ft.elem) // 8
+        if targets is None:
+            targets = [(torch.empty(tuple(s.shape) + (bb,), dtype=torch.uint8, device=c.device), torch.empty_like(s))
+                       for c, s in anchors]
+        if workspace is None:
+            workspace = torch.empty(max(16, L.mx_slice_and_scale_batched_workspace(n)), dtype=torch.uint8,
+                                    device=anchors[0][0].device)
+        self.anchors, self.targets, self.workspace = anchors, targets, workspace     # keep the tensors alive
+        self.fa, self.ft, self.n = fa, ft, n
+        self._A = (binding.MxPacked * n)(*[_packed(c, s, 1, s.numel()) for c, s in anchors])
+        self._T = (binding.MxPacked * n)(*[_packed(c, s, 1, s.numel()) for c, s in targets])
+        self._dev = anchors[0][0].device
+
+    def run(self):
+        torch = _torch()
+        stream = ctypes.c_void_p(torch.cuda.current_stream(self._dev).cuda_stream)
+        binding.check(binding.lib().mx_slice_and_scale_batched(
+            ctypes.byref(self.fa), ctypes.byref(self.ft), self.n, self._A, self._T,
+            ctypes.c_void_p(self.workspace.data_ptr()), self.workspace.numel(), stream), "mx_slice_and_scale_batched")
+        return self.targets
 
 
 def mx_fake_quant(src, target, anchor=None, out=None):
