@@ -109,7 +109,8 @@ def main():
     n_elem = nblocks * 32
     fa, ft = mx.make_format("e4m3"), mx.make_format("e2m1")
     t_codes, t_scales, t_views = alloc_targets(torch, mx, a_views, "e2m1")
-    ws = torch.empty(mx.binding.lib().mx_slice_and_scale_batched_workspace(len(a_views)), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(mx.binding.lib().mx_slice_and_scale_batched_workspace(len(a_views), nblocks), dtype=torch.uint8,
+                     device="cuda")
 
     batch = mx.SsBatch(a_views, fa, ft, t_views, ws)      # descriptors marshalled once; run() is one C call
 

@@ -112,12 +112,14 @@ mx_status_t mx_quantize(const mx_format_t* f, const mx_dense_t* src, const mx_pa
 mx_status_t mx_slice_and_scale(const mx_format_t* fa, const mx_packed_t* anchor, const mx_format_t* ft,
                                const mx_packed_t* target, void* stream);
 
-/* The same conversion for n tensors in ONE kernel launch (a whole checkpoint, Sec. 3.5
- * "Inference").  anchors / targets: host arrays of n descriptors.  workspace: device memory of
- * at least mx_slice_and_scale_batched_workspace(n) bytes, 16-byte aligned; the descriptor table
- * is copied there with hipMemcpyAsync on `stream`, so the host arrays may be reused as soon as
- * the call returns only if they are in pageable memory (the runtime stages those). */
-size_t mx_slice_and_scale_batched_workspace(int32_t n);
+/* The same conversion for n tensors in ONE conversion launch (a whole checkpoint, Sec. 3.5
+ * "Inference").  anchors / targets: host arrays of n descriptors, free to reuse when the call
+ * returns.  workspace: device memory of at least
+ * mx_slice_and_scale_batched_workspace(n, total number of blocks) bytes, 16-byte aligned; a few
+ * tiny set-up kernels write the launch tables there on `stream` ahead of the conversion kernel
+ * (nothing is copied from the host, so the call can be captured in a HIP graph).  The workspace
+ * must stay untouched until the work has completed.  MX_ERR_WORKSPACE if it is too small. */
+size_t mx_slice_and_scale_batched_workspace(int32_t n, int64_t total_blocks);
 mx_status_t mx_slice_and_scale_batched(const mx_format_t* fa, const mx_format_t* ft, int32_t n,
                                        const mx_packed_t* anchors, const mx_packed_t* targets,
                                        void* workspace, size_t workspace_bytes, void* stream);

@@ -119,7 +119,7 @@ def mx_slice_and_scale_batched(anchors, fa, ft, targets=None, workspace=None):
     if n == 0:
         return targets
     dev = anchors[0][0].device
-    need = L.mx_slice_and_scale_batched_workspace(n)
+    need = L.mx_slice_and_scale_batched_workspace(n, sum(s.numel() for _, s in anchors))
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     A = (binding.MxPacked * n)(*[_packed(c, s, 1, s.numel()) for c, s in anchors])
@@ -143,8 +143,8 @@ class SsBatch:
             targets = [(torch.empty(tuple(s.shape) + (bb,), dtype=torch.uint8, device=c.device), torch.empty_like(s))
                        for c, s in anchors]
         if workspace is None:
-            workspace = torch.empty(max(16, L.mx_slice_and_scale_batched_workspace(n)), dtype=torch.uint8,
-                                    device=anchors[0][0].device)
+            need = L.mx_slice_and_scale_batched_workspace(n, sum(s.numel() for _, s in anchors))
+            workspace = torch.empty(max(16, need), dtype=torch.uint8, device=anchors[0][0].device)
         self.anchors, self.targets, self.workspace = anchors, targets, workspace     # keep the tensors alive
         self.fa, self.ft, self.n = fa, ft, n
         self._A = (binding.MxPacked * n)(*[_packed(c, s, 1, s.numel()) for c, s in anchors])

@@ -62,7 +62,7 @@ def lib():
         L.mx_quantize.restype = st
         L.mx_slice_and_scale.argtypes = [P(MxFormat), P(MxPacked), P(MxFormat), P(MxPacked), vp]
         L.mx_slice_and_scale.restype = st
-        L.mx_slice_and_scale_batched_workspace.argtypes = [ctypes.c_int32]
+        L.mx_slice_and_scale_batched_workspace.argtypes = [ctypes.c_int32, ctypes.c_int64]
         L.mx_slice_and_scale_batched_workspace.restype = ctypes.c_size_t
         L.mx_slice_and_scale_batched.argtypes = [P(MxFormat), P(MxFormat), ctypes.c_int32, P(MxPacked), P(MxPacked), vp,
                                                  ctypes.c_size_t, vp]

@@ -138,7 +138,10 @@ mx_status_t mx_slice_and_scale(const mx_format_t* fa, const mx_packed_t* anchor,
                            static_cast<hipStream_t>(stream));
 }
 
-size_t mx_slice_and_scale_batched_workspace(int32_t n) { return n > 0 ? sizeof(mx::SsTensor) * (size_t)n : 0; }
+size_t mx_slice_and_scale_batched_workspace(int32_t n, int64_t total_blocks) {
+  if (n <= 0 || total_blocks < 0) return 0;
+  return mx::ss_workspace_bytes(n, total_blocks);
+}
 
 mx_status_t mx_slice_and_scale_batched(const mx_format_t* fa, const mx_format_t* ft, int32_t n, const mx_packed_t* anchors,
                                        const mx_packed_t* targets, void* workspace, size_t workspace_bytes, void* stream) {
@@ -149,7 +152,6 @@ mx_status_t mx_slice_and_scale_batched(const mx_format_t* fa, const mx_format_t*
   if (n == 0) return MX_OK;
   if (!anchors || !targets || !workspace) return MX_ERR_NULL;
   if (!aligned16(workspace)) return MX_ERR_ALIGN;
-  if (workspace_bytes < mx_slice_and_scale_batched_workspace(n)) return MX_ERR_WORKSPACE;
   std::vector<mx::SsTensor> t((size_t)n);
   for (int32_t i = 0; i < n; ++i) {
     if ((st = check_packed(&anchors[i])) != MX_OK) return st;
@@ -158,8 +160,8 @@ mx_status_t mx_slice_and_scale_batched(const mx_format_t* fa, const mx_format_t*
     if (nb != targets[i].outer * targets[i].nblocks) return MX_ERR_SHAPE;
     t[(size_t)i] = mx::SsTensor{anchors[i].codes, anchors[i].scales, targets[i].codes, targets[i].scales, nb, 0, 0};
   }
-  return mx::ss_launch_many((int)fa->elem, (int)ft->elem, hw_tie(it, ft->round), n, t.data(), workspace, (int)ft->round,
-                            static_cast<hipStream_t>(stream));
+  return mx::ss_launch_many((int)fa->elem, (int)ft->elem, it.bits, hw_tie(it, ft->round), n, t.data(), workspace,
+                            workspace_bytes, (int)ft->round, static_cast<hipStream_t>(stream));
 }
 
 mx_status_t mx_fake_quant(const mx_format_t* target, const mx_format_t* anchor, const mx_dense_t* src, const mx_dense_t* dst,

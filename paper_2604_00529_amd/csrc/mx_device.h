@@ -353,22 +353,24 @@ __device__ __forceinline__ uint32_t slice_e4m3_sw(uint32_t code, int tie) {
 }
 
 // ------------------------------------------------------------------ bit packing
-// 32 codes, one per byte in in[0..7], to W = bits dwords (little-endian bit string).
-template <int BITS>
-__device__ __forceinline__ void pack_block_bytes(const uint32_t (&in)[8], uint32_t (&out)[BITS]) {
+// 4 * NIN codes, one per byte in in[0..NIN-1], to NIN * BITS / 8 dwords (little-endian bit string).
+// NIN = 8 is a whole block, NIN = 4 half a block (even widths only).
+template <int BITS, int NIN>
+__device__ __forceinline__ void pack_bytes(const uint32_t (&in)[NIN], uint32_t (&out)[NIN * BITS / 8]) {
+  static_assert((NIN * BITS) % 8 == 0, "piece must end on a dword boundary");
   if constexpr (BITS == 8) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) out[i] = in[i];
+    for (int i = 0; i < NIN; ++i) out[i] = in[i];
   } else if constexpr (BITS == 4) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < NIN / 2; ++i) {
       uint32_t a = in[2 * i] | (in[2 * i] >> 4);          // bytes 0 and 2 hold two nibbles each
       uint32_t b = in[2 * i + 1] | (in[2 * i + 1] >> 4);
       out[i] = __builtin_amdgcn_perm(b, a, 0x06040200u);  // {a.b0, a.b2, b.b0, b.b2}
     }
   } else if constexpr (BITS == 6) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < NIN / 4; ++i) {
       uint32_t p[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -381,15 +383,20 @@ __device__ __forceinline__ void pack_block_bytes(const uint32_t (&in)[8], uint32
     }
   } else {
 #pragma unroll
-    for (int i = 0; i < BITS; ++i) out[i] = 0;
+    for (int i = 0; i < NIN * BITS / 8; ++i) out[i] = 0;
 #pragma unroll
-    for (int i = 0; i < 32; ++i) {
+    for (int i = 0; i < 4 * NIN; ++i) {
       uint32_t c = (in[i >> 2] >> (8 * (i & 3))) & ((1u << BITS) - 1u);
       const int pos = i * BITS, d = pos >> 5, sft = pos & 31;
       out[d] |= c << sft;
       if (sft + BITS > 32) out[d + 1] |= c >> (32 - sft);
     }
   }
+}
+
+template <int BITS>
+__device__ __forceinline__ void pack_block_bytes(const uint32_t (&in)[8], uint32_t (&out)[BITS]) {
+  pack_bytes<BITS, 8>(in, out);
 }
 
 // Store / load W consecutive dwords at a 4*W-byte stride per lane with the widest aligned accesses.
@@ -401,6 +408,11 @@ __device__ __forceinline__ void store_dwords(uint32_t* p, const uint32_t (&v)[W]
   } else if constexpr (W % 2 == 0) {
 #pragma unroll
     for (int i = 0; i < W / 2; ++i) reinterpret_cast<u32x2*>(p)[i] = u32x2{v[2 * i], v[2 * i + 1]};
+  } else if constexpr (W == 3) {
+    // one 96-bit store (needs only dword alignment)
+    typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+    typedef u32x3 __attribute__((aligned(4))) u32x3_a4;
+    *reinterpret_cast<u32x3_a4*>(p) = u32x3{v[0], v[1], v[2]};
   } else {
 #pragma unroll
     for (int i = 0; i < W; ++i) p[i] = v[i];

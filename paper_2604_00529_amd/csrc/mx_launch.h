@@ -9,16 +9,28 @@
 
 namespace mx {
 
-// One tensor of a Slice-and-Scale launch (device pointers).  wg_begin / wg_scale are filled in
-// by the batched launcher: first workgroup of the tensor's code part and of its scale part.
+// One tensor of a Slice-and-Scale launch (device pointers).  seg_begin / seg_scale are filled in
+// by the batched launcher: first segment of the tensor's code part and of its scale part.
 struct SsTensor {
   const void* codes_h;
   const uint8_t* scales_h;
   void* codes_l;
   uint8_t* scales_l;
   int64_t nblocks;
-  int64_t wg_begin;
-  int64_t wg_scale;
+  int64_t seg_begin;
+  int64_t seg_scale;
+};
+
+constexpr int kSsLanes = 64;       // one wave per workgroup, one load per lane
+constexpr int kSsSegWgs = 128;     // workgroups per segment of a batched launch (8192 pieces or scale chunks)
+
+// One segment of a batched launch: kind 0 = `count` code pieces, kind 1 = `count` scale bytes.
+struct SsSegment {
+  const void* in;
+  void* out;
+  int64_t count;
+  int32_t kind;
+  int32_t pad;
 };
 
 constexpr int kSsTableChunk = 64;  // descriptors per table-writer launch (kernel arguments stay under 4 KiB)
@@ -28,8 +40,9 @@ struct SsTableChunk {
 };
 
 mx_status_t ss_launch_one(int anchor, int target, bool hw, const SsTensor& t, int tie, hipStream_t stream);
-mx_status_t ss_launch_many(int anchor, int target, bool hw, int n, const SsTensor* h_tensors, void* workspace, int tie,
-                           hipStream_t stream);
+size_t ss_workspace_bytes(int n, int64_t total_blocks);
+mx_status_t ss_launch_many(int anchor, int target, int target_bits, bool hw, int n, const SsTensor* h_tensors,
+                           void* workspace, size_t workspace_bytes, int tie, hipStream_t stream);
 
 // Dense <-> packed kernels.  `dense` / `ld` in elements of dtype; outer / nblocks as in mx.h.
 struct DenseArg {
