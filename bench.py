@@ -89,6 +89,8 @@ def main():
     ap.add_argument("--layers", type=int, default=32, help="decoder layers of the synthetic checkpoint (32 = the 8B shape)")
     ap.add_argument("--no-rows", action="store_true", help="skip the secondary rows")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (for scaling the profiler's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives exist in this path); run with --gpus 1",
@@ -138,6 +140,14 @@ def main():
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC.get("ss_e4m3_e2m1")},
     }
+
+    if args.calibrate_copy:
+        src = torch.full((1 << 30,), 7, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---------------------------------------------------------------- CPU oracle beside it (bounded sample)
     if not args.no_cpu:
@@ -232,7 +242,7 @@ def row(nbytes, ms):
 
 # HBM bytes per launch of the headline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
 # scaled by the same counters on a plain copy of known size (see profiles/); None until measured.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {"ss_e4m3_e2m1": 10933240736}   # profiles/ss_e4m3_e2m1_llama8b_checkpoint.md
 
 
 def cpu_baseline(torch, a_views, tensors):
