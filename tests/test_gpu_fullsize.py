@@ -1,0 +1,160 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+Config 3 (Llama-8B-shaped checkpoint, 224 tensors, one batched launch): every output byte of the
+4-bit conversions is checked against a 256-entry table that the oracle computes one code at a
+time (the element map of Eq. (4) / Eq. (6) is a pure function of one anchor byte), every scale
+byte against the oracle's scale step, and windows of the 6-bit conversions and of the anchor
+quantization against the oracle proper.  Config 4 (fake-quant of 32768 x 4096 activations and of a
+4096 x 14336 weight down its columns): sampled rows / columns against the oracle.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2604_00529_amd import synth
+
+pytestmark = pytest.mark.gpu
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2604_00529_amd as mx
+    mx.binding.lib()
+    import bench
+    return torch, mx, bench
+
+
+def _bf16_to_host(t):
+    import torch
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def _windows(rng, nblocks, width, count):
+    out = [(0, min(width, nblocks)), (max(0, nblocks - width), nblocks)]
+    for _ in range(count):
+        s = int(rng.integers(0, max(1, nblocks - width)))
+        out.append((s, min(nblocks, s + width)))
+    return out
+
+
+@pytest.mark.parametrize("anchor,target4,targets6", [("e4m3", "e2m1", ("e3m2", "e2m3")), ("int8", "int4", ("int6",))])
+def test_config3_checkpoint(env, oracle, anchor, target4, targets6):
+    torch, mx, bench = env
+    rng = np.random.default_rng(33)
+    tensors, a_codes, a_scales, a_views = bench.build_checkpoint(torch, mx, synth, 32, anchor)
+    assert len(a_views) == 224 and a_scales.numel() == 218103808
+    fa = mx.make_format(anchor)
+
+    # --- anchor quantization itself: windows of rows of a few tensors, regenerated from their seeds
+    for ti in (0, 1, 4, 6, 223):
+        _, r, c = tensors[ti]
+        w = synth.torch_config3_weight(ti, r, c)
+        for r0 in (0, r - 8, int(rng.integers(0, r - 8))):
+            rows = _bf16_to_host(w[r0:r0 + 8].contiguous())
+            wc, ws = oracle.quantize(rows, anchor)
+            assert np.array_equal(a_views[ti][1][r0:r0 + 8].cpu().numpy(), ws), (ti, r0)
+            assert np.array_equal(a_views[ti][0][r0:r0 + 8].cpu().numpy(), wc), (ti, r0)
+        del w
+
+    # --- 4-bit target: the whole checkpoint, every byte
+    ft = mx.make_format(target4)
+    t_codes, t_scales, t_views = bench.alloc_targets(torch, mx, a_views, target4)
+    ws_bytes = mx.binding.lib().mx_slice_and_scale_batched_workspace(len(a_views), a_scales.numel())
+    wsp = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    t_codes.fill_(0xA5)
+    t_scales.fill_(0xA5)
+    mx.SsBatch(a_views, fa, ft, t_views, wsp).run()
+    torch.cuda.synchronize()
+    lut = torch.tensor([oracle.slice_code(anchor, target4, c) for c in range(256)], dtype=torch.uint8, device="cuda")
+    slut = torch.tensor([oracle.slice_byte(anchor, target4, b) for b in range(256)], dtype=torch.uint8, device="cuda")
+    assert torch.equal(slut[a_scales.long()], t_scales), "scale bytes"
+    step = 1 << 21                                   # blocks per comparison slab (64 Mi codes)
+    for b0 in range(0, a_scales.numel(), step):
+        a = a_codes[b0:b0 + step]                    # [n, 32] anchor codes
+        m = lut[a.long()]                            # expected 4-bit codes, one per byte
+        want = m[:, 0::2] | (m[:, 1::2] << 4)        # element 2j in the low nibble of byte j
+        assert torch.equal(want, t_codes[b0:b0 + step]), "codes in blocks %d.." % b0
+        del a, m, want
+    del t_codes, t_scales, t_views
+
+    # --- 6-bit targets: windows against the oracle proper (first / last blocks of tensors, random interior)
+    for tgt in targets6:
+        c6, s6, v6 = bench.alloc_targets(torch, mx, a_views, tgt)
+        c6.fill_(0xA5)
+        mx.SsBatch(a_views, fa, mx.make_format(tgt), v6, wsp).run()
+        torch.cuda.synchronize()
+        for ti in (0, 1, 2, 5, 100, 222, 223):
+            nb = a_views[ti][1].numel()
+            ac = a_views[ti][0].reshape(nb, 32)
+            asc = a_views[ti][1].reshape(nb)
+            gc = v6[ti][0].reshape(nb, 24)
+            gs = v6[ti][1].reshape(nb)
+            for s, e in _windows(rng, nb, 4096, 3):
+                wc, wsc = oracle.slice_and_scale(ac[s:e].cpu().numpy(), asc[s:e].cpu().numpy(), anchor, tgt)
+                assert np.array_equal(gs[s:e].cpu().numpy(), wsc), (tgt, ti, s)
+                assert np.array_equal(gc[s:e].cpu().numpy(), wc), (tgt, ti, s)
+        del c6, s6, v6
+    del a_codes, a_scales, a_views
+    torch.cuda.empty_cache()
+
+
+def test_config3_random_byte_anchor_full_size(env, oracle):
+    # adversarial pass at checkpoint scale: uniformly random code and scale bytes (every NaN code, -128, 0 / 254 / 255
+    # scales), one flat tensor of 2^27 blocks, all five benchmark conversions checked through the oracle's tables
+    torch, mx, _ = env
+    nb = 1 << 27
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    codes = torch.randint(0, 256, (nb, 32), dtype=torch.uint8, device="cuda", generator=g)
+    scales = torch.randint(0, 256, (nb,), dtype=torch.uint8, device="cuda", generator=g)
+    for anchor, target in (("e4m3", "e2m1"), ("int8", "int4")):
+        oc, os_ = mx.mx_slice_and_scale(codes, scales, mx.make_format(anchor), mx.make_format(target))
+        lut = torch.tensor([oracle.slice_code(anchor, target, c) for c in range(256)], dtype=torch.uint8, device="cuda")
+        slut = torch.tensor([oracle.slice_byte(anchor, target, b) for b in range(256)], dtype=torch.uint8, device="cuda")
+        assert torch.equal(slut[scales.long()], os_)
+        step = 1 << 21
+        for b0 in range(0, nb, step):
+            m = lut[codes[b0:b0 + step].long()]
+            assert torch.equal(m[:, 0::2] | (m[:, 1::2] << 4), oc[b0:b0 + step])
+        del oc, os_
+    for anchor, target in (("e4m3", "e3m2"), ("e4m3", "e2m3"), ("int8", "int6")):
+        oc, os_ = mx.mx_slice_and_scale(codes, scales, mx.make_format(anchor), mx.make_format(target))
+        for s in (0, nb - 2048, 12345678, 99999999):
+            wc, wsc = oracle.slice_and_scale(codes[s:s + 2048].cpu().numpy(), scales[s:s + 2048].cpu().numpy(), anchor, target)
+            assert np.array_equal(os_[s:s + 2048].cpu().numpy(), wsc) and np.array_equal(oc[s:s + 2048].cpu().numpy(), wc)
+        del oc, os_
+
+
+def test_config4_fake_quant_full_size(env, oracle):
+    torch, mx, _ = env
+    rng = np.random.default_rng(44)
+    act = synth.torch_config4_activations()                          # 32768 x 4096 bf16
+    out = torch.empty_like(act)
+    rows = np.sort(rng.choice(act.shape[0], size=24, replace=False))
+    rows[0], rows[-1] = 0, act.shape[0] - 1
+    host = _bf16_to_host(act[torch.as_tensor(rows, device="cuda")].contiguous())
+    for elem in synth.QAT_FORMATS:
+        for anchor in (None, "int8" if elem.startswith("int") else "e4m3"):
+            if anchor == elem:
+                continue
+            mx.mx_fake_quant(act, mx.make_format(elem), None if anchor is None else mx.make_format(anchor), out)
+            got = _bf16_to_host(out[torch.as_tensor(rows, device="cuda")].contiguous())
+            want = oracle.fake_quant(host, elem, anchor=anchor)
+            assert np.array_equal(got, want), (elem, anchor)
+    del act, out
+    # weights [K = 4096, N = 14336], blocks down the columns (the reduction axis of x @ W)
+    w = synth.torch_config3_weight(2000, 4096, 14336)
+    wo = torch.empty_like(w)
+    cols = np.sort(rng.choice(14336, size=32, replace=False))
+    cols[0], cols[-1] = 0, 14335
+    hostw = _bf16_to_host(w[:, torch.as_tensor(cols, device="cuda")].contiguous())
+    for elem in ("int4", "e2m1", "e3m2", "int8"):
+        mx.mx_fake_quant(w, mx.make_format(elem, axis=0), None, wo)
+        got = _bf16_to_host(wo[:, torch.as_tensor(cols, device="cuda")].contiguous())
+        want = oracle.fake_quant(hostw, elem, axis=0)
+        assert np.array_equal(got, want), elem
