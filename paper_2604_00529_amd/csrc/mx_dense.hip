@@ -10,6 +10,16 @@
 #include "mx_device.h"
 #include "mx_launch.h"
 
+#ifndef MX_ROWS_UNROLL
+#define MX_ROWS_UNROLL 1
+#endif
+#ifndef MX_ROWS_THREADS
+#define MX_ROWS_THREADS 256
+#endif
+#ifndef MX_FQ_THREADS
+#define MX_FQ_THREADS 64
+#endif
+
 namespace mx {
 
 // ------------------------------------------------------------------ dense chunks
@@ -142,21 +152,21 @@ __device__ __forceinline__ void store_chunk_codes(uint32_t* block_words, uint64_
 
 constexpr bool direct_code_store(int nb) { return nb == 64 || nb == 32 || nb == 16 || nb == 24 || nb == 48; }
 
-template <int ELEM, bool HW, int DT, int U>
-__global__ __launch_bounds__(256) void quantize_rows_kernel(const void* __restrict__ src, uint32_t* __restrict__ codes,
+template <int ELEM, bool HW, int DT, int U, int TPB>
+__global__ __launch_bounds__(TPB) void quantize_rows_kernel(const void* __restrict__ src, uint32_t* __restrict__ codes,
                                                             uint8_t* __restrict__ scales, int64_t nchunks,
                                                             uint32_t chunks_per_row, int64_t ld, int flat, int tie) {
   using E = Elem<ELEM>;
   constexpr int N = Dense<DT>::N, G = 32 / N, W = E::bits;
-  __shared__ uint32_t stage[direct_code_store(N * W) ? 1 : 256 * U * (N / 4)];
+  __shared__ uint32_t stage[direct_code_store(N * W) ? 1 : TPB * U * (N / 4)];
   int tid = threadIdx.x;
   if constexpr (HW && E::hw == HW_FP8) tid = set_fp8_saturation(tid);
-  int64_t q0 = (int64_t)blockIdx.x * (256 * U) + tid;
+  int64_t q0 = (int64_t)blockIdx.x * (TPB * U) + tid;
   float v[U][N];
   bool live[U];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    int64_t q = q0 + 256 * u;
+    int64_t q = q0 + TPB * u;
     live[u] = q < nchunks;
     if (live[u]) load_chunk<DT>(src, chunk_offset<N>(q, chunks_per_row, ld, flat), v[u]);
     else {
@@ -167,7 +177,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const void* __restri
   const int lig = tid & (G - 1);
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    int64_t q = q0 + 256 * u;
+    int64_t q = q0 + TPB * u;
     uint32_t byte = scale_byte_from_amax<E::emax>(group_max<G>(chunk_amax_bits(v[u])));
     uint64_t bits = byte == 255u ? 0ull : encode_chunk<ELEM, HW, N>(v[u], byte, tie);
     int64_t blk = q / G;  // blocks are numbered like the chunks: row-major
@@ -185,22 +195,22 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const void* __restri
         b4[i] = r;
       }
 #pragma unroll
-      for (int i = 0; i < N / 4; ++i) stage[(u * 256 + tid) * (N / 4) + i] = b4[i];
+      for (int i = 0; i < N / 4; ++i) stage[(u * TPB + tid) * (N / 4) + i] = b4[i];
     }
     if (live[u] && lig == 0) scales[blk] = (uint8_t)byte;
   }
   if constexpr (!direct_code_store(N * W)) {
     __syncthreads();
-    // 256 * U chunks = 256 * U / G blocks staged as 32 bytes each, in chunk order
-    constexpr int BLOCKS = 256 * U / G;
-    for (int b = tid; b < BLOCKS; b += 256) {
+    // TPB * U chunks = TPB * U / G blocks staged as 32 bytes each, in chunk order
+    constexpr int BLOCKS = TPB * U / G;
+    for (int b = tid; b < BLOCKS; b += TPB) {
       // chunk order inside the stage: u-major, then lane; block b of slab u' covers lanes [G*b', G*b'+G)
-      int u2 = b / (256 / G), bl = b % (256 / G);
-      int64_t blk = ((int64_t)blockIdx.x * (256 * U) + 256 * u2) / G + bl;
+      int u2 = b / (TPB / G), bl = b % (TPB / G);
+      int64_t blk = ((int64_t)blockIdx.x * (TPB * U) + TPB * u2) / G + bl;
       if (blk * G < nchunks) {
         uint32_t in[8], out[W];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) in[i] = stage[(u2 * 256 + bl * G) * (N / 4) + i];
+        for (int i = 0; i < 8; ++i) in[i] = stage[(u2 * TPB + bl * G) * (N / 4) + i];
         pack_block_bytes<W>(in, out);
         store_dwords<W>(codes + blk * W, out);
       }
@@ -209,38 +219,46 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const void* __restri
 }
 
 // ------------------------------------------------------------------ axis 1: dequantize
-// N * W code bits of this lane's chunk out of the block's W dwords.
+// N * W code bits of this lane's chunk out of the block's W dwords, with as few loads as the
+// width allows (the lanes of a block read neighbouring or the same dwords).
 template <int W, int N>
 __device__ __forceinline__ uint64_t load_chunk_codes(const uint32_t* block_words, int lig) {
   constexpr int NB = N * W;
-  int o = lig * NB, d = o >> 5, sh = o & 31;
-  uint32_t w0 = block_words[d];
-  uint32_t w1 = block_words[d + 1 < W ? d + 1 : W - 1];
-  uint64_t lohi = (uint64_t)w0 | ((uint64_t)w1 << 32);
-  uint64_t r = lohi >> sh;
-  if constexpr (NB > 33) {  // may straddle three dwords
-    uint32_t w2 = block_words[d + 2 < W ? d + 2 : W - 1];
-    if (sh) r |= (uint64_t)w2 << (64 - sh);
+  if constexpr (NB == 64) {
+    u32x2 t = *reinterpret_cast<const u32x2*>(block_words + 2 * lig);
+    return (uint64_t)t.x | ((uint64_t)t.y << 32);
+  } else if constexpr (NB == 32) {
+    return block_words[lig];
+  } else if constexpr (NB == 16) {
+    return (block_words[lig >> 1] >> (16 * (lig & 1))) & 0xFFFFu;
+  } else {
+    int o = lig * NB, d = o >> 5, sh = o & 31;
+    uint32_t w0 = block_words[d];
+    uint32_t w1 = block_words[d + 1 < W ? d + 1 : W - 1];
+    uint64_t r = ((uint64_t)w0 | ((uint64_t)w1 << 32)) >> sh;
+    if constexpr (NB > 48) {  // a 56-bit piece can straddle three dwords
+      uint32_t w2 = block_words[d + 2 < W ? d + 2 : W - 1];
+      if (sh) r |= (uint64_t)w2 << (64 - sh);
+    }
+    return r & ((1ull << NB) - 1ull);
   }
-  if constexpr (NB < 64) r &= (1ull << NB) - 1ull;
-  return r;
 }
 
-template <int ELEM, int DT, int U>
-__global__ __launch_bounds__(256) void dequant_rows_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restrict__ scales,
+template <int ELEM, int DT, int U, int TPB>
+__global__ __launch_bounds__(TPB) void dequant_rows_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restrict__ scales,
                                                            void* __restrict__ dst, int64_t nchunks, uint32_t chunks_per_row,
                                                            int64_t ld, int flat) {
   using E = Elem<ELEM>;
   constexpr int N = Dense<DT>::N, G = 32 / N, W = E::bits;
   constexpr bool HW = E::hw != HW_NONE;
   int tid = threadIdx.x;
-  int64_t q0 = (int64_t)blockIdx.x * (256 * U) + tid;
+  int64_t q0 = (int64_t)blockIdx.x * (TPB * U) + tid;
   const int lig = tid & (G - 1);
   uint64_t bits[U];
   uint32_t byte[U];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    int64_t q = q0 + 256 * u;
+    int64_t q = q0 + TPB * u;
     bits[u] = 0; byte[u] = 0;
     if (q < nchunks) {
       int64_t blk = q / G;
@@ -250,7 +268,7 @@ __global__ __launch_bounds__(256) void dequant_rows_kernel(const uint32_t* __res
   }
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    int64_t q = q0 + 256 * u;
+    int64_t q = q0 + TPB * u;
     if (q < nchunks) {
       float v[N];
       decode_chunk<ELEM, HW, N>(bits[u], byte[u], v);
@@ -276,6 +294,21 @@ __device__ __forceinline__ void fake_quant_chunk(float (&v)[N], uint32_t byte_fi
   if constexpr (ANCHOR < 0) {
     uint64_t c = encode_chunk<TARGET, HW, N>(v, byte_first, tie);
     decode_chunk<TARGET, HW, N>(c, byte_first, v);
+  } else if constexpr (Elem<ANCHOR>::is_int) {
+    // Eq. (7) with Eq. (4), all in integer registers: P_h = clip(Round(V / X_h)); P_l = clip(Round(P_h / 2^De)) is
+    // (P_h + h - [P_h < 0]) >> De for half-away-from-zero and (P_h + h - 1 + bit_De(P_h)) >> De for half-to-even
+    // (arithmetic shifts, h = 2^(De-1)); W_t = P_l * X_h * 2^De.
+    constexpr int BH = Elem<ANCHOR>::bits, BL = Elem<TARGET>::bits, DE = BH - BL;
+    constexpr int HALF = 1 << (DE - 1), LIM = (1 << (BL - 1)) - 1;
+    int sh = 127 - (int)byte_first;
+    uint32_t byte_l = byte_first + DE > 254u ? 254u : byte_first + DE;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      int ph = ((int)(encode_int_scaled<BH>(v[i], sh, tie) << (32 - BH))) >> (32 - BH);
+      int pl = (tie == MX_ROUND_HALF_EVEN) ? (ph + (HALF - 1) + ((ph >> DE) & 1)) >> DE : (ph + HALF + (ph >> 31)) >> DE;
+      pl = pl < -LIM ? -LIM : (pl > LIM ? LIM : pl);
+      v[i] = ldexpf((float)pl, (int)byte_l - 127);
+    }
   } else {
     // Eq. (7): W_A = Q_A(W); W_t = Q_{A->t}(W_A) = quantize_t(P_h / 2^De) with X_l = X_h 2^De
     constexpr int DE = Elem<ANCHOR>::emax - Elem<TARGET>::emax;
@@ -291,19 +324,19 @@ __device__ __forceinline__ void fake_quant_chunk(float (&v)[N], uint32_t byte_fi
 template <int TARGET, int ANCHOR>
 struct FirstFormat { static constexpr int elem = ANCHOR < 0 ? TARGET : ANCHOR; };
 
-template <int TARGET, int ANCHOR, bool HW, int DT, int U>
-__global__ __launch_bounds__(256) void fake_quant_rows_kernel(const void* __restrict__ src, void* __restrict__ dst,
+template <int TARGET, int ANCHOR, bool HW, int DT, int U, int TPB>
+__global__ __launch_bounds__(TPB) void fake_quant_rows_kernel(const void* __restrict__ src, void* __restrict__ dst,
                                                               int64_t nchunks, uint32_t chunks_per_row, int64_t ld_src,
                                                               int64_t ld_dst, int flat_src, int flat_dst, int tie) {
   constexpr int FIRST = FirstFormat<TARGET, ANCHOR>::elem;
   constexpr int N = Dense<DT>::N, G = 32 / N;
   int tid = threadIdx.x;
   if constexpr (HW && Elem<FIRST>::hw == HW_FP8) tid = set_fp8_saturation(tid);
-  int64_t q0 = (int64_t)blockIdx.x * (256 * U) + tid;
+  int64_t q0 = (int64_t)blockIdx.x * (TPB * U) + tid;
   float v[U][N];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    int64_t q = q0 + 256 * u;
+    int64_t q = q0 + TPB * u;
     if (q < nchunks) load_chunk<DT>(src, chunk_offset<N>(q, chunks_per_row, ld_src, flat_src), v[u]);
     else {
 #pragma unroll
@@ -312,7 +345,7 @@ __global__ __launch_bounds__(256) void fake_quant_rows_kernel(const void* __rest
   }
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    int64_t q = q0 + 256 * u;
+    int64_t q = q0 + TPB * u;
     uint32_t byte = scale_byte_from_amax<Elem<FIRST>::emax>(group_max<G>(chunk_amax_bits(v[u])));
     fake_quant_chunk<TARGET, ANCHOR, HW, N>(v[u], byte, tie);
     if (q < nchunks) store_chunk<DT>(dst, chunk_offset<N>(q, chunks_per_row, ld_dst, flat_dst), v[u]);
@@ -456,7 +489,10 @@ __global__ __launch_bounds__(256) void fake_quant_cols_kernel(const void* __rest
 }
 
 // ------------------------------------------------------------------ host launchers
-constexpr int kRowsUnroll = 4;
+#ifndef MX_DENSE_KERNELS_ONLY   // (a tuning harness can include this file for the kernels alone)
+constexpr int kRowsUnroll = MX_ROWS_UNROLL;   // chunks per lane
+constexpr int kRowsThreads = MX_ROWS_THREADS; // lanes per workgroup (quantize, dequantize)
+constexpr int kFqThreads = MX_FQ_THREADS;     // lanes per workgroup (fake-quant)
 
 static inline bool launch_ok() { return hipGetLastError() == hipSuccess; }
 
@@ -466,9 +502,9 @@ static mx_status_t run_quantize(int axis, int tie, const DenseArg& s, void* code
     constexpr int N = Dense<DT>::N;
     int64_t cpr = s.cols / N, nchunks = s.rows * cpr;
     if (cpr > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;
-    int64_t wgs = (nchunks + 256 * kRowsUnroll - 1) / (256 * kRowsUnroll);
+    int64_t wgs = (nchunks + kRowsThreads * kRowsUnroll - 1) / (kRowsThreads * kRowsUnroll);
     if (wgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((quantize_rows_kernel<ELEM, HW, DT, kRowsUnroll>), dim3((unsigned)wgs), dim3(256), 0, st, s.data,
+    hipLaunchKernelGGL((quantize_rows_kernel<ELEM, HW, DT, kRowsUnroll, kRowsThreads>), dim3((unsigned)wgs), dim3(kRowsThreads), 0, st, s.data,
                        static_cast<uint32_t*>(codes), scales, nchunks, (uint32_t)cpr, s.ld, (int)(s.ld == s.cols), tie);
   } else {
     if (s.cols % 4) return MX_ERR_UNSUPPORTED;
@@ -488,9 +524,9 @@ static mx_status_t run_dequant(int axis, const void* codes, const uint8_t* scale
     constexpr int N = Dense<DT>::N;
     int64_t cpr = d.cols / N, nchunks = d.rows * cpr;
     if (cpr > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;
-    int64_t wgs = (nchunks + 256 * kRowsUnroll - 1) / (256 * kRowsUnroll);
+    int64_t wgs = (nchunks + kRowsThreads * kRowsUnroll - 1) / (kRowsThreads * kRowsUnroll);
     if (wgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((dequant_rows_kernel<ELEM, DT, kRowsUnroll>), dim3((unsigned)wgs), dim3(256), 0, st,
+    hipLaunchKernelGGL((dequant_rows_kernel<ELEM, DT, kRowsUnroll, kRowsThreads>), dim3((unsigned)wgs), dim3(kRowsThreads), 0, st,
                        static_cast<const uint32_t*>(codes), scales, d.data, nchunks, (uint32_t)cpr, d.ld, (int)(d.ld == d.cols));
   } else {
     if (d.cols % 4) return MX_ERR_UNSUPPORTED;
@@ -510,9 +546,9 @@ static mx_status_t run_fake_quant(int axis, int tie, const DenseArg& s, const De
     constexpr int N = Dense<DT>::N;
     int64_t cpr = s.cols / N, nchunks = s.rows * cpr;
     if (cpr > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;
-    int64_t wgs = (nchunks + 256 * kRowsUnroll - 1) / (256 * kRowsUnroll);
+    int64_t wgs = (nchunks + kFqThreads * kRowsUnroll - 1) / (kFqThreads * kRowsUnroll);
     if (wgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((fake_quant_rows_kernel<TARGET, ANCHOR, HW, DT, kRowsUnroll>), dim3((unsigned)wgs), dim3(256), 0, st,
+    hipLaunchKernelGGL((fake_quant_rows_kernel<TARGET, ANCHOR, HW, DT, kRowsUnroll, kFqThreads>), dim3((unsigned)wgs), dim3(kFqThreads), 0, st,
                        s.data, d.data, nchunks, (uint32_t)cpr, s.ld, d.ld, (int)(s.ld == s.cols), (int)(d.ld == d.cols), tie);
   } else {
     if (s.cols % 4) return MX_ERR_UNSUPPORTED;
@@ -588,5 +624,7 @@ mx_status_t fake_quant_launch(int target, int anchor, int axis, int tie, const D
 #undef X
   return MX_ERR_FORMAT;
 }
+
+#endif  // MX_DENSE_KERNELS_ONLY
 
 }  // namespace mx

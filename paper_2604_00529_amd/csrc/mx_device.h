@@ -108,7 +108,7 @@ __device__ __forceinline__ int set_fp8_saturation(int dep) {
 }
 
 // ------------------------------------------------------------------ 32-element FP6 conversions
-// These instructions read 16 (or 6) consecutive registers and write 6 (or 32).  They are issued
+// These instructions read 16 consecutive registers and write 6.  They are issued
 // through inline assembly with an early-clobber destination and with every source lane defined,
 // so that the register allocator can never overlay the destination, the scale or another operand
 // on (otherwise unused) source lanes: with such overlays the results were wrong.
@@ -126,25 +126,27 @@ __device__ __forceinline__ u32x6 cvt_pk32_fp6_f16(f16x32 a, float s) {
   else asm("v_cvt_scalef32_pk32_fp6_f16 %0, %1, %2" : "=&v"(d) : "v"(a), "v"(s));
   return d;
 }
-template <bool BF6>
-__device__ __forceinline__ f32x32 cvt_pk32_f32_fp6(u32x6 a, float s) {
-  f32x32 d;
-  if constexpr (BF6) asm("v_cvt_scalef32_pk32_f32_bf6 %0, %1, %2" : "=&v"(d) : "v"(a), "v"(s));
-  else asm("v_cvt_scalef32_pk32_f32_fp6 %0, %1, %2" : "=&v"(d) : "v"(a), "v"(s));
-  return d;
+// ------------------------------------------------------------------ software element codecs
+// clip_b(Round(V / X)) for integer elements, X = 2^-sh.  Half away from zero: with q2 = trunc(2r)
+// (the conversion truncates toward zero; 2r is exact), Round(r) = (q2 + [q2 >= 0]) >> 1 with an
+// arithmetic shift, for both signs.  Half to even: the hardware's round-to-nearest-even.
+template <int BITS>
+__device__ __forceinline__ uint32_t encode_int_scaled(float v, int sh, int tie) {
+  constexpr int LIM = (1 << (BITS - 1)) - 1;
+  int q;
+  if (tie == MX_ROUND_HALF_EVEN) {
+    q = (int)rintf(ldexpf(v, sh));
+  } else {
+    int q2 = (int)ldexpf(v, sh + 1);
+    q = (q2 + 1 + (q2 >> 31)) >> 1;
+  }
+  q = q < -LIM ? -LIM : (q > LIM ? LIM : q);
+  return (uint32_t)q & ((1u << BITS) - 1u);
 }
 
-// ------------------------------------------------------------------ software element codecs
-// Round(|r|) for integer elements; r is exact (V / X), |r| < 2^(bits-1).
 template <int BITS>
 __device__ __forceinline__ uint32_t encode_int(float r, int tie) {
-  float a = fabsf(r);
-  float t = truncf(a);
-  float f = a - t;  // exact
-  bool up = (tie == MX_ROUND_HALF_EVEN) ? (f > 0.5f || (f == 0.5f && (((int)t) & 1))) : (f >= 0.5f);
-  float q = fminf(t + (up ? 1.0f : 0.0f), (float)((1 << (BITS - 1)) - 1));
-  int iq = (int)q;
-  return (uint32_t)(r < 0.0f ? -iq : iq) & ((1u << BITS) - 1u);
+  return encode_int_scaled<BITS>(r, 0, tie);
 }
 
 template <int BITS>
@@ -256,14 +258,26 @@ __device__ __forceinline__ uint64_t encode_chunk(const float (&v)[N], uint32_t b
     if constexpr (N == 4) return p[0] & 0xFFFFFFu;
     else return (uint64_t)p[0] | ((uint64_t)(p[1] & 0xFFFFu) << 32);
   } else {
-    uint64_t acc = 0;
+    uint32_t lo = 0, hi = 0;
     int sh = 127 - (int)byte;
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      float r = ldexpf(v[i], sh);  // V / X, exact (a result below fp32's normal range rounds to a value that still encodes as zero)
-      acc |= (uint64_t)encode_sw<ELEM>(r, tie) << (i * E::bits);
+      uint32_t c;
+      if constexpr (E::is_int) {
+        c = encode_int_scaled<E::bits>(v[i], sh, tie);
+      } else {
+        // V / X, exact (a result below fp32's normal range rounds to a value that still encodes as zero)
+        c = encode_fp_sw<E::eta, E::mu>(ldexpf(v[i], sh), tie);
+      }
+      const int pos = i * E::bits;   // compile-time after unrolling
+      if (pos < 32) {
+        lo |= c << pos;
+        if (pos + E::bits > 32) hi |= c >> (32 - pos);
+      } else {
+        hi |= c << (pos - 32);
+      }
     }
-    return acc;
+    return (uint64_t)lo | ((uint64_t)hi << 32);
   }
 }
 
@@ -290,11 +304,16 @@ __device__ __forceinline__ void decode_chunk(uint64_t codes, uint32_t byte, floa
       v[2 * I] = a.x; v[2 * I + 1] = a.y;
     });
   } else if constexpr (HW && (E::hw == HW_FP6 || E::hw == HW_BF6)) {
-    float s = scale_operand(byte);
-    u32x6 p = {(uint32_t)codes, (uint32_t)(codes >> 32), 0u, 0u, 0u, 0u};
-    f32x32 f = cvt_pk32_f32_fp6<E::hw == HW_BF6>(p, s);
+    // A minifloat without Inf / NaN placed in the top of an fp32's exponent / mantissa fields reads as
+    // its own value times 2^(bias - 127), subnormals included (both formats share the convention);
+    // one ldexp undoes that and applies the block scale.  Exact: at most mu + 1 significant bits.
+    int sh = (int)byte - 127 + (127 - E::bias);
 #pragma unroll
-    for (int i = 0; i < N; ++i) v[i] = f[i];
+    for (int i = 0; i < N; ++i) {
+      uint32_t c = (uint32_t)(codes >> (i * 6));
+      uint32_t f = ((c & 0x1Fu) << (23 - E::mu)) | ((c & 0x20u) << 26);
+      v[i] = ldexpf(__uint_as_float(f), sh);
+    }
   } else {
     int sh = (int)byte - 127;
 #pragma unroll
