@@ -389,70 +389,158 @@ __device__ __forceinline__ uint64_t extract_bits(const uint32_t (&in)[W]) {
   return r;
 }
 
+// The packed tensor of a column-blocked matrix is stored transposed ([cols][row blocks][W dwords]):
+// a workgroup of 4 waves takes a tile of 4 consecutive row blocks x 256 columns (wave w = row block
+// w, lane l = columns 4l..4l+3) and passes the codes through LDS, so that global memory sees, per
+// column, the 4 * W contiguous dwords of its four blocks instead of one isolated block per lane.
+// LDS layout: word[(rb_local * W + i) * 256 + col] -- a lane's 4 columns are one 128-bit access.
+constexpr int kColTileCols = 256, kColTileRbs = 4;
+
+template <int W>
+struct ColChunk {  // dwords per global access of the transposed side, by the alignment W guarantees
+  static constexpr int cd = (W % 4 == 0) ? 4 : ((W % 2 == 0) ? 2 : 1);
+  static constexpr int per_col = kColTileRbs * W / cd;
+};
+
+struct ColTile { int64_t rb0; int64_t c0; };
+__device__ __forceinline__ ColTile col_tile(uint32_t col_groups) {
+  uint32_t rbg = blockIdx.x / col_groups;
+  return ColTile{(int64_t)rbg * kColTileRbs, (int64_t)(blockIdx.x - rbg * col_groups) * kColTileCols};
+}
+
 template <int ELEM, bool HW, int DT>
 __global__ __launch_bounds__(256) void quantize_cols_kernel(const void* __restrict__ src, uint32_t* __restrict__ codes,
-                                                            uint8_t* __restrict__ scales, int64_t nitems,
-                                                            uint32_t quads_per_row, int64_t ld, int64_t nrb, int tie) {
+                                                            uint8_t* __restrict__ scales, int64_t cols, uint32_t col_groups,
+                                                            int64_t ld, int64_t nrb, int tie) {
   using E = Elem<ELEM>;
-  constexpr int W = E::bits;
+  constexpr int W = E::bits, CD = ColChunk<W>::cd, PER_COL = ColChunk<W>::per_col;
+  __shared__ __attribute__((aligned(16))) uint32_t tile[kColTileRbs * W * kColTileCols];
+  __shared__ __attribute__((aligned(4))) uint8_t tile_scales[kColTileCols * kColTileRbs];
   int tid = threadIdx.x;
   if constexpr (HW && E::hw == HW_FP8) tid = set_fp8_saturation(tid);
-  int64_t item = (int64_t)blockIdx.x * 256 + tid;
-  if (item >= nitems) return;
-  ColItem it = col_item(item, quads_per_row);
-  float v[32][4];
-  int64_t off = it.rb * 32 * ld + (int64_t)it.cq * 4;
+  const int wave = tid >> 6, lane = tid & 63;
+  const ColTile t = col_tile(col_groups);
+  const int64_t rb = t.rb0 + wave, col = t.c0 + 4 * lane;
+  if (rb < nrb && col < cols) {
+    float v[32][4];
+    int64_t off = rb * 32 * ld + col;
 #pragma unroll
-  for (int r = 0; r < 32; ++r) load_quad<DT>(src, off + r * ld, v[r]);
-  uint32_t byte[4];
-  column_bytes<E::emax>(v, byte);
+    for (int r = 0; r < 32; ++r) load_quad<DT>(src, off + r * ld, v[r]);
+    uint32_t byte[4];
+    column_bytes<E::emax>(v, byte);
+    uint32_t out[4][W];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    uint32_t out[W];
+    for (int j = 0; j < 4; ++j) {
 #pragma unroll
-    for (int i = 0; i < W; ++i) out[i] = 0;
-    static_for<0, 4>([&](auto cc) {
-      constexpr int C = decltype(cc)::value;
-      float x[8];
+      for (int i = 0; i < W; ++i) out[j][i] = 0;
+      static_for<0, 4>([&](auto cc) {
+        constexpr int C = decltype(cc)::value;
+        float x[8];
 #pragma unroll
-      for (int r = 0; r < 8; ++r) x[r] = v[8 * C + r][j];
-      uint64_t bits = byte[j] == 255u ? 0ull : encode_chunk<ELEM, HW, 8>(x, byte[j], tie);
-      insert_bits<W, C * 8 * W, 8 * W>(out, bits);
-    });
-    int64_t blk = ((int64_t)it.cq * 4 + j) * nrb + it.rb;  // packed tensor is [cols][row blocks]
-    store_dwords<W>(codes + blk * W, out);
-    scales[blk] = (uint8_t)byte[j];
+        for (int r = 0; r < 8; ++r) x[r] = v[8 * C + r][j];
+        uint64_t bits = byte[j] == 255u ? 0ull : encode_chunk<ELEM, HW, 8>(x, byte[j], tie);
+        insert_bits<W, C * 8 * W, 8 * W>(out[j], bits);
+      });
+      tile_scales[(4 * lane + j) * kColTileRbs + wave] = (uint8_t)byte[j];
+    }
+#pragma unroll
+    for (int i = 0; i < W; ++i)
+      *reinterpret_cast<u32x4*>(&tile[(wave * W + i) * kColTileCols + 4 * lane]) = u32x4{out[0][i], out[1][i], out[2][i], out[3][i]};
+  }
+  __syncthreads();
+  const int64_t valid_rb = nrb - t.rb0 < kColTileRbs ? nrb - t.rb0 : kColTileRbs;
+  const int valid_dw = (int)valid_rb * W;
+  // codes: chunk k = (column k / PER_COL, part k % PER_COL) -> CD consecutive dwords of that column's run
+#pragma unroll
+  for (int it = 0; it < PER_COL; ++it) {
+    int k = it * 256 + tid;
+    int c = k / PER_COL, part = k - c * PER_COL;
+    int d0 = part * CD;
+    if (t.c0 + c < cols && d0 < valid_dw) {
+      uint32_t w[CD];
+#pragma unroll
+      for (int q = 0; q < CD; ++q) w[q] = tile[(d0 + q) * kColTileCols + c];
+      uint32_t* g = codes + ((t.c0 + c) * nrb + t.rb0) * W + d0;
+      if (d0 + CD <= valid_dw) {
+        store_dwords<CD>(g, w);
+      } else {
+#pragma unroll
+        for (int q = 0; q < CD; ++q)
+          if (d0 + q < valid_dw) g[q] = w[q];
+      }
+    }
+  }
+  // scales: one column per thread, its (up to) 4 consecutive bytes
+  if (t.c0 + tid < cols) {
+    uint8_t* g = scales + (t.c0 + tid) * nrb + t.rb0;
+    if (valid_rb == kColTileRbs && (nrb & 3) == 0) {
+      *reinterpret_cast<uint32_t*>(g) = *reinterpret_cast<const uint32_t*>(&tile_scales[tid * kColTileRbs]);
+    } else {
+      for (int q = 0; q < (int)valid_rb; ++q) g[q] = tile_scales[tid * kColTileRbs + q];
+    }
   }
 }
 
 template <int ELEM, int DT>
 __global__ __launch_bounds__(256) void dequant_cols_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restrict__ scales,
-                                                           void* __restrict__ dst, int64_t nitems, uint32_t quads_per_row,
+                                                           void* __restrict__ dst, int64_t cols, uint32_t col_groups,
                                                            int64_t ld, int64_t nrb) {
   using E = Elem<ELEM>;
-  constexpr int W = E::bits;
+  constexpr int W = E::bits, CD = ColChunk<W>::cd, PER_COL = ColChunk<W>::per_col;
   constexpr bool HW = E::hw != HW_NONE;
-  int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (item >= nitems) return;
-  ColItem it = col_item(item, quads_per_row);
-  float v[32][4];
+  __shared__ __attribute__((aligned(16))) uint32_t tile[kColTileRbs * W * kColTileCols];
+  __shared__ __attribute__((aligned(4))) uint8_t tile_scales[kColTileCols * kColTileRbs];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const ColTile t = col_tile(col_groups);
+  const int64_t valid_rb = nrb - t.rb0 < kColTileRbs ? nrb - t.rb0 : kColTileRbs;
+  const int valid_dw = (int)valid_rb * W;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    int64_t blk = ((int64_t)it.cq * 4 + j) * nrb + it.rb;
-    uint32_t in[W];
-    load_dwords<W>(codes + blk * W, in);
-    uint32_t byte = scales[blk];
-    static_for<0, 4>([&](auto cc) {
-      constexpr int C = decltype(cc)::value;
-      float x[8];
-      decode_chunk<ELEM, HW, 8>(extract_bits<W, C * 8 * W, 8 * W>(in), byte, x);
+  for (int it = 0; it < PER_COL; ++it) {
+    int k = it * 256 + tid;
+    int c = k / PER_COL, part = k - c * PER_COL;
+    int d0 = part * CD;
+    if (t.c0 + c < cols && d0 < valid_dw) {
+      const uint32_t* g = codes + ((t.c0 + c) * nrb + t.rb0) * W + d0;
+      uint32_t w[CD];
+      if (d0 + CD <= valid_dw) {
+        load_dwords<CD>(g, w);
+      } else {
 #pragma unroll
-      for (int r = 0; r < 8; ++r) v[8 * C + r][j] = byte == 255u ? __uint_as_float(0x7FC00000u) : x[r];
-    });
+        for (int q = 0; q < CD; ++q) w[q] = d0 + q < valid_dw ? g[q] : 0u;
+      }
+#pragma unroll
+      for (int q = 0; q < CD; ++q) tile[(d0 + q) * kColTileCols + c] = w[q];
+    }
   }
-  int64_t off = it.rb * 32 * ld + (int64_t)it.cq * 4;
+  if (t.c0 + tid < cols) {
+    const uint8_t* g = scales + (t.c0 + tid) * nrb + t.rb0;
+    for (int q = 0; q < (int)valid_rb; ++q) tile_scales[tid * kColTileRbs + q] = g[q];
+  }
+  __syncthreads();
+  const int64_t rb = t.rb0 + wave, col = t.c0 + 4 * lane;
+  if (rb < nrb && col < cols) {
+    float v[32][4];
+    uint32_t in[4][W];
 #pragma unroll
-  for (int r = 0; r < 32; ++r) store_quad<DT>(dst, off + r * ld, v[r]);
+    for (int i = 0; i < W; ++i) {
+      u32x4 q = *reinterpret_cast<const u32x4*>(&tile[(wave * W + i) * kColTileCols + 4 * lane]);
+      in[0][i] = q.x; in[1][i] = q.y; in[2][i] = q.z; in[3][i] = q.w;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint32_t byte = tile_scales[(4 * lane + j) * kColTileRbs + wave];
+      static_for<0, 4>([&](auto cc) {
+        constexpr int C = decltype(cc)::value;
+        float x[8];
+        decode_chunk<ELEM, HW, 8>(extract_bits<W, C * 8 * W, 8 * W>(in[j]), byte, x);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) v[8 * C + r][j] = byte == 255u ? __uint_as_float(0x7FC00000u) : x[r];
+      });
+    }
+    int64_t off = rb * 32 * ld + col;
+#pragma unroll
+    for (int r = 0; r < 32; ++r) store_quad<DT>(dst, off + r * ld, v[r]);
+  }
 }
 
 template <int TARGET, int ANCHOR, bool HW, int DT>
@@ -508,12 +596,11 @@ static mx_status_t run_quantize(int axis, int tie, const DenseArg& s, void* code
                        static_cast<uint32_t*>(codes), scales, nchunks, (uint32_t)cpr, s.ld, (int)(s.ld == s.cols), tie);
   } else {
     if (s.cols % 4) return MX_ERR_UNSUPPORTED;
-    int64_t qpr = s.cols / 4, nrb = s.rows / 32, nitems = qpr * nrb;
-    if (qpr > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;
-    int64_t wgs = (nitems + 255) / 256;
-    if (wgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((quantize_cols_kernel<ELEM, HW, DT>), dim3((unsigned)wgs), dim3(256), 0, st, s.data,
-                       static_cast<uint32_t*>(codes), scales, nitems, (uint32_t)qpr, s.ld, nrb, tie);
+    int64_t nrb = s.rows / 32;
+    int64_t cgs = (s.cols + kColTileCols - 1) / kColTileCols, rbgs = (nrb + kColTileRbs - 1) / kColTileRbs;
+    if (cgs * rbgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((quantize_cols_kernel<ELEM, HW, DT>), dim3((unsigned)(cgs * rbgs)), dim3(256), 0, st, s.data,
+                       static_cast<uint32_t*>(codes), scales, s.cols, (uint32_t)cgs, s.ld, nrb, tie);
   }
   return launch_ok() ? MX_OK : MX_ERR_LAUNCH;
 }
@@ -530,12 +617,11 @@ static mx_status_t run_dequant(int axis, const void* codes, const uint8_t* scale
                        static_cast<const uint32_t*>(codes), scales, d.data, nchunks, (uint32_t)cpr, d.ld, (int)(d.ld == d.cols));
   } else {
     if (d.cols % 4) return MX_ERR_UNSUPPORTED;
-    int64_t qpr = d.cols / 4, nrb = d.rows / 32, nitems = qpr * nrb;
-    if (qpr > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;
-    int64_t wgs = (nitems + 255) / 256;
-    if (wgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((dequant_cols_kernel<ELEM, DT>), dim3((unsigned)wgs), dim3(256), 0, st,
-                       static_cast<const uint32_t*>(codes), scales, d.data, nitems, (uint32_t)qpr, d.ld, nrb);
+    int64_t nrb = d.rows / 32;
+    int64_t cgs = (d.cols + kColTileCols - 1) / kColTileCols, rbgs = (nrb + kColTileRbs - 1) / kColTileRbs;
+    if (cgs * rbgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((dequant_cols_kernel<ELEM, DT>), dim3((unsigned)(cgs * rbgs)), dim3(256), 0, st,
+                       static_cast<const uint32_t*>(codes), scales, d.data, d.cols, (uint32_t)cgs, d.ld, nrb);
   }
   return launch_ok() ? MX_OK : MX_ERR_LAUNCH;
 }
