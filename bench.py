@@ -178,29 +178,20 @@ def main():
             del c2, s2, v2
         del a_codes, a_scales, a_views
         torch.cuda.empty_cache()
-        # quantize / dequantize on the largest decoder weight (gate_proj, 14336 x 4096 bf16, 58.7 M elements):
-        # 8 distinct copies are rotated so that the 256 MB last-level cache cannot hold the working set
-        r, c = 14336, 4096
-        ws_list = [synth.torch_config3_weight(1000 + i, r, c) for i in range(8)]
-        state = {"i": 0}
-        for elem, bits in (("e4m3", 8), ("int8", 8), ("e2m1", 4)):
+        # quantize / dequantize on four stacked copies of the largest decoder weight (gate_proj 14336 x 4096 bf16;
+        # 57344 x 4096 = 234.9 M elements, 470 MB dense): twice the 256 MB last-level cache, so every pass streams HBM
+        r, c = 4 * 14336, 4096
+        wbig = torch.cat([synth.torch_config3_weight(1000 + i, 14336, c) for i in range(4)], dim=0)
+        for elem, bits in (("e4m3", 8), ("int8", 8), ("e2m1", 4), ("int4", 4), ("e3m2", 6)):
             f = mx.make_format(elem)
-            outs = [mx.mx_quantize(w, f) for w in ws_list]
-
-            def q():
-                i = state["i"] = (state["i"] + 1) % 8
-                mx.mx_quantize(ws_list[i], f, *outs[i])
-            m, _, _ = time_region(torch, q, 16, 8)
+            pc, ps = mx.mx_quantize(wbig, f)
+            m, _, _ = time_region(torch, lambda: mx.mx_quantize(wbig, f, pc, ps), 10, 3)
             rows["quantize_bf16_%s" % elem] = row(r * c * 2 + r * c // 32 * (4 * bits + 1), m)
-            deq = [torch.empty((r, c), dtype=torch.bfloat16, device="cuda") for _ in range(8)]
-
-            def dq():
-                i = state["i"] = (state["i"] + 1) % 8
-                mx.mx_dequant(outs[i][0], outs[i][1], f, r, c, out=deq[i])
-            m, _, _ = time_region(torch, dq, 16, 8)
+            deq = torch.empty((r, c), dtype=torch.bfloat16, device="cuda")
+            m, _, _ = time_region(torch, lambda: mx.mx_dequant(pc, ps, f, r, c, out=deq), 10, 3)
             rows["dequant_%s_bf16" % elem] = row(r * c * 2 + r * c // 32 * (4 * bits + 1), m)
-            del outs, deq
-        del ws_list
+            del pc, ps, deq
+        del wbig
         torch.cuda.empty_cache()
         # fake-quant step of multi-format QAT (configs[3]): bf16 activations 32768 x 4096, blocks along the
         # reduction axis, one sampled format per step, direct and through the 8-bit anchor
@@ -224,12 +215,17 @@ def main():
             f = mx.make_format(elem)
             m, _, _ = time_region(torch, lambda: mx.mx_fake_quant(act, f, None, out), 10, 3)
             rows["fake_quant_bf16_%s" % elem] = row(nby, m)
-        wt = synth.torch_config3_weight(2000, 4096, 14336)       # [K, N] weight, blocks down the columns (axis 0)
-        wo = torch.empty_like(wt)
-        for elem in ("int4", "e2m1"):
+        # blocks down the columns (axis 0) on the same 256 MiB activation tensor: fake-quant, quantize, dequantize
+        for elem, bits in (("e2m1", 4), ("int4", 4), ("e4m3", 8)):
             f0 = mx.make_format(elem, axis=0)
-            m, _, _ = time_region(torch, lambda: mx.mx_fake_quant(wt, f0, None, wo), 10, 3)
-            rows["fake_quant_bf16_%s_axis0_cache_resident" % elem] = row(wt.numel() * 4, m)
+            m, _, _ = time_region(torch, lambda: mx.mx_fake_quant(act, f0, None, out), 10, 3)
+            rows["fake_quant_bf16_%s_axis0" % elem] = row(nby, m)
+            pc, ps = mx.mx_quantize(act, f0)
+            m, _, _ = time_region(torch, lambda: mx.mx_quantize(act, f0, pc, ps), 10, 3)
+            rows["quantize_bf16_%s_axis0" % elem] = row(act.numel() * 2 + act.numel() // 32 * (4 * bits + 1), m)
+            m, _, _ = time_region(torch, lambda: mx.mx_dequant(pc, ps, f0, act.shape[0], act.shape[1], out=out), 10, 3)
+            rows["dequant_%s_bf16_axis0" % elem] = row(act.numel() * 2 + act.numel() // 32 * (4 * bits + 1), m)
+            del pc, ps
         result["rows"] = rows
 
     print(json.dumps(result), flush=True)
