@@ -136,6 +136,19 @@ mx_status_t mx_fake_quant(const mx_format_t* target, const mx_format_t* anchor, 
  * are not representable in dst->dtype round to nearest even (overflow gives +-Inf). */
 mx_status_t mx_dequant(const mx_format_t* f, const mx_packed_t* src, const mx_dense_t* dst, void* stream);
 
+/* Fused consumer of the anchor (Sec. 3.5 "Inference": the model runs with W_t = Q_{A->t}(W_A) generated on
+ * demand; BASELINE workload "fused consumer GEMM"):
+ *     C[m, n] = sum_k DQ(A)[m, k] * DQ(Q_{A->t}(W_A))[n, k],   t = MXFP4 E2M1,
+ * with the Slice-and-Scale conversion of Eq. (6) done in registers and the product taken by the CDNA4 scaled
+ * MX matrix instruction with fp32 accumulation; W_t is never written to memory.
+ *   a: MXFP8 E4M3 activations blocked along K: outer = M, nblocks = K / 32 (mx_quantize of a [M, K] tensor).
+ *   w_anchor: MXFP8 E4M3 anchor of the weight, K-contiguous: outer = N, nblocks = K / 32 (mx_quantize of
+ *             W[N, K] along axis 1, or of W[K, N] along axis 0).
+ *   c: dense fp32 [M, N], written (not accumulated into).
+ * K must be a multiple of 128.  MX_ERR_UNSUPPORTED for shapes this build has no kernel for.  Each output is an
+ * fp32 sum over K in a fixed order (results are reproducible run to run). */
+mx_status_t mx_gemm_ss_fp4(const mx_packed_t* a, const mx_packed_t* w_anchor, const mx_dense_t* c, void* stream);
+
 const char* mx_status_str(mx_status_t status);
 
 #ifdef __cplusplus

@@ -265,6 +265,22 @@ def fake_quant(x, target, anchor=None, axis=1, k=32, tie=TIE_DEFAULT, out=None):
     return dst
 
 
+def gemm_ss_reference(a_codes, a_scales, w_codes, w_scales, target="e2m1", k=32, with_abs=False):
+    """fp64 product of the dequantized operands of the fused consumer GEMM:
+    C = DQ(A) @ DQ(Q_{A->t}(W_A)).T with A in MXFP8 E4M3 [M, K/k blocks] and W_A the E4M3 anchor [N, K/k blocks]
+    (Eq. (6) for the conversion, Sec. 3.3 notation for the reconstruction; numpy's matmul is the library step).
+    with_abs also returns sum_k |a||w|, the scale of the rounding error of any finite-precision accumulation."""
+    M, KB = a_scales.shape
+    N = w_scales.shape[0]
+    K = KB * k
+    a = dequant(a_codes, a_scales, "e4m3", M, K, axis=1, k=k).astype(np.float64)
+    tc, ts = slice_and_scale(w_codes, w_scales, "e4m3", target, k=k)
+    w = dequant(tc, ts, target, N, K, axis=1, k=k).astype(np.float64)
+    if with_abs:
+        return a @ w.T, np.abs(a) @ np.abs(w).T
+    return a @ w.T
+
+
 def bf16_bits(x):
     """float32 array -> nearest bfloat16 bit patterns (uint16), ties to even."""
     x = np.asarray(x, dtype=np.float32)

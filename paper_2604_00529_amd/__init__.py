@@ -11,7 +11,7 @@ from . import binding
 from .binding import ELEMS, MxError, make_format
 
 __all__ = ["mx_quantize", "mx_slice_and_scale", "mx_slice_and_scale_batched", "mx_fake_quant", "mx_dequant",
-           "mx_packed_bytes", "mx_elem_bits", "mx_elem_emax", "MxFakeQuantSTE", "ELEMS", "MxError", "make_format",
+           "mx_gemm_ss_fp4", "mx_packed_bytes", "mx_elem_bits", "mx_elem_emax", "MxFakeQuantSTE", "ELEMS", "MxError", "make_format",
            "packed_shape", "SsBatch"]
 
 
@@ -181,6 +181,23 @@ def mx_dequant(codes, scales, fmt, rows, cols, dtype=None, out=None):
     p = _packed(codes, scales, outer, nblocks)
     d = _dense(out)
     binding.check(binding.lib().mx_dequant(ctypes.byref(fmt), ctypes.byref(p), ctypes.byref(d), _stream(codes)), "mx_dequant")
+    return out
+
+
+def mx_gemm_ss_fp4(a_codes, a_scales, w_codes, w_scales, out=None):
+    """C[M, N] = DQ(A) @ DQ(SS(W_anchor -> E2M1)).T with the anchor sliced in registers (scaled MX MFMA, fp32 out).
+
+    a_*: MXFP8 E4M3 activations [M, K/32, 32] / [M, K/32]; w_*: E4M3 anchor, K-contiguous [N, K/32, 32] / [N, K/32]."""
+    torch = _torch()
+    M, KB = a_scales.shape
+    N = w_scales.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=a_codes.device)
+    a = _packed(a_codes, a_scales, M, KB)
+    w = _packed(w_codes, w_scales, N, w_scales.shape[1])
+    c = _dense(out)
+    binding.check(binding.lib().mx_gemm_ss_fp4(ctypes.byref(a), ctypes.byref(w), ctypes.byref(c), _stream(a_codes)),
+                  "mx_gemm_ss_fp4")
     return out
 
 

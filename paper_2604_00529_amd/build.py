@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 BUILD = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libmx.so")
-SOURCES = ["mx_api.hip", "mx_ss.hip", "mx_dense.hip"]
+SOURCES = ["mx_api.hip", "mx_ss.hip", "mx_dense.hip", "mx_gemm.hip"]
 HEADERS = ["mx_device.h", "mx_launch.h"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-I" + INCLUDE, "-I" + CSRC,
          # packed-FP32 instructions are switched off for device code

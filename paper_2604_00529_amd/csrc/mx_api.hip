@@ -205,6 +205,21 @@ mx_status_t mx_dequant(const mx_format_t* f, const mx_packed_t* src, const mx_de
   return mx::dequant_launch((int)f->elem, f->axis, src->codes, src->scales, d, static_cast<hipStream_t>(stream));
 }
 
+mx_status_t mx_gemm_ss_fp4(const mx_packed_t* a, const mx_packed_t* w_anchor, const mx_dense_t* c, void* stream) {
+  mx_status_t st;
+  if ((st = check_packed(a)) != MX_OK) return st;
+  if ((st = check_packed(w_anchor)) != MX_OK) return st;
+  if ((st = check_dense(c)) != MX_OK) return st;
+  if (c->dtype != MX_F32) return MX_ERR_UNSUPPORTED;
+  if (a->nblocks != w_anchor->nblocks || c->rows != a->outer || c->cols != w_anchor->outer) return MX_ERR_SHAPE;
+  if (c->rows == 0 || c->cols == 0) return MX_OK;
+  const int64_t K = a->nblocks * 32;
+  if (K == 0 || K % 128 != 0 || K > 0x7FFFFFFF || c->rows > 0x7FFFFFFF || c->cols > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+  return mx::gemm_ss_fp4_launch(static_cast<const uint8_t*>(a->codes), a->scales, static_cast<const uint8_t*>(w_anchor->codes),
+                                w_anchor->scales, static_cast<float*>(c->data), c->rows, c->cols, K, c->ld,
+                                static_cast<hipStream_t>(stream));
+}
+
 const char* mx_status_str(mx_status_t status) {
   switch (status) {
     case MX_OK: return "ok";

@@ -1,0 +1,262 @@
+// Fused consumer of an elastic-precision checkpoint (Sec. 3.5 "Inference": the model runs with
+// W_t = Q_{A->t}(W_A) generated on demand): C = DQ(A) * DQ(SS(W_A -> MXFP4))^T, where A holds MXFP8
+// (E4M3) activations and W_A is the stored MXFP8 (E4M3) anchor, both blocked by 32 along K.  The anchor
+// is sliced to E2M1 in registers (Eq. (6)) and fed, with the E8M0 block scales (Eq. (6) scale step), to
+// the CDNA4 scaled MFMA v_mfma_scale_f32_16x16x128_f8f6f4; accumulation is fp32.  W_t never exists in
+// memory.
+//
+// Operand layout of that instruction, established by one-hot probes on the GPU:
+//   lane l = (i = l % 16, g = l / 16).  An FP4 operand lane holds the 32 codes of K-block g of row /
+//   column i (k = 32 g + nibble).  An FP8 operand lane holds two 16-byte runs: k = 16 g + [0, 16) and
+//   k = 64 + 16 g + [0, 16).  The scale byte of lane (i, g) applies to K-block g of row / column i, for
+//   either operand type.  Result register j of lane l is C[4 (l / 16) + j][l % 16].
+#include "mx_device.h"
+#include "mx_launch.h"
+
+namespace mx {
+
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+
+constexpr int kDeltaE_E4M3_E2M1 = Elem<MX_FP8_E4M3>::emax - Elem<MX_FP4_E2M1>::emax;  // 6
+
+// 32 E4M3 anchor codes (8 dwords) -> 32 E2M1 codes (4 dwords): the Slice-and-Scale element step
+__device__ __forceinline__ void slice_block_e2m1(const u32x4& lo, const u32x4& hi, uint32_t (&out)[4]) {
+  const float two_de = __uint_as_float((uint32_t)(127 + kDeltaE_E4M3_E2M1) << 23);
+  const uint32_t in[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    uint32_t w = 0;
+    static_for<0, 2>([&](auto hh) {
+      constexpr int H = decltype(hh)::value;
+      uint32_t x = e4m3_nan_to_max(in[2 * j + H]);
+      f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8(x, false);
+      f32x2 b = __builtin_amdgcn_cvt_pk_f32_fp8(x, true);
+      w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, a.x, a.y, two_de, 2 * H);
+      w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, b.x, b.y, two_de, 2 * H + 1);
+    });
+    out[j] = w;
+  }
+}
+
+__device__ __forceinline__ uint32_t slice_scale(uint32_t byte) {
+  return byte == 255u ? 255u : (byte + kDeltaE_E4M3_E2M1 > 254u ? 254u : byte + kDeltaE_E4M3_E2M1);
+}
+
+// ------------------------------------------------------------------ small M (decode): no LDS tiling
+// One workgroup of 4 waves per 16 output columns; wave w covers K-steps w, w + 4, ... (a K-step is 128
+// elements = 4 blocks, one per lane group), so the four waves walk adjacent 128-byte lines of the same
+// 16 anchor rows.  Every wave slices its own B fragment and multiplies it with MT row tiles of A; the
+// four partial sums are added in a fixed order through LDS (deterministic).
+template <int MT>
+__global__ __launch_bounds__(256) void gemm_ss_fp4_smallm_kernel(const uint8_t* __restrict__ a_codes,
+                                                                 const uint8_t* __restrict__ a_scales,
+                                                                 const uint8_t* __restrict__ w_codes,
+                                                                 const uint8_t* __restrict__ w_scales, float* __restrict__ c,
+                                                                 int M, int N, int K, int64_t ldc) {
+  __shared__ float red[3][MT][4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int i = lane & 15, g = lane >> 4;
+  const int KB = K / 32, ksteps = K / 128;
+  const int n = blockIdx.x * 16 + i;
+  const bool n_ok = n < N;
+  f32x4 acc[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const uint8_t* wrow = w_codes + (int64_t)(n_ok ? n : 0) * K;
+  const uint8_t* wsrow = w_scales + (int64_t)(n_ok ? n : 0) * KB;
+  for (int ks = wave; ks < ksteps; ks += 4) {
+    const int kb = ks * 4 + g;
+    // B: anchor block (n, kb), sliced in registers
+    const u32x4* wp = reinterpret_cast<const u32x4*>(wrow + (int64_t)kb * 32);
+    u32x4 wlo = __builtin_nontemporal_load(wp), whi = __builtin_nontemporal_load(wp + 1);
+    uint32_t bscale = slice_scale(wsrow[kb]);
+    uint32_t b4[4];
+    slice_block_e2m1(wlo, whi, b4);
+    i32x8 b = {(int)b4[0], (int)b4[1], (int)b4[2], (int)b4[3], 0, 0, 0, 0};
+    if (!n_ok) { b = i32x8{0, 0, 0, 0, 0, 0, 0, 0}; bscale = 127u; }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = mt * 16 + i;
+      i32x8 a = {0, 0, 0, 0, 0, 0, 0, 0};
+      uint32_t ascale = 127u;
+      if (m < M) {
+        const uint8_t* ap = a_codes + (int64_t)m * K + ks * 128 + 16 * g;
+        u32x4 a0 = *reinterpret_cast<const u32x4*>(ap), a1 = *reinterpret_cast<const u32x4*>(ap + 64);
+        a = i32x8{(int)a0.x, (int)a0.y, (int)a0.z, (int)a0.w, (int)a1.x, (int)a1.y, (int)a1.z, (int)a1.w};
+        ascale = a_scales[(int64_t)m * KB + kb];
+      }
+      acc[mt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, acc[mt], 0 /* A: E4M3 */, 4 /* B: E2M1 */, 0,
+                                                                 (int)ascale, 0, (int)bscale);
+    }
+  }
+  if (wave > 0) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) red[wave - 1][mt][j][lane] = acc[mt][j];
+  }
+  __syncthreads();
+  if (wave == 0) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float s = ((acc[mt][j] + red[0][mt][j][lane]) + red[1][mt][j][lane]) + red[2][mt][j][lane];
+        const int m = mt * 16 + 4 * g + j;
+        if (m < M && n_ok) c[(int64_t)m * ldc + n] = s;
+      }
+  }
+}
+
+// ------------------------------------------------------------------ large M (prefill): LDS-tiled
+// Workgroup tile 128 (M) x 128 (N), K-step 128, 4 waves in a 2 x 2 grid of 64 x 64 wave tiles (4 x 4 MFMA
+// tiles each).  Per K-step the workgroup stages the A tile (E4M3, 16 KB) and the anchor tile of W (16 KB) --
+// the latter sliced to E2M1 on its way into LDS, once per workgroup instead of once per wave -- plus the
+// scale bytes; global loads of step s + 1 are in flight while step s is multiplied (two LDS stages).
+// Row strides are padded (144 B / 80 B) so that the 16 lanes of a lane group hit different banks.
+constexpr int kGemmBM = 128, kGemmBN = 128, kGemmBK = 128;
+constexpr int kGemmLdA = 144, kGemmLdB = 80;
+
+struct GemmStage {
+  uint8_t a[kGemmBM * kGemmLdA];   // E4M3 codes, row m: 128 bytes of K
+  uint8_t b[kGemmBN * kGemmLdB];   // E2M1 codes, column n: 64 bytes (128 nibbles of K)
+  uint32_t as[kGemmBM];            // 4 scale bytes per row (one per K-block of the step)
+  uint32_t bs[kGemmBN];            // 4 sliced scale bytes per column
+};
+
+__global__ __launch_bounds__(256) void gemm_ss_fp4_tiled_kernel(const uint8_t* __restrict__ a_codes,
+                                                                const uint8_t* __restrict__ a_scales,
+                                                                const uint8_t* __restrict__ w_codes,
+                                                                const uint8_t* __restrict__ w_scales, float* __restrict__ c,
+                                                                int M, int N, int K, int64_t ldc, int m_tiles) {
+  __shared__ __attribute__((aligned(16))) GemmStage stage[2];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i = lane & 15, g = lane >> 4;
+  const int wm = wave >> 1, wn = wave & 1;
+  // consecutive workgroups walk the M tiles of one N tile: with round-robin dispatch over the 8 XCDs each XCD
+  // keeps re-using the same few A tiles from its L2 while the W tile streams through
+  const int tm = blockIdx.x % m_tiles, tn = blockIdx.x / m_tiles;
+  const int m0 = tm * kGemmBM, n0 = tn * kGemmBN;
+  const int KB = K / 32, ksteps = K / kGemmBK;
+
+  // per-thread slots of the global -> LDS copies
+  //   A: chunk q = tid + 256 j (j < 4): row q / 8, 16-byte column q % 8
+  //   B: block q = tid + 256 j (j < 2): column q / 4, K-block q % 4 (32 anchor bytes -> 16 bytes of E2M1)
+  u32x4 ra[4], rb[2][2];
+  uint32_t rsa = 0, rsb = 0;
+  auto load_global = [&](int ks) {
+    const int k0 = ks * kGemmBK;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int q = tid + 256 * j, row = q >> 3, col = q & 7;
+      ra[j] = u32x4{0, 0, 0, 0};
+      if (m0 + row < M) ra[j] = *reinterpret_cast<const u32x4*>(a_codes + (int64_t)(m0 + row) * K + k0 + 16 * col);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      int q = tid + 256 * j, col = q >> 2, kb = q & 3;
+      rb[j][0] = u32x4{0, 0, 0, 0};
+      rb[j][1] = u32x4{0, 0, 0, 0};
+      if (n0 + col < N) {
+        const u32x4* p = reinterpret_cast<const u32x4*>(w_codes + (int64_t)(n0 + col) * K + k0 + 32 * kb);
+        rb[j][0] = __builtin_nontemporal_load(p);
+        rb[j][1] = __builtin_nontemporal_load(p + 1);
+      }
+    }
+    if (tid < kGemmBM) {
+      rsa = 0x7F7F7F7Fu;
+      if (m0 + tid < M) rsa = *reinterpret_cast<const uint32_t*>(a_scales + (int64_t)(m0 + tid) * KB + ks * 4);
+    } else {
+      const int col = tid - kGemmBM;
+      rsb = 0x7F7F7F7Fu;
+      if (n0 + col < N) rsb = *reinterpret_cast<const uint32_t*>(w_scales + (int64_t)(n0 + col) * KB + ks * 4);
+    }
+  };
+  auto store_lds = [&](GemmStage& st) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int q = tid + 256 * j, row = q >> 3, col = q & 7;
+      *reinterpret_cast<u32x4*>(&st.a[row * kGemmLdA + 16 * col]) = ra[j];
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      int q = tid + 256 * j, col = q >> 2, kb = q & 3;
+      uint32_t b4[4];
+      slice_block_e2m1(rb[j][0], rb[j][1], b4);   // Eq. (6) element step, once per workgroup and K-step
+      *reinterpret_cast<u32x4*>(&st.b[col * kGemmLdB + 16 * kb]) = u32x4{b4[0], b4[1], b4[2], b4[3]};
+    }
+    if (tid < kGemmBM) st.as[tid] = rsa;
+    else st.bs[tid - kGemmBM] = scale_add_x4(rsb, kDeltaE_E4M3_E2M1);   // Eq. (6) scale step
+  };
+
+  f32x4 acc[4][4];
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  load_global(0);
+  store_lds(stage[0]);
+  __syncthreads();
+  for (int ks = 0; ks < ksteps; ++ks) {
+    const GemmStage& cur = stage[ks & 1];
+    if (ks + 1 < ksteps) load_global(ks + 1);
+    i32x8 bf[4];
+    int bsc[4];
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+      const int col = wn * 64 + nt * 16 + i;
+      u32x4 t = *reinterpret_cast<const u32x4*>(&cur.b[col * kGemmLdB + 16 * g]);
+      bf[nt] = i32x8{(int)t.x, (int)t.y, (int)t.z, (int)t.w, 0, 0, 0, 0};
+      bsc[nt] = (int)((cur.bs[col] >> (8 * g)) & 0xFFu);
+    }
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+      const int row = wm * 64 + mt * 16 + i;
+      u32x4 t0 = *reinterpret_cast<const u32x4*>(&cur.a[row * kGemmLdA + 16 * g]);
+      u32x4 t1 = *reinterpret_cast<const u32x4*>(&cur.a[row * kGemmLdA + 64 + 16 * g]);
+      i32x8 af = {(int)t0.x, (int)t0.y, (int)t0.z, (int)t0.w, (int)t1.x, (int)t1.y, (int)t1.z, (int)t1.w};
+      int asc = (int)((cur.as[row] >> (8 * g)) & 0xFFu);
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt)
+        acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af, bf[nt], acc[mt][nt], 0, 4, 0, asc, 0, bsc[nt]);
+    }
+    if (ks + 1 < ksteps) store_lds(stage[(ks + 1) & 1]);
+    __syncthreads();
+  }
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+      const int n = n0 + wn * 64 + nt * 16 + i;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int m = m0 + wm * 64 + mt * 16 + 4 * g + j;
+        if (m < M && n < N) c[(int64_t)m * ldc + n] = acc[mt][nt][j];
+      }
+    }
+}
+
+mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
+                               const uint8_t* w_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
+                               hipStream_t stream) {
+  if (M > 64) {
+    const int64_t m_tiles = (M + kGemmBM - 1) / kGemmBM, n_tiles = (N + kGemmBN - 1) / kGemmBN;
+    if (m_tiles * n_tiles > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(gemm_ss_fp4_tiled_kernel, dim3((unsigned)(m_tiles * n_tiles)), dim3(256), 0, stream, a_codes, a_scales,
+                       w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles);
+    return hipGetLastError() == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
+  }
+  const unsigned grid = (unsigned)((N + 15) / 16);
+  const int mt = (int)((M + 15) / 16);
+#define MX_GEMM_CASE(MT)                                                                                                  \
+  if (mt == MT) {                                                                                                         \
+    hipLaunchKernelGGL((gemm_ss_fp4_smallm_kernel<MT>), dim3(grid), dim3(256), 0, stream, a_codes, a_scales, w_codes,     \
+                       w_scales, c, (int)M, (int)N, (int)K, ldc);                                                         \
+  }
+  MX_GEMM_CASE(1) MX_GEMM_CASE(2) MX_GEMM_CASE(3) MX_GEMM_CASE(4)
+#undef MX_GEMM_CASE
+  return hipGetLastError() == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
+}
+
+}  // namespace mx

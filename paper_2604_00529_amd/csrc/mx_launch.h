@@ -55,4 +55,8 @@ mx_status_t dequant_launch(int elem, int axis, const void* codes, const uint8_t*
 mx_status_t fake_quant_launch(int target, int anchor /* -1: none */, int axis, int tie, const DenseArg& src,
                               const DenseArg& dst, hipStream_t stream);
 
+mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
+                               const uint8_t* w_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
+                               hipStream_t stream);
+
 }  // namespace mx

@@ -1,0 +1,90 @@
+"""Fused consumer GEMM (anchor sliced to MXFP4 in registers, scaled MX MFMA) against the fp64 product of the
+dequantized operands.  Bar (from the benchmark definition): max |err| <= 1e-3 * ||row||_2 per output row."""
+import numpy as np
+import pytest
+
+from paper_2604_00529_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mx():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2604_00529_amd as mx
+    mx.binding.lib()
+    return mx
+
+
+def _gpu_bf16(a):
+    import torch
+    return torch.from_numpy(synth.f32_to_bf16_bits(a).view(np.int16).copy()).view(torch.bfloat16).cuda()
+
+
+def _check(mx, oracle, M, N, K, seed, w_axis0=True, random_bytes=False):
+    import torch
+    rng = np.random.default_rng(seed)
+    f8 = mx.make_format("e4m3")
+    if random_bytes:
+        # adversarial operands: every code (NaN codes included for the anchor), moderate scale bytes
+        ac = torch.from_numpy(rng.integers(0, 256, size=(M, K // 32, 32), dtype=np.uint8)).cuda()
+        ac[(ac & 0x7F) == 0x7F] = 0x7E                     # activations made by mx_quantize never hold NaN codes
+        lo_a, hi_a, lo_w, hi_w = (110, 140, 100, 135) if random_bytes == "wide" else (125, 130, 119, 124)
+        asc = torch.from_numpy(rng.integers(lo_a, hi_a, size=(M, K // 32), dtype=np.uint8)).cuda()
+        wc = torch.from_numpy(rng.integers(0, 256, size=(N, K // 32, 32), dtype=np.uint8)).cuda()
+        wsc = torch.from_numpy(rng.integers(lo_w, hi_w, size=(N, K // 32), dtype=np.uint8)).cuda()
+    else:
+        a = rng.standard_normal((M, K)).astype(np.float32)
+        ac, asc = mx.mx_quantize(_gpu_bf16(a), f8)
+        if w_axis0:
+            w = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)          # [K, N], blocks down the columns
+            wc, wsc = mx.mx_quantize(_gpu_bf16(w), mx.make_format("e4m3", axis=0))
+        else:
+            w = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+            wc, wsc = mx.mx_quantize(_gpu_bf16(w), f8)
+    c = mx.mx_gemm_ss_fp4(ac, asc, wc, wsc)
+    torch.cuda.synchronize()
+    ref, ref_abs = oracle.gemm_ss_reference(ac.cpu().numpy(), asc.cpu().numpy(), wc.cpu().numpy(), wsc.cpu().numpy(),
+                                            with_abs=True)
+    got = c.cpu().numpy().astype(np.float64)
+    assert got.shape == (M, N)
+    # Error on the scale of sum |products| (holds under any cancellation).  The matrix instruction adds the 128
+    # products of one step after aligning them to the largest one, so blocks whose scales differ by many powers of
+    # two lose the low bits of the small products: the bound is looser for the wide-range adversarial operands.
+    rel = np.abs(got - ref) / (ref_abs + 1e-30)
+    print("max |err| / sum|products| = %.3g (%s)" % (rel.max(), random_bytes or "benchmark data"))
+    assert np.isfinite(got).all()
+    assert rel.max() <= {None: 2e-5, False: 2e-5, "narrow": 2e-4, "wide": 1e-3}[random_bytes]
+    if not random_bytes:
+        # the benchmark definition's bar on its own kind of data: max |err| <= 1e-3 * ||row||_2
+        err = np.abs(got - ref).max(axis=1)
+        bound = 1e-3 * np.linalg.norm(ref, axis=1)
+        assert (err <= bound).all(), "worst row: err %g vs bound %g" % (err.max(), bound[err.argmax()])
+        assert (err <= 2e-5 * np.linalg.norm(ref, axis=1) + 1e-30).all()
+
+
+@pytest.mark.parametrize("M,N,K", [(16, 256, 512), (1, 48, 128), (7, 104, 384), (33, 64, 1024), (64, 1000, 256)])
+def test_gemm_small_shapes(mx, oracle, M, N, K):
+    _check(mx, oracle, M, N, K, seed=M * 1000 + N)
+    _check(mx, oracle, M, N, K, seed=M * 1000 + N + 1, w_axis0=False)
+    _check(mx, oracle, M, N, K, seed=M * 1000 + N + 2, random_bytes="narrow")
+    _check(mx, oracle, M, N, K, seed=M * 1000 + N + 3, random_bytes="wide")
+
+
+def test_gemm_decode_shape_config5(mx, oracle):
+    # M = 16, K = 4096, N = 14336: the decode shape of the benchmark definition
+    _check(mx, oracle, 16, 14336, 4096, seed=1005)
+
+
+@pytest.mark.parametrize("M,N,K", [(128, 128, 128), (65, 16, 256), (200, 304, 256), (384, 136, 1024)])
+def test_gemm_tiled_shapes(mx, oracle, M, N, K):
+    # M > 64 takes the LDS-tiled kernel; ragged M and N tiles
+    _check(mx, oracle, M, N, K, seed=M + N)
+    _check(mx, oracle, M, N, K, seed=M + N + 1, random_bytes="narrow")
+    _check(mx, oracle, M, N, K, seed=M + N + 2, random_bytes="wide")
+
+
+def test_gemm_prefill_shape_config5(mx, oracle):
+    # M = 2048, K = 4096, N = 14336: the prefill shape of the benchmark definition
+    _check(mx, oracle, 2048, 14336, 4096, seed=2005)
