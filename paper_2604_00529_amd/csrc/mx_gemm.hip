@@ -43,68 +43,146 @@ __device__ __forceinline__ uint32_t slice_scale(uint32_t byte) {
 }
 
 // ------------------------------------------------------------------ small M (decode): no LDS tiling
-// One workgroup of 4 waves per 16 output columns; wave w covers K-steps w, w + 4, ... (a K-step is 128
-// elements = 4 blocks, one per lane group), so the four waves walk adjacent 128-byte lines of the same
-// 16 anchor rows.  Every wave slices its own B fragment and multiplies it with MT row tiles of A; the
-// four partial sums are added in a fixed order through LDS (deterministic).
+// One workgroup of 4 waves per 16 * NT output columns.  K is cut into chunks of 8 K-steps (a K-step is 128
+// elements = 4 blocks, one per lane group; a chunk is 1024 elements) dealt round-robin to the waves, so a wave
+// reads, per row, 1 KB of contiguous codes and the chunk's 32 scale bytes with two 128-bit loads.  Every wave
+// slices its own B fragments (Eq. (6)) and multiplies them with MT row tiles of A; the loads of 4 K-steps are in
+// flight together.  The four partial sums are added in a fixed order through LDS (deterministic).
+constexpr int kSmallmNT = 2;
+
+// scale byte of K-step p (0..7) of a chunk for lane group g, out of the chunk's 32 bytes
+__device__ __forceinline__ uint32_t chunk_scale(const u32x4& lo, const u32x4& hi, int p, int g) {
+  const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+  return (w[p] >> (8 * g)) & 0xFFu;
+}
+
+// the 32 scale bytes of chunk `chunk` of one row (KB bytes long); a ragged last chunk is read byte by byte
+__device__ __forceinline__ void load_chunk_scales(const uint8_t* row, int chunk, int KB, u32x4& lo, u32x4& hi) {
+  const int b0 = chunk * 32;
+  if (b0 + 32 <= KB) {
+    lo = *reinterpret_cast<const u32x4*>(row + b0);
+    hi = *reinterpret_cast<const u32x4*>(row + b0 + 16);
+  } else {
+    uint32_t w[8];
+#pragma unroll
+    for (int d = 0; d < 8; ++d) {
+      w[d] = 0x7F7F7F7Fu;
+      if (b0 + 4 * d + 4 <= KB) w[d] = *reinterpret_cast<const uint32_t*>(row + b0 + 4 * d);
+    }
+    lo = u32x4{w[0], w[1], w[2], w[3]};
+    hi = u32x4{w[4], w[5], w[6], w[7]};
+  }
+}
+
 template <int MT>
 __global__ __launch_bounds__(256) void gemm_ss_fp4_smallm_kernel(const uint8_t* __restrict__ a_codes,
                                                                  const uint8_t* __restrict__ a_scales,
                                                                  const uint8_t* __restrict__ w_codes,
                                                                  const uint8_t* __restrict__ w_scales, float* __restrict__ c,
                                                                  int M, int N, int K, int64_t ldc) {
-  __shared__ float red[3][MT][4][64];
+  constexpr int NT = kSmallmNT, PF = 4;
+  __shared__ float red[3][MT][NT][4][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i = lane & 15, g = lane >> 4;
-  const int KB = K / 32, ksteps = K / 128;
-  const int n = blockIdx.x * 16 + i;
-  const bool n_ok = n < N;
-  f32x4 acc[MT];
+  const int KB = K / 32, ksteps = K / 128, chunks = (ksteps + 7) / 8;
+  f32x4 acc[MT][NT];
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const uint8_t* wrow = w_codes + (int64_t)(n_ok ? n : 0) * K;
-  const uint8_t* wsrow = w_scales + (int64_t)(n_ok ? n : 0) * KB;
-  for (int ks = wave; ks < ksteps; ks += 4) {
-    const int kb = ks * 4 + g;
-    // B: anchor block (n, kb), sliced in registers
-    const u32x4* wp = reinterpret_cast<const u32x4*>(wrow + (int64_t)kb * 32);
-    u32x4 wlo = __builtin_nontemporal_load(wp), whi = __builtin_nontemporal_load(wp + 1);
-    uint32_t bscale = slice_scale(wsrow[kb]);
-    uint32_t b4[4];
-    slice_block_e2m1(wlo, whi, b4);
-    i32x8 b = {(int)b4[0], (int)b4[1], (int)b4[2], (int)b4[3], 0, 0, 0, 0};
-    if (!n_ok) { b = i32x8{0, 0, 0, 0, 0, 0, 0, 0}; bscale = 127u; }
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  int ncol[NT];
+  bool n_ok[NT];
+  const uint8_t* wrow[NT];
+  const uint8_t* wsrow[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    ncol[nt] = (blockIdx.x * NT + nt) * 16 + i;
+    n_ok[nt] = ncol[nt] < N;
+    wrow[nt] = w_codes + (int64_t)(n_ok[nt] ? ncol[nt] : 0) * K;
+    wsrow[nt] = w_scales + (int64_t)(n_ok[nt] ? ncol[nt] : 0) * KB;
+  }
+  for (int chunk = wave; chunk < chunks; chunk += 4) {
+    u32x4 wslo[NT], wshi[NT], aslo[MT], ashi[MT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) load_chunk_scales(wsrow[nt], chunk, KB, wslo[nt], wshi[nt]);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const int m = mt * 16 + i;
-      i32x8 a = {0, 0, 0, 0, 0, 0, 0, 0};
-      uint32_t ascale = 127u;
-      if (m < M) {
-        const uint8_t* ap = a_codes + (int64_t)m * K + ks * 128 + 16 * g;
-        u32x4 a0 = *reinterpret_cast<const u32x4*>(ap), a1 = *reinterpret_cast<const u32x4*>(ap + 64);
-        a = i32x8{(int)a0.x, (int)a0.y, (int)a0.z, (int)a0.w, (int)a1.x, (int)a1.y, (int)a1.z, (int)a1.w};
-        ascale = a_scales[(int64_t)m * KB + kb];
+      aslo[mt] = ashi[mt] = u32x4{0x7F7F7F7Fu, 0x7F7F7F7Fu, 0x7F7F7F7Fu, 0x7F7F7F7Fu};
+      if (m < M) load_chunk_scales(a_scales + (int64_t)m * KB, chunk, KB, aslo[mt], ashi[mt]);
+    }
+#pragma unroll
+    for (int half = 0; half < 8 / PF; ++half) {
+      u32x4 wlo[PF][NT], whi[PF][NT], a0[PF][MT], a1[PF][MT];
+#pragma unroll
+      for (int p = 0; p < PF; ++p) {
+        const int ks = chunk * 8 + half * PF + p;
+        const bool live = ks < ksteps;
+        const int kb = (live ? ks : 0) * 4 + g;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          const u32x4* wp = reinterpret_cast<const u32x4*>(wrow[nt] + (int64_t)kb * 32);
+          wlo[p][nt] = __builtin_nontemporal_load(wp);
+          whi[p][nt] = __builtin_nontemporal_load(wp + 1);
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const int m = mt * 16 + i;
+          a0[p][mt] = a1[p][mt] = u32x4{0, 0, 0, 0};
+          if (m < M && live) {
+            const uint8_t* ap = a_codes + (int64_t)m * K + ks * 128 + 16 * g;
+            a0[p][mt] = *reinterpret_cast<const u32x4*>(ap);
+            a1[p][mt] = *reinterpret_cast<const u32x4*>(ap + 64);
+          }
+        }
       }
-      acc[mt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, acc[mt], 0 /* A: E4M3 */, 4 /* B: E2M1 */, 0,
-                                                                 (int)ascale, 0, (int)bscale);
+#pragma unroll
+      for (int p = 0; p < PF; ++p) {
+        const bool live = chunk * 8 + half * PF + p < ksteps;
+        i32x8 b[NT];
+        int bscale[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          // B: anchor block (n, kb), sliced in registers (Eq. (6)); dead steps and columns multiply zeros
+          uint32_t b4[4];
+          slice_block_e2m1(wlo[p][nt], whi[p][nt], b4);
+          bscale[nt] = (int)slice_scale(chunk_scale(wslo[nt], wshi[nt], half * PF + p, g));
+          b[nt] = i32x8{(int)b4[0], (int)b4[1], (int)b4[2], (int)b4[3], 0, 0, 0, 0};
+          if (!n_ok[nt] || !live) { b[nt] = i32x8{0, 0, 0, 0, 0, 0, 0, 0}; bscale[nt] = 127; }
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          i32x8 a = {(int)a0[p][mt].x, (int)a0[p][mt].y, (int)a0[p][mt].z, (int)a0[p][mt].w,
+                     (int)a1[p][mt].x, (int)a1[p][mt].y, (int)a1[p][mt].z, (int)a1[p][mt].w};
+          int ascale = (int)chunk_scale(aslo[mt], ashi[mt], half * PF + p, g);
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+            acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b[nt], acc[mt][nt], 0 /* A: E4M3 */,
+                                                                           4 /* B: E2M1 */, 0, ascale, 0, bscale[nt]);
+        }
+      }
     }
   }
   if (wave > 0) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) red[wave - 1][mt][j][lane] = acc[mt][j];
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) red[wave - 1][mt][nt][j][lane] = acc[mt][nt][j];
   }
   __syncthreads();
   if (wave == 0) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        float s = ((acc[mt][j] + red[0][mt][j][lane]) + red[1][mt][j][lane]) + red[2][mt][j][lane];
-        const int m = mt * 16 + 4 * g + j;
-        if (m < M && n_ok) c[(int64_t)m * ldc + n] = s;
-      }
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float s = ((acc[mt][nt][j] + red[0][mt][nt][j][lane]) + red[1][mt][nt][j][lane]) + red[2][mt][nt][j][lane];
+          const int m = mt * 16 + 4 * g + j;
+          if (m < M && n_ok[nt]) c[(int64_t)m * ldc + ncol[nt]] = s;
+        }
   }
 }
 
@@ -247,7 +325,7 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
                        w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles);
     return hipGetLastError() == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
   }
-  const unsigned grid = (unsigned)((N + 15) / 16);
+  const unsigned grid = (unsigned)((N + 16 * kSmallmNT - 1) / (16 * kSmallmNT));
   const int mt = (int)((M + 15) / 16);
 #define MX_GEMM_CASE(MT)                                                                                                  \
   if (mt == MT) {                                                                                                         \
