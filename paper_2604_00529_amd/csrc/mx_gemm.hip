@@ -187,13 +187,17 @@ __global__ __launch_bounds__(256) void gemm_ss_fp4_smallm_kernel(const uint8_t* 
 }
 
 // ------------------------------------------------------------------ large M (prefill): LDS-tiled
-// Workgroup tile 128 (M) x 128 (N), K-step 128, 4 waves in a 2 x 2 grid of 64 x 64 wave tiles (4 x 4 MFMA
-// tiles each).  Per K-step the workgroup stages the A tile (E4M3, 16 KB) and the anchor tile of W (16 KB) --
-// the latter sliced to E2M1 on its way into LDS, once per workgroup instead of once per wave -- plus the
-// scale bytes; global loads of step s + 1 are in flight while step s is multiplied (two LDS stages).
-// Row strides are padded (144 B / 80 B) so that the 16 lanes of a lane group hit different banks.
-constexpr int kGemmBM = 128, kGemmBN = 128, kGemmBK = 128;
+// Workgroup tile 256 (M) x 128 (N), K-step 128, 4 waves in a 2 x 2 grid of 128 x 64 wave tiles (8 x 4 MFMA tiles,
+// 32 MFMAs per wave and K-step).  Per K-step the workgroup stages the A tile (E4M3, 32 KB) and the anchor tile of W
+// (16 KB) -- the latter sliced to E2M1 on its way into LDS, once per workgroup instead of once per wave; the tall
+// tile is what amortizes that slicing (about 2.3 vector instructions per element) against the matrix work -- plus
+// the scale bytes.  Global loads run ahead in registers, LDS is double-buffered.  Row strides are padded
+// (144 B / 80 B) so that the 16 lanes of a lane group hit different banks.
+constexpr int kGemmBM = 256, kGemmBN = 128, kGemmBK = 128;
+constexpr int kGemmMT = 8, kGemmNT = 4;      // MFMA tiles per wave
 constexpr int kGemmLdA = 144, kGemmLdB = 80;
+constexpr int kGemmPrefetch = 2;             // K-steps of global loads in flight per thread
+constexpr int kGemmAChunks = kGemmBM * kGemmBK / 16 / 256;   // 16-byte A chunks per thread and K-step (8)
 
 struct GemmStage {
   uint8_t a[kGemmBM * kGemmLdA];   // E4M3 codes, row m: 128 bytes of K
@@ -202,12 +206,16 @@ struct GemmStage {
   uint32_t bs[kGemmBN];            // 4 sliced scale bytes per column
 };
 
+// SKIP is 0 in the library; a tuning harness instantiates other values to take parts of the kernel out
+// (1: no slicing, 2: no LDS fragment reads after the first K-step, 4: no MFMA, 8: no global loads after the prologue).
+template <int SKIP>
 __global__ __launch_bounds__(256) void gemm_ss_fp4_tiled_kernel(const uint8_t* __restrict__ a_codes,
                                                                 const uint8_t* __restrict__ a_scales,
                                                                 const uint8_t* __restrict__ w_codes,
                                                                 const uint8_t* __restrict__ w_scales, float* __restrict__ c,
                                                                 int M, int N, int K, int64_t ldc, int m_tiles) {
-  __shared__ __attribute__((aligned(16))) GemmStage stage[2];
+  extern __shared__ __attribute__((aligned(16))) uint8_t gemm_smem[];
+  GemmStage* stage = reinterpret_cast<GemmStage*>(gemm_smem);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i = lane & 15, g = lane >> 4;
   const int wm = wave >> 1, wn = wave & 1;
@@ -218,98 +226,146 @@ __global__ __launch_bounds__(256) void gemm_ss_fp4_tiled_kernel(const uint8_t* _
   const int KB = K / 32, ksteps = K / kGemmBK;
 
   // per-thread slots of the global -> LDS copies
-  //   A: chunk q = tid + 256 j (j < 4): row q / 8, 16-byte column q % 8
+  //   A: chunk q = tid + 256 j (j < 8): row q / 8, 16-byte column q % 8
   //   B: block q = tid + 256 j (j < 2): column q / 4, K-block q % 4 (32 anchor bytes -> 16 bytes of E2M1)
-  u32x4 ra[4], rb[2][2];
-  uint32_t rsa = 0, rsb = 0;
-  auto load_global = [&](int ks) {
+  //   scales: thread t < 256 one row of A (4 bytes); thread t < 128 also one column of W
+  // Rows / columns past the edge are clamped to the last valid one instead of branched around: their products land
+  // in outputs that are never stored, and straight-line code lets the loads of several K-steps stay in flight (the
+  // compiler counts outstanding loads exactly only without control flow).
+  constexpr int D = kGemmPrefetch;
+  const uint8_t* pa[kGemmAChunks];
+  const uint8_t* pw[2];
+#pragma unroll
+  for (int j = 0; j < kGemmAChunks; ++j) {
+    int q = tid + 256 * j, row = q >> 3, col = q & 7;
+    int m = m0 + row < M ? m0 + row : M - 1;
+    pa[j] = a_codes + (int64_t)m * K + 16 * col;
+  }
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    int q = tid + 256 * j, col = q >> 2, kb = q & 3;
+    int n = n0 + col < N ? n0 + col : N - 1;
+    pw[j] = w_codes + (int64_t)n * K + 32 * kb;
+  }
+  const uint8_t* psa = a_scales + (int64_t)(m0 + tid < M ? m0 + tid : M - 1) * KB;
+  const uint8_t* psw = w_scales + (int64_t)(n0 + (tid & 127) < N ? n0 + (tid & 127) : N - 1) * KB;
+
+  u32x4 ra[D][kGemmAChunks], rb[D][2][2];
+  uint32_t rsa[D], rsw[D];
+  auto load_global = [&](int ks, auto slot_c) {
+    constexpr int S = decltype(slot_c)::value;
     const int k0 = ks * kGemmBK;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      int q = tid + 256 * j, row = q >> 3, col = q & 7;
-      ra[j] = u32x4{0, 0, 0, 0};
-      if (m0 + row < M) ra[j] = *reinterpret_cast<const u32x4*>(a_codes + (int64_t)(m0 + row) * K + k0 + 16 * col);
-    }
+    for (int j = 0; j < kGemmAChunks; ++j) ra[S][j] = *reinterpret_cast<const u32x4*>(pa[j] + k0);
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      int q = tid + 256 * j, col = q >> 2, kb = q & 3;
-      rb[j][0] = u32x4{0, 0, 0, 0};
-      rb[j][1] = u32x4{0, 0, 0, 0};
-      if (n0 + col < N) {
-        const u32x4* p = reinterpret_cast<const u32x4*>(w_codes + (int64_t)(n0 + col) * K + k0 + 32 * kb);
-        rb[j][0] = __builtin_nontemporal_load(p);
-        rb[j][1] = __builtin_nontemporal_load(p + 1);
-      }
+      const u32x4* p = reinterpret_cast<const u32x4*>(pw[j] + k0);
+      rb[S][j][0] = __builtin_nontemporal_load(p);
+      rb[S][j][1] = __builtin_nontemporal_load(p + 1);
     }
-    if (tid < kGemmBM) {
-      rsa = 0x7F7F7F7Fu;
-      if (m0 + tid < M) rsa = *reinterpret_cast<const uint32_t*>(a_scales + (int64_t)(m0 + tid) * KB + ks * 4);
-    } else {
-      const int col = tid - kGemmBM;
-      rsb = 0x7F7F7F7Fu;
-      if (n0 + col < N) rsb = *reinterpret_cast<const uint32_t*>(w_scales + (int64_t)(n0 + col) * KB + ks * 4);
-    }
+    rsa[S] = *reinterpret_cast<const uint32_t*>(psa + ks * 4);
+    rsw[S] = *reinterpret_cast<const uint32_t*>(psw + ks * 4);
   };
-  auto store_lds = [&](GemmStage& st) {
+  auto store_lds = [&](GemmStage& st, auto slot_c) {
+    constexpr int S = decltype(slot_c)::value;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < kGemmAChunks; ++j) {
       int q = tid + 256 * j, row = q >> 3, col = q & 7;
-      *reinterpret_cast<u32x4*>(&st.a[row * kGemmLdA + 16 * col]) = ra[j];
+      *reinterpret_cast<u32x4*>(&st.a[row * kGemmLdA + 16 * col]) = ra[S][j];
     }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       int q = tid + 256 * j, col = q >> 2, kb = q & 3;
       uint32_t b4[4];
-      slice_block_e2m1(rb[j][0], rb[j][1], b4);   // Eq. (6) element step, once per workgroup and K-step
+      if constexpr (SKIP & 1) {
+        b4[0] = rb[S][j][0].x ^ rb[S][j][1].x; b4[1] = rb[S][j][0].y ^ rb[S][j][1].y;
+        b4[2] = rb[S][j][0].z ^ rb[S][j][1].z; b4[3] = rb[S][j][0].w ^ rb[S][j][1].w;
+      } else {
+        slice_block_e2m1(rb[S][j][0], rb[S][j][1], b4);   // Eq. (6) element step, once per workgroup and K-step
+      }
       *reinterpret_cast<u32x4*>(&st.b[col * kGemmLdB + 16 * kb]) = u32x4{b4[0], b4[1], b4[2], b4[3]};
     }
-    if (tid < kGemmBM) st.as[tid] = rsa;
-    else st.bs[tid - kGemmBM] = scale_add_x4(rsb, kDeltaE_E4M3_E2M1);   // Eq. (6) scale step
+    st.as[tid] = rsa[S];
+    if (tid < kGemmBN) st.bs[tid] = scale_add_x4(rsw[S], kDeltaE_E4M3_E2M1);   // Eq. (6) scale step
   };
 
-  f32x4 acc[4][4];
+  f32x4 acc[kGemmMT][kGemmNT];
 #pragma unroll
-  for (int mt = 0; mt < 4; ++mt)
+  for (int mt = 0; mt < kGemmMT; ++mt)
 #pragma unroll
-    for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int nt = 0; nt < kGemmNT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  load_global(0);
-  store_lds(stage[0]);
-  __syncthreads();
-  for (int ks = 0; ks < ksteps; ++ks) {
-    const GemmStage& cur = stage[ks & 1];
-    if (ks + 1 < ksteps) load_global(ks + 1);
-    i32x8 bf[4];
-    int bsc[4];
+  // B operands: only the low 4 dwords carry FP4 codes; the upper 4 stay zero for the whole kernel
+  i32x8 bf[kGemmNT];
 #pragma unroll
-    for (int nt = 0; nt < 4; ++nt) {
-      const int col = wn * 64 + nt * 16 + i;
-      u32x4 t = *reinterpret_cast<const u32x4*>(&cur.b[col * kGemmLdB + 16 * g]);
-      bf[nt] = i32x8{(int)t.x, (int)t.y, (int)t.z, (int)t.w, 0, 0, 0, 0};
-      bsc[nt] = (int)((cur.bs[col] >> (8 * g)) & 0xFFu);
+  for (int nt = 0; nt < kGemmNT; ++nt) bf[nt] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
+  const int a_off = (wm * 128 + i) * kGemmLdA + 16 * g;   // + mt * 16 rows
+  const int b_off = (wn * 64 + i) * kGemmLdB + 16 * g;    // + nt * 16 columns
+  auto compute = [&](const GemmStage& cur_in) {
+    const GemmStage& cur = (SKIP & 2) ? stage[0] : cur_in;
+    int bsc[kGemmNT];
+#pragma unroll
+    for (int nt = 0; nt < kGemmNT; ++nt) {
+      u32x4 t = *reinterpret_cast<const u32x4*>(&cur.b[b_off + nt * 16 * kGemmLdB]);
+      bf[nt][0] = (int)t.x; bf[nt][1] = (int)t.y; bf[nt][2] = (int)t.z; bf[nt][3] = (int)t.w;
+      bsc[nt] = (int)(cur.bs[wn * 64 + nt * 16 + i] >> (8 * g));   // the instruction reads the low byte
     }
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
-      const int row = wm * 64 + mt * 16 + i;
-      u32x4 t0 = *reinterpret_cast<const u32x4*>(&cur.a[row * kGemmLdA + 16 * g]);
-      u32x4 t1 = *reinterpret_cast<const u32x4*>(&cur.a[row * kGemmLdA + 64 + 16 * g]);
+    for (int mt = 0; mt < kGemmMT; ++mt) {
+      u32x4 t0 = *reinterpret_cast<const u32x4*>(&cur.a[a_off + mt * 16 * kGemmLdA]);
+      u32x4 t1 = *reinterpret_cast<const u32x4*>(&cur.a[a_off + mt * 16 * kGemmLdA + 64]);
       i32x8 af = {(int)t0.x, (int)t0.y, (int)t0.z, (int)t0.w, (int)t1.x, (int)t1.y, (int)t1.z, (int)t1.w};
-      int asc = (int)((cur.as[row] >> (8 * g)) & 0xFFu);
+      int asc = (int)(cur.as[wm * 128 + mt * 16 + i] >> (8 * g));
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt)
-        acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af, bf[nt], acc[mt][nt], 0, 4, 0, asc, 0, bsc[nt]);
+      for (int nt = 0; nt < kGemmNT; ++nt) {
+        if constexpr (SKIP & 4) {
+          acc[mt][nt][0] += __int_as_float(af[0] ^ bf[nt][0] ^ asc); acc[mt][nt][1] += __int_as_float(af[7] ^ bf[nt][3] ^ bsc[nt]);
+        } else {
+          acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af, bf[nt], acc[mt][nt], 0, 4, 0, asc, 0, bsc[nt]);
+        }
+      }
     }
-    if (ks + 1 < ksteps) store_lds(stage[(ks + 1) & 1]);
-    __syncthreads();
+  };
+
+  // Software pipeline without branches around the loads (a branch makes the compiler wait for ALL outstanding
+  // loads): K-steps past the end are clamped to the last one, their data is loaded again and never used.
+  const int last = ksteps - 1;
+  auto clamp_ks = [&](int ks) { return ks < last ? ks : last; };
+  // prologue: K-steps 0 .. D-1 in flight, step 0 staged, step D in flight in its place
+  static_for<0, D>([&](auto d) { load_global(clamp_ks(decltype(d)::value), d); });
+  store_lds(stage[0], std::integral_constant<int, 0>{});
+  load_global(clamp_ks(D), std::integral_constant<int, 0>{});
+  __syncthreads();
+  const int rounds = ksteps / D;
+  for (int r = 0; r < rounds; ++r) {
+    static_for<0, D>([&](auto d) {
+      constexpr int DD = decltype(d)::value;
+      constexpr int NEXT = (DD + 1) % D;
+      const int k = r * D + DD;
+      compute(stage[k & 1]);
+      store_lds(stage[(k + 1) & 1], std::integral_constant<int, NEXT>{});
+      if constexpr (!(SKIP & 8)) load_global(clamp_ks(k + 1 + D), std::integral_constant<int, NEXT>{});
+      __syncthreads();
+    });
   }
+  // the K-steps left over when their number is not a multiple of D (at most D - 1; no more loads are needed)
+  static_for<0, D - 1>([&](auto d) {
+    constexpr int DD = decltype(d)::value;
+    const int k = rounds * D + DD;
+    if (k < ksteps) {
+      compute(stage[k & 1]);
+      store_lds(stage[(k + 1) & 1], std::integral_constant<int, (DD + 1) % D>{});
+      __syncthreads();
+    }
+  });
 #pragma unroll
-  for (int mt = 0; mt < 4; ++mt)
+  for (int mt = 0; mt < kGemmMT; ++mt)
 #pragma unroll
-    for (int nt = 0; nt < 4; ++nt) {
+    for (int nt = 0; nt < kGemmNT; ++nt) {
       const int n = n0 + wn * 64 + nt * 16 + i;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int m = m0 + wm * 64 + mt * 16 + 4 * g + j;
+        const int m = m0 + wm * 128 + mt * 16 + 4 * g + j;
         if (m < M && n < N) c[(int64_t)m * ldc + n] = acc[mt][nt][j];
       }
     }
@@ -321,8 +377,17 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
   if (M > 64) {
     const int64_t m_tiles = (M + kGemmBM - 1) / kGemmBM, n_tiles = (N + kGemmBN - 1) / kGemmBN;
     if (m_tiles * n_tiles > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(gemm_ss_fp4_tiled_kernel, dim3((unsigned)(m_tiles * n_tiles)), dim3(256), 0, stream, a_codes, a_scales,
-                       w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles);
+    // 2 stages x 49.5 KB: above the 64 KB a kernel gets by default, so the dynamic size is requested explicitly
+    constexpr int kSmem = 2 * (int)sizeof(GemmStage);
+    static bool attr_set = false;
+    if (!attr_set) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ss_fp4_tiled_kernel<0>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) != hipSuccess)
+        return MX_ERR_LAUNCH;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(gemm_ss_fp4_tiled_kernel<0>, dim3((unsigned)(m_tiles * n_tiles)), dim3(256), kSmem, stream, a_codes,
+                       a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles);
     return hipGetLastError() == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
   }
   const unsigned grid = (unsigned)((N + 16 * kSmallmNT - 1) / (16 * kSmallmNT));
