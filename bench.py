@@ -163,6 +163,13 @@ def main():
             m, _, _ = time_region(torch, mx.SsBatch(a_views, fa, f2, v2, ws).run, steps2, 2)
             rows["ss_e4m3_%s" % tgt] = row(ss_bytes(nblocks, 8, 6), m)
             del c2, s2, v2
+        # every lower MXFP format from ONE pass over the anchor (read once, three targets written)
+        trip = [alloc_targets(torch, mx, a_views, t) for t in ("e3m2", "e2m3", "e2m1")]
+        tv = [[trip[q][2][i] for q in range(3)] for i in range(len(a_views))]
+        b3 = mx.SsBatch(a_views, fa, [mx.make_format(t) for t in ("e3m2", "e2m3", "e2m1")], tv, ws)
+        m, _, _ = time_region(torch, b3.run, steps2, 2)
+        rows["ss_e4m3_to_e3m2_e2m3_e2m1_one_pass"] = row(nblocks * (32 + 1 + 24 + 24 + 16 + 3), m)
+        del trip, tv, b3
         del t_codes, t_scales, t_views, batch
         torch.cuda.empty_cache()
         # MXINT8 anchor -> MXINT6 / MXINT4: the anchor arena is re-quantized in place of the FP8 one

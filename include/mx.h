@@ -124,6 +124,19 @@ mx_status_t mx_slice_and_scale_batched(const mx_format_t* fa, const mx_format_t*
                                        const mx_packed_t* anchors, const mx_packed_t* targets,
                                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* Several targets from one pass over the anchor (the "convert the anchor to every lower format" workload of
+ * Sec. 3.5 "Inference"): the anchor codes and scales are read once and n_targets (1..3) packed tensors are written,
+ * each exactly what mx_slice_and_scale gives for its format.  fts / targets: host arrays of n_targets entries, the
+ * formats in increasing mx_elem_t order and with one rounding mode.  Sets with a kernel: any single target;
+ * {INT6, INT4}; {E3M2, E2M3, E2M1} and its pairs.  MX_ERR_UNSUPPORTED for other sets.
+ * The batched form takes targets[i * n_targets + q] = target q of tensor i; workspace as for
+ * mx_slice_and_scale_batched. */
+mx_status_t mx_slice_and_scale_multi(const mx_format_t* fa, const mx_packed_t* anchor, int32_t n_targets,
+                                     const mx_format_t* fts, const mx_packed_t* targets, void* stream);
+mx_status_t mx_slice_and_scale_multi_batched(const mx_format_t* fa, int32_t n_targets, const mx_format_t* fts, int32_t n,
+                                             const mx_packed_t* anchors, const mx_packed_t* targets, void* workspace,
+                                             size_t workspace_bytes, void* stream);
+
 /* Fake-quant of the QAT forward pass.  anchor == NULL: dst = DQ(Q_target(src)) (Sec. 3.2).
  * anchor != NULL: dst = DQ(Q_{A->t}(Q_A(src))) (Eq. (7)).  src and dst have the same shape;
  * dst may be src itself (in place) but must not partially overlap it.  Nothing but dst is

@@ -10,7 +10,7 @@ import ctypes
 from . import binding
 from .binding import ELEMS, MxError, make_format
 
-__all__ = ["mx_quantize", "mx_slice_and_scale", "mx_slice_and_scale_batched", "mx_fake_quant", "mx_dequant",
+__all__ = ["mx_quantize", "mx_slice_and_scale", "mx_slice_and_scale_batched", "mx_slice_and_scale_multi", "mx_fake_quant", "mx_dequant",
            "mx_gemm_ss_fp4", "mx_packed_bytes", "mx_elem_bits", "mx_elem_emax", "MxFakeQuantSTE", "ELEMS", "MxError", "make_format",
            "packed_shape", "SsBatch"]
 
@@ -107,6 +107,22 @@ def mx_slice_and_scale(codes, scales, fa, ft, out_codes=None, out_scales=None):
     return out_codes, out_scales
 
 
+def mx_slice_and_scale_multi(codes, scales, fa, fts, outs=None):
+    """Several targets from one pass over the anchor; returns [(codes, scales)] in the order of fts."""
+    torch = _torch()
+    L = binding.lib()
+    nb = scales.numel()
+    if outs is None:
+        outs = [(torch.empty(tuple(scales.shape) + (f.block * L.mx_elem_bits(f.elem) // 8,), dtype=torch.uint8,
+                             device=codes.device), torch.empty_like(scales)) for f in fts]
+    a = _packed(codes, scales, 1, nb)
+    F = (binding.MxFormat * len(fts))(*fts)
+    T = (binding.MxPacked * len(fts))(*[_packed(c, s, 1, nb) for c, s in outs])
+    binding.check(L.mx_slice_and_scale_multi(ctypes.byref(fa), ctypes.byref(a), len(fts), F, T, _stream(codes)),
+                  "mx_slice_and_scale_multi")
+    return outs
+
+
 def mx_slice_and_scale_batched(anchors, fa, ft, targets=None, workspace=None):
     """One launch over a list of (codes, scales) anchors (a checkpoint).  Returns the target list."""
     torch = _torch()
@@ -132,32 +148,38 @@ def mx_slice_and_scale_batched(anchors, fa, ft, targets=None, workspace=None):
 
 class SsBatch:
     """A batched Slice-and-Scale call with its descriptor arrays marshalled once (a checkpoint's
-    layout is static): `run()` is then a single C call."""
+    layout is static): `run()` is then a single C call.  `ft` is one target format, or a list of
+    formats (increasing element order) that are all produced from one pass over the anchors; `targets`
+    is then a list, per anchor tensor, of one (codes, scales) pair per format."""
 
     def __init__(self, anchors, fa, ft, targets=None, workspace=None):
         torch = _torch()
         L = binding.lib()
         n = len(anchors)
-        bb = ft.block * L.mx_elem_bits(ft.elem) // 8
+        self.multi = isinstance(ft, (list, tuple))
+        fts = list(ft) if self.multi else [ft]
         if targets is None:
-            targets = [(torch.empty(tuple(s.shape) + (bb,), dtype=torch.uint8, device=c.device), torch.empty_like(s))
-                       for c, s in anchors]
+            targets = [[(torch.empty(tuple(s.shape) + (f.block * L.mx_elem_bits(f.elem) // 8,), dtype=torch.uint8,
+                                     device=c.device), torch.empty_like(s)) for f in fts] for c, s in anchors]
+        elif not self.multi:
+            targets = [[t] for t in targets]
         if workspace is None:
             need = L.mx_slice_and_scale_batched_workspace(n, sum(s.numel() for _, s in anchors))
             workspace = torch.empty(max(16, need), dtype=torch.uint8, device=anchors[0][0].device)
         self.anchors, self.targets, self.workspace = anchors, targets, workspace     # keep the tensors alive
-        self.fa, self.ft, self.n = fa, ft, n
+        self.fa, self.n, self.nt = fa, n, len(fts)
+        self._F = (binding.MxFormat * len(fts))(*fts)
         self._A = (binding.MxPacked * n)(*[_packed(c, s, 1, s.numel()) for c, s in anchors])
-        self._T = (binding.MxPacked * n)(*[_packed(c, s, 1, s.numel()) for c, s in targets])
+        self._T = (binding.MxPacked * (n * len(fts)))(*[_packed(c, s, 1, s.numel()) for row in targets for c, s in row])
         self._dev = anchors[0][0].device
 
     def run(self):
         torch = _torch()
         stream = ctypes.c_void_p(torch.cuda.current_stream(self._dev).cuda_stream)
-        binding.check(binding.lib().mx_slice_and_scale_batched(
-            ctypes.byref(self.fa), ctypes.byref(self.ft), self.n, self._A, self._T,
-            ctypes.c_void_p(self.workspace.data_ptr()), self.workspace.numel(), stream), "mx_slice_and_scale_batched")
-        return self.targets
+        binding.check(binding.lib().mx_slice_and_scale_multi_batched(
+            ctypes.byref(self.fa), self.nt, self._F, self.n, self._A, self._T,
+            ctypes.c_void_p(self.workspace.data_ptr()), self.workspace.numel(), stream), "mx_slice_and_scale_multi_batched")
+        return self.targets if self.multi else [row[0] for row in self.targets]
 
 
 def mx_fake_quant(src, target, anchor=None, out=None):

@@ -123,19 +123,51 @@ mx_status_t mx_quantize(const mx_format_t* f, const mx_dense_t* src, const mx_pa
   return mx::quantize_launch((int)f->elem, f->axis, (int)f->round, s, dst->codes, dst->scales, static_cast<hipStream_t>(stream));
 }
 
+// Validate an anchor format with n target formats; fill the launch's target list.
+static mx_status_t check_ss_targets(const mx_format_t* fa, int32_t n_targets, const mx_format_t* fts, mx::SsTargets* tg,
+                                    bool* hw) {
+  if (!fts) return MX_ERR_NULL;
+  if (n_targets < 1 || n_targets > mx::kSsMaxTargets) return MX_ERR_UNSUPPORTED;
+  tg->n = n_targets;
+  *hw = true;
+  for (int q = 0; q < mx::kSsMaxTargets; ++q) { tg->elem[q] = -1; tg->bits[q] = 0; }
+  for (int32_t q = 0; q < n_targets; ++q) {
+    ElemInfo ia, it;
+    mx_status_t st = check_ss_pair(fa, &fts[q], &ia, &it);
+    if (st != MX_OK) return st;
+    if (q > 0 && (int)fts[q].elem <= (int)fts[q - 1].elem) return MX_ERR_UNSUPPORTED;   // increasing enum order
+    if (fts[q].round != fts[0].round) return MX_ERR_FORMAT;
+    tg->elem[q] = (int)fts[q].elem;
+    tg->bits[q] = it.bits;
+    *hw = *hw && hw_tie(it, fts[q].round);
+  }
+  return MX_OK;
+}
+
+mx_status_t mx_slice_and_scale_multi(const mx_format_t* fa, const mx_packed_t* anchor, int32_t n_targets,
+                                     const mx_format_t* fts, const mx_packed_t* targets, void* stream) {
+  mx::SsTargets tg;
+  bool hw;
+  mx_status_t st = check_ss_targets(fa, n_targets, fts, &tg, &hw);
+  if (st != MX_OK) return st;
+  if (!targets) return MX_ERR_NULL;
+  if ((st = check_packed(anchor)) != MX_OK) return st;
+  int64_t nb = anchor->outer * anchor->nblocks;
+  mx::SsTensor t{};
+  t.codes_h = anchor->codes; t.scales_h = anchor->scales; t.nblocks = nb;
+  for (int32_t q = 0; q < n_targets; ++q) {
+    if ((st = check_packed(&targets[q])) != MX_OK) return st;
+    if (nb != targets[q].outer * targets[q].nblocks) return MX_ERR_SHAPE;
+    t.codes_l[q] = targets[q].codes; t.scales_l[q] = targets[q].scales;
+  }
+  if (nb == 0) return MX_OK;
+  return mx::ss_launch_one((int)fa->elem, tg, hw, t, (int)fts[0].round, static_cast<hipStream_t>(stream));
+}
+
 mx_status_t mx_slice_and_scale(const mx_format_t* fa, const mx_packed_t* anchor, const mx_format_t* ft,
                                const mx_packed_t* target, void* stream) {
-  ElemInfo ia, it;
-  mx_status_t st = check_ss_pair(fa, ft, &ia, &it);
-  if (st != MX_OK) return st;
-  if ((st = check_packed(anchor)) != MX_OK) return st;
-  if ((st = check_packed(target)) != MX_OK) return st;
-  int64_t nb = anchor->outer * anchor->nblocks;
-  if (nb != target->outer * target->nblocks) return MX_ERR_SHAPE;
-  if (nb == 0) return MX_OK;
-  mx::SsTensor t{anchor->codes, anchor->scales, target->codes, target->scales, nb, 0, 0};
-  return mx::ss_launch_one((int)fa->elem, (int)ft->elem, hw_tie(it, ft->round), t, (int)ft->round,
-                           static_cast<hipStream_t>(stream));
+  if (!ft) return MX_ERR_NULL;
+  return mx_slice_and_scale_multi(fa, anchor, 1, ft, target, stream);
 }
 
 size_t mx_slice_and_scale_batched_workspace(int32_t n, int64_t total_blocks) {
@@ -143,10 +175,12 @@ size_t mx_slice_and_scale_batched_workspace(int32_t n, int64_t total_blocks) {
   return mx::ss_workspace_bytes(n, total_blocks);
 }
 
-mx_status_t mx_slice_and_scale_batched(const mx_format_t* fa, const mx_format_t* ft, int32_t n, const mx_packed_t* anchors,
-                                       const mx_packed_t* targets, void* workspace, size_t workspace_bytes, void* stream) {
-  ElemInfo ia, it;
-  mx_status_t st = check_ss_pair(fa, ft, &ia, &it);
+mx_status_t mx_slice_and_scale_multi_batched(const mx_format_t* fa, int32_t n_targets, const mx_format_t* fts, int32_t n,
+                                             const mx_packed_t* anchors, const mx_packed_t* targets, void* workspace,
+                                             size_t workspace_bytes, void* stream) {
+  mx::SsTargets tg;
+  bool hw;
+  mx_status_t st = check_ss_targets(fa, n_targets, fts, &tg, &hw);
   if (st != MX_OK) return st;
   if (n < 0) return MX_ERR_SHAPE;
   if (n == 0) return MX_OK;
@@ -155,13 +189,25 @@ mx_status_t mx_slice_and_scale_batched(const mx_format_t* fa, const mx_format_t*
   std::vector<mx::SsTensor> t((size_t)n);
   for (int32_t i = 0; i < n; ++i) {
     if ((st = check_packed(&anchors[i])) != MX_OK) return st;
-    if ((st = check_packed(&targets[i])) != MX_OK) return st;
     int64_t nb = anchors[i].outer * anchors[i].nblocks;
-    if (nb != targets[i].outer * targets[i].nblocks) return MX_ERR_SHAPE;
-    t[(size_t)i] = mx::SsTensor{anchors[i].codes, anchors[i].scales, targets[i].codes, targets[i].scales, nb, 0, 0};
+    mx::SsTensor d{};
+    d.codes_h = anchors[i].codes; d.scales_h = anchors[i].scales; d.nblocks = nb;
+    for (int32_t q = 0; q < n_targets; ++q) {
+      const mx_packed_t* tq = &targets[(size_t)i * n_targets + q];
+      if ((st = check_packed(tq)) != MX_OK) return st;
+      if (nb != tq->outer * tq->nblocks) return MX_ERR_SHAPE;
+      d.codes_l[q] = tq->codes; d.scales_l[q] = tq->scales;
+    }
+    t[(size_t)i] = d;
   }
-  return mx::ss_launch_many((int)fa->elem, (int)ft->elem, it.bits, hw_tie(it, ft->round), n, t.data(), workspace,
-                            workspace_bytes, (int)ft->round, static_cast<hipStream_t>(stream));
+  return mx::ss_launch_many((int)fa->elem, tg, hw, n, t.data(), workspace, workspace_bytes, (int)fts[0].round,
+                            static_cast<hipStream_t>(stream));
+}
+
+mx_status_t mx_slice_and_scale_batched(const mx_format_t* fa, const mx_format_t* ft, int32_t n, const mx_packed_t* anchors,
+                                       const mx_packed_t* targets, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!ft) return MX_ERR_NULL;
+  return mx_slice_and_scale_multi_batched(fa, 1, ft, n, anchors, targets, workspace, workspace_bytes, stream);
 }
 
 mx_status_t mx_fake_quant(const mx_format_t* target, const mx_format_t* anchor, const mx_dense_t* src, const mx_dense_t* dst,

@@ -9,13 +9,15 @@
 
 namespace mx {
 
-// One tensor of a Slice-and-Scale launch (device pointers).  seg_begin / seg_scale are filled in
-// by the batched launcher: first segment of the tensor's code part and of its scale part.
+// One tensor of a Slice-and-Scale launch (device pointers): one anchor, up to kSsMaxTargets targets
+// converted in the same pass.  seg_begin / seg_scale are filled in by the batched launcher: first
+// segment of the tensor's code part and of its scale part.
+constexpr int kSsMaxTargets = 3;
 struct SsTensor {
   const void* codes_h;
   const uint8_t* scales_h;
-  void* codes_l;
-  uint8_t* scales_l;
+  void* codes_l[kSsMaxTargets];
+  uint8_t* scales_l[kSsMaxTargets];
   int64_t nblocks;
   int64_t seg_begin;
   int64_t seg_scale;
@@ -27,22 +29,30 @@ constexpr int kSsSegWgs = 128;     // workgroups per segment of a batched launch
 // One segment of a batched launch: kind 0 = `count` code pieces, kind 1 = `count` scale bytes.
 struct SsSegment {
   const void* in;
-  void* out;
+  void* out[kSsMaxTargets];
   int64_t count;
   int32_t kind;
   int32_t pad;
+  int64_t pad2[2];                 // 64 bytes: one descriptor per scalar cache line
 };
 
-constexpr int kSsTableChunk = 64;  // descriptors per table-writer launch (kernel arguments stay under 4 KiB)
+constexpr int kSsTableChunk = 40;  // descriptors per table-writer launch (kernel arguments stay under 4 KiB)
 struct SsTableChunk {
   SsTensor t[kSsTableChunk];
   int base, count;
 };
 
-mx_status_t ss_launch_one(int anchor, int target, bool hw, const SsTensor& t, int tie, hipStream_t stream);
+// The target list of one launch: element ids in increasing enum order, -1 = unused slot.
+struct SsTargets {
+  int elem[kSsMaxTargets];
+  int bits[kSsMaxTargets];
+  int n;
+};
+
+mx_status_t ss_launch_one(int anchor, const SsTargets& tg, bool hw, const SsTensor& t, int tie, hipStream_t stream);
 size_t ss_workspace_bytes(int n, int64_t total_blocks);
-mx_status_t ss_launch_many(int anchor, int target, int target_bits, bool hw, int n, const SsTensor* h_tensors,
-                           void* workspace, size_t workspace_bytes, int tie, hipStream_t stream);
+mx_status_t ss_launch_many(int anchor, const SsTargets& tg, bool hw, int n, const SsTensor* h_tensors, void* workspace,
+                           size_t workspace_bytes, int tie, hipStream_t stream);
 
 // Dense <-> packed kernels.  `dense` / `ld` in elements of dtype; outer / nblocks as in mx.h.
 struct DenseArg {

@@ -72,71 +72,93 @@ __device__ __forceinline__ void slice_piece(const uint32_t (&in)[CPL / 4], uint3
   }
 }
 
-// codes per lane: half a block when that ends on a dword boundary, else a whole block
-template <int TARGET>
-struct Piece { static constexpr int cpl = (Elem<TARGET>::bits % 2 == 0) ? 16 : 32; };
+// codes per lane: half a block when every target width ends on a dword boundary there, else a whole block
+template <int... TARGETS>
+struct Piece { static constexpr int cpl = (((Elem<TARGETS>::bits % 2 == 0) && ...)) ? 16 : 32; };
 
-// ---- piece p of a run of pieces: load, convert, store
-template <int ANCHOR, int TARGET, bool HW>
-__device__ __forceinline__ void ss_piece(const void* __restrict__ in, void* __restrict__ out, int64_t p, int tie) {
-  constexpr int CPL = Piece<TARGET>::cpl, NIN = CPL / 4, NOUT = CPL * Elem<TARGET>::bits / 32;
-  uint32_t x[NIN], y[NOUT];
+// ---- piece p of a run of pieces: load once, convert and store for every target of the launch
+template <int ANCHOR, bool HW, int... TARGETS>
+__device__ __forceinline__ void ss_piece(const void* __restrict__ in, void* const (&out)[kSsMaxTargets], int64_t p, int tie) {
+  constexpr int CPL = Piece<TARGETS...>::cpl, NIN = CPL / 4;
+  uint32_t x[NIN];
   const u32x4* src = reinterpret_cast<const u32x4*>(in) + p * (NIN / 4);
 #pragma unroll
   for (int i = 0; i < NIN / 4; ++i) {
     u32x4 t = __builtin_nontemporal_load(src + i);
     x[4 * i] = t.x; x[4 * i + 1] = t.y; x[4 * i + 2] = t.z; x[4 * i + 3] = t.w;
   }
-  slice_piece<ANCHOR, TARGET, HW, CPL>(x, y, tie);
-  store_dwords<NOUT>(reinterpret_cast<uint32_t*>(out) + p * NOUT, y);
+  int slot = 0;
+  ([&] {
+    constexpr int NOUT = CPL * Elem<TARGETS>::bits / 32;
+    uint32_t y[NOUT];
+    slice_piece<ANCHOR, TARGETS, HW && Elem<TARGETS>::hw != HW_NONE, CPL>(x, y, tie);
+    store_dwords<NOUT>(reinterpret_cast<uint32_t*>(out[slot]) + p * NOUT, y);
+    ++slot;
+  }(), ...);
 }
 
-// ---- 16 scale bytes per lane
-template <int DE>
-__device__ __forceinline__ void ss_scale_chunk(const uint8_t* __restrict__ sh, uint8_t* __restrict__ sl, int64_t chunk,
+// ---- 16 scale bytes per lane, for every target
+template <int ANCHOR, int... TARGETS>
+__device__ __forceinline__ void ss_scale_chunk(const uint8_t* __restrict__ sh, void* const (&out)[kSsMaxTargets], int64_t chunk,
                                                int64_t nbytes) {
   int64_t i0 = chunk * 16;
   if (i0 + 16 <= nbytes) {
     u32x4 v = *reinterpret_cast<const u32x4*>(sh + i0);
-    v.x = scale_add_x4(v.x, DE); v.y = scale_add_x4(v.y, DE); v.z = scale_add_x4(v.z, DE); v.w = scale_add_x4(v.w, DE);
-    *reinterpret_cast<u32x4*>(sl + i0) = v;
+    int slot = 0;
+    ([&] {
+      constexpr uint32_t DE = Elem<ANCHOR>::emax - Elem<TARGETS>::emax;
+      u32x4 r = {scale_add_x4(v.x, DE), scale_add_x4(v.y, DE), scale_add_x4(v.z, DE), scale_add_x4(v.w, DE)};
+      *reinterpret_cast<u32x4*>(static_cast<uint8_t*>(out[slot]) + i0) = r;
+      ++slot;
+    }(), ...);
   } else {
     for (int64_t i = i0; i < nbytes; ++i) {
       uint32_t b = sh[i];
-      sl[i] = (uint8_t)(b == 255u ? 255u : (b + DE > 254u ? 254u : b + DE));
+      int slot = 0;
+      ([&] {
+        constexpr uint32_t DE = Elem<ANCHOR>::emax - Elem<TARGETS>::emax;
+        static_cast<uint8_t*>(out[slot])[i] = (uint8_t)(b == 255u ? 255u : (b + DE > 254u ? 254u : b + DE));
+        ++slot;
+      }(), ...);
     }
   }
 }
 
+// kernel-argument form of one tensor (the flat launch needs no table)
+struct SsFlatArgs {
+  const void* codes_h;
+  const uint8_t* scales_h;
+  void* codes_l[kSsMaxTargets];
+  void* scales_l[kSsMaxTargets];
+  int64_t nblocks;
+  int64_t code_wgs;
+};
+
 // ---- one tensor: workgroups [0, code_wgs) convert pieces, the rest scale bytes
-template <int ANCHOR, int TARGET, bool HW>
-__global__ __launch_bounds__(kSsLanes) void ss_kernel(const void* __restrict__ ch, const uint8_t* __restrict__ sh,
-                                                      void* __restrict__ cl, uint8_t* __restrict__ sl, int64_t nblocks,
-                                                      int64_t code_wgs, int tie) {
-  constexpr int DE = Elem<ANCHOR>::emax - Elem<TARGET>::emax;
-  constexpr int CPL = Piece<TARGET>::cpl;
+template <int ANCHOR, bool HW, int... TARGETS>
+__global__ __launch_bounds__(kSsLanes) void ss_kernel(SsFlatArgs a, int tie) {
+  constexpr int CPL = Piece<TARGETS...>::cpl;
   int64_t wg = blockIdx.x;
-  if (wg < code_wgs) {
+  if (wg < a.code_wgs) {
     int64_t p = wg * kSsLanes + threadIdx.x;
-    if (p < nblocks * (32 / CPL)) ss_piece<ANCHOR, TARGET, HW>(ch, cl, p, tie);
+    if (p < a.nblocks * (32 / CPL)) ss_piece<ANCHOR, HW, TARGETS...>(a.codes_h, a.codes_l, p, tie);
   } else {
-    int64_t c = (wg - code_wgs) * kSsLanes + threadIdx.x;
-    if (c * 16 < nblocks) ss_scale_chunk<DE>(sh, sl, c, nblocks);
+    int64_t c = (wg - a.code_wgs) * kSsLanes + threadIdx.x;
+    if (c * 16 < a.nblocks) ss_scale_chunk<ANCHOR, TARGETS...>(a.scales_h, a.scales_l, c, a.nblocks);
   }
 }
 
 // ---- many tensors in one launch.  The work is cut into fixed-size segments (kSsSegWgs
 // workgroups each), so a workgroup finds its segment with a shift and needs ONE dependent
-// scalar load (the 32-byte segment descriptor) before its data load.
-template <int ANCHOR, int TARGET, bool HW>
+// scalar load (the 64-byte segment descriptor) before its data load.
+template <int ANCHOR, bool HW, int... TARGETS>
 __global__ __launch_bounds__(kSsLanes) void ss_batched_kernel(const SsSegment* __restrict__ segs, int tie) {
-  constexpr int DE = Elem<ANCHOR>::emax - Elem<TARGET>::emax;
   const SsSegment s = segs[blockIdx.x / kSsSegWgs];
   int64_t item = (int64_t)(blockIdx.x % kSsSegWgs) * kSsLanes + threadIdx.x;
   if (s.kind == 0) {
-    if (item < s.count) ss_piece<ANCHOR, TARGET, HW>(s.in, s.out, item, tie);
+    if (item < s.count) ss_piece<ANCHOR, HW, TARGETS...>(s.in, s.out, item, tie);
   } else {
-    if (item * 16 < s.count) ss_scale_chunk<DE>(static_cast<const uint8_t*>(s.in), static_cast<uint8_t*>(s.out), item, s.count);
+    if (item * 16 < s.count) ss_scale_chunk<ANCHOR, TARGETS...>(static_cast<const uint8_t*>(s.in), s.out, item, s.count);
   }
 }
 
@@ -146,9 +168,11 @@ __global__ void ss_table_kernel(SsTableChunk chunk, SsTensor* __restrict__ table
   if (i < chunk.count) table[chunk.base + i] = chunk.t[i];
 }
 
+struct SsPieceBytes { int out[kSsMaxTargets]; int n; int cpl; };
+
 // Segment table from the tensor table: thread s describes segment s.
 __global__ void ss_segments_kernel(const SsTensor* __restrict__ tensors, int n, SsSegment* __restrict__ segs, int64_t nseg,
-                                   int cpl, int out_bytes_per_piece) {
+                                   SsPieceBytes pb) {
   int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (s >= nseg) return;
   int lo = 0, hi = n;  // tensors[lo].seg_begin <= s < tensors[hi].seg_begin (hi == n: end)
@@ -158,19 +182,21 @@ __global__ void ss_segments_kernel(const SsTensor* __restrict__ tensors, int n, 
   }
   const SsTensor t = tensors[lo];
   SsSegment d;
+  d.pad = 0; d.pad2[0] = d.pad2[1] = 0;
   constexpr int64_t ITEMS = (int64_t)kSsSegWgs * kSsLanes;  // pieces, or 16-byte scale chunks, per segment
   if (s < t.seg_scale) {
     int64_t j = s - t.seg_begin;
-    int64_t pieces = t.nblocks * (32 / cpl) - j * ITEMS;
-    d.in = static_cast<const char*>(t.codes_h) + j * ITEMS * cpl;
-    d.out = static_cast<char*>(t.codes_l) + j * ITEMS * out_bytes_per_piece;
+    int64_t pieces = t.nblocks * (32 / pb.cpl) - j * ITEMS;
+    d.in = static_cast<const char*>(t.codes_h) + j * ITEMS * pb.cpl;
+    for (int q = 0; q < kSsMaxTargets; ++q)
+      d.out[q] = q < pb.n ? static_cast<char*>(t.codes_l[q]) + j * ITEMS * pb.out[q] : nullptr;
     d.count = pieces < ITEMS ? pieces : ITEMS;
     d.kind = 0;
   } else {
     int64_t j = s - t.seg_scale;
     int64_t bytes = t.nblocks - j * ITEMS * 16;
     d.in = t.scales_h + j * ITEMS * 16;
-    d.out = t.scales_l + j * ITEMS * 16;
+    for (int q = 0; q < kSsMaxTargets; ++q) d.out[q] = q < pb.n ? t.scales_l[q] + j * ITEMS * 16 : nullptr;
     d.count = bytes < ITEMS * 16 ? bytes : ITEMS * 16;
     d.kind = 1;
   }
@@ -180,31 +206,44 @@ __global__ void ss_segments_kernel(const SsTensor* __restrict__ tensors, int n, 
 // ---- host side -----------------------------------------------------------------------------
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-template <int ANCHOR, int TARGET, bool HW>
+static inline int ss_cpl(const SsTargets& tg) {
+  for (int q = 0; q < tg.n; ++q)
+    if (tg.bits[q] % 2) return 32;
+  return 16;
+}
+
+template <int ANCHOR, bool HW, int... TARGETS>
 static mx_status_t launch_ss(const SsTensor& t, int tie, hipStream_t stream) {
-  constexpr int CPL = Piece<TARGET>::cpl;
+  constexpr int CPL = Piece<TARGETS...>::cpl;
   int64_t cw = ceil_div(t.nblocks * (32 / CPL), kSsLanes), sw = ceil_div(ceil_div(t.nblocks, 16), kSsLanes);
   if (cw + sw == 0) return MX_OK;
   if (cw + sw > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL((ss_kernel<ANCHOR, TARGET, HW>), dim3((unsigned)(cw + sw)), dim3(kSsLanes), 0, stream, t.codes_h,
-                     t.scales_h, t.codes_l, t.scales_l, t.nblocks, cw, tie);
+  SsFlatArgs a;
+  a.codes_h = t.codes_h; a.scales_h = t.scales_h; a.nblocks = t.nblocks; a.code_wgs = cw;
+  for (int q = 0; q < kSsMaxTargets; ++q) { a.codes_l[q] = t.codes_l[q]; a.scales_l[q] = t.scales_l[q]; }
+  hipLaunchKernelGGL((ss_kernel<ANCHOR, HW, TARGETS...>), dim3((unsigned)(cw + sw)), dim3(kSsLanes), 0, stream, a, tie);
   return hipGetLastError() == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
 }
 
-template <int ANCHOR, int TARGET, bool HW>
+template <int ANCHOR, bool HW, int... TARGETS>
 static mx_status_t launch_ss_batched(const SsSegment* segs, int64_t nseg, int tie, hipStream_t stream) {
-  hipLaunchKernelGGL((ss_batched_kernel<ANCHOR, TARGET, HW>), dim3((unsigned)(nseg * kSsSegWgs)), dim3(kSsLanes), 0, stream,
+  hipLaunchKernelGGL((ss_batched_kernel<ANCHOR, HW, TARGETS...>), dim3((unsigned)(nseg * kSsSegWgs)), dim3(kSsLanes), 0, stream,
                      segs, tie);
   return hipGetLastError() == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
 }
 
-// Dispatch on (anchor, target, hw path) -> instantiated launcher.
+// Dispatch on (anchor, target list, hw path) -> instantiated launcher.  Single targets: every narrower format of
+// the family.  Several targets in one pass (the anchor is read once): the benchmark's "every lower format" sets.
 template <typename F>
-static mx_status_t ss_dispatch(int anchor, int target, bool hw, F&& f) {
-#define MX_SS_CASE(A, T)                                              \
-  if (anchor == A && target == T) {                                   \
-    if (hw && Elem<T>::hw != HW_NONE) return f.template operator()<A, T, true>(); \
-    return f.template operator()<A, T, false>();                      \
+static mx_status_t ss_dispatch(int anchor, const SsTargets& tg, bool hw, F&& f) {
+  const int t0 = tg.elem[0], t1 = tg.n > 1 ? tg.elem[1] : -1, t2 = tg.n > 2 ? tg.elem[2] : -1;
+#define MX_SS_CASE(A, ...)                                                   \
+  {                                                                          \
+    constexpr int want[] = {__VA_ARGS__, -1, -1};                            \
+    if (anchor == A && t0 == want[0] && t1 == want[1] && t2 == want[2]) {    \
+      if (hw) return f.template operator()<A, true, __VA_ARGS__>();          \
+      return f.template operator()<A, false, __VA_ARGS__>();                 \
+    }                                                                        \
   }
   MX_SS_CASE(MX_INT8, MX_INT7)
   MX_SS_CASE(MX_INT8, MX_INT6)
@@ -217,24 +256,31 @@ static mx_status_t ss_dispatch(int anchor, int target, bool hw, F&& f) {
   MX_SS_CASE(MX_FP8_E4M3, MX_FP6_E2M3)
   MX_SS_CASE(MX_FP8_E4M3, MX_FP5_E2M2)
   MX_SS_CASE(MX_FP8_E4M3, MX_FP4_E2M1)
+  MX_SS_CASE(MX_INT8, MX_INT6, MX_INT4)
+  MX_SS_CASE(MX_FP8_E4M3, MX_FP6_E3M2, MX_FP6_E2M3, MX_FP4_E2M1)
+  MX_SS_CASE(MX_FP8_E4M3, MX_FP6_E3M2, MX_FP4_E2M1)
+  MX_SS_CASE(MX_FP8_E4M3, MX_FP6_E2M3, MX_FP4_E2M1)
+  MX_SS_CASE(MX_FP8_E4M3, MX_FP6_E3M2, MX_FP6_E2M3)
 #undef MX_SS_CASE
   return MX_ERR_UNSUPPORTED;
 }
 
 struct SsOne {
   const SsTensor& t; int tie; hipStream_t stream;
-  template <int A, int T, bool HW> mx_status_t operator()() const { return launch_ss<A, T, HW>(t, tie, stream); }
+  template <int A, bool HW, int... T> mx_status_t operator()() const { return launch_ss<A, HW, T...>(t, tie, stream); }
 };
 struct SsMany {
   const SsSegment* segs; int64_t nseg; int tie; hipStream_t stream;
-  template <int A, int T, bool HW> mx_status_t operator()() const { return launch_ss_batched<A, T, HW>(segs, nseg, tie, stream); }
+  template <int A, bool HW, int... T> mx_status_t operator()() const { return launch_ss_batched<A, HW, T...>(segs, nseg, tie, stream); }
 };
 
-mx_status_t ss_launch_one(int anchor, int target, bool hw, const SsTensor& t, int tie, hipStream_t stream) {
-  return ss_dispatch(anchor, target, hw, SsOne{t, tie, stream});
-}
+struct SsProbe {   // "is there a kernel for this target list?" without launching anything
+  template <int A, bool HW, int... T> mx_status_t operator()() const { return MX_OK; }
+};
 
-static inline int ss_cpl(int target_bits) { return target_bits % 2 == 0 ? 16 : 32; }
+mx_status_t ss_launch_one(int anchor, const SsTargets& tg, bool hw, const SsTensor& t, int tie, hipStream_t stream) {
+  return ss_dispatch(anchor, tg, hw, SsOne{t, tie, stream});
+}
 
 // Segments a tensor of nblocks blocks needs: code segments, scale segments.
 static inline void ss_segments_of(int64_t nblocks, int cpl, int64_t* code_segs, int64_t* scale_segs) {
@@ -247,12 +293,12 @@ size_t ss_workspace_bytes(int n, int64_t total_blocks) {
   // bound over both piece sizes: every tensor rounds up by at most one code and one scale segment
   const int64_t items = (int64_t)kSsSegWgs * kSsLanes;
   int64_t segs = total_blocks * 2 / items + total_blocks / (16 * items) + 2 * (int64_t)n + 2;
-  return sizeof(SsTensor) * (size_t)n + sizeof(SsSegment) * (size_t)segs;
+  return (sizeof(SsTensor) * (size_t)n + 63) / 64 * 64 + sizeof(SsSegment) * (size_t)segs;
 }
 
-mx_status_t ss_launch_many(int anchor, int target, int target_bits, bool hw, int n, const SsTensor* h_tensors,
-                           void* workspace, size_t workspace_bytes, int tie, hipStream_t stream) {
-  const int cpl = ss_cpl(target_bits);
+mx_status_t ss_launch_many(int anchor, const SsTargets& tg, bool hw, int n, const SsTensor* h_tensors, void* workspace,
+                           size_t workspace_bytes, int tie, hipStream_t stream) {
+  const int cpl = ss_cpl(tg);
   // pass 1 on the host: segment ranges; nothing is launched before the sizes are known to fit
   int64_t nseg = 0;
   for (int i = 0; i < n; ++i) {
@@ -262,8 +308,13 @@ mx_status_t ss_launch_many(int anchor, int target, int target_bits, bool hw, int
   }
   if (nseg == 0) return MX_OK;
   if (nseg * kSsSegWgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-  size_t tb = sizeof(SsTensor) * (size_t)n;
+  size_t tb = (sizeof(SsTensor) * (size_t)n + 63) / 64 * 64;
   if (workspace_bytes < tb + sizeof(SsSegment) * (size_t)nseg) return MX_ERR_WORKSPACE;
+  // an unsupported target list must fail before anything is launched
+  {
+    mx_status_t st = ss_dispatch(anchor, tg, hw, SsProbe{});
+    if (st != MX_OK) return st;
+  }
   SsTensor* table = static_cast<SsTensor*>(workspace);
   SsSegment* segs = reinterpret_cast<SsSegment*>(static_cast<char*>(workspace) + tb);
   int64_t acc = 0;
@@ -280,13 +331,15 @@ mx_status_t ss_launch_many(int anchor, int target, int target_bits, bool hw, int
       acc += cs + ss;
       chunk.t[i] = t;
     }
-    hipLaunchKernelGGL(ss_table_kernel, dim3(1), dim3(kSsTableChunk), 0, stream, chunk, table);
+    hipLaunchKernelGGL(ss_table_kernel, dim3(1), dim3(64), 0, stream, chunk, table);
     if (hipGetLastError() != hipSuccess) return MX_ERR_LAUNCH;
   }
-  hipLaunchKernelGGL(ss_segments_kernel, dim3((unsigned)ceil_div(nseg, 256)), dim3(256), 0, stream, table, n, segs, nseg, cpl,
-                     cpl * target_bits / 8);
+  SsPieceBytes pb;
+  pb.n = tg.n; pb.cpl = cpl;
+  for (int q = 0; q < kSsMaxTargets; ++q) pb.out[q] = q < tg.n ? cpl * tg.bits[q] / 8 : 0;
+  hipLaunchKernelGGL(ss_segments_kernel, dim3((unsigned)ceil_div(nseg, 256)), dim3(256), 0, stream, table, n, segs, nseg, pb);
   if (hipGetLastError() != hipSuccess) return MX_ERR_LAUNCH;
-  return ss_dispatch(anchor, target, hw, SsMany{segs, nseg, tie, stream});
+  return ss_dispatch(anchor, tg, hw, SsMany{segs, nseg, tie, stream});
 }
 
 }  // namespace mx

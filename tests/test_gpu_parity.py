@@ -108,6 +108,54 @@ def test_slice_and_scale_batched(mx, oracle, anchor, target):
         assert np.array_equal(to_host(gc), wc), i
 
 
+MULTI_SETS = [("int8", ["int6", "int4"]), ("e4m3", ["e3m2", "e2m3", "e2m1"]), ("e4m3", ["e3m2", "e2m1"]),
+              ("e4m3", ["e2m3", "e2m1"]), ("e4m3", ["e3m2", "e2m3"])]
+
+
+@pytest.mark.parametrize("anchor,targets", MULTI_SETS)
+def test_slice_and_scale_multi_target(mx, oracle, anchor, targets):
+    # several targets from one pass over the anchor: each output is what the single conversion gives
+    fa = mx.make_format(anchor)
+    for nblocks, seed in ((1, 11), (33, 12), (8192 + 17, 13)):
+        codes = synth.random_bytes(seed, nblocks * 32).reshape(nblocks, 32)
+        scales = synth.random_bytes(seed + 100, nblocks)
+        outs = mx.mx_slice_and_scale_multi(to_gpu(codes), to_gpu(scales), fa, [mx.make_format(t) for t in targets])
+        for t, (gc, gs) in zip(targets, outs):
+            wc, ws = oracle.slice_and_scale(codes, scales, anchor, t)
+            assert np.array_equal(to_host(gs), ws), (t, nblocks)
+            assert np.array_equal(to_host(gc), wc), (t, nblocks)
+
+
+def test_slice_and_scale_multi_target_batched(mx, oracle):
+    import torch
+    sizes = [1, 33, 9000, 7, 4096, 300] * 9            # 54 tensors: more than one table chunk
+    anchors, host = [], []
+    for i, nb in enumerate(sizes):
+        codes = synth.random_bytes(700 + i, nb * 32).reshape(nb, 32)
+        scales = synth.random_bytes(1700 + i, nb)
+        anchors.append((to_gpu(codes), to_gpu(scales)))
+        host.append((codes, scales))
+    targets = ["e3m2", "e2m3", "e2m1"]
+    got = mx.SsBatch(anchors, mx.make_format("e4m3"), [mx.make_format(t) for t in targets]).run()
+    torch.cuda.synchronize()
+    for i, row in enumerate(got):
+        for t, (gc, gs) in zip(targets, row):
+            wc, ws = oracle.slice_and_scale(host[i][0], host[i][1], "e4m3", t)
+            assert np.array_equal(to_host(gs), ws), (i, t)
+            assert np.array_equal(to_host(gc), wc), (i, t)
+
+
+def test_slice_and_scale_multi_target_rejections(mx):
+    import torch
+    c = torch.zeros((4, 32), dtype=torch.uint8, device="cuda")
+    s = torch.zeros((4,), dtype=torch.uint8, device="cuda")
+    for anchor, targets in (("e4m3", ["e2m1", "e3m2"]),          # not in increasing element order
+                            ("int8", ["int6", "int5", "int4"]),  # a set without a kernel
+                            ("e4m3", ["e3m2", "int4"])):         # mixed families
+        with pytest.raises(mx.MxError):
+            mx.mx_slice_and_scale_multi(c, s, mx.make_format(anchor), [mx.make_format(t) for t in targets])
+
+
 # ------------------------------------------------------------------------------------ quantize
 def _quant_inputs(dtype):
     w1 = synth.config1_weight(seed=1001, rows=96, cols=1024 + 96)          # several tiles + ragged tail
