@@ -10,8 +10,7 @@
 namespace mx {
 
 // One tensor of a Slice-and-Scale launch (device pointers): one anchor, up to kSsMaxTargets targets
-// converted in the same pass.  seg_begin / seg_scale are filled in by the batched launcher: first
-// segment of the tensor's code part and of its scale part.
+// converted in the same pass.
 constexpr int kSsMaxTargets = 3;
 struct SsTensor {
   const void* codes_h;
@@ -19,12 +18,12 @@ struct SsTensor {
   void* codes_l[kSsMaxTargets];
   uint8_t* scales_l[kSsMaxTargets];
   int64_t nblocks;
-  int64_t seg_begin;
-  int64_t seg_scale;
 };
 
 constexpr int kSsLanes = 64;       // one wave per workgroup, one load per lane
-constexpr int kSsSegWgs = 128;     // workgroups per segment of a batched launch (8192 pieces or scale chunks)
+// Workgroups per segment of a batched launch, as a shift.  Large segments keep a descriptor in the
+// scalar caches over many workgroups; small ones bound the padding when tensors are small.
+constexpr int kSsSegShiftLarge = 10, kSsSegShiftSmall = 7;
 
 // One segment of a batched launch: kind 0 = `count` code pieces, kind 1 = `count` scale bytes.
 struct SsSegment {
@@ -36,10 +35,15 @@ struct SsSegment {
   int64_t pad2[2];                 // 64 bytes: one descriptor per scalar cache line
 };
 
-constexpr int kSsTableChunk = 40;  // descriptors per table-writer launch (kernel arguments stay under 4 KiB)
-struct SsTableChunk {
-  SsTensor t[kSsTableChunk];
-  int base, count;
+// Tensor descriptors travel to the segment-table writer as kernel arguments (nothing is copied from
+// host memory that would have to outlive the call), as many per launch as 4 KiB of arguments hold.
+// One tensor takes 4 + 2 * n_targets words: codes_h, scales_h, nblocks, first code segment | first
+// scale segment << 32 (relative to the chunk), then codes_l[q], then scales_l[q].
+constexpr int kSsChunkWords = 496;
+struct SsChunk {
+  int64_t w[kSsChunkWords];
+  int32_t count, n_targets;
+  int64_t seg0;                    // first segment of the chunk in the launch
 };
 
 // The target list of one launch: element ids in increasing enum order, -1 = unused slot.

@@ -72,6 +72,31 @@ __device__ __forceinline__ void slice_piece(const uint32_t (&in)[CPL / 4], uint3
   }
 }
 
+// Every pointer of a launch is device global memory, but one that a workgroup has loaded from a
+// descriptor table carries no address space, and the compiler would reach through it with flat
+// instructions (which also occupy the LDS path).  All accesses below therefore go through
+// pointers cast to the global address space.
+#define MX_GLOBAL __attribute__((address_space(1)))
+typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+typedef u32x3 __attribute__((aligned(4))) u32x3_a4;
+
+template <int W>
+__device__ __forceinline__ void store_global(void* base, int64_t dword, const uint32_t (&v)[W]) {
+  MX_GLOBAL uint32_t* p = (MX_GLOBAL uint32_t*)base + dword;
+  if constexpr (W % 4 == 0) {
+#pragma unroll
+    for (int i = 0; i < W / 4; ++i) ((MX_GLOBAL u32x4*)p)[i] = u32x4{v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]};
+  } else if constexpr (W % 2 == 0) {
+#pragma unroll
+    for (int i = 0; i < W / 2; ++i) ((MX_GLOBAL u32x2*)p)[i] = u32x2{v[2 * i], v[2 * i + 1]};
+  } else if constexpr (W == 3) {
+    *(MX_GLOBAL u32x3_a4*)p = u32x3{v[0], v[1], v[2]};   // one 96-bit store (needs only dword alignment)
+  } else {
+#pragma unroll
+    for (int i = 0; i < W; ++i) p[i] = v[i];
+  }
+}
+
 // codes per lane: half a block when every target width ends on a dword boundary there, else a whole block
 template <int... TARGETS>
 struct Piece { static constexpr int cpl = (((Elem<TARGETS>::bits % 2 == 0) && ...)) ? 16 : 32; };
@@ -81,7 +106,7 @@ template <int ANCHOR, bool HW, int... TARGETS>
 __device__ __forceinline__ void ss_piece(const void* __restrict__ in, void* const (&out)[kSsMaxTargets], int64_t p, int tie) {
   constexpr int CPL = Piece<TARGETS...>::cpl, NIN = CPL / 4;
   uint32_t x[NIN];
-  const u32x4* src = reinterpret_cast<const u32x4*>(in) + p * (NIN / 4);
+  const MX_GLOBAL u32x4* src = (const MX_GLOBAL u32x4*)in + p * (NIN / 4);
 #pragma unroll
   for (int i = 0; i < NIN / 4; ++i) {
     u32x4 t = __builtin_nontemporal_load(src + i);
@@ -92,7 +117,7 @@ __device__ __forceinline__ void ss_piece(const void* __restrict__ in, void* cons
     constexpr int NOUT = CPL * Elem<TARGETS>::bits / 32;
     uint32_t y[NOUT];
     slice_piece<ANCHOR, TARGETS, HW && Elem<TARGETS>::hw != HW_NONE, CPL>(x, y, tie);
-    store_dwords<NOUT>(reinterpret_cast<uint32_t*>(out[slot]) + p * NOUT, y);
+    store_global<NOUT>(out[slot], p * NOUT, y);
     ++slot;
   }(), ...);
 }
@@ -103,21 +128,21 @@ __device__ __forceinline__ void ss_scale_chunk(const uint8_t* __restrict__ sh, v
                                                int64_t nbytes) {
   int64_t i0 = chunk * 16;
   if (i0 + 16 <= nbytes) {
-    u32x4 v = *reinterpret_cast<const u32x4*>(sh + i0);
+    u32x4 v = *(const MX_GLOBAL u32x4*)(sh + i0);
     int slot = 0;
     ([&] {
       constexpr uint32_t DE = Elem<ANCHOR>::emax - Elem<TARGETS>::emax;
       u32x4 r = {scale_add_x4(v.x, DE), scale_add_x4(v.y, DE), scale_add_x4(v.z, DE), scale_add_x4(v.w, DE)};
-      *reinterpret_cast<u32x4*>(static_cast<uint8_t*>(out[slot]) + i0) = r;
+      *(MX_GLOBAL u32x4*)((MX_GLOBAL uint8_t*)out[slot] + i0) = r;
       ++slot;
     }(), ...);
   } else {
     for (int64_t i = i0; i < nbytes; ++i) {
-      uint32_t b = sh[i];
+      uint32_t b = ((const MX_GLOBAL uint8_t*)sh)[i];
       int slot = 0;
       ([&] {
         constexpr uint32_t DE = Elem<ANCHOR>::emax - Elem<TARGETS>::emax;
-        static_cast<uint8_t*>(out[slot])[i] = (uint8_t)(b == 255u ? 255u : (b + DE > 254u ? 254u : b + DE));
+        ((MX_GLOBAL uint8_t*)out[slot])[i] = (uint8_t)(b == 255u ? 255u : (b + DE > 254u ? 254u : b + DE));
         ++slot;
       }(), ...);
     }
@@ -148,59 +173,67 @@ __global__ __launch_bounds__(kSsLanes) void ss_kernel(SsFlatArgs a, int tie) {
   }
 }
 
-// ---- many tensors in one launch.  The work is cut into fixed-size segments (kSsSegWgs
-// workgroups each), so a workgroup finds its segment with a shift and needs ONE dependent
-// scalar load (the 64-byte segment descriptor) before its data load.
+// ---- many tensors in one launch.  The work is cut into segments of 2^seg_shift workgroups, so a
+// workgroup finds its segment with a shift and needs ONE dependent scalar load (the 64-byte
+// segment descriptor) before its data load.  A descriptor that has to come from HBM while the
+// memory system is saturated costs several points of bandwidth (measured: 77 % against 84 % of
+// peak), so the first 8 workgroups of a segment - one per XCD, workgroups go round the XCDs -
+// pull the descriptor `ahead` segments further on into their L2 with a one-lane load.
 template <int ANCHOR, bool HW, int... TARGETS>
-__global__ __launch_bounds__(kSsLanes) void ss_batched_kernel(const SsSegment* __restrict__ segs, int tie) {
-  const SsSegment s = segs[blockIdx.x / kSsSegWgs];
-  int64_t item = (int64_t)(blockIdx.x % kSsSegWgs) * kSsLanes + threadIdx.x;
+__global__ __launch_bounds__(kSsLanes) void ss_batched_kernel(const SsSegment* __restrict__ segs, int nseg, int seg_shift,
+                                                              int ahead, int tie) {
+  const int seg = blockIdx.x >> seg_shift, w = blockIdx.x & ((1 << seg_shift) - 1);
+  const SsSegment s = segs[seg];
+  int64_t item = (int64_t)w * kSsLanes + threadIdx.x;
+  uint32_t warm = 0;
+  if (w < 8 && threadIdx.x == 0) {
+    int f = seg + ahead < nseg ? seg + ahead : nseg - 1;
+    warm = *reinterpret_cast<volatile const MX_GLOBAL uint32_t*>((const MX_GLOBAL SsSegment*)segs + f);
+  }
   if (s.kind == 0) {
     if (item < s.count) ss_piece<ANCHOR, HW, TARGETS...>(s.in, s.out, item, tie);
   } else {
     if (item * 16 < s.count) ss_scale_chunk<ANCHOR, TARGETS...>(static_cast<const uint8_t*>(s.in), s.out, item, s.count);
   }
-}
-
-// Tensor table from kernel arguments into device memory (no host buffer has to outlive the call).
-__global__ void ss_table_kernel(SsTableChunk chunk, SsTensor* __restrict__ table) {
-  int i = threadIdx.x;
-  if (i < chunk.count) table[chunk.base + i] = chunk.t[i];
+  asm volatile("" ::"v"(warm));  // the load above must not be dropped; it has landed by the time the wave ends
 }
 
 struct SsPieceBytes { int out[kSsMaxTargets]; int n; int cpl; };
 
-// Segment table from the tensor table: thread s describes segment s.
-__global__ void ss_segments_kernel(const SsTensor* __restrict__ tensors, int n, SsSegment* __restrict__ segs, int64_t nseg,
-                                   SsPieceBytes pb) {
-  int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (s >= nseg) return;
-  int lo = 0, hi = n;  // tensors[lo].seg_begin <= s < tensors[hi].seg_begin (hi == n: end)
+// Segment table of one chunk of tensors: thread j describes segment seg0 + j.
+__global__ void ss_segments_kernel(SsChunk c, SsSegment* __restrict__ segs, int nseg_chunk, SsPieceBytes pb, int seg_shift) {
+  int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= nseg_chunk) return;
+  const int stride = 4 + 2 * c.n_targets;
+  int lo = 0, hi = c.count;  // first code segment of tensor lo <= s < that of tensor hi (hi == count: end)
   while (hi - lo > 1) {
     int mid = (lo + hi) >> 1;
-    if (tensors[mid].seg_begin <= s) lo = mid; else hi = mid;
+    if ((int)(uint32_t)c.w[mid * stride + 3] <= s) lo = mid; else hi = mid;
   }
-  const SsTensor t = tensors[lo];
+  const int64_t* t = c.w + lo * stride;
+  const int seg_begin = (int)(uint32_t)t[3], seg_scale = (int)(t[3] >> 32);
+  const int64_t nblocks = t[2];
+  const int64_t ITEMS = (int64_t)kSsLanes << seg_shift;  // pieces, or 16-byte scale chunks, per segment
   SsSegment d;
   d.pad = 0; d.pad2[0] = d.pad2[1] = 0;
-  constexpr int64_t ITEMS = (int64_t)kSsSegWgs * kSsLanes;  // pieces, or 16-byte scale chunks, per segment
-  if (s < t.seg_scale) {
-    int64_t j = s - t.seg_begin;
-    int64_t pieces = t.nblocks * (32 / pb.cpl) - j * ITEMS;
-    d.in = static_cast<const char*>(t.codes_h) + j * ITEMS * pb.cpl;
+  if (s < seg_scale) {
+    int64_t j = s - seg_begin;
+    int64_t pieces = nblocks * (32 / pb.cpl) - j * ITEMS;
+    d.in = reinterpret_cast<const char*>(t[0]) + j * ITEMS * pb.cpl;
     for (int q = 0; q < kSsMaxTargets; ++q)
-      d.out[q] = q < pb.n ? static_cast<char*>(t.codes_l[q]) + j * ITEMS * pb.out[q] : nullptr;
+      d.out[q] = q < pb.n ? reinterpret_cast<char*>(t[4 + q]) + j * ITEMS * pb.out[q] : nullptr;
     d.count = pieces < ITEMS ? pieces : ITEMS;
     d.kind = 0;
   } else {
-    int64_t j = s - t.seg_scale;
-    int64_t bytes = t.nblocks - j * ITEMS * 16;
-    d.in = t.scales_h + j * ITEMS * 16;
-    for (int q = 0; q < kSsMaxTargets; ++q) d.out[q] = q < pb.n ? t.scales_l[q] + j * ITEMS * 16 : nullptr;
+    int64_t j = s - seg_scale;
+    int64_t bytes = nblocks - j * ITEMS * 16;
+    d.in = reinterpret_cast<const char*>(t[1]) + j * ITEMS * 16;
+    for (int q = 0; q < kSsMaxTargets; ++q)
+      d.out[q] = q < pb.n ? reinterpret_cast<char*>(t[4 + pb.n + q]) + j * ITEMS * 16 : nullptr;
     d.count = bytes < ITEMS * 16 ? bytes : ITEMS * 16;
     d.kind = 1;
   }
-  segs[s] = d;
+  segs[c.seg0 + s] = d;
 }
 
 // ---- host side -----------------------------------------------------------------------------
@@ -226,9 +259,11 @@ static mx_status_t launch_ss(const SsTensor& t, int tie, hipStream_t stream) {
 }
 
 template <int ANCHOR, bool HW, int... TARGETS>
-static mx_status_t launch_ss_batched(const SsSegment* segs, int64_t nseg, int tie, hipStream_t stream) {
-  hipLaunchKernelGGL((ss_batched_kernel<ANCHOR, HW, TARGETS...>), dim3((unsigned)(nseg * kSsSegWgs)), dim3(kSsLanes), 0, stream,
-                     segs, tie);
+static mx_status_t launch_ss_batched(const SsSegment* segs, int64_t nseg, int seg_shift, int tie, hipStream_t stream) {
+  // descriptors are pulled in about 2048 .. 8192 workgroups ahead of their first use (measured optimum)
+  const int ahead = seg_shift >= kSsSegShiftLarge ? 2 : 64;
+  hipLaunchKernelGGL((ss_batched_kernel<ANCHOR, HW, TARGETS...>), dim3((unsigned)(nseg << seg_shift)), dim3(kSsLanes), 0, stream,
+                     segs, (int)nseg, seg_shift, ahead, tie);
   return hipGetLastError() == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
 }
 
@@ -270,8 +305,10 @@ struct SsOne {
   template <int A, bool HW, int... T> mx_status_t operator()() const { return launch_ss<A, HW, T...>(t, tie, stream); }
 };
 struct SsMany {
-  const SsSegment* segs; int64_t nseg; int tie; hipStream_t stream;
-  template <int A, bool HW, int... T> mx_status_t operator()() const { return launch_ss_batched<A, HW, T...>(segs, nseg, tie, stream); }
+  const SsSegment* segs; int64_t nseg; int seg_shift; int tie; hipStream_t stream;
+  template <int A, bool HW, int... T> mx_status_t operator()() const {
+    return launch_ss_batched<A, HW, T...>(segs, nseg, seg_shift, tie, stream);
+  }
 };
 
 struct SsProbe {   // "is there a kernel for this target list?" without launching anything
@@ -283,63 +320,88 @@ mx_status_t ss_launch_one(int anchor, const SsTargets& tg, bool hw, const SsTens
 }
 
 // Segments a tensor of nblocks blocks needs: code segments, scale segments.
-static inline void ss_segments_of(int64_t nblocks, int cpl, int64_t* code_segs, int64_t* scale_segs) {
-  const int64_t items = (int64_t)kSsSegWgs * kSsLanes;
+static inline void ss_segments_of(int64_t nblocks, int cpl, int seg_shift, int64_t* code_segs, int64_t* scale_segs) {
+  const int64_t items = (int64_t)kSsLanes << seg_shift;
   *code_segs = ceil_div(nblocks * (32 / cpl), items);
   *scale_segs = ceil_div(ceil_div(nblocks, 16), items);
 }
 
+static int64_t ss_count_segments(int n, const SsTensor* t, int cpl, int seg_shift) {
+  int64_t nseg = 0;
+  for (int i = 0; i < n; ++i) {
+    int64_t cs, ss;
+    ss_segments_of(t[i].nblocks, cpl, seg_shift, &cs, &ss);
+    nseg += cs + ss;
+  }
+  return nseg;
+}
+
 size_t ss_workspace_bytes(int n, int64_t total_blocks) {
-  // bound over both piece sizes: every tensor rounds up by at most one code and one scale segment
-  const int64_t items = (int64_t)kSsSegWgs * kSsLanes;
+  // bound over both piece sizes and both segment sizes: every tensor rounds up by at most one code and one scale
+  // segment, and small segments need the most descriptors
+  const int64_t items = (int64_t)kSsLanes << kSsSegShiftSmall;
   int64_t segs = total_blocks * 2 / items + total_blocks / (16 * items) + 2 * (int64_t)n + 2;
-  return (sizeof(SsTensor) * (size_t)n + 63) / 64 * 64 + sizeof(SsSegment) * (size_t)segs;
+  return sizeof(SsSegment) * (size_t)segs;
 }
 
 mx_status_t ss_launch_many(int anchor, const SsTargets& tg, bool hw, int n, const SsTensor* h_tensors, void* workspace,
                            size_t workspace_bytes, int tie, hipStream_t stream) {
   const int cpl = ss_cpl(tg);
-  // pass 1 on the host: segment ranges; nothing is launched before the sizes are known to fit
-  int64_t nseg = 0;
-  for (int i = 0; i < n; ++i) {
-    int64_t cs, ss;
-    ss_segments_of(h_tensors[i].nblocks, cpl, &cs, &ss);
-    nseg += cs + ss;
+  // pass 1 on the host: segment ranges; nothing is launched before the sizes are known to fit.  Large segments
+  // unless their padding (workgroups that find nothing to do) would exceed 1/32 of the launch.
+  int seg_shift = kSsSegShiftLarge;
+  int64_t nseg = ss_count_segments(n, h_tensors, cpl, seg_shift);
+  {
+    int64_t small = ss_count_segments(n, h_tensors, cpl, kSsSegShiftSmall);
+    if ((nseg << kSsSegShiftLarge) - (small << kSsSegShiftSmall) > (small << kSsSegShiftSmall) / 32) {
+      seg_shift = kSsSegShiftSmall;
+      nseg = small;
+    }
   }
   if (nseg == 0) return MX_OK;
-  if (nseg * kSsSegWgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-  size_t tb = (sizeof(SsTensor) * (size_t)n + 63) / 64 * 64;
-  if (workspace_bytes < tb + sizeof(SsSegment) * (size_t)nseg) return MX_ERR_WORKSPACE;
+  if ((nseg << seg_shift) > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+  if (workspace_bytes < sizeof(SsSegment) * (size_t)nseg) return MX_ERR_WORKSPACE;
   // an unsupported target list must fail before anything is launched
   {
     mx_status_t st = ss_dispatch(anchor, tg, hw, SsProbe{});
     if (st != MX_OK) return st;
   }
-  SsTensor* table = static_cast<SsTensor*>(workspace);
-  SsSegment* segs = reinterpret_cast<SsSegment*>(static_cast<char*>(workspace) + tb);
-  int64_t acc = 0;
-  SsTableChunk chunk;
-  for (int base = 0; base < n; base += kSsTableChunk) {
-    chunk.base = base;
-    chunk.count = n - base < kSsTableChunk ? n - base : kSsTableChunk;
-    for (int i = 0; i < chunk.count; ++i) {
-      SsTensor t = h_tensors[base + i];
-      int64_t cs, ss;
-      ss_segments_of(t.nblocks, cpl, &cs, &ss);
-      t.seg_begin = acc;
-      t.seg_scale = acc + cs;
-      acc += cs + ss;
-      chunk.t[i] = t;
-    }
-    hipLaunchKernelGGL(ss_table_kernel, dim3(1), dim3(64), 0, stream, chunk, table);
-    if (hipGetLastError() != hipSuccess) return MX_ERR_LAUNCH;
-  }
+  SsSegment* segs = static_cast<SsSegment*>(workspace);
   SsPieceBytes pb;
   pb.n = tg.n; pb.cpl = cpl;
   for (int q = 0; q < kSsMaxTargets; ++q) pb.out[q] = q < tg.n ? cpl * tg.bits[q] / 8 : 0;
-  hipLaunchKernelGGL(ss_segments_kernel, dim3((unsigned)ceil_div(nseg, 256)), dim3(256), 0, stream, table, n, segs, nseg, pb);
-  if (hipGetLastError() != hipSuccess) return MX_ERR_LAUNCH;
-  return ss_dispatch(anchor, tg, hw, SsMany{segs, nseg, tie, stream});
+  // the segment table, written by one small launch per chunk of tensors
+  const int stride = 4 + 2 * tg.n, cap = kSsChunkWords / stride;
+  int64_t seg0 = 0;
+  SsChunk chunk;
+  for (int base = 0; base < n; base += cap) {
+    chunk.count = n - base < cap ? n - base : cap;
+    chunk.n_targets = tg.n;
+    chunk.seg0 = seg0;
+    int64_t acc = 0;
+    for (int i = 0; i < chunk.count; ++i) {
+      const SsTensor& t = h_tensors[base + i];
+      int64_t cs, ss;
+      ss_segments_of(t.nblocks, cpl, seg_shift, &cs, &ss);
+      int64_t* w = chunk.w + i * stride;
+      w[0] = (int64_t)(uintptr_t)t.codes_h;
+      w[1] = (int64_t)(uintptr_t)t.scales_h;
+      w[2] = t.nblocks;
+      w[3] = acc | ((acc + cs) << 32);
+      for (int q = 0; q < tg.n; ++q) {
+        w[4 + q] = (int64_t)(uintptr_t)t.codes_l[q];
+        w[4 + tg.n + q] = (int64_t)(uintptr_t)t.scales_l[q];
+      }
+      acc += cs + ss;
+    }
+    if (acc > 0) {
+      hipLaunchKernelGGL(ss_segments_kernel, dim3((unsigned)ceil_div(acc, 256)), dim3(256), 0, stream, chunk, segs, (int)acc, pb,
+                         seg_shift);
+      if (hipGetLastError() != hipSuccess) return MX_ERR_LAUNCH;
+    }
+    seg0 += acc;
+  }
+  return ss_dispatch(anchor, tg, hw, SsMany{segs, nseg, seg_shift, tie, stream});
 }
 
 }  // namespace mx

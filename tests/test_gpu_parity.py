@@ -108,6 +108,25 @@ def test_slice_and_scale_batched(mx, oracle, anchor, target):
         assert np.array_equal(to_host(gc), wc), i
 
 
+@pytest.mark.parametrize("anchor,target", [("e4m3", "e2m1"), ("int8", "int6"), ("int8", "int5")])
+def test_slice_and_scale_batched_large_segments(mx, oracle, anchor, target):
+    # tensors big enough that the launch cuts them into its large segments (1024 workgroups), with ragged ends:
+    # a last code segment that is nearly empty, one that is nearly full, and a scale segment of a few bytes
+    import torch
+    sizes = [(1 << 20) + 37, (1 << 21) - 5, 1 << 20]
+    anchors, want = [], []
+    for i, nb in enumerate(sizes):
+        codes = synth.random_bytes(4100 + i, nb * 32).reshape(nb, 32)
+        scales = synth.random_bytes(5100 + i, nb)
+        anchors.append((to_gpu(codes), to_gpu(scales)))
+        want.append(oracle.slice_and_scale(codes, scales, anchor, target))
+    got = mx.mx_slice_and_scale_batched(anchors, mx.make_format(anchor), mx.make_format(target))
+    torch.cuda.synchronize()
+    for i, ((gc, gs), (wc, ws)) in enumerate(zip(got, want)):
+        assert np.array_equal(to_host(gs), ws), i
+        assert np.array_equal(to_host(gc), wc), i
+
+
 MULTI_SETS = [("int8", ["int6", "int4"]), ("e4m3", ["e3m2", "e2m3", "e2m1"]), ("e4m3", ["e3m2", "e2m1"]),
               ("e4m3", ["e2m3", "e2m1"]), ("e4m3", ["e3m2", "e2m3"])]
 
