@@ -101,10 +101,20 @@ __device__ __forceinline__ void store_global(void* base, int64_t dword, const ui
 template <int... TARGETS>
 struct Piece { static constexpr int cpl = (((Elem<TARGETS>::bits % 2 == 0) && ...)) ? 16 : 32; };
 
-// ---- piece p of a run of pieces: load once, convert and store for every target of the launch
+// ---- the 64 pieces [p0, p0 + 64) of a run of `count` pieces, one per lane: load once, convert and
+// store for every target of the launch.  A 6-bit target gives 12 bytes per lane; 96-bit stores cost
+// about four points of HBM bandwidth against 128-bit ones (measured), so a wave that is all inside
+// the run regroups its 192 result dwords through LDS and stores them 16 bytes per lane from 48 lanes.
 template <int ANCHOR, bool HW, int... TARGETS>
-__device__ __forceinline__ void ss_piece(const void* __restrict__ in, void* const (&out)[kSsMaxTargets], int64_t p, int tie) {
+__device__ __forceinline__ void ss_pieces(const void* __restrict__ in, void* const (&out)[kSsMaxTargets], int64_t p0, int64_t count,
+                                          int tie) {
   constexpr int CPL = Piece<TARGETS...>::cpl, NIN = CPL / 4;
+  constexpr int NSTAGED = ((CPL * Elem<TARGETS>::bits / 32 == 3 ? 1 : 0) + ...);
+  __shared__ uint32_t stage[NSTAGED > 0 ? NSTAGED : 1][kSsLanes * 3];
+  const int lane = threadIdx.x;
+  const int64_t p = p0 + lane;
+  const bool whole = p0 + kSsLanes <= count;   // the same for every lane of the wave
+  if (!whole && p >= count) return;
   uint32_t x[NIN];
   const MX_GLOBAL u32x4* src = (const MX_GLOBAL u32x4*)in + p * (NIN / 4);
 #pragma unroll
@@ -112,12 +122,27 @@ __device__ __forceinline__ void ss_piece(const void* __restrict__ in, void* cons
     u32x4 t = __builtin_nontemporal_load(src + i);
     x[4 * i] = t.x; x[4 * i + 1] = t.y; x[4 * i + 2] = t.z; x[4 * i + 3] = t.w;
   }
-  int slot = 0;
+  int slot = 0, staged = 0;
   ([&] {
     constexpr int NOUT = CPL * Elem<TARGETS>::bits / 32;
     uint32_t y[NOUT];
     slice_piece<ANCHOR, TARGETS, HW && Elem<TARGETS>::hw != HW_NONE, CPL>(x, y, tie);
-    store_global<NOUT>(out[slot], p * NOUT, y);
+    if constexpr (NOUT == 3) {
+      if (whole) {
+        uint32_t* st = stage[staged];
+        st[lane * 3] = y[0]; st[lane * 3 + 1] = y[1]; st[lane * 3 + 2] = y[2];
+        __syncthreads();   // one wave per workgroup: orders the LDS writes before the reads below
+        if (lane < 48) {
+          u32x4 v = *reinterpret_cast<const u32x4*>(st + lane * 4);
+          ((MX_GLOBAL u32x4*)((MX_GLOBAL uint32_t*)out[slot] + p0 * 3))[lane] = v;
+        }
+      } else {
+        store_global<NOUT>(out[slot], p * NOUT, y);
+      }
+      ++staged;
+    } else {
+      store_global<NOUT>(out[slot], p * NOUT, y);
+    }
     ++slot;
   }(), ...);
 }
@@ -165,8 +190,7 @@ __global__ __launch_bounds__(kSsLanes) void ss_kernel(SsFlatArgs a, int tie) {
   constexpr int CPL = Piece<TARGETS...>::cpl;
   int64_t wg = blockIdx.x;
   if (wg < a.code_wgs) {
-    int64_t p = wg * kSsLanes + threadIdx.x;
-    if (p < a.nblocks * (32 / CPL)) ss_piece<ANCHOR, HW, TARGETS...>(a.codes_h, a.codes_l, p, tie);
+    ss_pieces<ANCHOR, HW, TARGETS...>(a.codes_h, a.codes_l, wg * kSsLanes, a.nblocks * (32 / CPL), tie);
   } else {
     int64_t c = (wg - a.code_wgs) * kSsLanes + threadIdx.x;
     if (c * 16 < a.nblocks) ss_scale_chunk<ANCHOR, TARGETS...>(a.scales_h, a.scales_l, c, a.nblocks);
@@ -188,14 +212,14 @@ __global__ __launch_bounds__(kSsLanes) void ss_batched_kernel(const SsSegment* _
   uint32_t warm = 0;
   if (w < 8 && threadIdx.x == 0) {
     int f = seg + ahead < nseg ? seg + ahead : nseg - 1;
-    warm = *reinterpret_cast<volatile const MX_GLOBAL uint32_t*>((const MX_GLOBAL SsSegment*)segs + f);
+    warm = *reinterpret_cast<const MX_GLOBAL uint32_t*>((const MX_GLOBAL SsSegment*)segs + f);
   }
   if (s.kind == 0) {
-    if (item < s.count) ss_piece<ANCHOR, HW, TARGETS...>(s.in, s.out, item, tie);
+    ss_pieces<ANCHOR, HW, TARGETS...>(s.in, s.out, (int64_t)w * kSsLanes, s.count, tie);
   } else {
     if (item * 16 < s.count) ss_scale_chunk<ANCHOR, TARGETS...>(static_cast<const uint8_t*>(s.in), s.out, item, s.count);
   }
-  asm volatile("" ::"v"(warm));  // the load above must not be dropped; it has landed by the time the wave ends
+  asm volatile("" ::"v"(warm));  // keeps the load above alive; nothing waits for it before the wave's last instruction
 }
 
 struct SsPieceBytes { int out[kSsMaxTargets]; int n; int cpl; };
@@ -262,7 +286,11 @@ template <int ANCHOR, bool HW, int... TARGETS>
 static mx_status_t launch_ss_batched(const SsSegment* segs, int64_t nseg, int seg_shift, int tie, hipStream_t stream) {
   // descriptors are pulled in about 2048 .. 8192 workgroups ahead of their first use (measured optimum)
   const int ahead = seg_shift >= kSsSegShiftLarge ? 2 : 64;
-  hipLaunchKernelGGL((ss_batched_kernel<ANCHOR, HW, TARGETS...>), dim3((unsigned)(nseg << seg_shift)), dim3(kSsLanes), 0, stream,
+  // With three targets the launch writes twice what it reads, and HBM then does better with fewer waves in
+  // flight (a narrower front of open pages): unused dynamic LDS holds a CU at about 22 workgroups (measured:
+  // 69.9 -> 72.3 % of peak; every launch with fewer targets loses bandwidth under any such cap).
+  constexpr unsigned occupancy_pad = sizeof...(TARGETS) >= 3 ? 5632 : 0;
+  hipLaunchKernelGGL((ss_batched_kernel<ANCHOR, HW, TARGETS...>), dim3((unsigned)(nseg << seg_shift)), dim3(kSsLanes), occupancy_pad, stream,
                      segs, (int)nseg, seg_shift, ahead, tie);
   return hipGetLastError() == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
 }
