@@ -72,6 +72,8 @@ __device__ __forceinline__ void slice_piece(const uint32_t (&in)[CPL / 4], uint3
   }
 }
 
+// Results are written once and not read again by this launch: non-temporal stores (measured: one to
+// five points of HBM bandwidth, depending on the launch shape).
 // Every pointer of a launch is device global memory, but one that a workgroup has loaded from a
 // descriptor table carries no address space, and the compiler would reach through it with flat
 // instructions (which also occupy the LDS path).  All accesses below therefore go through
@@ -85,10 +87,11 @@ __device__ __forceinline__ void store_global(void* base, int64_t dword, const ui
   MX_GLOBAL uint32_t* p = (MX_GLOBAL uint32_t*)base + dword;
   if constexpr (W % 4 == 0) {
 #pragma unroll
-    for (int i = 0; i < W / 4; ++i) ((MX_GLOBAL u32x4*)p)[i] = u32x4{v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]};
+    for (int i = 0; i < W / 4; ++i)
+      __builtin_nontemporal_store(u32x4{v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]}, (MX_GLOBAL u32x4*)p + i);
   } else if constexpr (W % 2 == 0) {
 #pragma unroll
-    for (int i = 0; i < W / 2; ++i) ((MX_GLOBAL u32x2*)p)[i] = u32x2{v[2 * i], v[2 * i + 1]};
+    for (int i = 0; i < W / 2; ++i) __builtin_nontemporal_store(u32x2{v[2 * i], v[2 * i + 1]}, (MX_GLOBAL u32x2*)p + i);
   } else if constexpr (W == 3) {
     *(MX_GLOBAL u32x3_a4*)p = u32x3{v[0], v[1], v[2]};   // one 96-bit store (needs only dword alignment)
   } else {
@@ -134,7 +137,7 @@ __device__ __forceinline__ void ss_pieces(const void* __restrict__ in, void* con
         __syncthreads();   // one wave per workgroup: orders the LDS writes before the reads below
         if (lane < 48) {
           u32x4 v = *reinterpret_cast<const u32x4*>(st + lane * 4);
-          ((MX_GLOBAL u32x4*)((MX_GLOBAL uint32_t*)out[slot] + p0 * 3))[lane] = v;
+          __builtin_nontemporal_store(v, (MX_GLOBAL u32x4*)((MX_GLOBAL uint32_t*)out[slot] + p0 * 3) + lane);
         }
       } else {
         store_global<NOUT>(out[slot], p * NOUT, y);
@@ -289,7 +292,10 @@ static mx_status_t launch_ss_batched(const SsSegment* segs, int64_t nseg, int se
   // With three targets the launch writes twice what it reads, and HBM then does better with fewer waves in
   // flight (a narrower front of open pages): unused dynamic LDS holds a CU at about 22 workgroups (measured:
   // 69.9 -> 72.3 % of peak; every launch with fewer targets loses bandwidth under any such cap).
-  constexpr unsigned occupancy_pad = sizeof...(TARGETS) >= 3 ? 5632 : 0;
+#ifndef MX_SS_PAD
+#define MX_SS_PAD 5632
+#endif
+  constexpr unsigned occupancy_pad = sizeof...(TARGETS) >= 3 ? MX_SS_PAD : 0;
   hipLaunchKernelGGL((ss_batched_kernel<ANCHOR, HW, TARGETS...>), dim3((unsigned)(nseg << seg_shift)), dim3(kSsLanes), occupancy_pad, stream,
                      segs, (int)nseg, seg_shift, ahead, tie);
   return hipGetLastError() == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
