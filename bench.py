@@ -185,10 +185,11 @@ def main():
             del c2, s2, v2
         del a_codes, a_scales, a_views
         torch.cuda.empty_cache()
-        # quantize / dequantize on four stacked copies of the largest decoder weight (gate_proj 14336 x 4096 bf16;
-        # 57344 x 4096 = 234.9 M elements, 470 MB dense): twice the 256 MB last-level cache, so every pass streams HBM
-        r, c = 4 * 14336, 4096
-        wbig = torch.cat([synth.torch_config3_weight(1000 + i, 14336, c) for i in range(4)], dim=0)
+        # quantize / dequantize on eight stacked copies of the largest decoder weight (gate_proj 14336 x 4096 bf16;
+        # 114688 x 4096 = 469.8 M elements, 940 MB dense): several times the 256 MB last-level cache, so every pass
+        # streams HBM
+        r, c = 8 * 14336, 4096
+        wbig = torch.cat([synth.torch_config3_weight(1000 + i, 14336, c) for i in range(8)], dim=0)
         for elem, bits in (("e4m3", 8), ("int8", 8), ("e2m1", 4), ("int4", 4), ("e3m2", 6)):
             f = mx.make_format(elem)
             pc, ps = mx.mx_quantize(wbig, f)

@@ -10,17 +10,31 @@
 #include "mx_device.h"
 #include "mx_launch.h"
 
-#ifndef MX_ROWS_UNROLL
-#define MX_ROWS_UNROLL 1
-#endif
-#ifndef MX_ROWS_THREADS
-#define MX_ROWS_THREADS 256
-#endif
 #ifndef MX_FQ_THREADS
 #define MX_FQ_THREADS 64
 #endif
 
+#ifndef MX_NT_LOAD
+#define MX_NT_LOAD 1
+#endif
+#ifndef MX_NT_STORE
+#define MX_NT_STORE 1
+#endif
+
 namespace mx {
+
+// Streaming accesses: every input is read once and every output written once per launch.  Non-temporal
+// loads and stores are worth two to five points of HBM bandwidth here, and far more with several chunks per lane.
+template <typename T>
+__device__ __forceinline__ T stream_load(const T* p) {
+  if constexpr (MX_NT_LOAD) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+template <typename T>
+__device__ __forceinline__ void stream_store(T* p, T v) {
+  if constexpr (MX_NT_STORE) __builtin_nontemporal_store(v, p);
+  else *p = v;
+}
 
 // ------------------------------------------------------------------ dense chunks
 template <int DT> struct Dense;
@@ -37,7 +51,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 // 16-byte chunk at element offset `off` -> N floats
 template <int DT>
 __device__ __forceinline__ void load_chunk(const void* base, int64_t off, float (&v)[Dense<DT>::N]) {
-  u32x4 t = *reinterpret_cast<const u32x4*>(static_cast<const char*>(base) + off * Dense<DT>::ESZ);
+  u32x4 t = stream_load(reinterpret_cast<const u32x4*>(static_cast<const char*>(base) + off * Dense<DT>::ESZ));
   if constexpr (DT == MX_F32) {
     v[0] = __uint_as_float(t.x); v[1] = __uint_as_float(t.y); v[2] = __uint_as_float(t.z); v[3] = __uint_as_float(t.w);
   } else {
@@ -54,17 +68,17 @@ __device__ __forceinline__ void store_chunk(void* base, int64_t off, const float
   } else {
     t = u32x4{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
   }
-  *reinterpret_cast<u32x4*>(static_cast<char*>(base) + off * Dense<DT>::ESZ) = t;
+  stream_store(reinterpret_cast<u32x4*>(static_cast<char*>(base) + off * Dense<DT>::ESZ), t);
 }
 
 // 4 elements (one lane's columns of one row) for the column-axis kernels: 16 B fp32 / 8 B bf16
 template <int DT>
 __device__ __forceinline__ void load_quad(const void* base, int64_t off, float (&v)[4]) {
   if constexpr (DT == MX_F32) {
-    u32x4 t = *reinterpret_cast<const u32x4*>(static_cast<const char*>(base) + off * 4);
+    u32x4 t = stream_load(reinterpret_cast<const u32x4*>(static_cast<const char*>(base) + off * 4));
     v[0] = __uint_as_float(t.x); v[1] = __uint_as_float(t.y); v[2] = __uint_as_float(t.z); v[3] = __uint_as_float(t.w);
   } else {
-    u32x2 t = *reinterpret_cast<const u32x2*>(static_cast<const char*>(base) + off * 2);
+    u32x2 t = stream_load(reinterpret_cast<const u32x2*>(static_cast<const char*>(base) + off * 2));
     v[0] = bf16_lo(t.x); v[1] = bf16_hi(t.x); v[2] = bf16_lo(t.y); v[3] = bf16_hi(t.y);
   }
 }
@@ -72,10 +86,10 @@ __device__ __forceinline__ void load_quad(const void* base, int64_t off, float (
 template <int DT>
 __device__ __forceinline__ void store_quad(void* base, int64_t off, const float (&v)[4]) {
   if constexpr (DT == MX_F32) {
-    *reinterpret_cast<u32x4*>(static_cast<char*>(base) + off * 4) =
-        u32x4{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
+    stream_store(reinterpret_cast<u32x4*>(static_cast<char*>(base) + off * 4),
+                 u32x4{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])});
   } else {
-    *reinterpret_cast<u32x2*>(static_cast<char*>(base) + off * 2) = u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+    stream_store(reinterpret_cast<u32x2*>(static_cast<char*>(base) + off * 2), u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])});
   }
 }
 
@@ -122,28 +136,28 @@ template <int W, int N>
 __device__ __forceinline__ void store_chunk_codes(uint32_t* block_words, uint64_t bits, int lig) {
   constexpr int NB = N * W;  // bits per lane
   if constexpr (NB == 64) {
-    *reinterpret_cast<u32x2*>(block_words + 2 * lig) = u32x2{(uint32_t)bits, (uint32_t)(bits >> 32)};
+    stream_store(reinterpret_cast<u32x2*>(block_words + 2 * lig), u32x2{(uint32_t)bits, (uint32_t)(bits >> 32)});
   } else if constexpr (NB == 32) {
-    block_words[lig] = (uint32_t)bits;
+    stream_store(block_words + lig, (uint32_t)bits);
   } else if constexpr (NB == 16) {
     // pairs of lanes make one dword; the even lane stores
     uint32_t nxt = dpp<DPP_ROW_SHL1>((uint32_t)bits);
-    if ((lig & 1) == 0) block_words[lig >> 1] = (uint32_t)bits | (nxt << 16);
+    if ((lig & 1) == 0) stream_store(block_words + (lig >> 1), (uint32_t)bits | (nxt << 16));
   } else if constexpr (NB == 24) {
     // 4 lanes make 3 dwords: lane j < 3 of the quad stores (p_j >> 8j) | (p_{j+1} << (24 - 8j))
     uint32_t nxt = dpp<DPP_ROW_SHL1>((uint32_t)bits);
     int j = lig & 3;
     uint32_t d = ((uint32_t)bits >> (8 * j)) | (nxt << (24 - 8 * j));
-    if (j < 3) block_words[(lig >> 2) * 3 + j] = d;
+    if (j < 3) stream_store(block_words + (lig >> 2) * 3 + j, d);
   } else if constexpr (NB == 48) {
     // 2 lanes make 3 dwords: even lane stores dwords 0 and 1, odd lane dword 2
     uint32_t nxt = dpp<DPP_ROW_SHL1>((uint32_t)bits);
     uint32_t* p = block_words + (lig >> 1) * 3;
     if ((lig & 1) == 0) {
-      p[0] = (uint32_t)bits;
-      p[1] = (uint32_t)(bits >> 32) | (nxt << 16);
+      stream_store(p, (uint32_t)bits);
+      stream_store(p + 1, (uint32_t)(bits >> 32) | (nxt << 16));
     } else {
-      p[2] = (uint32_t)(bits >> 16);
+      stream_store(p + 2, (uint32_t)(bits >> 16));
     }
   } else {
     static_assert(NB == 64, "odd element widths take the byte-staged path");
@@ -225,7 +239,7 @@ template <int W, int N>
 __device__ __forceinline__ uint64_t load_chunk_codes(const uint32_t* block_words, int lig) {
   constexpr int NB = N * W;
   if constexpr (NB == 64) {
-    u32x2 t = *reinterpret_cast<const u32x2*>(block_words + 2 * lig);
+    u32x2 t = stream_load(reinterpret_cast<const u32x2*>(block_words + 2 * lig));
     return (uint64_t)t.x | ((uint64_t)t.y << 32);
   } else if constexpr (NB == 32) {
     return block_words[lig];
@@ -578,9 +592,27 @@ __global__ __launch_bounds__(256) void fake_quant_cols_kernel(const void* __rest
 
 // ------------------------------------------------------------------ host launchers
 #ifndef MX_DENSE_KERNELS_ONLY   // (a tuning harness can include this file for the kernels alone)
-constexpr int kRowsUnroll = MX_ROWS_UNROLL;   // chunks per lane
-constexpr int kRowsThreads = MX_ROWS_THREADS; // lanes per workgroup (quantize, dequantize)
-constexpr int kFqThreads = MX_FQ_THREADS;     // lanes per workgroup (fake-quant)
+// Launch shape of the row-axis kernels: chunks per lane and lanes per workgroup.  Which shape streams best
+// depends on the read : write mix and on the arithmetic per element, so it is chosen per element format
+// (measured on 1 GiB bf16 tensors; the figures are percent of the 8 TB/s HBM peak).
+struct RowsShape { int unroll, threads; };
+template <int ELEM>
+constexpr RowsShape quantize_shape() {
+  using E = Elem<ELEM>;
+  if (E::is_int) return E::bits == 8 ? RowsShape{4, 256} : RowsShape{4, 64};  // 80 (1 x 64: 67); 77 - 79 (1 x 64: 67 - 70)
+  if (E::hw == HW_FP8) return RowsShape{2, 128};                               // 83
+  if (E::hw != HW_NONE) return RowsShape{2, 64};                               // E2M1 85 (1 x 64: 73), FP6 79
+  return RowsShape{1, 256};
+}
+template <int ELEM>
+constexpr RowsShape dequant_shape() {
+  using E = Elem<ELEM>;
+  if (E::bits == 4) return E::is_int ? RowsShape{4, 256} : RowsShape{2, 256};  // 79, 83 (1 x 64: 63, 65)
+  if (E::bits == 6) return RowsShape{2, 64};                                   // 72
+  return RowsShape{1, 64};                                                     // 8-bit: 83
+}
+constexpr int kFqUnroll = 1;                  // fake-quant: one chunk per lane, one wave per workgroup (82 - 83)
+constexpr int kFqThreads = MX_FQ_THREADS;
 
 static inline bool launch_ok() { return hipGetLastError() == hipSuccess; }
 
@@ -590,9 +622,10 @@ static mx_status_t run_quantize(int axis, int tie, const DenseArg& s, void* code
     constexpr int N = Dense<DT>::N;
     int64_t cpr = s.cols / N, nchunks = s.rows * cpr;
     if (cpr > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;
-    int64_t wgs = (nchunks + kRowsThreads * kRowsUnroll - 1) / (kRowsThreads * kRowsUnroll);
+    constexpr RowsShape shape = quantize_shape<ELEM>();
+    int64_t wgs = (nchunks + shape.threads * shape.unroll - 1) / (shape.threads * shape.unroll);
     if (wgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((quantize_rows_kernel<ELEM, HW, DT, kRowsUnroll, kRowsThreads>), dim3((unsigned)wgs), dim3(kRowsThreads), 0, st, s.data,
+    hipLaunchKernelGGL((quantize_rows_kernel<ELEM, HW, DT, shape.unroll, shape.threads>), dim3((unsigned)wgs), dim3(shape.threads), 0, st, s.data,
                        static_cast<uint32_t*>(codes), scales, nchunks, (uint32_t)cpr, s.ld, (int)(s.ld == s.cols), tie);
   } else {
     if (s.cols % 4) return MX_ERR_UNSUPPORTED;
@@ -611,9 +644,10 @@ static mx_status_t run_dequant(int axis, const void* codes, const uint8_t* scale
     constexpr int N = Dense<DT>::N;
     int64_t cpr = d.cols / N, nchunks = d.rows * cpr;
     if (cpr > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;
-    int64_t wgs = (nchunks + kRowsThreads * kRowsUnroll - 1) / (kRowsThreads * kRowsUnroll);
+    constexpr RowsShape shape = dequant_shape<ELEM>();
+    int64_t wgs = (nchunks + shape.threads * shape.unroll - 1) / (shape.threads * shape.unroll);
     if (wgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((dequant_rows_kernel<ELEM, DT, kRowsUnroll, kRowsThreads>), dim3((unsigned)wgs), dim3(kRowsThreads), 0, st,
+    hipLaunchKernelGGL((dequant_rows_kernel<ELEM, DT, shape.unroll, shape.threads>), dim3((unsigned)wgs), dim3(shape.threads), 0, st,
                        static_cast<const uint32_t*>(codes), scales, d.data, nchunks, (uint32_t)cpr, d.ld, (int)(d.ld == d.cols));
   } else {
     if (d.cols % 4) return MX_ERR_UNSUPPORTED;
@@ -632,9 +666,9 @@ static mx_status_t run_fake_quant(int axis, int tie, const DenseArg& s, const De
     constexpr int N = Dense<DT>::N;
     int64_t cpr = s.cols / N, nchunks = s.rows * cpr;
     if (cpr > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;
-    int64_t wgs = (nchunks + kFqThreads * kRowsUnroll - 1) / (kFqThreads * kRowsUnroll);
+    int64_t wgs = (nchunks + kFqThreads * kFqUnroll - 1) / (kFqThreads * kFqUnroll);
     if (wgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((fake_quant_rows_kernel<TARGET, ANCHOR, HW, DT, kRowsUnroll, kFqThreads>), dim3((unsigned)wgs), dim3(kFqThreads), 0, st,
+    hipLaunchKernelGGL((fake_quant_rows_kernel<TARGET, ANCHOR, HW, DT, kFqUnroll, kFqThreads>), dim3((unsigned)wgs), dim3(kFqThreads), 0, st,
                        s.data, d.data, nchunks, (uint32_t)cpr, s.ld, d.ld, (int)(s.ld == s.cols), (int)(d.ld == d.cols), tie);
   } else {
     if (s.cols % 4) return MX_ERR_UNSUPPORTED;
