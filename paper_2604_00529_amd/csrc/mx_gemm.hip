@@ -187,17 +187,29 @@ __global__ __launch_bounds__(256) void gemm_ss_fp4_smallm_kernel(const uint8_t* 
 }
 
 // ------------------------------------------------------------------ large M (prefill): LDS-tiled
-// Workgroup tile 256 (M) x 128 (N), K-step 128, 4 waves in a 2 x 2 grid of 128 x 64 wave tiles (8 x 4 MFMA tiles,
-// 32 MFMAs per wave and K-step).  Per K-step the workgroup stages the A tile (E4M3, 32 KB) and the anchor tile of W
-// (16 KB) -- the latter sliced to E2M1 on its way into LDS, once per workgroup instead of once per wave; the tall
-// tile is what amortizes that slicing (about 2.3 vector instructions per element) against the matrix work -- plus
-// the scale bytes.  Global loads run ahead in registers, LDS is double-buffered.  Row strides are padded
-// (144 B / 80 B) so that the 16 lanes of a lane group hit different banks.
+// Workgroup tile 256 (M) x 128 (N), K-step 128.  Eight waves in two roles, one wave of each role per SIMD:
+//   waves 0-3, the consumers: a 2 x 2 grid of 128 x 64 wave tiles (8 x 4 MFMA tiles, 32 MFMAs per wave and
+//     K-step); they read fragments from LDS and issue the MFMAs, nothing else;
+//   waves 4-7, the producers: they load the A tile (E4M3, 32 KB per K-step) and the anchor tile of W (16 KB)
+//     several K-steps ahead into registers, slice the anchor to E2M1 (Eq. (6)) on its way into LDS -- once per
+//     workgroup instead of once per wave; the tall tile is what amortizes the slicing (about 2.5 vector
+//     instructions per element) against the matrix work -- and stage the scale bytes.
+// The SIMD's scheduler interleaves the producer's loads and vector work with the consumer's MFMAs; with a
+// single role per wave the same work ran back to back (measured: 308 us against 52 us of pure MFMA time).
+// LDS is double-buffered, one barrier per K-step.  Row strides are padded (144 B / 80 B) so that the 16 lanes
+// of a lane group hit different banks.
 constexpr int kGemmBM = 256, kGemmBN = 128, kGemmBK = 128;
-constexpr int kGemmMT = 8, kGemmNT = 4;      // MFMA tiles per wave
+constexpr int kGemmMT = 8, kGemmNT = 4;      // MFMA tiles per consumer wave
 constexpr int kGemmLdA = 144, kGemmLdB = 80;
-constexpr int kGemmPrefetch = 2;             // K-steps of global loads in flight per thread
-constexpr int kGemmAChunks = kGemmBM * kGemmBK / 16 / 256;   // 16-byte A chunks per thread and K-step (8)
+#ifndef MX_GEMM_PREFETCH
+#define MX_GEMM_PREFETCH 2
+#endif
+constexpr int kGemmPrefetch = MX_GEMM_PREFETCH;   // K-steps of global loads in flight per producer thread
+constexpr int kGemmAChunks = kGemmBM * kGemmBK / 16 / 256;   // 16-byte A chunks per producer thread and K-step (8)
+constexpr int kGemmThreads = 512;
+#ifndef MX_GEMM_GROUP
+#define MX_GEMM_GROUP 4
+#endif
 
 struct GemmStage {
   uint8_t a[kGemmBM * kGemmLdA];   // E4M3 codes, row m: 128 bytes of K
@@ -207,157 +219,215 @@ struct GemmStage {
 };
 
 // SKIP is 0 in the library; a tuning harness instantiates other values to take parts of the kernel out
-// (1: no slicing, 2: no LDS fragment reads after the first K-step, 4: no MFMA, 8: no global loads after the prologue).
+// (1: no slicing, 2: no producer work after the prologue, 4: no MFMA, 8: no global loads after the prologue,
+// 16: consumers read their fragments from LDS only in the first K-step, 32: no LDS stores after the prologue,
+// 64 / 128: no loads of W / of A after the first K-steps, 256: non-temporal loads of W).
 template <int SKIP>
-__global__ __launch_bounds__(256) void gemm_ss_fp4_tiled_kernel(const uint8_t* __restrict__ a_codes,
-                                                                const uint8_t* __restrict__ a_scales,
-                                                                const uint8_t* __restrict__ w_codes,
-                                                                const uint8_t* __restrict__ w_scales, float* __restrict__ c,
-                                                                int M, int N, int K, int64_t ldc, int m_tiles) {
+__global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const uint8_t* __restrict__ a_codes,
+                                                                         const uint8_t* __restrict__ a_scales,
+                                                                         const uint8_t* __restrict__ w_codes,
+                                                                         const uint8_t* __restrict__ w_scales,
+                                                                         float* __restrict__ c, int M, int N, int K,
+                                                                         int64_t ldc, int m_tiles) {
   extern __shared__ __attribute__((aligned(16))) uint8_t gemm_smem[];
   GemmStage* stage = reinterpret_cast<GemmStage*>(gemm_smem);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // a scalar: the role branch is uniform
+  const int tid = threadIdx.x & 255;   // index inside the role's 256 threads
   const int i = lane & 15, g = lane >> 4;
-  const int wm = wave >> 1, wn = wave & 1;
   // consecutive workgroups walk the M tiles of one N tile: with round-robin dispatch over the 8 XCDs each XCD
   // keeps re-using the same few A tiles from its L2 while the W tile streams through
   const int tm = blockIdx.x % m_tiles, tn = blockIdx.x / m_tiles;
   const int m0 = tm * kGemmBM, n0 = tn * kGemmBN;
   const int KB = K / 32, ksteps = K / kGemmBK;
 
-  // per-thread slots of the global -> LDS copies
-  //   A: chunk q = tid + 256 j (j < 8): row q / 8, 16-byte column q % 8
-  //   B: block q = tid + 256 j (j < 2): column q / 4, K-block q % 4 (32 anchor bytes -> 16 bytes of E2M1)
-  //   scales: thread t < 256 one row of A (4 bytes); thread t < 128 also one column of W
-  // Rows / columns past the edge are clamped to the last valid one instead of branched around: their products land
-  // in outputs that are never stored, and straight-line code lets the loads of several K-steps stay in flight (the
-  // compiler counts outstanding loads exactly only without control flow).
-  constexpr int D = kGemmPrefetch;
-  const uint8_t* pa[kGemmAChunks];
-  const uint8_t* pw[2];
-#pragma unroll
-  for (int j = 0; j < kGemmAChunks; ++j) {
-    int q = tid + 256 * j, row = q >> 3, col = q & 7;
-    int m = m0 + row < M ? m0 + row : M - 1;
-    pa[j] = a_codes + (int64_t)m * K + 16 * col;
-  }
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    int q = tid + 256 * j, col = q >> 2, kb = q & 3;
-    int n = n0 + col < N ? n0 + col : N - 1;
-    pw[j] = w_codes + (int64_t)n * K + 32 * kb;
-  }
-  const uint8_t* psa = a_scales + (int64_t)(m0 + tid < M ? m0 + tid : M - 1) * KB;
-  const uint8_t* psw = w_scales + (int64_t)(n0 + (tid & 127) < N ? n0 + (tid & 127) : N - 1) * KB;
-
-  u32x4 ra[D][kGemmAChunks], rb[D][2][2];
-  uint32_t rsa[D], rsw[D];
-  auto load_global = [&](int ks, auto slot_c) {
-    constexpr int S = decltype(slot_c)::value;
-    const int k0 = ks * kGemmBK;
-#pragma unroll
-    for (int j = 0; j < kGemmAChunks; ++j) ra[S][j] = *reinterpret_cast<const u32x4*>(pa[j] + k0);
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const u32x4* p = reinterpret_cast<const u32x4*>(pw[j] + k0);
-      rb[S][j][0] = __builtin_nontemporal_load(p);
-      rb[S][j][1] = __builtin_nontemporal_load(p + 1);
-    }
-    rsa[S] = *reinterpret_cast<const uint32_t*>(psa + ks * 4);
-    rsw[S] = *reinterpret_cast<const uint32_t*>(psw + ks * 4);
-  };
-  auto store_lds = [&](GemmStage& st, auto slot_c) {
-    constexpr int S = decltype(slot_c)::value;
+  // The two roles run separate loops (so that a wave's registers hold either the accumulators or the prefetched
+  // tiles, not both) with the same number of barriers: one after the prologue, one per K-step.
+  if (wave >= 4) {
+    // ---- producers: per-thread slots of the global -> LDS copies
+    //   A: chunk q = tid + 256 j (j < 8): row q / 8, 16-byte column q % 8
+    //   B: block q = tid + 256 j (j < 2): column q / 4, K-block q % 4 (32 anchor bytes -> 16 bytes of E2M1)
+    //   scales: thread t one row of A (4 bytes); thread t < 128 also one column of W
+    // Rows / columns past the edge are clamped to the last valid one instead of branched around: their products
+    // land in outputs that are never stored, and straight-line code lets the loads of several K-steps stay in
+    // flight (the compiler counts outstanding loads exactly only without control flow).
+    constexpr int D = kGemmPrefetch;
+    const uint8_t* pa[kGemmAChunks];
+    const uint8_t* pw[2];
 #pragma unroll
     for (int j = 0; j < kGemmAChunks; ++j) {
       int q = tid + 256 * j, row = q >> 3, col = q & 7;
-      *reinterpret_cast<u32x4*>(&st.a[row * kGemmLdA + 16 * col]) = ra[S][j];
+      int m = m0 + row < M ? m0 + row : M - 1;
+      pa[j] = a_codes + (int64_t)m * K + 16 * col;
     }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       int q = tid + 256 * j, col = q >> 2, kb = q & 3;
-      uint32_t b4[4];
-      if constexpr (SKIP & 1) {
-        b4[0] = rb[S][j][0].x ^ rb[S][j][1].x; b4[1] = rb[S][j][0].y ^ rb[S][j][1].y;
-        b4[2] = rb[S][j][0].z ^ rb[S][j][1].z; b4[3] = rb[S][j][0].w ^ rb[S][j][1].w;
-      } else {
-        slice_block_e2m1(rb[S][j][0], rb[S][j][1], b4);   // Eq. (6) element step, once per workgroup and K-step
-      }
-      *reinterpret_cast<u32x4*>(&st.b[col * kGemmLdB + 16 * kb]) = u32x4{b4[0], b4[1], b4[2], b4[3]};
+      int n = n0 + col < N ? n0 + col : N - 1;
+      pw[j] = w_codes + (int64_t)n * K + 32 * kb;
     }
-    st.as[tid] = rsa[S];
-    if (tid < kGemmBN) st.bs[tid] = scale_add_x4(rsw[S], kDeltaE_E4M3_E2M1);   // Eq. (6) scale step
-  };
+    const uint8_t* psa = a_scales + (int64_t)(m0 + tid < M ? m0 + tid : M - 1) * KB;
+    const uint8_t* psw = w_scales + (int64_t)(n0 + (tid & 127) < N ? n0 + (tid & 127) : N - 1) * KB;
 
+    u32x4 ra[D][kGemmAChunks], rb[D][2][2];
+    uint32_t rsa[D], rsw[D];
+    auto load_global = [&](int ks, auto slot_c) {
+      constexpr int S = decltype(slot_c)::value;
+      const int k0 = ks * kGemmBK;
+      if (!(SKIP & 128) || ks < D) {
+#pragma unroll
+        for (int j = 0; j < kGemmAChunks; ++j) ra[S][j] = *reinterpret_cast<const u32x4*>(pa[j] + k0);
+      }
+      if (!(SKIP & 64) || ks < D) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const u32x4* p = reinterpret_cast<const u32x4*>(pw[j] + k0);
+          // plain loads: the 8 workgroups that share this W tile run on 8 different XCDs at about the same time,
+          // and non-temporal loads made each of them fetch it from HBM (269 us against 196 us for the kernel)
+          if constexpr (SKIP & 256) { rb[S][j][0] = __builtin_nontemporal_load(p); rb[S][j][1] = __builtin_nontemporal_load(p + 1); }
+          else { rb[S][j][0] = p[0]; rb[S][j][1] = p[1]; }
+        }
+      }
+      rsa[S] = *reinterpret_cast<const uint32_t*>(psa + ks * 4);
+      rsw[S] = *reinterpret_cast<const uint32_t*>(psw + ks * 4);
+    };
+    auto store_lds = [&](GemmStage& st, auto slot_c) {
+      constexpr int S = decltype(slot_c)::value;
+#pragma unroll
+      for (int j = 0; j < kGemmAChunks; ++j) {
+        int q = tid + 256 * j, row = q >> 3, col = q & 7;
+        *reinterpret_cast<u32x4*>(&st.a[row * kGemmLdA + 16 * col]) = ra[S][j];
+      }
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        int q = tid + 256 * j, col = q >> 2, kb = q & 3;
+        uint32_t b4[4];
+        if constexpr (SKIP & 1) {
+          b4[0] = rb[S][j][0].x ^ rb[S][j][1].x; b4[1] = rb[S][j][0].y ^ rb[S][j][1].y;
+          b4[2] = rb[S][j][0].z ^ rb[S][j][1].z; b4[3] = rb[S][j][0].w ^ rb[S][j][1].w;
+        } else {
+          slice_block_e2m1(rb[S][j][0], rb[S][j][1], b4);   // Eq. (6) element step, once per workgroup and K-step
+        }
+        *reinterpret_cast<u32x4*>(&st.b[col * kGemmLdB + 16 * kb]) = u32x4{b4[0], b4[1], b4[2], b4[3]};
+      }
+      st.as[tid] = rsa[S];
+      if (tid < kGemmBN) st.bs[tid] = scale_add_x4(rsw[S], kDeltaE_E4M3_E2M1);   // Eq. (6) scale step
+    };
+    // Software pipeline without branches around the loads (a branch makes the compiler wait for ALL outstanding
+    // loads): K-steps past the end are clamped to the last one, their data is loaded again and never used.
+    const int last = ksteps - 1;
+    auto clamp_ks = [&](int ks) { return ks < last ? ks : last; };
+    // prologue: K-steps 0 .. D-1 in flight, step 0 staged, step D in flight in its place
+    static_for<0, D>([&](auto d) { load_global(clamp_ks(decltype(d)::value), d); });
+    store_lds(stage[0], std::integral_constant<int, 0>{});
+    load_global(clamp_ks(D), std::integral_constant<int, 0>{});
+    __syncthreads();
+    // during K-step k the other stage is filled with step k + 1
+    const int rounds = ksteps / D;
+    for (int r = 0; r < rounds; ++r) {
+      static_for<0, D>([&](auto d) {
+        constexpr int DD = decltype(d)::value;
+        constexpr int NEXT = (DD + 1) % D;
+        const int k = r * D + DD;
+        if constexpr (!(SKIP & 2)) {
+          if constexpr (!(SKIP & 32)) store_lds(stage[(k + 1) & 1], std::integral_constant<int, NEXT>{});
+          if constexpr (!(SKIP & 8)) load_global(clamp_ks(k + 1 + D), std::integral_constant<int, NEXT>{});
+        }
+        __syncthreads();
+      });
+    }
+    // the K-steps left over when their number is not a multiple of D (at most D - 1; no more loads are needed)
+    static_for<0, D - 1>([&](auto d) {
+      constexpr int DD = decltype(d)::value;
+      const int k = rounds * D + DD;
+      if (k < ksteps) {
+        store_lds(stage[(k + 1) & 1], std::integral_constant<int, (DD + 1) % D>{});
+        __syncthreads();
+      }
+    });
+    return;
+  }
+
+  // ---- consumers
+  // A K-step is worked in groups of GM row tiles, with two sets of A-fragment registers: the reads of the next
+  // group are in flight while the MFMAs of the current one run, across the barrier too -- the barrier of K-step k
+  // sits before the MFMAs of its last group, when the last read of stage k & 1 has landed, and the first group
+  // of step k + 1 is read right after it.  The B fragments (single set) are replaced column tile by column tile
+  // inside the last group, as soon as the MFMAs that use them have been issued.  Scheduling barriers keep the
+  // compiler from moving the reads back to their uses.
+  const int wm = wave >> 1, wn = wave & 1;
+  constexpr int GM = MX_GEMM_GROUP, NG = kGemmMT / GM;
+  static_assert(NG % 2 == 0, "the two register sets must alternate with period one K-step");
   f32x4 acc[kGemmMT][kGemmNT];
 #pragma unroll
   for (int mt = 0; mt < kGemmMT; ++mt)
 #pragma unroll
     for (int nt = 0; nt < kGemmNT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-
+  const int a_off = (wm * 128 + i) * kGemmLdA + 16 * g;   // + mt * 16 rows
+  const int b_off = (wn * 64 + i) * kGemmLdB + 16 * g;    // + nt * 16 columns
+  i32x8 af[2][GM];   // two 16-byte runs of K per lane
+  uint32_t sa[2][GM], sb[kGemmNT];
   // B operands: only the low 4 dwords carry FP4 codes; the upper 4 stay zero for the whole kernel
   i32x8 bf[kGemmNT];
 #pragma unroll
   for (int nt = 0; nt < kGemmNT; ++nt) bf[nt] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
-  const int a_off = (wm * 128 + i) * kGemmLdA + 16 * g;   // + mt * 16 rows
-  const int b_off = (wn * 64 + i) * kGemmLdB + 16 * g;    // + nt * 16 columns
-  auto compute = [&](const GemmStage& cur_in) {
-    const GemmStage& cur = (SKIP & 2) ? stage[0] : cur_in;
-    int bsc[kGemmNT];
+  auto read_b = [&](const GemmStage& st, int nt) {
+    u32x4 t = *reinterpret_cast<const u32x4*>(&st.b[b_off + nt * 16 * kGemmLdB]);
+    bf[nt][0] = (int)t.x; bf[nt][1] = (int)t.y; bf[nt][2] = (int)t.z; bf[nt][3] = (int)t.w;
+    sb[nt] = st.bs[wn * 64 + nt * 16 + i] >> (8 * g);   // the instruction reads the low byte
+  };
+  auto read_a = [&](const GemmStage& st, auto group_c) {
+    constexpr int G = decltype(group_c)::value, SET = G & 1;
 #pragma unroll
-    for (int nt = 0; nt < kGemmNT; ++nt) {
-      u32x4 t = *reinterpret_cast<const u32x4*>(&cur.b[b_off + nt * 16 * kGemmLdB]);
-      bf[nt][0] = (int)t.x; bf[nt][1] = (int)t.y; bf[nt][2] = (int)t.z; bf[nt][3] = (int)t.w;
-      bsc[nt] = (int)(cur.bs[wn * 64 + nt * 16 + i] >> (8 * g));   // the instruction reads the low byte
-    }
-#pragma unroll
-    for (int mt = 0; mt < kGemmMT; ++mt) {
-      u32x4 t0 = *reinterpret_cast<const u32x4*>(&cur.a[a_off + mt * 16 * kGemmLdA]);
-      u32x4 t1 = *reinterpret_cast<const u32x4*>(&cur.a[a_off + mt * 16 * kGemmLdA + 64]);
-      i32x8 af = {(int)t0.x, (int)t0.y, (int)t0.z, (int)t0.w, (int)t1.x, (int)t1.y, (int)t1.z, (int)t1.w};
-      int asc = (int)(cur.as[wm * 128 + mt * 16 + i] >> (8 * g));
-#pragma unroll
-      for (int nt = 0; nt < kGemmNT; ++nt) {
-        if constexpr (SKIP & 4) {
-          acc[mt][nt][0] += __int_as_float(af[0] ^ bf[nt][0] ^ asc); acc[mt][nt][1] += __int_as_float(af[7] ^ bf[nt][3] ^ bsc[nt]);
-        } else {
-          acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af, bf[nt], acc[mt][nt], 0, 4, 0, asc, 0, bsc[nt]);
-        }
-      }
+    for (int m = 0; m < GM; ++m) {
+      const int mt = G * GM + m;
+      u32x4 t0 = *reinterpret_cast<const u32x4*>(&st.a[a_off + mt * 16 * kGemmLdA]);
+      u32x4 t1 = *reinterpret_cast<const u32x4*>(&st.a[a_off + mt * 16 * kGemmLdA + 64]);
+      af[SET][m] = i32x8{(int)t0.x, (int)t0.y, (int)t0.z, (int)t0.w, (int)t1.x, (int)t1.y, (int)t1.z, (int)t1.w};
+      sa[SET][m] = st.as[wm * 128 + mt * 16 + i] >> (8 * g);   // the instruction reads the low byte
     }
   };
-
-  // Software pipeline without branches around the loads (a branch makes the compiler wait for ALL outstanding
-  // loads): K-steps past the end are clamped to the last one, their data is loaded again and never used.
-  const int last = ksteps - 1;
-  auto clamp_ks = [&](int ks) { return ks < last ? ks : last; };
-  // prologue: K-steps 0 .. D-1 in flight, step 0 staged, step D in flight in its place
-  static_for<0, D>([&](auto d) { load_global(clamp_ks(decltype(d)::value), d); });
-  store_lds(stage[0], std::integral_constant<int, 0>{});
-  load_global(clamp_ks(D), std::integral_constant<int, 0>{});
-  __syncthreads();
-  const int rounds = ksteps / D;
-  for (int r = 0; r < rounds; ++r) {
-    static_for<0, D>([&](auto d) {
-      constexpr int DD = decltype(d)::value;
-      constexpr int NEXT = (DD + 1) % D;
-      const int k = r * D + DD;
-      compute(stage[k & 1]);
-      store_lds(stage[(k + 1) & 1], std::integral_constant<int, NEXT>{});
-      if constexpr (!(SKIP & 8)) load_global(clamp_ks(k + 1 + D), std::integral_constant<int, NEXT>{});
-      __syncthreads();
-    });
-  }
-  // the K-steps left over when their number is not a multiple of D (at most D - 1; no more loads are needed)
-  static_for<0, D - 1>([&](auto d) {
-    constexpr int DD = decltype(d)::value;
-    const int k = rounds * D + DD;
-    if (k < ksteps) {
-      compute(stage[k & 1]);
-      store_lds(stage[(k + 1) & 1], std::integral_constant<int, (DD + 1) % D>{});
-      __syncthreads();
+  auto mfma_one = [&](auto group_c, int m, int nt) {
+    constexpr int G = decltype(group_c)::value, SET = G & 1;
+    const int mt = G * GM + m;
+    if constexpr (SKIP & 4) {
+      acc[mt][nt][0] += __int_as_float(af[SET][m][0] ^ bf[nt][0] ^ (int)sa[SET][m]);
+      acc[mt][nt][1] += __int_as_float(af[SET][m][7] ^ bf[nt][3] ^ (int)sb[nt]);
+    } else {
+      acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af[SET][m], bf[nt], acc[mt][nt], 0, 4, 0, (int)sa[SET][m],
+                                                                     0, (int)sb[nt]);
     }
-  });
+  };
+  __syncthreads();   // stage 0 is filled
+#pragma unroll
+  for (int nt = 0; nt < kGemmNT; ++nt) read_b(stage[0], nt);
+  read_a(stage[0], std::integral_constant<int, 0>{});
+  __builtin_amdgcn_sched_barrier(0);
+  for (int k = 0; k < ksteps; ++k) {
+    const GemmStage& cur = stage[(SKIP & 16) ? 0 : (k & 1)];
+    const GemmStage& nxt = stage[(SKIP & 16) ? 0 : ((k + 1) & 1)];
+    static_for<0, NG - 1>([&](auto gc) {
+      constexpr int G = decltype(gc)::value;
+      read_a(cur, std::integral_constant<int, G + 1>{});
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int m = 0; m < GM; ++m)
+#pragma unroll
+        for (int nt = 0; nt < kGemmNT; ++nt) mfma_one(gc, m, nt);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    __syncthreads();   // every read of this stage has landed; the producers have filled the other stage
+    read_a(nxt, std::integral_constant<int, 0>{});   // (after the last K-step: a read of stale data that nothing uses)
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int nt = 0; nt < kGemmNT; ++nt) {
+#pragma unroll
+      for (int m = 0; m < GM; ++m) mfma_one(std::integral_constant<int, NG - 1>{}, m, nt);
+      __builtin_amdgcn_sched_barrier(0);
+      read_b(nxt, nt);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
 #pragma unroll
   for (int mt = 0; mt < kGemmMT; ++mt)
 #pragma unroll
@@ -386,7 +456,7 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
         return MX_ERR_LAUNCH;
       attr_set = true;
     }
-    hipLaunchKernelGGL(gemm_ss_fp4_tiled_kernel<0>, dim3((unsigned)(m_tiles * n_tiles)), dim3(256), kSmem, stream, a_codes,
+    hipLaunchKernelGGL(gemm_ss_fp4_tiled_kernel<0>, dim3((unsigned)(m_tiles * n_tiles)), dim3(kGemmThreads), kSmem, stream, a_codes,
                        a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles);
     return hipGetLastError() == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
   }
