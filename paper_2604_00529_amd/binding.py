@@ -49,6 +49,10 @@ def lib():
         if not os.path.exists(_LIB_PATH):
             raise RuntimeError("libmx.so is missing: build it with `python -m paper_2604_00529_amd.build` "
                                "(there is no fallback path)")
+        # torch first: it brings its own copy of the HIP runtime, and the kernels of libmx.so must be registered
+        # with that same runtime (the one that owns the tensors' memory and streams).  Loaded the other way round,
+        # libmx.so binds to the system's runtime and its launches fail with "no ROCm-capable device".
+        import torch  # noqa: F401
         L = ctypes.CDLL(_LIB_PATH)
         P = ctypes.POINTER
         vp, st = ctypes.c_void_p, ctypes.c_int

@@ -2,6 +2,7 @@
 // Nothing here allocates, frees or synchronizes; a call that fails validation launches nothing.
 #include "mx_device.h"
 #include "mx_launch.h"
+#include <cstdio>
 
 namespace {
 
@@ -84,6 +85,20 @@ mx_status_t check_ss_pair(const mx_format_t* fa, const mx_format_t* ft, ElemInfo
 
 }  // namespace
 
+// hipGetLastError() after a launch also reports an error that an earlier, unrelated runtime call of this thread left
+// behind (another library's event query that was "not ready", for instance).  Every entry point drops such a stale
+// error before its first launch, so that MX_ERR_LAUNCH always means one of this library's own launches failed.
+static inline void drop_stale_error() { (void)hipGetLastError(); }
+
+namespace mx {
+mx_status_t launch_status(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return MX_OK;
+  fprintf(stderr, "libmx: launch of %s failed: %s\n", what, hipGetErrorString(e));
+  return MX_ERR_LAUNCH;
+}
+}  // namespace mx
+
 extern "C" {
 
 int mx_elem_bits(mx_elem_t elem) {
@@ -120,6 +135,7 @@ mx_status_t mx_quantize(const mx_format_t* f, const mx_dense_t* src, const mx_pa
   if (outer != dst->outer || nblocks != dst->nblocks) return MX_ERR_SHAPE;
   if (outer == 0 || nblocks == 0) return MX_OK;
   mx::DenseArg s{src->data, (int)src->dtype, src->rows, src->cols, src->ld};
+  drop_stale_error();
   return mx::quantize_launch((int)f->elem, f->axis, (int)f->round, s, dst->codes, dst->scales, static_cast<hipStream_t>(stream));
 }
 
@@ -161,6 +177,7 @@ mx_status_t mx_slice_and_scale_multi(const mx_format_t* fa, const mx_packed_t* a
     t.codes_l[q] = targets[q].codes; t.scales_l[q] = targets[q].scales;
   }
   if (nb == 0) return MX_OK;
+  drop_stale_error();
   return mx::ss_launch_one((int)fa->elem, tg, hw, t, (int)fts[0].round, static_cast<hipStream_t>(stream));
 }
 
@@ -200,6 +217,7 @@ mx_status_t mx_slice_and_scale_multi_batched(const mx_format_t* fa, int32_t n_ta
     }
     t[(size_t)i] = d;
   }
+  drop_stale_error();
   return mx::ss_launch_many((int)fa->elem, tg, hw, n, t.data(), workspace, workspace_bytes, (int)fts[0].round,
                             static_cast<hipStream_t>(stream));
 }
@@ -233,6 +251,7 @@ mx_status_t mx_fake_quant(const mx_format_t* target, const mx_format_t* anchor, 
   if (outer == 0 || nblocks == 0) return MX_OK;
   mx::DenseArg s{src->data, (int)src->dtype, src->rows, src->cols, src->ld};
   mx::DenseArg d{dst->data, (int)dst->dtype, dst->rows, dst->cols, dst->ld};
+  drop_stale_error();
   return mx::fake_quant_launch((int)target->elem, anchor_elem, target->axis, (int)target->round, s, d,
                                static_cast<hipStream_t>(stream));
 }
@@ -248,6 +267,7 @@ mx_status_t mx_dequant(const mx_format_t* f, const mx_packed_t* src, const mx_de
   if (outer != src->outer || nblocks != src->nblocks) return MX_ERR_SHAPE;
   if (outer == 0 || nblocks == 0) return MX_OK;
   mx::DenseArg d{dst->data, (int)dst->dtype, dst->rows, dst->cols, dst->ld};
+  drop_stale_error();
   return mx::dequant_launch((int)f->elem, f->axis, src->codes, src->scales, d, static_cast<hipStream_t>(stream));
 }
 
@@ -261,6 +281,7 @@ mx_status_t mx_gemm_ss_fp4(const mx_packed_t* a, const mx_packed_t* w_anchor, co
   if (c->rows == 0 || c->cols == 0) return MX_OK;
   const int64_t K = a->nblocks * 32;
   if (K == 0 || K % 128 != 0 || K > 0x7FFFFFFF || c->rows > 0x7FFFFFFF || c->cols > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+  drop_stale_error();
   return mx::gemm_ss_fp4_launch(static_cast<const uint8_t*>(a->codes), a->scales, static_cast<const uint8_t*>(w_anchor->codes),
                                 w_anchor->scales, static_cast<float*>(c->data), c->rows, c->cols, K, c->ld,
                                 static_cast<hipStream_t>(stream));

@@ -614,7 +614,6 @@ constexpr RowsShape dequant_shape() {
 constexpr int kFqUnroll = 1;                  // fake-quant: one chunk per lane, one wave per workgroup (82 - 83)
 constexpr int kFqThreads = MX_FQ_THREADS;
 
-static inline bool launch_ok() { return hipGetLastError() == hipSuccess; }
 
 template <int ELEM, bool HW, int DT>
 static mx_status_t run_quantize(int axis, int tie, const DenseArg& s, void* codes, uint8_t* scales, hipStream_t st) {
@@ -635,7 +634,7 @@ static mx_status_t run_quantize(int axis, int tie, const DenseArg& s, void* code
     hipLaunchKernelGGL((quantize_cols_kernel<ELEM, HW, DT>), dim3((unsigned)(cgs * rbgs)), dim3(256), 0, st, s.data,
                        static_cast<uint32_t*>(codes), scales, s.cols, (uint32_t)cgs, s.ld, nrb, tie);
   }
-  return launch_ok() ? MX_OK : MX_ERR_LAUNCH;
+  return launch_status("a dense kernel");
 }
 
 template <int ELEM, int DT>
@@ -657,7 +656,7 @@ static mx_status_t run_dequant(int axis, const void* codes, const uint8_t* scale
     hipLaunchKernelGGL((dequant_cols_kernel<ELEM, DT>), dim3((unsigned)(cgs * rbgs)), dim3(256), 0, st,
                        static_cast<const uint32_t*>(codes), scales, d.data, d.cols, (uint32_t)cgs, d.ld, nrb);
   }
-  return launch_ok() ? MX_OK : MX_ERR_LAUNCH;
+  return launch_status("a dense kernel");
 }
 
 template <int TARGET, int ANCHOR, bool HW, int DT>
@@ -680,7 +679,7 @@ static mx_status_t run_fake_quant(int axis, int tie, const DenseArg& s, const De
     hipLaunchKernelGGL((fake_quant_cols_kernel<TARGET, ANCHOR, HW, DT, kFqColsThreads>), dim3((unsigned)wgs), dim3(kFqColsThreads), 0, st, s.data, d.data,
                        nitems, (uint32_t)qpr, s.ld, d.ld, tie);
   }
-  return launch_ok() ? MX_OK : MX_ERR_LAUNCH;
+  return launch_status("a dense kernel");
 }
 
 // ---- runtime -> template dispatch

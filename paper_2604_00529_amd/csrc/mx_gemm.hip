@@ -458,7 +458,7 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
     }
     hipLaunchKernelGGL(gemm_ss_fp4_tiled_kernel<0>, dim3((unsigned)(m_tiles * n_tiles)), dim3(kGemmThreads), kSmem, stream, a_codes,
                        a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles);
-    return hipGetLastError() == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
+    return launch_status("the fused GEMM");
   }
   const unsigned grid = (unsigned)((N + 16 * kSmallmNT - 1) / (16 * kSmallmNT));
   const int mt = (int)((M + 15) / 16);
@@ -469,7 +469,7 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
   }
   MX_GEMM_CASE(1) MX_GEMM_CASE(2) MX_GEMM_CASE(3) MX_GEMM_CASE(4)
 #undef MX_GEMM_CASE
-  return hipGetLastError() == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
+  return launch_status("the fused GEMM");
 }
 
 }  // namespace mx

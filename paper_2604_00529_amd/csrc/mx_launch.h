@@ -9,6 +9,9 @@
 
 namespace mx {
 
+// Status of the launch just made; a failure is reported on stderr with the runtime's own message.
+mx_status_t launch_status(const char* what);
+
 // One tensor of a Slice-and-Scale launch (device pointers): one anchor, up to kSsMaxTargets targets
 // converted in the same pass.
 constexpr int kSsMaxTargets = 3;

@@ -282,7 +282,7 @@ static mx_status_t launch_ss(const SsTensor& t, int tie, hipStream_t stream) {
   a.codes_h = t.codes_h; a.scales_h = t.scales_h; a.nblocks = t.nblocks; a.code_wgs = cw;
   for (int q = 0; q < kSsMaxTargets; ++q) { a.codes_l[q] = t.codes_l[q]; a.scales_l[q] = t.scales_l[q]; }
   hipLaunchKernelGGL((ss_kernel<ANCHOR, HW, TARGETS...>), dim3((unsigned)(cw + sw)), dim3(kSsLanes), 0, stream, a, tie);
-  return hipGetLastError() == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
+  return launch_status("a Slice-and-Scale kernel");
 }
 
 template <int ANCHOR, bool HW, int... TARGETS>
@@ -298,7 +298,7 @@ static mx_status_t launch_ss_batched(const SsSegment* segs, int64_t nseg, int se
   constexpr unsigned occupancy_pad = sizeof...(TARGETS) >= 3 ? MX_SS_PAD : 0;
   hipLaunchKernelGGL((ss_batched_kernel<ANCHOR, HW, TARGETS...>), dim3((unsigned)(nseg << seg_shift)), dim3(kSsLanes), occupancy_pad, stream,
                      segs, (int)nseg, seg_shift, ahead, tie);
-  return hipGetLastError() == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
+  return launch_status("a Slice-and-Scale kernel");
 }
 
 // Dispatch on (anchor, target list, hw path) -> instantiated launcher.  Single targets: every narrower format of
@@ -431,7 +431,7 @@ mx_status_t ss_launch_many(int anchor, const SsTargets& tg, bool hw, int n, cons
     if (acc > 0) {
       hipLaunchKernelGGL(ss_segments_kernel, dim3((unsigned)ceil_div(acc, 256)), dim3(256), 0, stream, chunk, segs, (int)acc, pb,
                          seg_shift);
-      if (hipGetLastError() != hipSuccess) return MX_ERR_LAUNCH;
+      if (launch_status("the segment table writer") != MX_OK) return MX_ERR_LAUNCH;
     }
     seg0 += acc;
   }
