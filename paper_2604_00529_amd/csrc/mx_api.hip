@@ -34,7 +34,7 @@ mx_status_t check_format(const mx_format_t* f, ElemInfo* info) {
   if ((int)f->round < MX_ROUND_DEFAULT || (int)f->round > MX_ROUND_HALF_EVEN) return MX_ERR_FORMAT;
   if (f->axis != 0 && f->axis != 1) return MX_ERR_SHAPE;
   if (f->block <= 0) return MX_ERR_SHAPE;
-  if (f->block != 32) return MX_ERR_UNSUPPORTED;
+  if (f->block != 16 && f->block != 32 && f->block != 64 && f->block != 128) return MX_ERR_UNSUPPORTED;
   return MX_OK;
 }
 
@@ -136,7 +136,8 @@ mx_status_t mx_quantize(const mx_format_t* f, const mx_dense_t* src, const mx_pa
   if (outer == 0 || nblocks == 0) return MX_OK;
   mx::DenseArg s{src->data, (int)src->dtype, src->rows, src->cols, src->ld};
   drop_stale_error();
-  return mx::quantize_launch((int)f->elem, f->axis, (int)f->round, s, dst->codes, dst->scales, static_cast<hipStream_t>(stream));
+  if (f->axis == 0 && f->block != 32) return MX_ERR_UNSUPPORTED;   // column blocks: 32 rows only
+  return mx::quantize_launch((int)f->elem, f->axis, f->block, (int)f->round, s, dst->codes, dst->scales, static_cast<hipStream_t>(stream));
 }
 
 // Validate an anchor format with n target formats; fill the launch's target list.
@@ -178,7 +179,7 @@ mx_status_t mx_slice_and_scale_multi(const mx_format_t* fa, const mx_packed_t* a
   }
   if (nb == 0) return MX_OK;
   drop_stale_error();
-  return mx::ss_launch_one((int)fa->elem, tg, hw, t, (int)fts[0].round, static_cast<hipStream_t>(stream));
+  return mx::ss_launch_one((int)fa->elem, tg, hw, t, fa->block, (int)fts[0].round, static_cast<hipStream_t>(stream));
 }
 
 mx_status_t mx_slice_and_scale(const mx_format_t* fa, const mx_packed_t* anchor, const mx_format_t* ft,
@@ -218,7 +219,7 @@ mx_status_t mx_slice_and_scale_multi_batched(const mx_format_t* fa, int32_t n_ta
     t[(size_t)i] = d;
   }
   drop_stale_error();
-  return mx::ss_launch_many((int)fa->elem, tg, hw, n, t.data(), workspace, workspace_bytes, (int)fts[0].round,
+  return mx::ss_launch_many((int)fa->elem, tg, hw, n, t.data(), fa->block, workspace, workspace_bytes, (int)fts[0].round,
                             static_cast<hipStream_t>(stream));
 }
 
@@ -252,7 +253,8 @@ mx_status_t mx_fake_quant(const mx_format_t* target, const mx_format_t* anchor, 
   mx::DenseArg s{src->data, (int)src->dtype, src->rows, src->cols, src->ld};
   mx::DenseArg d{dst->data, (int)dst->dtype, dst->rows, dst->cols, dst->ld};
   drop_stale_error();
-  return mx::fake_quant_launch((int)target->elem, anchor_elem, target->axis, (int)target->round, s, d,
+  if (target->axis == 0 && target->block != 32) return MX_ERR_UNSUPPORTED;   // column blocks: 32 rows only
+  return mx::fake_quant_launch((int)target->elem, anchor_elem, target->axis, target->block, (int)target->round, s, d,
                                static_cast<hipStream_t>(stream));
 }
 
@@ -268,7 +270,8 @@ mx_status_t mx_dequant(const mx_format_t* f, const mx_packed_t* src, const mx_de
   if (outer == 0 || nblocks == 0) return MX_OK;
   mx::DenseArg d{dst->data, (int)dst->dtype, dst->rows, dst->cols, dst->ld};
   drop_stale_error();
-  return mx::dequant_launch((int)f->elem, f->axis, src->codes, src->scales, d, static_cast<hipStream_t>(stream));
+  if (f->axis == 0 && f->block != 32) return MX_ERR_UNSUPPORTED;   // column blocks: 32 rows only
+  return mx::dequant_launch((int)f->elem, f->axis, f->block, src->codes, src->scales, d, static_cast<hipStream_t>(stream));
 }
 
 mx_status_t mx_gemm_ss_fp4(const mx_packed_t* a, const mx_packed_t* w_anchor, const mx_dense_t* c, void* stream) {

@@ -112,6 +112,23 @@ __device__ __forceinline__ uint32_t group_max(uint32_t m) {
   return m;
 }
 
+// the same for a block size chosen at run time: `lanes` = 2, 4, 8, 16 or 32 adjacent lanes per block (wave-uniform)
+constexpr int DPP_ROW_MIRROR = 0x140;  // lane i <-> 15 - i inside each row of 16
+__device__ __forceinline__ uint32_t group_max_lanes(uint32_t m, int lanes) {
+  uint32_t o = dpp<DPP_XOR1>(m); m = m > o ? m : o;
+  if (lanes >= 4) { o = dpp<DPP_XOR2>(m); m = m > o ? m : o; }
+  if (lanes >= 8) { o = dpp<DPP_HALF_MIRROR>(m); m = m > o ? m : o; }
+  if (lanes >= 16) { o = dpp<DPP_ROW_MIRROR>(m); m = m > o ? m : o; }
+  if (lanes >= 32) { o = (uint32_t)__shfl_xor((int)m, 16, 64); m = m > o ? m : o; }
+  return m;
+}
+// KG = false: blocks of 32 (group size known at compile time); KG = true: 2^log2_lanes lanes per block
+template <int G, bool KG>
+__device__ __forceinline__ uint32_t block_max(uint32_t m, int log2_lanes) {
+  if constexpr (KG) return group_max_lanes(m, 1 << log2_lanes);
+  else return group_max<G>(m);
+}
+
 template <int N>
 __device__ __forceinline__ uint32_t chunk_amax_bits(const float (&v)[N]) {
   uint32_t m = 0;
@@ -166,10 +183,14 @@ __device__ __forceinline__ void store_chunk_codes(uint32_t* block_words, uint64_
 
 constexpr bool direct_code_store(int nb) { return nb == 64 || nb == 32 || nb == 16 || nb == 24 || nb == 48; }
 
-template <int ELEM, bool HW, int DT, int U, int TPB>
+// Block sizes other than 32 (KG): the codes of a row are one bit string whatever the block size, so they are packed
+// and stored in windows of 32 codes exactly as for k = 32; only the lanes that share a maximum, and the index of the
+// scale byte, follow the block size (2^log2_lanes lanes of N elements).
+template <int ELEM, bool HW, int DT, int U, int TPB, bool KG>
 __global__ __launch_bounds__(TPB) void quantize_rows_kernel(const void* __restrict__ src, uint32_t* __restrict__ codes,
                                                             uint8_t* __restrict__ scales, int64_t nchunks,
-                                                            uint32_t chunks_per_row, int64_t ld, int flat, int tie) {
+                                                            uint32_t chunks_per_row, int64_t ld, int flat, int tie,
+                                                            int log2_lanes) {
   using E = Elem<ELEM>;
   constexpr int N = Dense<DT>::N, G = 32 / N, W = E::bits;
   __shared__ uint32_t stage[direct_code_store(N * W) ? 1 : TPB * U * (N / 4)];
@@ -188,15 +209,16 @@ __global__ __launch_bounds__(TPB) void quantize_rows_kernel(const void* __restri
       for (int i = 0; i < N; ++i) v[u][i] = 0.0f;
     }
   }
-  const int lig = tid & (G - 1);
+  const int lig = tid & (G - 1);                                  // lane inside its window of 32 codes
+  const int lane_in_block = KG ? (tid & ((1 << log2_lanes) - 1)) : lig;
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     int64_t q = q0 + TPB * u;
-    uint32_t byte = scale_byte_from_amax<E::emax>(group_max<G>(chunk_amax_bits(v[u])));
+    uint32_t byte = scale_byte_from_amax<E::emax>(block_max<G, KG>(chunk_amax_bits(v[u]), log2_lanes));
     uint64_t bits = byte == 255u ? 0ull : encode_chunk<ELEM, HW, N>(v[u], byte, tie);
-    int64_t blk = q / G;  // blocks are numbered like the chunks: row-major
+    int64_t blk = q / G;  // windows of 32 codes are numbered like the chunks: row-major
     if constexpr (direct_code_store(N * W)) {
-      // a block's lanes are all live or all not (chunks per row is a multiple of the group size)
+      // a window's lanes are all live or all not (chunks per row is a multiple of the group size)
       if (live[u]) store_chunk_codes<W, N>(codes + blk * W, bits, lig);
     } else {
       // odd widths: stage one byte per code, repack one block per lane below
@@ -211,7 +233,7 @@ __global__ __launch_bounds__(TPB) void quantize_rows_kernel(const void* __restri
 #pragma unroll
       for (int i = 0; i < N / 4; ++i) stage[(u * TPB + tid) * (N / 4) + i] = b4[i];
     }
-    if (live[u] && lig == 0) scales[blk] = (uint8_t)byte;
+    if (live[u] && lane_in_block == 0) scales[KG ? (q >> log2_lanes) : blk] = (uint8_t)byte;
   }
   if constexpr (!direct_code_store(N * W)) {
     __syncthreads();
@@ -258,10 +280,10 @@ __device__ __forceinline__ uint64_t load_chunk_codes(const uint32_t* block_words
   }
 }
 
-template <int ELEM, int DT, int U, int TPB>
+template <int ELEM, int DT, int U, int TPB, bool KG>
 __global__ __launch_bounds__(TPB) void dequant_rows_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restrict__ scales,
                                                            void* __restrict__ dst, int64_t nchunks, uint32_t chunks_per_row,
-                                                           int64_t ld, int flat) {
+                                                           int64_t ld, int flat, int log2_lanes) {
   using E = Elem<ELEM>;
   constexpr int N = Dense<DT>::N, G = 32 / N, W = E::bits;
   constexpr bool HW = E::hw != HW_NONE;
@@ -275,9 +297,9 @@ __global__ __launch_bounds__(TPB) void dequant_rows_kernel(const uint32_t* __res
     int64_t q = q0 + TPB * u;
     bits[u] = 0; byte[u] = 0;
     if (q < nchunks) {
-      int64_t blk = q / G;
+      int64_t blk = q / G;   // window of 32 codes
       bits[u] = load_chunk_codes<W, N>(codes + blk * W, lig);
-      byte[u] = scales[blk];
+      byte[u] = scales[KG ? (q >> log2_lanes) : blk];
     }
   }
 #pragma unroll
@@ -338,10 +360,11 @@ __device__ __forceinline__ void fake_quant_chunk(float (&v)[N], uint32_t byte_fi
 template <int TARGET, int ANCHOR>
 struct FirstFormat { static constexpr int elem = ANCHOR < 0 ? TARGET : ANCHOR; };
 
-template <int TARGET, int ANCHOR, bool HW, int DT, int U, int TPB>
+template <int TARGET, int ANCHOR, bool HW, int DT, int U, int TPB, bool KG>
 __global__ __launch_bounds__(TPB) void fake_quant_rows_kernel(const void* __restrict__ src, void* __restrict__ dst,
                                                               int64_t nchunks, uint32_t chunks_per_row, int64_t ld_src,
-                                                              int64_t ld_dst, int flat_src, int flat_dst, int tie) {
+                                                              int64_t ld_dst, int flat_src, int flat_dst, int tie,
+                                                              int log2_lanes) {
   constexpr int FIRST = FirstFormat<TARGET, ANCHOR>::elem;
   constexpr int N = Dense<DT>::N, G = 32 / N;
   int tid = threadIdx.x;
@@ -360,7 +383,7 @@ __global__ __launch_bounds__(TPB) void fake_quant_rows_kernel(const void* __rest
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     int64_t q = q0 + TPB * u;
-    uint32_t byte = scale_byte_from_amax<Elem<FIRST>::emax>(group_max<G>(chunk_amax_bits(v[u])));
+    uint32_t byte = scale_byte_from_amax<Elem<FIRST>::emax>(block_max<G, KG>(chunk_amax_bits(v[u]), log2_lanes));
     fake_quant_chunk<TARGET, ANCHOR, HW, N>(v[u], byte, tie);
     if (q < nchunks) store_chunk<DT>(dst, chunk_offset<N>(q, chunks_per_row, ld_dst, flat_dst), v[u]);
   }
@@ -615,8 +638,15 @@ constexpr int kFqUnroll = 1;                  // fake-quant: one chunk per lane,
 constexpr int kFqThreads = MX_FQ_THREADS;
 
 
+// lanes of N elements per block of `block` elements, as a power of two (block = 16 .. 128, N = 4 or 8)
+static inline int log2_lanes_of(int block, int n) {
+  int lanes = block / n, l = 0;
+  while ((1 << l) < lanes) ++l;
+  return l;
+}
+
 template <int ELEM, bool HW, int DT>
-static mx_status_t run_quantize(int axis, int tie, const DenseArg& s, void* codes, uint8_t* scales, hipStream_t st) {
+static mx_status_t run_quantize(int axis, int block, int tie, const DenseArg& s, void* codes, uint8_t* scales, hipStream_t st) {
   if (axis == 1) {
     constexpr int N = Dense<DT>::N;
     int64_t cpr = s.cols / N, nchunks = s.rows * cpr;
@@ -624,8 +654,13 @@ static mx_status_t run_quantize(int axis, int tie, const DenseArg& s, void* code
     constexpr RowsShape shape = quantize_shape<ELEM>();
     int64_t wgs = (nchunks + shape.threads * shape.unroll - 1) / (shape.threads * shape.unroll);
     if (wgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((quantize_rows_kernel<ELEM, HW, DT, shape.unroll, shape.threads>), dim3((unsigned)wgs), dim3(shape.threads), 0, st, s.data,
-                       static_cast<uint32_t*>(codes), scales, nchunks, (uint32_t)cpr, s.ld, (int)(s.ld == s.cols), tie);
+    if (block == 32)
+      hipLaunchKernelGGL((quantize_rows_kernel<ELEM, HW, DT, shape.unroll, shape.threads, false>), dim3((unsigned)wgs), dim3(shape.threads), 0, st,
+                         s.data, static_cast<uint32_t*>(codes), scales, nchunks, (uint32_t)cpr, s.ld, (int)(s.ld == s.cols), tie, 0);
+    else
+      hipLaunchKernelGGL((quantize_rows_kernel<ELEM, HW, DT, shape.unroll, shape.threads, true>), dim3((unsigned)wgs), dim3(shape.threads), 0, st,
+                         s.data, static_cast<uint32_t*>(codes), scales, nchunks, (uint32_t)cpr, s.ld, (int)(s.ld == s.cols), tie,
+                         log2_lanes_of(block, N));
   } else {
     if (s.cols % 4) return MX_ERR_UNSUPPORTED;
     int64_t nrb = s.rows / 32;
@@ -638,7 +673,7 @@ static mx_status_t run_quantize(int axis, int tie, const DenseArg& s, void* code
 }
 
 template <int ELEM, int DT>
-static mx_status_t run_dequant(int axis, const void* codes, const uint8_t* scales, const DenseArg& d, hipStream_t st) {
+static mx_status_t run_dequant(int axis, int block, const void* codes, const uint8_t* scales, const DenseArg& d, hipStream_t st) {
   if (axis == 1) {
     constexpr int N = Dense<DT>::N;
     int64_t cpr = d.cols / N, nchunks = d.rows * cpr;
@@ -646,8 +681,13 @@ static mx_status_t run_dequant(int axis, const void* codes, const uint8_t* scale
     constexpr RowsShape shape = dequant_shape<ELEM>();
     int64_t wgs = (nchunks + shape.threads * shape.unroll - 1) / (shape.threads * shape.unroll);
     if (wgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((dequant_rows_kernel<ELEM, DT, shape.unroll, shape.threads>), dim3((unsigned)wgs), dim3(shape.threads), 0, st,
-                       static_cast<const uint32_t*>(codes), scales, d.data, nchunks, (uint32_t)cpr, d.ld, (int)(d.ld == d.cols));
+    if (block == 32)
+      hipLaunchKernelGGL((dequant_rows_kernel<ELEM, DT, shape.unroll, shape.threads, false>), dim3((unsigned)wgs), dim3(shape.threads), 0, st,
+                         static_cast<const uint32_t*>(codes), scales, d.data, nchunks, (uint32_t)cpr, d.ld, (int)(d.ld == d.cols), 0);
+    else
+      hipLaunchKernelGGL((dequant_rows_kernel<ELEM, DT, shape.unroll, shape.threads, true>), dim3((unsigned)wgs), dim3(shape.threads), 0, st,
+                         static_cast<const uint32_t*>(codes), scales, d.data, nchunks, (uint32_t)cpr, d.ld, (int)(d.ld == d.cols),
+                         log2_lanes_of(block, N));
   } else {
     if (d.cols % 4) return MX_ERR_UNSUPPORTED;
     int64_t nrb = d.rows / 32;
@@ -660,15 +700,20 @@ static mx_status_t run_dequant(int axis, const void* codes, const uint8_t* scale
 }
 
 template <int TARGET, int ANCHOR, bool HW, int DT>
-static mx_status_t run_fake_quant(int axis, int tie, const DenseArg& s, const DenseArg& d, hipStream_t st) {
+static mx_status_t run_fake_quant(int axis, int block, int tie, const DenseArg& s, const DenseArg& d, hipStream_t st) {
   if (axis == 1) {
     constexpr int N = Dense<DT>::N;
     int64_t cpr = s.cols / N, nchunks = s.rows * cpr;
     if (cpr > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;
     int64_t wgs = (nchunks + kFqThreads * kFqUnroll - 1) / (kFqThreads * kFqUnroll);
     if (wgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((fake_quant_rows_kernel<TARGET, ANCHOR, HW, DT, kFqUnroll, kFqThreads>), dim3((unsigned)wgs), dim3(kFqThreads), 0, st,
-                       s.data, d.data, nchunks, (uint32_t)cpr, s.ld, d.ld, (int)(s.ld == s.cols), (int)(d.ld == d.cols), tie);
+    if (block == 32)
+      hipLaunchKernelGGL((fake_quant_rows_kernel<TARGET, ANCHOR, HW, DT, kFqUnroll, kFqThreads, false>), dim3((unsigned)wgs), dim3(kFqThreads), 0,
+                         st, s.data, d.data, nchunks, (uint32_t)cpr, s.ld, d.ld, (int)(s.ld == s.cols), (int)(d.ld == d.cols), tie, 0);
+    else
+      hipLaunchKernelGGL((fake_quant_rows_kernel<TARGET, ANCHOR, HW, DT, kFqUnroll, kFqThreads, true>), dim3((unsigned)wgs), dim3(kFqThreads), 0,
+                         st, s.data, d.data, nchunks, (uint32_t)cpr, s.ld, d.ld, (int)(s.ld == s.cols), (int)(d.ld == d.cols), tie,
+                         log2_lanes_of(block, N));
   } else {
     if (s.cols % 4) return MX_ERR_UNSUPPORTED;
     int64_t qpr = s.cols / 4, nrb = s.rows / 32, nitems = qpr * nrb;
@@ -689,27 +734,29 @@ static mx_status_t run_fake_quant(int axis, int tie, const DenseArg& s, const De
 
 static inline bool use_hw(int elem_is_fp, int tie) { return elem_is_fp && (tie == MX_ROUND_DEFAULT || tie == MX_ROUND_HALF_EVEN); }
 
-mx_status_t quantize_launch(int elem, int axis, int tie, const DenseArg& src, void* codes, uint8_t* scales, hipStream_t stream) {
+mx_status_t quantize_launch(int elem, int axis, int block, int tie, const DenseArg& src, void* codes, uint8_t* scales,
+                            hipStream_t stream) {
 #define X(ID)                                                                                              \
   if (elem == ID) {                                                                                        \
     constexpr bool CAN = Elem<ID>::hw != HW_NONE;                                                          \
     bool hw = CAN && use_hw(!Elem<ID>::is_int, tie);                                                       \
     if (src.dtype == MX_F32)                                                                               \
-      return hw ? run_quantize<ID, CAN, MX_F32>(axis, tie, src, codes, scales, stream)                     \
-                : run_quantize<ID, false, MX_F32>(axis, tie, src, codes, scales, stream);                  \
-    return hw ? run_quantize<ID, CAN, MX_BF16>(axis, tie, src, codes, scales, stream)                      \
-              : run_quantize<ID, false, MX_BF16>(axis, tie, src, codes, scales, stream);                   \
+      return hw ? run_quantize<ID, CAN, MX_F32>(axis, block, tie, src, codes, scales, stream)                     \
+                : run_quantize<ID, false, MX_F32>(axis, block, tie, src, codes, scales, stream);                  \
+    return hw ? run_quantize<ID, CAN, MX_BF16>(axis, block, tie, src, codes, scales, stream)                      \
+              : run_quantize<ID, false, MX_BF16>(axis, block, tie, src, codes, scales, stream);                   \
   }
   MX_FOR_EACH_ELEM(X)
 #undef X
   return MX_ERR_FORMAT;
 }
 
-mx_status_t dequant_launch(int elem, int axis, const void* codes, const uint8_t* scales, const DenseArg& dst, hipStream_t stream) {
+mx_status_t dequant_launch(int elem, int axis, int block, const void* codes, const uint8_t* scales, const DenseArg& dst,
+                           hipStream_t stream) {
 #define X(ID)                                                                               \
   if (elem == ID) {                                                                         \
-    if (dst.dtype == MX_F32) return run_dequant<ID, MX_F32>(axis, codes, scales, dst, stream); \
-    return run_dequant<ID, MX_BF16>(axis, codes, scales, dst, stream);                      \
+    if (dst.dtype == MX_F32) return run_dequant<ID, MX_F32>(axis, block, codes, scales, dst, stream); \
+    return run_dequant<ID, MX_BF16>(axis, block, codes, scales, dst, stream);                      \
   }
   MX_FOR_EACH_ELEM(X)
 #undef X
@@ -717,26 +764,26 @@ mx_status_t dequant_launch(int elem, int axis, const void* codes, const uint8_t*
 }
 
 template <int TARGET, int ANCHOR>
-static mx_status_t fake_quant_pick(int axis, int tie, const DenseArg& s, const DenseArg& d, hipStream_t stream) {
+static mx_status_t fake_quant_pick(int axis, int block, int tie, const DenseArg& s, const DenseArg& d, hipStream_t stream) {
   constexpr bool CAN = Elem<TARGET>::hw != HW_NONE;  // the 8-bit FP anchor always has a hardware path
   bool hw = CAN && use_hw(!Elem<TARGET>::is_int, tie);
   if (s.dtype == MX_F32)
-    return hw ? run_fake_quant<TARGET, ANCHOR, CAN, MX_F32>(axis, tie, s, d, stream)
-              : run_fake_quant<TARGET, ANCHOR, false, MX_F32>(axis, tie, s, d, stream);
-  return hw ? run_fake_quant<TARGET, ANCHOR, CAN, MX_BF16>(axis, tie, s, d, stream)
-            : run_fake_quant<TARGET, ANCHOR, false, MX_BF16>(axis, tie, s, d, stream);
+    return hw ? run_fake_quant<TARGET, ANCHOR, CAN, MX_F32>(axis, block, tie, s, d, stream)
+              : run_fake_quant<TARGET, ANCHOR, false, MX_F32>(axis, block, tie, s, d, stream);
+  return hw ? run_fake_quant<TARGET, ANCHOR, CAN, MX_BF16>(axis, block, tie, s, d, stream)
+            : run_fake_quant<TARGET, ANCHOR, false, MX_BF16>(axis, block, tie, s, d, stream);
 }
 
-mx_status_t fake_quant_launch(int target, int anchor, int axis, int tie, const DenseArg& src, const DenseArg& dst,
+mx_status_t fake_quant_launch(int target, int anchor, int axis, int block, int tie, const DenseArg& src, const DenseArg& dst,
                               hipStream_t stream) {
 #define X(ID)                                                                                             \
   if (target == ID) {                                                                                     \
-    if (anchor < 0) return fake_quant_pick<ID, -1>(axis, tie, src, dst, stream);                          \
+    if (anchor < 0) return fake_quant_pick<ID, -1>(axis, block, tie, src, dst, stream);                          \
     if constexpr (Elem<ID>::is_int && Elem<ID>::bits < 8) {                                               \
-      if (anchor == MX_INT8) return fake_quant_pick<ID, MX_INT8>(axis, tie, src, dst, stream);            \
+      if (anchor == MX_INT8) return fake_quant_pick<ID, MX_INT8>(axis, block, tie, src, dst, stream);            \
     }                                                                                                     \
     if constexpr (!Elem<ID>::is_int && Elem<ID>::bits < 8) {                                              \
-      if (anchor == MX_FP8_E4M3) return fake_quant_pick<ID, MX_FP8_E4M3>(axis, tie, src, dst, stream);    \
+      if (anchor == MX_FP8_E4M3) return fake_quant_pick<ID, MX_FP8_E4M3>(axis, block, tie, src, dst, stream);    \
     }                                                                                                     \
     return MX_ERR_FORMAT;                                                                                 \
   }

@@ -56,9 +56,9 @@ struct SsTargets {
   int n;
 };
 
-mx_status_t ss_launch_one(int anchor, const SsTargets& tg, bool hw, const SsTensor& t, int tie, hipStream_t stream);
+mx_status_t ss_launch_one(int anchor, const SsTargets& tg, bool hw, const SsTensor& t, int block, int tie, hipStream_t stream);
 size_t ss_workspace_bytes(int n, int64_t total_blocks);
-mx_status_t ss_launch_many(int anchor, const SsTargets& tg, bool hw, int n, const SsTensor* h_tensors, void* workspace,
+mx_status_t ss_launch_many(int anchor, const SsTargets& tg, bool hw, int n, const SsTensor* h_tensors, int block, void* workspace,
                            size_t workspace_bytes, int tie, hipStream_t stream);
 
 // Dense <-> packed kernels.  `dense` / `ld` in elements of dtype; outer / nblocks as in mx.h.
@@ -67,9 +67,11 @@ struct DenseArg {
   int dtype;
   int64_t rows, cols, ld;
 };
-mx_status_t quantize_launch(int elem, int axis, int tie, const DenseArg& src, void* codes, uint8_t* scales, hipStream_t stream);
-mx_status_t dequant_launch(int elem, int axis, const void* codes, const uint8_t* scales, const DenseArg& dst, hipStream_t stream);
-mx_status_t fake_quant_launch(int target, int anchor /* -1: none */, int axis, int tie, const DenseArg& src,
+mx_status_t quantize_launch(int elem, int axis, int block, int tie, const DenseArg& src, void* codes, uint8_t* scales,
+                            hipStream_t stream);
+mx_status_t dequant_launch(int elem, int axis, int block, const void* codes, const uint8_t* scales, const DenseArg& dst,
+                           hipStream_t stream);
+mx_status_t fake_quant_launch(int target, int anchor /* -1: none */, int axis, int block, int tie, const DenseArg& src,
                               const DenseArg& dst, hipStream_t stream);
 
 mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,

@@ -183,17 +183,17 @@ struct SsFlatArgs {
   const uint8_t* scales_h;
   void* codes_l[kSsMaxTargets];
   void* scales_l[kSsMaxTargets];
-  int64_t nblocks;
+  int64_t nblocks;    // scale bytes
+  int64_t npieces;    // nblocks * block / CPL
   int64_t code_wgs;
 };
 
 // ---- one tensor: workgroups [0, code_wgs) convert pieces, the rest scale bytes
 template <int ANCHOR, bool HW, int... TARGETS>
 __global__ __launch_bounds__(kSsLanes) void ss_kernel(SsFlatArgs a, int tie) {
-  constexpr int CPL = Piece<TARGETS...>::cpl;
   int64_t wg = blockIdx.x;
   if (wg < a.code_wgs) {
-    ss_pieces<ANCHOR, HW, TARGETS...>(a.codes_h, a.codes_l, wg * kSsLanes, a.nblocks * (32 / CPL), tie);
+    ss_pieces<ANCHOR, HW, TARGETS...>(a.codes_h, a.codes_l, wg * kSsLanes, a.npieces, tie);
   } else {
     int64_t c = (wg - a.code_wgs) * kSsLanes + threadIdx.x;
     if (c * 16 < a.nblocks) ss_scale_chunk<ANCHOR, TARGETS...>(a.scales_h, a.scales_l, c, a.nblocks);
@@ -228,7 +228,8 @@ __global__ __launch_bounds__(kSsLanes) void ss_batched_kernel(const SsSegment* _
 struct SsPieceBytes { int out[kSsMaxTargets]; int n; int cpl; };
 
 // Segment table of one chunk of tensors: thread j describes segment seg0 + j.
-__global__ void ss_segments_kernel(SsChunk c, SsSegment* __restrict__ segs, int nseg_chunk, SsPieceBytes pb, int seg_shift) {
+__global__ void ss_segments_kernel(SsChunk c, SsSegment* __restrict__ segs, int nseg_chunk, SsPieceBytes pb, int seg_shift,
+                                   int block) {
   int s = blockIdx.x * blockDim.x + threadIdx.x;
   if (s >= nseg_chunk) return;
   const int stride = 4 + 2 * c.n_targets;
@@ -245,7 +246,7 @@ __global__ void ss_segments_kernel(SsChunk c, SsSegment* __restrict__ segs, int 
   d.pad = 0; d.pad2[0] = d.pad2[1] = 0;
   if (s < seg_scale) {
     int64_t j = s - seg_begin;
-    int64_t pieces = nblocks * (32 / pb.cpl) - j * ITEMS;
+    int64_t pieces = nblocks * block / pb.cpl - j * ITEMS;
     d.in = reinterpret_cast<const char*>(t[0]) + j * ITEMS * pb.cpl;
     for (int q = 0; q < kSsMaxTargets; ++q)
       d.out[q] = q < pb.n ? reinterpret_cast<char*>(t[4 + q]) + j * ITEMS * pb.out[q] : nullptr;
@@ -273,13 +274,15 @@ static inline int ss_cpl(const SsTargets& tg) {
 }
 
 template <int ANCHOR, bool HW, int... TARGETS>
-static mx_status_t launch_ss(const SsTensor& t, int tie, hipStream_t stream) {
+static mx_status_t launch_ss(const SsTensor& t, int block, int tie, hipStream_t stream) {
   constexpr int CPL = Piece<TARGETS...>::cpl;
-  int64_t cw = ceil_div(t.nblocks * (32 / CPL), kSsLanes), sw = ceil_div(ceil_div(t.nblocks, 16), kSsLanes);
+  if ((t.nblocks * block) % CPL) return MX_ERR_UNSUPPORTED;   // odd widths convert whole runs of 32 codes
+  const int64_t npieces = t.nblocks * block / CPL;
+  int64_t cw = ceil_div(npieces, kSsLanes), sw = ceil_div(ceil_div(t.nblocks, 16), kSsLanes);
   if (cw + sw == 0) return MX_OK;
   if (cw + sw > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
   SsFlatArgs a;
-  a.codes_h = t.codes_h; a.scales_h = t.scales_h; a.nblocks = t.nblocks; a.code_wgs = cw;
+  a.codes_h = t.codes_h; a.scales_h = t.scales_h; a.nblocks = t.nblocks; a.npieces = npieces; a.code_wgs = cw;
   for (int q = 0; q < kSsMaxTargets; ++q) { a.codes_l[q] = t.codes_l[q]; a.scales_l[q] = t.scales_l[q]; }
   hipLaunchKernelGGL((ss_kernel<ANCHOR, HW, TARGETS...>), dim3((unsigned)(cw + sw)), dim3(kSsLanes), 0, stream, a, tie);
   return launch_status("a Slice-and-Scale kernel");
@@ -335,8 +338,8 @@ static mx_status_t ss_dispatch(int anchor, const SsTargets& tg, bool hw, F&& f) 
 }
 
 struct SsOne {
-  const SsTensor& t; int tie; hipStream_t stream;
-  template <int A, bool HW, int... T> mx_status_t operator()() const { return launch_ss<A, HW, T...>(t, tie, stream); }
+  const SsTensor& t; int block; int tie; hipStream_t stream;
+  template <int A, bool HW, int... T> mx_status_t operator()() const { return launch_ss<A, HW, T...>(t, block, tie, stream); }
 };
 struct SsMany {
   const SsSegment* segs; int64_t nseg; int seg_shift; int tie; hipStream_t stream;
@@ -349,44 +352,47 @@ struct SsProbe {   // "is there a kernel for this target list?" without launchin
   template <int A, bool HW, int... T> mx_status_t operator()() const { return MX_OK; }
 };
 
-mx_status_t ss_launch_one(int anchor, const SsTargets& tg, bool hw, const SsTensor& t, int tie, hipStream_t stream) {
-  return ss_dispatch(anchor, tg, hw, SsOne{t, tie, stream});
+mx_status_t ss_launch_one(int anchor, const SsTargets& tg, bool hw, const SsTensor& t, int block, int tie, hipStream_t stream) {
+  return ss_dispatch(anchor, tg, hw, SsOne{t, block, tie, stream});
 }
 
 // Segments a tensor of nblocks blocks needs: code segments, scale segments.
-static inline void ss_segments_of(int64_t nblocks, int cpl, int seg_shift, int64_t* code_segs, int64_t* scale_segs) {
+static inline void ss_segments_of(int64_t nblocks, int block, int cpl, int seg_shift, int64_t* code_segs, int64_t* scale_segs) {
   const int64_t items = (int64_t)kSsLanes << seg_shift;
-  *code_segs = ceil_div(nblocks * (32 / cpl), items);
+  *code_segs = ceil_div(nblocks * block / cpl, items);
   *scale_segs = ceil_div(ceil_div(nblocks, 16), items);
 }
 
-static int64_t ss_count_segments(int n, const SsTensor* t, int cpl, int seg_shift) {
+static int64_t ss_count_segments(int n, const SsTensor* t, int block, int cpl, int seg_shift) {
   int64_t nseg = 0;
   for (int i = 0; i < n; ++i) {
     int64_t cs, ss;
-    ss_segments_of(t[i].nblocks, cpl, seg_shift, &cs, &ss);
+    ss_segments_of(t[i].nblocks, block, cpl, seg_shift, &cs, &ss);
     nseg += cs + ss;
   }
   return nseg;
 }
 
 size_t ss_workspace_bytes(int n, int64_t total_blocks) {
-  // bound over both piece sizes and both segment sizes: every tensor rounds up by at most one code and one scale
-  // segment, and small segments need the most descriptors
+  // bound over every block size (up to 128: 8 pieces of 16 codes per block), both piece sizes and both segment
+  // sizes: every tensor rounds up by at most one code and one scale segment, and small segments need the most
+  // descriptors
   const int64_t items = (int64_t)kSsLanes << kSsSegShiftSmall;
-  int64_t segs = total_blocks * 2 / items + total_blocks / (16 * items) + 2 * (int64_t)n + 2;
+  int64_t segs = total_blocks * 8 / items + total_blocks / (16 * items) + 2 * (int64_t)n + 2;
   return sizeof(SsSegment) * (size_t)segs;
 }
 
-mx_status_t ss_launch_many(int anchor, const SsTargets& tg, bool hw, int n, const SsTensor* h_tensors, void* workspace,
+mx_status_t ss_launch_many(int anchor, const SsTargets& tg, bool hw, int n, const SsTensor* h_tensors, int block, void* workspace,
                            size_t workspace_bytes, int tie, hipStream_t stream) {
   const int cpl = ss_cpl(tg);
+  for (int i = 0; i < n; ++i)
+    if ((h_tensors[i].nblocks * block) % cpl) return MX_ERR_UNSUPPORTED;   // odd widths convert whole runs of 32 codes
   // pass 1 on the host: segment ranges; nothing is launched before the sizes are known to fit.  Large segments
   // unless their padding (workgroups that find nothing to do) would exceed 1/32 of the launch.
   int seg_shift = kSsSegShiftLarge;
-  int64_t nseg = ss_count_segments(n, h_tensors, cpl, seg_shift);
+  int64_t nseg = ss_count_segments(n, h_tensors, block, cpl, seg_shift);
   {
-    int64_t small = ss_count_segments(n, h_tensors, cpl, kSsSegShiftSmall);
+    int64_t small = ss_count_segments(n, h_tensors, block, cpl, kSsSegShiftSmall);
     if ((nseg << kSsSegShiftLarge) - (small << kSsSegShiftSmall) > (small << kSsSegShiftSmall) / 32) {
       seg_shift = kSsSegShiftSmall;
       nseg = small;
@@ -416,7 +422,7 @@ mx_status_t ss_launch_many(int anchor, const SsTargets& tg, bool hw, int n, cons
     for (int i = 0; i < chunk.count; ++i) {
       const SsTensor& t = h_tensors[base + i];
       int64_t cs, ss;
-      ss_segments_of(t.nblocks, cpl, seg_shift, &cs, &ss);
+      ss_segments_of(t.nblocks, block, cpl, seg_shift, &cs, &ss);
       int64_t* w = chunk.w + i * stride;
       w[0] = (int64_t)(uintptr_t)t.codes_h;
       w[1] = (int64_t)(uintptr_t)t.scales_h;
@@ -430,7 +436,7 @@ mx_status_t ss_launch_many(int anchor, const SsTargets& tg, bool hw, int n, cons
     }
     if (acc > 0) {
       hipLaunchKernelGGL(ss_segments_kernel, dim3((unsigned)ceil_div(acc, 256)), dim3(256), 0, stream, chunk, segs, (int)acc, pb,
-                         seg_shift);
+                         seg_shift, block);
       if (launch_status("the segment table writer") != MX_OK) return MX_ERR_LAUNCH;
     }
     seg0 += acc;

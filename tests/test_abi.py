@@ -52,8 +52,10 @@ def test_packed_bytes(mx):
         mx.mx_packed_bytes(mx.make_format("int8"), 10, 33)            # 33 is not a multiple of the block
     assert e.value.status == 3
     with pytest.raises(mx.MxError) as e:
-        mx.mx_packed_bytes(mx.make_format("int8", block=64), 10, 64)  # only k = 32 has kernels
+        mx.mx_packed_bytes(mx.make_format("int8", block=48), 10, 96)  # k = 16, 32, 64, 128 have kernels
     assert e.value.status == 5
+    assert mx.mx_packed_bytes(mx.make_format("int6", block=64), 10, 128) == (10 * 2 * 48, 20)
+    assert mx.mx_packed_bytes(mx.make_format("e2m1", block=16), 4, 64) == (4 * 4 * 8, 16)
 
 
 def _dense(ptr, dtype, rows, cols, ld=None):
