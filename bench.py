@@ -89,6 +89,8 @@ def main():
     ap.add_argument("--layers", type=int, default=32, help="decoder layers of the synthetic checkpoint (32 = the 8B shape)")
     ap.add_argument("--no-rows", action="store_true", help="skip the secondary rows")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--only", default=None, choices=["gemm"],
+                    help="profiling aid: run only this group of secondary rows (no headline, no CPU baseline)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling the profiler's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -103,6 +105,12 @@ def main():
     mx.binding.lib()
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
+
+    if args.only == "gemm":
+        rows = {}
+        gemm_rows(torch, mx, synth, rows)
+        print(json.dumps({"rows": rows}), flush=True)
+        return
 
     # ---------------------------------------------------------------- headline: SS E4M3 -> E2M1, whole checkpoint
     log("[bench] building the MXFP8 anchor checkpoint (%d layers)" % args.layers)
@@ -234,38 +242,42 @@ def main():
             m, _, _ = time_region(torch, lambda: mx.mx_dequant(pc, ps, f0, act.shape[0], act.shape[1], out=out), 10, 3)
             rows["dequant_%s_bf16_axis0" % elem] = row(act.numel() * 2 + act.numel() // 32 * (4 * bits + 1), m)
             del pc, ps
-        # fused consumer GEMM (configs[4]): bf16 activations -> MXFP8 (not timed), weight anchor E4M3 [N, K/32, 32]
-        # sliced to E2M1 in registers, scaled MX MFMA.  Decode (M = 16) is bound by reading the anchor: 8 weights are
-        # rotated (484 MB) so that they stream from HBM; prefill (M = 2048) is bound by the matrix cores (operand A is
-        # FP8, so the FP8 dense peak applies).
-        Kg, Ng = 4096, 14336
-        f8 = mx.make_format("e4m3")
-        wlist = []
-        for i in range(8):
-            w = synth.torch_config3_weight(3000 + i, Ng, Kg)
-            wlist.append(mx.mx_quantize(w, f8))
-            del w
-        for Mg in (16, 2048):
-            a = torch.randn((Mg, Kg), device="cuda", dtype=torch.float32, generator=torch.Generator(device="cuda").manual_seed(1005)).to(torch.bfloat16)
-            ac, asc = mx.mx_quantize(a, f8)
-            cbuf = torch.empty((Mg, Ng), dtype=torch.float32, device="cuda")
-            st = {"i": 0}
-
-            def gemm():
-                i = st["i"] = (st["i"] + 1) % 8
-                mx.mx_gemm_ss_fp4(ac, asc, wlist[i][0], wlist[i][1], cbuf)
-            m, _, _ = time_region(torch, gemm, 24, 8)
-            flops = 2.0 * Mg * Ng * Kg
-            nbytes_g = Ng * Kg + Ng * Kg // 32 + Mg * Kg + Mg * Kg // 32 + Mg * Ng * 4
-            rows["gemm_ss_fp4_M%d" % Mg] = {"ms": round(m, 4), "TFLOP/s": round(flops / (m * 1e-3) / 1e12, 1),
-                                            "frac_fp8_mfma_peak": round(flops / (m * 1e-3) / 5.0e15, 4),
-                                            "GB/s": round(nbytes_g / (m * 1e-3) / 1e9, 1),
-                                            "frac_hbm_peak": round(nbytes_g / (m * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-            del a, ac, asc, cbuf
-        del wlist
+        gemm_rows(torch, mx, synth, rows)
         result["rows"] = rows
 
     print(json.dumps(result), flush=True)
+
+
+def gemm_rows(torch, mx, synth, rows):
+    # fused consumer GEMM (configs[4]): bf16 activations -> MXFP8 (not timed), weight anchor E4M3 [N, K/32, 32]
+    # sliced to E2M1 in registers, scaled MX MFMA.  Decode (M = 16) is bound by reading the anchor: 8 weights are
+    # rotated (484 MB) so that they stream from HBM; prefill (M = 2048) is bound by the matrix cores (operand A is
+    # FP8, so the FP8 dense peak applies).
+    Kg, Ng = 4096, 14336
+    f8 = mx.make_format("e4m3")
+    wlist = []
+    for i in range(8):
+        w = synth.torch_config3_weight(3000 + i, Ng, Kg)
+        wlist.append(mx.mx_quantize(w, f8))
+        del w
+    for Mg in (16, 2048):
+        a = torch.randn((Mg, Kg), device="cuda", dtype=torch.float32, generator=torch.Generator(device="cuda").manual_seed(1005)).to(torch.bfloat16)
+        ac, asc = mx.mx_quantize(a, f8)
+        cbuf = torch.empty((Mg, Ng), dtype=torch.float32, device="cuda")
+        st = {"i": 0}
+
+        def gemm():
+            i = st["i"] = (st["i"] + 1) % 8
+            mx.mx_gemm_ss_fp4(ac, asc, wlist[i][0], wlist[i][1], cbuf)
+        m, _, _ = time_region(torch, gemm, 24, 8)
+        flops = 2.0 * Mg * Ng * Kg
+        nbytes_g = Ng * Kg + Ng * Kg // 32 + Mg * Kg + Mg * Kg // 32 + Mg * Ng * 4
+        rows["gemm_ss_fp4_M%d" % Mg] = {"ms": round(m, 4), "TFLOP/s": round(flops / (m * 1e-3) / 1e12, 1),
+                                        "frac_fp8_mfma_peak": round(flops / (m * 1e-3) / 5.0e15, 4),
+                                        "GB/s": round(nbytes_g / (m * 1e-3) / 1e9, 1),
+                                        "frac_hbm_peak": round(nbytes_g / (m * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del a, ac, asc, cbuf
+    del wlist
 
 
 def row(nbytes, ms):
@@ -275,7 +287,7 @@ def row(nbytes, ms):
 
 # HBM bytes per launch of the headline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
 # scaled by the same counters on a plain copy of known size (see profiles/); None until measured.
-MEASURED_TRAFFIC = {"ss_e4m3_e2m1": 10933240736}   # profiles/ss_e4m3_e2m1_llama8b_checkpoint.md
+MEASURED_TRAFFIC = {"ss_e4m3_e2m1": 10912148107}   # profiles/ss_e4m3_e2m1_llama8b_checkpoint.md
 
 
 def cpu_baseline(torch, a_views, tensors):
