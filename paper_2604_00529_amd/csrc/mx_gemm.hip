@@ -200,7 +200,7 @@ __global__ __launch_bounds__(256) void gemm_ss_fp4_smallm_kernel(const uint8_t* 
 // of a lane group hit different banks.
 constexpr int kGemmBM = 256, kGemmBN = 128, kGemmBK = 128;
 constexpr int kGemmMT = 8, kGemmNT = 4;      // MFMA tiles per consumer wave
-constexpr int kGemmLdA = 144, kGemmLdB = 80;
+constexpr int kGemmLdA = 128, kGemmLdB = 64;   // unpadded rows; 16-byte chunks are XOR-swizzled (see GemmStage)
 #ifndef MX_GEMM_PREFETCH
 #define MX_GEMM_PREFETCH 2
 #endif
@@ -211,6 +211,10 @@ constexpr int kGemmThreads = 512;
 #define MX_GEMM_GROUP 4
 #endif
 
+// LDS layout of one K-step.  The 16-byte chunk c of row r of A lives at chunk c ^ ((r >> 1) & 7) of that row, chunk c
+// of column n of B at chunk c ^ ((n >> 2) & 3): with 64 banks of 4 bytes, the 16 lanes of a 128-bit access then hit 64
+// different banks both when a producer writes (8 or 4 consecutive chunks of 2 or 4 consecutive rows) and when a
+// consumer reads a fragment (the same chunk of 16 consecutive rows).
 struct GemmStage {
   uint8_t a[kGemmBM * kGemmLdA];   // E4M3 codes, row m: 128 bytes of K
   uint8_t b[kGemmBN * kGemmLdB];   // E2M1 codes, column n: 64 bytes (128 nibbles of K)
@@ -269,8 +273,11 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
     const uint8_t* psa = a_scales + (int64_t)(m0 + tid < M ? m0 + tid : M - 1) * KB;
     const uint8_t* psw = w_scales + (int64_t)(n0 + (tid & 127) < N ? n0 + (tid & 127) : N - 1) * KB;
 
-    u32x4 ra[D][kGemmAChunks], rb[D][2][2];
-    uint32_t rsa[D], rsw[D];
+    // R = D + 1 register slots: the loads of K-step k + 1 + D are issued first in K-step k, into the slot that
+    // step k's data left, so that the memory pipe works on them while this wave writes LDS and slices
+    constexpr int R = D + 1;
+    u32x4 ra[R][kGemmAChunks], rb[R][2][2];
+    uint32_t rsa[R], rsw[R];
     auto load_global = [&](int ks, auto slot_c) {
       constexpr int S = decltype(slot_c)::value;
       const int k0 = ks * kGemmBK;
@@ -296,7 +303,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
 #pragma unroll
       for (int j = 0; j < kGemmAChunks; ++j) {
         int q = tid + 256 * j, row = q >> 3, col = q & 7;
-        *reinterpret_cast<u32x4*>(&st.a[row * kGemmLdA + 16 * col]) = ra[S][j];
+        *reinterpret_cast<u32x4*>(&st.a[row * kGemmLdA + 16 * (col ^ ((row >> 1) & 7))]) = ra[S][j];
       }
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
@@ -308,7 +315,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
         } else {
           slice_block_e2m1(rb[S][j][0], rb[S][j][1], b4);   // Eq. (6) element step, once per workgroup and K-step
         }
-        *reinterpret_cast<u32x4*>(&st.b[col * kGemmLdB + 16 * kb]) = u32x4{b4[0], b4[1], b4[2], b4[3]};
+        *reinterpret_cast<u32x4*>(&st.b[col * kGemmLdB + 16 * (kb ^ ((col >> 2) & 3))]) = u32x4{b4[0], b4[1], b4[2], b4[3]};
       }
       st.as[tid] = rsa[S];
       if (tid < kGemmBN) st.bs[tid] = scale_add_x4(rsw[S], kDeltaE_E4M3_E2M1);   // Eq. (6) scale step
@@ -317,31 +324,31 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
     // loads): K-steps past the end are clamped to the last one, their data is loaded again and never used.
     const int last = ksteps - 1;
     auto clamp_ks = [&](int ks) { return ks < last ? ks : last; };
-    // prologue: K-steps 0 .. D-1 in flight, step 0 staged, step D in flight in its place
-    static_for<0, D>([&](auto d) { load_global(clamp_ks(decltype(d)::value), d); });
+    // prologue: K-steps 0 .. D in flight, step 0 staged
+    static_for<0, R>([&](auto d) { load_global(clamp_ks(decltype(d)::value), d); });
     store_lds(stage[0], std::integral_constant<int, 0>{});
-    load_global(clamp_ks(D), std::integral_constant<int, 0>{});
     __syncthreads();
-    // during K-step k the other stage is filled with step k + 1
-    const int rounds = ksteps / D;
+    // during K-step k: loads of step k + 1 + D (slot k % R, free since step k was staged), then step k + 1 (slot
+    // (k + 1) % R) goes into the other stage
+    const int rounds = ksteps / R;
     for (int r = 0; r < rounds; ++r) {
-      static_for<0, D>([&](auto d) {
+      static_for<0, R>([&](auto d) {
         constexpr int DD = decltype(d)::value;
-        constexpr int NEXT = (DD + 1) % D;
-        const int k = r * D + DD;
+        constexpr int NEXT = (DD + 1) % R;
+        const int k = r * R + DD;
         if constexpr (!(SKIP & 2)) {
+          if constexpr (!(SKIP & 8)) load_global(clamp_ks(k + 1 + D), d);
           if constexpr (!(SKIP & 32)) store_lds(stage[(k + 1) & 1], std::integral_constant<int, NEXT>{});
-          if constexpr (!(SKIP & 8)) load_global(clamp_ks(k + 1 + D), std::integral_constant<int, NEXT>{});
         }
         __syncthreads();
       });
     }
-    // the K-steps left over when their number is not a multiple of D (at most D - 1; no more loads are needed)
-    static_for<0, D - 1>([&](auto d) {
+    // the K-steps left over when their number is not a multiple of R (at most R - 1; no more loads are needed)
+    static_for<0, R - 1>([&](auto d) {
       constexpr int DD = decltype(d)::value;
-      const int k = rounds * D + DD;
+      const int k = rounds * R + DD;
       if (k < ksteps) {
-        store_lds(stage[(k + 1) & 1], std::integral_constant<int, (DD + 1) % D>{});
+        store_lds(stage[(k + 1) & 1], std::integral_constant<int, (DD + 1) % R>{});
         __syncthreads();
       }
     });
@@ -363,8 +370,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   for (int mt = 0; mt < kGemmMT; ++mt)
 #pragma unroll
     for (int nt = 0; nt < kGemmNT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const int a_off = (wm * 128 + i) * kGemmLdA + 16 * g;   // + mt * 16 rows
-  const int b_off = (wn * 64 + i) * kGemmLdB + 16 * g;    // + nt * 16 columns
+  // (the tile offsets wm * 128, mt * 16, wn * 64, nt * 16 do not change the swizzle term of a lane)
+  const int a_off = (wm * 128 + i) * kGemmLdA + 16 * (g ^ ((i >> 1) & 7));   // + mt * 16 rows; second run of K: ^ 64
+  const int b_off = (wn * 64 + i) * kGemmLdB + 16 * (g ^ ((i >> 2) & 3));    // + nt * 16 columns
   i32x8 af[2][GM];   // two 16-byte runs of K per lane
   uint32_t sa[2][GM], sb[kGemmNT];
   // B operands: only the low 4 dwords carry FP4 codes; the upper 4 stay zero for the whole kernel
@@ -382,7 +390,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
     for (int m = 0; m < GM; ++m) {
       const int mt = G * GM + m;
       u32x4 t0 = *reinterpret_cast<const u32x4*>(&st.a[a_off + mt * 16 * kGemmLdA]);
-      u32x4 t1 = *reinterpret_cast<const u32x4*>(&st.a[a_off + mt * 16 * kGemmLdA + 64]);
+      u32x4 t1 = *reinterpret_cast<const u32x4*>(&st.a[(a_off ^ 64) + mt * 16 * kGemmLdA]);
       af[SET][m] = i32x8{(int)t0.x, (int)t0.y, (int)t0.z, (int)t0.w, (int)t1.x, (int)t1.y, (int)t1.z, (int)t1.w};
       sa[SET][m] = st.as[wm * 128 + mt * 16 + i] >> (8 * g);   // the instruction reads the low byte
     }
@@ -447,7 +455,7 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
   if (M > 64) {
     const int64_t m_tiles = (M + kGemmBM - 1) / kGemmBM, n_tiles = (N + kGemmBN - 1) / kGemmBN;
     if (m_tiles * n_tiles > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-    // 2 stages x 49.5 KB: above the 64 KB a kernel gets by default, so the dynamic size is requested explicitly
+    // 2 stages x 41.5 KB: above the 64 KB a kernel gets by default, so the dynamic size is requested explicitly
     constexpr int kSmem = 2 * (int)sizeof(GemmStage);
     static bool attr_set = false;
     if (!attr_set) {
