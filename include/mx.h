@@ -108,7 +108,8 @@ mx_status_t mx_quantize(const mx_format_t* f, const mx_dense_t* src, const mx_pa
  * (MX_INT8 or MX_FP8_E4M3) and the target a narrower format of the same family with the same
  * block size; the axis is irrelevant (a flat run of blocks).  The scale byte saturates at 254;
  * 255 stays 255.  target->outer * target->nblocks must equal the anchor's block count.
- * The target must not overlap the anchor. */
+ * The target must not overlap the anchor.  Targets of odd width are converted in runs of 32 codes:
+ * MX_ERR_UNSUPPORTED if a tensor's code count is not a multiple of 32 (only possible with block 16). */
 mx_status_t mx_slice_and_scale(const mx_format_t* fa, const mx_packed_t* anchor, const mx_format_t* ft,
                                const mx_packed_t* target, void* stream);
 
