@@ -33,6 +33,23 @@ def test_every_declared_symbol_is_exported(mx):
         assert hasattr(L, n), n
 
 
+def test_header_is_plain_c(tmp_path):
+    # the boundary is a C ABI: the header compiles as strict C99, with no C++ or HIP types in any signature
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "use_mx.c"
+    src.write_text('#include "mx.h"\n'
+                   'int main(void) {\n'
+                   '  mx_format_t f = {MX_FP4_E2M1, MX_SCALE_E8M0, 32, 1, MX_ROUND_DEFAULT};\n'
+                   '  mx_status_t (*q)(const mx_format_t*, const mx_dense_t*, const mx_packed_t*, void*) = mx_quantize;\n'
+                   '  (void)q; return mx_elem_bits(f.elem) == 4 ? 0 : 1;\n'
+                   '}\n')
+    r = subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(root, "include"),
+                        "-fsyntax-only", str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
 def test_element_table(mx):
     bits = {"int8": 8, "int7": 7, "int6": 6, "int5": 5, "int4": 4, "int3": 3, "int2": 2,
             "e4m3": 8, "e3m3": 7, "e3m2": 6, "e2m3": 6, "e2m2": 5, "e2m1": 4}
