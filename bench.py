@@ -26,11 +26,21 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def time_region(torch, fn, steps, warmup):
+WARM_MS = 30.0   # secondary rows: untimed calls for at least this long first (the GPU takes ~10 ms of sustained
+                 # work to reach its steady state: clocks, page tables; measured 72-80 % -> 82-83 % on one kernel)
+
+
+def time_region(torch, fn, steps, warmup, warm_ms=0.0):
     """Average milliseconds per call: events on the current stream, bracketed by synchronize."""
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
+    if warm_ms > 0.0:
+        t0 = time.perf_counter()
+        while (time.perf_counter() - t0) * 1e3 < warm_ms:
+            for _ in range(4):
+                fn()
+            torch.cuda.synchronize()
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t0 = time.perf_counter()
     ev[0].record()
@@ -85,7 +95,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--layers", type=int, default=32, help="decoder layers of the synthetic checkpoint (32 = the 8B shape)")
     ap.add_argument("--no-rows", action="store_true", help="skip the secondary rows")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
@@ -168,14 +178,14 @@ def main():
         for tgt in ("e3m2", "e2m3"):
             c2, s2, v2 = alloc_targets(torch, mx, a_views, tgt)
             f2 = mx.make_format(tgt)
-            m, _, _ = time_region(torch, mx.SsBatch(a_views, fa, f2, v2, ws).run, steps2, 2)
+            m, _, _ = time_region(torch, mx.SsBatch(a_views, fa, f2, v2, ws).run, steps2, 2, WARM_MS)
             rows["ss_e4m3_%s" % tgt] = row(ss_bytes(nblocks, 8, 6), m)
             del c2, s2, v2
         # every lower MXFP format from ONE pass over the anchor (read once, three targets written)
         trip = [alloc_targets(torch, mx, a_views, t) for t in ("e3m2", "e2m3", "e2m1")]
         tv = [[trip[q][2][i] for q in range(3)] for i in range(len(a_views))]
         b3 = mx.SsBatch(a_views, fa, [mx.make_format(t) for t in ("e3m2", "e2m3", "e2m1")], tv, ws)
-        m, _, _ = time_region(torch, b3.run, steps2, 2)
+        m, _, _ = time_region(torch, b3.run, steps2, 2, WARM_MS)
         rows["ss_e4m3_to_e3m2_e2m3_e2m1_one_pass"] = row(nblocks * (32 + 1 + 24 + 24 + 16 + 3), m)
         del trip, tv, b3
         del t_codes, t_scales, t_views, batch
@@ -188,7 +198,7 @@ def main():
         for tgt, bits in (("int4", 4), ("int6", 6)):
             c2, s2, v2 = alloc_targets(torch, mx, a_views, tgt)
             f2 = mx.make_format(tgt)
-            m, _, _ = time_region(torch, mx.SsBatch(a_views, fi, f2, v2, ws).run, steps2, 2)
+            m, _, _ = time_region(torch, mx.SsBatch(a_views, fi, f2, v2, ws).run, steps2, 2, WARM_MS)
             rows["ss_int8_%s" % tgt] = row(ss_bytes(nblocks, 8, bits), m)
             del c2, s2, v2
         del a_codes, a_scales, a_views
@@ -201,10 +211,10 @@ def main():
         for elem, bits in (("e4m3", 8), ("int8", 8), ("e2m1", 4), ("int4", 4), ("e3m2", 6)):
             f = mx.make_format(elem)
             pc, ps = mx.mx_quantize(wbig, f)
-            m, _, _ = time_region(torch, lambda: mx.mx_quantize(wbig, f, pc, ps), 10, 3)
+            m, _, _ = time_region(torch, lambda: mx.mx_quantize(wbig, f, pc, ps), 10, 3, WARM_MS)
             rows["quantize_bf16_%s" % elem] = row(r * c * 2 + r * c // 32 * (4 * bits + 1), m)
             deq = torch.empty((r, c), dtype=torch.bfloat16, device="cuda")
-            m, _, _ = time_region(torch, lambda: mx.mx_dequant(pc, ps, f, r, c, out=deq), 10, 3)
+            m, _, _ = time_region(torch, lambda: mx.mx_dequant(pc, ps, f, r, c, out=deq), 10, 3, WARM_MS)
             rows["dequant_%s_bf16" % elem] = row(r * c * 2 + r * c // 32 * (4 * bits + 1), m)
             del pc, ps, deq
         del wbig
@@ -225,21 +235,21 @@ def main():
                 if via and elem not in ("int8", "e4m3"):
                     anchor = mx.make_format("int8" if elem.startswith("int") else "e4m3")
                 mx.mx_fake_quant(act, mx.make_format(elem), anchor, out)
-            m, _, _ = time_region(torch, fq, 64, 6)
+            m, _, _ = time_region(torch, fq, 64, 6, WARM_MS)
             rows["fake_quant_bf16_mixed_formats" + ("_via_anchor" if via else "")] = row(nby, m)
         for elem in ("int8", "int4", "e4m3", "e3m2", "e2m1"):
             f = mx.make_format(elem)
-            m, _, _ = time_region(torch, lambda: mx.mx_fake_quant(act, f, None, out), 10, 3)
+            m, _, _ = time_region(torch, lambda: mx.mx_fake_quant(act, f, None, out), 10, 3, WARM_MS)
             rows["fake_quant_bf16_%s" % elem] = row(nby, m)
         # blocks down the columns (axis 0) on the same 256 MiB activation tensor: fake-quant, quantize, dequantize
         for elem, bits in (("e2m1", 4), ("int4", 4), ("e4m3", 8)):
             f0 = mx.make_format(elem, axis=0)
-            m, _, _ = time_region(torch, lambda: mx.mx_fake_quant(act, f0, None, out), 10, 3)
+            m, _, _ = time_region(torch, lambda: mx.mx_fake_quant(act, f0, None, out), 10, 3, WARM_MS)
             rows["fake_quant_bf16_%s_axis0" % elem] = row(nby, m)
             pc, ps = mx.mx_quantize(act, f0)
-            m, _, _ = time_region(torch, lambda: mx.mx_quantize(act, f0, pc, ps), 10, 3)
+            m, _, _ = time_region(torch, lambda: mx.mx_quantize(act, f0, pc, ps), 10, 3, WARM_MS)
             rows["quantize_bf16_%s_axis0" % elem] = row(act.numel() * 2 + act.numel() // 32 * (4 * bits + 1), m)
-            m, _, _ = time_region(torch, lambda: mx.mx_dequant(pc, ps, f0, act.shape[0], act.shape[1], out=out), 10, 3)
+            m, _, _ = time_region(torch, lambda: mx.mx_dequant(pc, ps, f0, act.shape[0], act.shape[1], out=out), 10, 3, WARM_MS)
             rows["dequant_%s_bf16_axis0" % elem] = row(act.numel() * 2 + act.numel() // 32 * (4 * bits + 1), m)
             del pc, ps
         gemm_rows(torch, mx, synth, rows)
@@ -269,7 +279,7 @@ def gemm_rows(torch, mx, synth, rows):
         def gemm():
             i = st["i"] = (st["i"] + 1) % 8
             mx.mx_gemm_ss_fp4(ac, asc, wlist[i][0], wlist[i][1], cbuf)
-        m, _, _ = time_region(torch, gemm, 24, 8)
+        m, _, _ = time_region(torch, gemm, 24, 8, WARM_MS)
         flops = 2.0 * Mg * Ng * Kg
         nbytes_g = Ng * Kg + Ng * Kg // 32 + Mg * Kg + Mg * Kg // 32 + Mg * Ng * 4
         rows["gemm_ss_fp4_M%d" % Mg] = {"ms": round(m, 4), "TFLOP/s": round(flops / (m * 1e-3) / 1e12, 1),

@@ -306,13 +306,23 @@ __global__ __launch_bounds__(TPB) void dequant_rows_kernel(const uint32_t* __res
   for (int u = 0; u < U; ++u) {
     int64_t q = q0 + TPB * u;
     if (q < nchunks) {
-      float v[N];
-      decode_chunk<ELEM, HW, N>(bits[u], byte[u], v);
-      if (byte[u] == 255u) {
+      if constexpr (DT == MX_BF16 && (E::hw == HW_FP6 || E::hw == HW_BF6)) {
+        // 6-bit minifloat codes straight to bf16: one conversion instruction for the lane's 8 codes (the other 24
+        // inputs are zeros), its first 4 result dwords are the 16-byte output chunk
+        u32x6 a = {(uint32_t)bits[u], (uint32_t)(bits[u] >> 32), 0u, 0u, 0u, 0u};
+        u32x16 r = cvt_pk32_bf16_fp6<E::hw == HW_BF6>(a, scale_operand(byte[u]));
+        u32x4 t = {r[0], r[1], r[2], r[3]};
+        if (byte[u] == 255u) t = u32x4{0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u};
+        stream_store(reinterpret_cast<u32x4*>(static_cast<char*>(dst) + chunk_offset<N>(q, chunks_per_row, ld, flat) * 2), t);
+      } else {
+        float v[N];
+        decode_chunk<ELEM, HW, N>(bits[u], byte[u], v);
+        if (byte[u] == 255u) {
 #pragma unroll
-        for (int i = 0; i < N; ++i) v[i] = __uint_as_float(0x7FC00000u);
+          for (int i = 0; i < N; ++i) v[i] = __uint_as_float(0x7FC00000u);
+        }
+        store_chunk<DT>(dst, chunk_offset<N>(q, chunks_per_row, ld, flat), v);
       }
-      store_chunk<DT>(dst, chunk_offset<N>(q, chunks_per_row, ld, flat), v);
     }
   }
 }
@@ -631,7 +641,7 @@ template <int ELEM>
 constexpr RowsShape dequant_shape() {
   using E = Elem<ELEM>;
   if (E::bits == 4) return E::is_int ? RowsShape{4, 256} : RowsShape{2, 256};  // 79, 83 (1 x 64: 63, 65)
-  if (E::bits == 6) return RowsShape{2, 64};                                   // 72
+  if (E::bits == 6) return RowsShape{1, 256};                                  // FP6 79 (one conversion per lane), MXINT6 73
   return RowsShape{1, 64};                                                     // 8-bit: 83
 }
 constexpr int kFqUnroll = 1;                  // fake-quant: one chunk per lane, one wave per workgroup (82 - 83)

@@ -126,6 +126,16 @@ __device__ __forceinline__ u32x6 cvt_pk32_fp6_f16(f16x32 a, float s) {
   else asm("v_cvt_scalef32_pk32_fp6_f16 %0, %1, %2" : "=&v"(d) : "v"(a), "v"(s));
   return d;
 }
+// 32 FP6 codes (6 dwords) times the E8M0 scale -> 32 bf16 (16 dwords), exact for every code and scale byte
+// (the products have at most 4 significant bits; subnormal results included -- enumerated on the GPU).
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+template <bool BF6>
+__device__ __forceinline__ u32x16 cvt_pk32_bf16_fp6(u32x6 a, float s) {
+  u32x16 d;
+  if constexpr (BF6) asm("v_cvt_scalef32_pk32_bf16_bf6 %0, %1, %2" : "=&v"(d) : "v"(a), "v"(s));
+  else asm("v_cvt_scalef32_pk32_bf16_fp6 %0, %1, %2" : "=&v"(d) : "v"(a), "v"(s));
+  return d;
+}
 // ------------------------------------------------------------------ software element codecs
 // clip_b(Round(V / X)) for integer elements, X = 2^-sh.  Half away from zero: with q2 = trunc(2r)
 // (the conversion truncates toward zero; 2r is exact), Round(r) = (q2 + [q2 >= 0]) >> 1 with an
