@@ -99,6 +99,8 @@ def main():
     ap.add_argument("--layers", type=int, default=32, help="decoder layers of the synthetic checkpoint (32 = the 8B shape)")
     ap.add_argument("--no-rows", action="store_true", help="skip the secondary rows")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--warm-ms", type=float, default=None,
+                    help="untimed warm-up time per secondary row in ms (default 30; 0 keeps counter profiles small)")
     ap.add_argument("--only", default=None, choices=["gemm"],
                     help="profiling aid: run only this group of secondary rows (no headline, no CPU baseline)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -116,6 +118,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
 
+    global WARM_MS
+    if args.warm_ms is not None:
+        WARM_MS = args.warm_ms
     if args.only == "gemm":
         rows = {}
         gemm_rows(torch, mx, synth, rows)

@@ -215,7 +215,7 @@ __global__ __launch_bounds__(TPB) void quantize_rows_kernel(const void* __restri
   for (int u = 0; u < U; ++u) {
     int64_t q = q0 + TPB * u;
     uint32_t byte = scale_byte_from_amax<E::emax>(block_max<G, KG>(chunk_amax_bits(v[u]), log2_lanes));
-    uint64_t bits = byte == 255u ? 0ull : encode_chunk<ELEM, HW, N>(v[u], byte, tie);
+    uint64_t bits = byte == 255u ? 0ull : encode_chunk<ELEM, HW, N, DT == MX_BF16>(v[u], byte, tie);
     int64_t blk = q / G;  // windows of 32 codes are numbered like the chunks: row-major
     if constexpr (direct_code_store(N * W)) {
       // a window's lanes are all live or all not (chunks per row is a multiple of the group size)
@@ -329,7 +329,7 @@ __global__ __launch_bounds__(TPB) void dequant_rows_kernel(const uint32_t* __res
 
 // ------------------------------------------------------------------ fake-quant of one chunk / column piece
 // v (N elements of a block whose scale byte(s) are given) -> DQ(Q(v)) in place.
-template <int TARGET, int ANCHOR, bool HW, int N>
+template <int TARGET, int ANCHOR, bool HW, int N, bool NARROW = false>
 __device__ __forceinline__ void fake_quant_chunk(float (&v)[N], uint32_t byte_first, int tie) {
   // byte_first: scale byte of the format quantized first (the anchor if there is one)
   if (byte_first == 255u) {
@@ -338,7 +338,16 @@ __device__ __forceinline__ void fake_quant_chunk(float (&v)[N], uint32_t byte_fi
     return;
   }
   if constexpr (ANCHOR < 0) {
-    uint64_t c = encode_chunk<TARGET, HW, N>(v, byte_first, tie);
+    if constexpr (Elem<TARGET>::is_int && NARROW) {
+      if (tie != MX_ROUND_HALF_EVEN) {
+        // bf16 source, MXINT target: Round in one fma (see round_int_narrow), and X * P without going through codes
+        const float scale = ldexpf(1.0f, 127 - (int)byte_first), x = ldexpf(1.0f, (int)byte_first - 127);
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] = (float)round_int_narrow<Elem<TARGET>::bits>(v[i], scale) * x;
+        return;
+      }
+    }
+    uint64_t c = encode_chunk<TARGET, HW, N, NARROW>(v, byte_first, tie);
     decode_chunk<TARGET, HW, N>(c, byte_first, v);
   } else if constexpr (Elem<ANCHOR>::is_int) {
     // Eq. (7) with Eq. (4), all in integer registers: P_h = clip(Round(V / X_h)); P_l = clip(Round(P_h / 2^De)) is
@@ -348,9 +357,12 @@ __device__ __forceinline__ void fake_quant_chunk(float (&v)[N], uint32_t byte_fi
     constexpr int HALF = 1 << (DE - 1), LIM = (1 << (BL - 1)) - 1;
     int sh = 127 - (int)byte_first;
     uint32_t byte_l = byte_first + DE > 254u ? 254u : byte_first + DE;
+    const float scale_h = ldexpf(1.0f, sh);
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      int ph = ((int)(encode_int_scaled<BH>(v[i], sh, tie) << (32 - BH))) >> (32 - BH);
+      int ph;
+      if (NARROW && tie != MX_ROUND_HALF_EVEN) ph = round_int_narrow<BH>(v[i], scale_h);
+      else ph = ((int)(encode_int_scaled<BH>(v[i], sh, tie) << (32 - BH))) >> (32 - BH);
       int pl = (tie == MX_ROUND_HALF_EVEN) ? (ph + (HALF - 1) + ((ph >> DE) & 1)) >> DE : (ph + HALF + (ph >> 31)) >> DE;
       pl = pl < -LIM ? -LIM : (pl > LIM ? LIM : pl);
       v[i] = ldexpf((float)pl, (int)byte_l - 127);
@@ -394,7 +406,7 @@ __global__ __launch_bounds__(TPB) void fake_quant_rows_kernel(const void* __rest
   for (int u = 0; u < U; ++u) {
     int64_t q = q0 + TPB * u;
     uint32_t byte = scale_byte_from_amax<Elem<FIRST>::emax>(block_max<G, KG>(chunk_amax_bits(v[u]), log2_lanes));
-    fake_quant_chunk<TARGET, ANCHOR, HW, N>(v[u], byte, tie);
+    fake_quant_chunk<TARGET, ANCHOR, HW, N, DT == MX_BF16>(v[u], byte, tie);
     if (q < nchunks) store_chunk<DT>(dst, chunk_offset<N>(q, chunks_per_row, ld_dst, flat_dst), v[u]);
   }
 }
@@ -485,7 +497,7 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(const void* __restri
         float x[8];
 #pragma unroll
         for (int r = 0; r < 8; ++r) x[r] = v[8 * C + r][j];
-        uint64_t bits = byte[j] == 255u ? 0ull : encode_chunk<ELEM, HW, 8>(x, byte[j], tie);
+        uint64_t bits = byte[j] == 255u ? 0ull : encode_chunk<ELEM, HW, 8, DT == MX_BF16>(x, byte[j], tie);
         insert_bits<W, C * 8 * W, 8 * W>(out[j], bits);
       });
       tile_scales[(4 * lane + j) * kColTileRbs + wave] = (uint8_t)byte[j];
@@ -613,7 +625,7 @@ __global__ __launch_bounds__(TPB) void fake_quant_cols_kernel(const void* __rest
       float x[8];
 #pragma unroll
       for (int r = 0; r < 8; ++r) x[r] = v[8 * c + r][j];
-      fake_quant_chunk<TARGET, ANCHOR, HW, 8>(x, byte[j], tie);
+      fake_quant_chunk<TARGET, ANCHOR, HW, 8, DT == MX_BF16>(x, byte[j], tie);
 #pragma unroll
       for (int r = 0; r < 8; ++r) v[8 * c + r][j] = x[r];
     }
@@ -632,7 +644,7 @@ struct RowsShape { int unroll, threads; };
 template <int ELEM>
 constexpr RowsShape quantize_shape() {
   using E = Elem<ELEM>;
-  if (E::is_int) return E::bits == 8 ? RowsShape{4, 256} : RowsShape{4, 64};  // 80 (1 x 64: 67); 77 - 79 (1 x 64: 67 - 70)
+  if (E::is_int) return RowsShape{4, 64};                                      // MXINT8 / 6 / 4: 82 / 79 / 82 (1 x 64: 70 - 75)
   if (E::hw == HW_FP8) return RowsShape{2, 128};                               // 83
   if (E::hw != HW_NONE) return RowsShape{2, 64};                               // E2M1 85 (1 x 64: 73), FP6 79
   return RowsShape{1, 256};

@@ -154,6 +154,18 @@ __device__ __forceinline__ uint32_t encode_int_scaled(float v, int sh, int tie) 
   return (uint32_t)q & ((1u << BITS) - 1u);
 }
 
+// The same for sources with at most 8 significant bits (bf16), half away from zero only: V * 2^sh + copysign(1/2, V)
+// is then exact in fp32 unless |V * 2^sh| < 2^-16 (where the sum still truncates to 0), so one fma and the
+// truncating conversion give Round.  (An fp32 source can sit half an ulp below a tie and would round up twice.)
+// `scale` = 2^sh, subnormal for sh = -127.  Returns the clipped integer, not yet masked.
+template <int BITS>
+__device__ __forceinline__ int round_int_narrow(float v, float scale) {
+  constexpr int LIM = (1 << (BITS - 1)) - 1;
+  float half = __uint_as_float((__float_as_uint(v) & 0x80000000u) | 0x3F000000u);
+  int q = (int)fmaf(v, scale, half);
+  return q < -LIM ? -LIM : (q > LIM ? LIM : q);
+}
+
 template <int BITS>
 __device__ __forceinline__ uint32_t encode_int(float r, int tie) {
   return encode_int_scaled<BITS>(r, 0, tie);
@@ -230,7 +242,8 @@ __device__ __forceinline__ float decode_sw(uint32_t c) {
 // A "chunk" is N consecutive elements of one block held by one lane (N = 4 or 8), already as
 // fp32.  encode_chunk returns their codes as a little-endian bit string of N * bits bits
 // (element 0 in the low bits).  HW selects the scaled conversion instructions (ties to even).
-template <int ELEM, bool HW, int N>
+// NARROW: the values have at most 8 significant bits (they came from bf16).
+template <int ELEM, bool HW, int N, bool NARROW = false>
 __device__ __forceinline__ uint64_t encode_chunk(const float (&v)[N], uint32_t byte, int tie) {
   using E = Elem<ELEM>;
   static_assert(N == 4 || N == 8, "chunk of 4 or 8 elements");
@@ -270,6 +283,37 @@ __device__ __forceinline__ uint64_t encode_chunk(const float (&v)[N], uint32_t b
   } else {
     uint32_t lo = 0, hi = 0;
     int sh = 127 - (int)byte;
+    if constexpr (E::is_int && NARROW) {
+      if (tie != MX_ROUND_HALF_EVEN) {
+        const float scale = ldexpf(1.0f, sh);
+        int q[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) q[i] = round_int_narrow<E::bits>(v[i], scale);
+        if constexpr (E::bits == 8) {
+          // 4 low bytes -> one dword with byte permutes (no masks)
+#pragma unroll
+          for (int d = 0; d < N / 4; ++d) {
+            uint32_t p01 = __builtin_amdgcn_perm((uint32_t)q[4 * d + 1], (uint32_t)q[4 * d], 0x0c0c0400u);
+            uint32_t p23 = __builtin_amdgcn_perm((uint32_t)q[4 * d + 3], (uint32_t)q[4 * d + 2], 0x0c0c0400u);
+            uint32_t w = __builtin_amdgcn_perm(p23, p01, 0x05040100u);
+            if (d == 0) lo = w; else hi = w;
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < N; ++i) {
+            uint32_t c = (uint32_t)q[i] & ((1u << E::bits) - 1u);
+            const int pos = i * E::bits;
+            if (pos < 32) {
+              lo |= c << pos;
+              if (pos + E::bits > 32) hi |= c >> (32 - pos);
+            } else {
+              hi |= c << (pos - 32);
+            }
+          }
+        }
+        return (uint64_t)lo | ((uint64_t)hi << 32);
+      }
+    }
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       uint32_t c;
