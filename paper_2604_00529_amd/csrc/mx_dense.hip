@@ -406,8 +406,32 @@ __global__ __launch_bounds__(TPB) void fake_quant_rows_kernel(const void* __rest
   for (int u = 0; u < U; ++u) {
     int64_t q = q0 + TPB * u;
     uint32_t byte = scale_byte_from_amax<Elem<FIRST>::emax>(block_max<G, KG>(chunk_amax_bits(v[u]), log2_lanes));
-    fake_quant_chunk<TARGET, ANCHOR, HW, N, DT == MX_BF16>(v[u], byte, tie);
-    if (q < nchunks) store_chunk<DT>(dst, chunk_offset<N>(q, chunks_per_row, ld_dst, flat_dst), v[u]);
+    using T = Elem<TARGET>;
+    if constexpr (HW && DT == MX_BF16 && (T::hw == HW_FP6 || T::hw == HW_BF6) && (ANCHOR < 0 || !Elem<FIRST>::is_int)) {
+      // 6-bit minifloat target, bf16 tensor: the codes go back to bf16 with one hardware conversion (exact for every
+      // code and scale byte) instead of eight software decodes and four packs
+      uint64_t c;
+      uint32_t byte_t = byte;
+      if constexpr (ANCHOR < 0) {
+        c = encode_chunk<TARGET, HW, N>(v[u], byte, tie);
+      } else {
+        constexpr int DE = Elem<ANCHOR>::emax - T::emax;   // Eq. (7) through the MXFP8 anchor
+        uint64_t ch = encode_chunk<ANCHOR, HW, N>(v[u], byte, tie);
+        float ph[N];
+        decode_chunk<ANCHOR, HW, N>(ch, 127u, ph);
+        c = encode_chunk<TARGET, HW, N>(ph, 127u + DE, tie);
+        byte_t = byte + DE > 254u ? 254u : byte + DE;
+      }
+      u32x6 a = {(uint32_t)c, (uint32_t)(c >> 32), 0u, 0u, 0u, 0u};
+      u32x16 r = cvt_pk32_bf16_fp6<T::hw == HW_BF6>(a, scale_operand(byte_t));
+      u32x4 t = {r[0], r[1], r[2], r[3]};
+      if (byte == 255u) t = u32x4{0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u};
+      if (q < nchunks)
+        stream_store(reinterpret_cast<u32x4*>(static_cast<char*>(dst) + chunk_offset<N>(q, chunks_per_row, ld_dst, flat_dst) * 2), t);
+    } else {
+      fake_quant_chunk<TARGET, ANCHOR, HW, N, DT == MX_BF16>(v[u], byte, tie);
+      if (q < nchunks) store_chunk<DT>(dst, chunk_offset<N>(q, chunks_per_row, ld_dst, flat_dst), v[u]);
+    }
   }
 }
 
