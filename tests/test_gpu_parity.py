@@ -310,3 +310,37 @@ def test_config2_end_to_end(mx, oracle, axis):
         gc, gs = mx.mx_slice_and_scale(c8, s8, f8, mx.make_format(t, axis=axis))
         wc, ws = oracle.slice_and_scale(wc8, ws8, "e4m3", t)
         assert np.array_equal(to_host(gc), wc) and np.array_equal(to_host(gs), ws)
+
+
+# ------------------------------------------------------------------------------------ every bf16 value
+def _all_bf16_blocks():
+    """Every one of the 65536 bf16 bit patterns (NaN / Inf included), 31 to a block, behind a leading element that
+    sets the block's scale from far below to far above the values' own magnitudes."""
+    vals = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    pad = (-len(vals)) % 31
+    vals = np.concatenate([vals, np.zeros(pad, dtype=np.uint16)]).reshape(-1, 31)
+    rows = []
+    for leader in (0x0000, 0x0080, 0x2000, 0x3800, 0x3F80, 0x4300, 0x5000, 0x7F00, 0xBF80):   # 0, 2^-126, ..., 1, 128, ..., -1
+        lead = np.full((vals.shape[0], 1), leader, dtype=np.uint16)
+        rows.append(np.concatenate([lead, vals], axis=1).reshape(-1))
+    flat = np.concatenate(rows)
+    cols = 1024
+    n = len(flat) // cols * cols
+    return flat[:n].reshape(-1, cols)
+
+
+@pytest.mark.parametrize("fmt", CORE + EXTRA)
+def test_every_bf16_value(mx, oracle, fmt):
+    m = _all_bf16_blocks()
+    g = to_gpu(m)
+    anchor = None if fmt in ("int8", "e4m3") else ("int8" if fmt.startswith("int") else "e4m3")
+    for tie in ("default", "away", "even"):
+        f = mx.make_format(fmt, round=tie)
+        want_c, want_s = oracle.quantize(m, fmt, tie=TIES[tie])
+        got_c, got_s = mx.mx_quantize(g, f)
+        assert np.array_equal(to_host(got_s), want_s), tie
+        assert np.array_equal(to_host(got_c), want_c), tie
+        assert_same_values(to_host(mx.mx_fake_quant(g, f)), oracle.fake_quant(m, fmt, tie=TIES[tie]))
+        if anchor is not None:
+            fa = mx.make_format(anchor, round=tie)
+            assert_same_values(to_host(mx.mx_fake_quant(g, f, anchor=fa)), oracle.fake_quant(m, fmt, anchor=anchor, tie=TIES[tie]))
