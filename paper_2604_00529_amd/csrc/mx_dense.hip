@@ -197,16 +197,25 @@ __global__ __launch_bounds__(TPB) void quantize_rows_kernel(const void* __restri
   int tid = threadIdx.x;
   if constexpr (HW && E::hw == HW_FP8) tid = set_fp8_saturation(tid);
   int64_t q0 = (int64_t)blockIdx.x * (TPB * U) + tid;
+  // bf16 tensor and a 6-bit minifloat with a hardware conversion: the 8 bf16 values of a chunk are converted as they
+  // were loaded (one 32-wide conversion whose other 24 inputs are zeros), and |V| is maximised on the 16-bit halves
+  constexpr bool RAW6 = HW && DT == MX_BF16 && (E::hw == HW_FP6 || E::hw == HW_BF6);
   float v[U][N];
+  u32x4 raw[U];
   bool live[U];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     int64_t q = q0 + TPB * u;
     live[u] = q < nchunks;
-    if (live[u]) load_chunk<DT>(src, chunk_offset<N>(q, chunks_per_row, ld, flat), v[u]);
-    else {
+    if constexpr (RAW6) {
+      raw[u] = u32x4{0u, 0u, 0u, 0u};
+      if (live[u]) raw[u] = stream_load(reinterpret_cast<const u32x4*>(static_cast<const char*>(src) + chunk_offset<N>(q, chunks_per_row, ld, flat) * 2));
+    } else {
+      if (live[u]) load_chunk<DT>(src, chunk_offset<N>(q, chunks_per_row, ld, flat), v[u]);
+      else {
 #pragma unroll
-      for (int i = 0; i < N; ++i) v[u][i] = 0.0f;
+        for (int i = 0; i < N; ++i) v[u][i] = 0.0f;
+      }
     }
   }
   const int lig = tid & (G - 1);                                  // lane inside its window of 32 codes
@@ -214,8 +223,22 @@ __global__ __launch_bounds__(TPB) void quantize_rows_kernel(const void* __restri
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     int64_t q = q0 + TPB * u;
-    uint32_t byte = scale_byte_from_amax<E::emax>(block_max<G, KG>(chunk_amax_bits(v[u]), log2_lanes));
-    uint64_t bits = byte == 255u ? 0ull : encode_chunk<ELEM, HW, N, DT == MX_BF16>(v[u], byte, tie);
+    uint32_t byte;
+    uint64_t bits;
+    if constexpr (RAW6) {
+      typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+      u16x2 m0 = __builtin_bit_cast(u16x2, raw[u].x & 0x7FFF7FFFu), m1 = __builtin_bit_cast(u16x2, raw[u].y & 0x7FFF7FFFu);
+      u16x2 m2 = __builtin_bit_cast(u16x2, raw[u].z & 0x7FFF7FFFu), m3 = __builtin_bit_cast(u16x2, raw[u].w & 0x7FFF7FFFu);
+      u16x2 m = __builtin_elementwise_max(__builtin_elementwise_max(m0, m1), __builtin_elementwise_max(m2, m3));
+      uint32_t amax = (uint32_t)(m.x > m.y ? m.x : m.y) << 16;   // the fp32 bit pattern of the largest |V|
+      byte = scale_byte_from_amax<E::emax>(block_max<G, KG>(amax, log2_lanes));
+      u32x16 a = {raw[u].x, raw[u].y, raw[u].z, raw[u].w, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+      u32x6 p = cvt_pk32_fp6_bf16<E::hw == HW_BF6>(a, scale_operand(byte));
+      bits = byte == 255u ? 0ull : ((uint64_t)p[0] | ((uint64_t)(p[1] & 0xFFFFu) << 32));
+    } else {
+      byte = scale_byte_from_amax<E::emax>(block_max<G, KG>(chunk_amax_bits(v[u]), log2_lanes));
+      bits = byte == 255u ? 0ull : encode_chunk<ELEM, HW, N, DT == MX_BF16>(v[u], byte, tie);
+    }
     int64_t blk = q / G;  // windows of 32 codes are numbered like the chunks: row-major
     if constexpr (direct_code_store(N * W)) {
       // a window's lanes are all live or all not (chunks per row is a multiple of the group size)

@@ -136,6 +136,14 @@ __device__ __forceinline__ u32x16 cvt_pk32_bf16_fp6(u32x6 a, float s) {
   else asm("v_cvt_scalef32_pk32_bf16_fp6 %0, %1, %2" : "=&v"(d) : "v"(a), "v"(s));
   return d;
 }
+// 32 bf16 values (16 dwords) divided by the E8M0 scale -> 32 FP6 codes (6 dwords): round to nearest even, saturating.
+template <bool BF6>
+__device__ __forceinline__ u32x6 cvt_pk32_fp6_bf16(u32x16 a, float s) {
+  u32x6 d;
+  if constexpr (BF6) asm("v_cvt_scalef32_pk32_bf6_bf16 %0, %1, %2" : "=&v"(d) : "v"(a), "v"(s));
+  else asm("v_cvt_scalef32_pk32_fp6_bf16 %0, %1, %2" : "=&v"(d) : "v"(a), "v"(s));
+  return d;
+}
 // ------------------------------------------------------------------ software element codecs
 // clip_b(Round(V / X)) for integer elements, X = 2^-sh.  Half away from zero: with q2 = trunc(2r)
 // (the conversion truncates toward zero; 2r is exact), Round(r) = (q2 + [q2 >= 0]) >> 1 with an
