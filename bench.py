@@ -246,6 +246,10 @@ def main():
             f = mx.make_format(elem)
             m, _, _ = time_region(torch, lambda: mx.mx_fake_quant(act, f, None, out), 10, 3, WARM_MS)
             rows["fake_quant_bf16_%s" % elem] = row(nby, m)
+        # for scale: the framework's own device-to-device copy of the same tensor (same 2 B read + 2 B written per
+        # element as fake-quant; not a kernel of this library)
+        m, _, _ = time_region(torch, lambda: out.copy_(act), 10, 3, WARM_MS)
+        rows["reference_torch_copy_bf16"] = row(nby, m)
         # blocks down the columns (axis 0) on the same 256 MiB activation tensor: fake-quant, quantize, dequantize
         for elem, bits in (("e2m1", 4), ("int4", 4), ("e4m3", 8)):
             f0 = mx.make_format(elem, axis=0)
