@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the MX hot path on one MI355X.
 
-Headline (the benchmark's metric): Slice-and-Scale MXFP8 (E4M3) -> MXFP4 (E2M1) over a
+Headline: Slice-and-Scale MXFP8 (E4M3) -> MXFP4 (E2M1) over a
 Llama-8B-shaped decoder checkpoint (224 linear weights, 6 979 321 856 elements, block 32), as
 GB/s of algorithmic traffic (anchor codes + anchor scales read, target codes + target scales
 written) and as a fraction of the 8 TB/s HBM peak.  One step = one such pass over the whole

@@ -151,7 +151,7 @@ mx_status_t mx_fake_quant(const mx_format_t* target, const mx_format_t* anchor, 
 mx_status_t mx_dequant(const mx_format_t* f, const mx_packed_t* src, const mx_dense_t* dst, void* stream);
 
 /* Fused consumer of the anchor (Sec. 3.5 "Inference": the model runs with W_t = Q_{A->t}(W_A) generated on
- * demand; BASELINE workload "fused consumer GEMM"):
+ * demand):
  *     C[m, n] = sum_k DQ(A)[m, k] * DQ(Q_{A->t}(W_A))[n, k],   t = MXFP4 E2M1,
  * with the Slice-and-Scale conversion of Eq. (6) done in registers and the product taken by the CDNA4 scaled
  * MX matrix instruction with fp32 accumulation; W_t is never written to memory.

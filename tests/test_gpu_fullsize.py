@@ -158,3 +158,58 @@ def test_config4_fake_quant_full_size(env, oracle):
         got = _bf16_to_host(wo[:, torch.as_tensor(cols, device="cuda")].contiguous())
         want = oracle.fake_quant(hostw, elem, axis=0)
         assert np.array_equal(got, want), elem
+
+
+def test_offsets_beyond_4_gib(env, oracle):
+    """One tensor of 4.3 G elements: element and byte offsets pass 2^31 and 2^32 inside a single call of every entry point
+    (row 2^18 starts at byte 2^31 of the bf16 matrix, row 2^19 at byte 2^32 = element 2^31, row 2^20 at element 2^32 = byte
+    2^32 of the 8-bit codes = byte 2^31 of the 4-bit codes).  Rows on both sides of each boundary, the first and the last
+    row are compared with the oracle."""
+    torch, mx, _ = env
+    rows, cols = (1 << 20) + 96, 4096
+    x = torch.empty((rows, cols), dtype=torch.bfloat16, device="cuda")
+    g = torch.Generator(device="cuda").manual_seed(4096)
+    for r0 in range(0, rows, 1 << 16):
+        r1 = min(rows, r0 + (1 << 16))
+        x[r0:r1] = torch.randn((r1 - r0, cols), device="cuda", generator=g, dtype=torch.float32).mul_(0.02).to(torch.bfloat16)
+    probe = sorted({0, rows - 1, 699050, 699051} | {b + d for b in (1 << 18, 1 << 19, 3 << 18, 1 << 20) for d in (-1, 0)})
+    idx = torch.as_tensor(probe, device="cuda")
+    host = _bf16_to_host(x[idx].contiguous())
+    f8, f4, f6 = mx.make_format("e4m3"), mx.make_format("e2m1"), mx.make_format("e3m2")
+
+    ac, asc = mx.mx_quantize(x, f8)                                   # 4.3 GB of codes
+    oc, osc = oracle.quantize(host, "e4m3")
+    assert np.array_equal(ac[idx].cpu().numpy(), oc) and np.array_equal(asc[idx].cpu().numpy(), osc)
+    for ft, name in ((f4, "e2m1"), (f6, "e3m2")):                     # 6-bit codes: byte 2^31 falls in row 699050
+        tc, ts = mx.mx_slice_and_scale(ac, asc, f8, ft)
+        wc, ws = oracle.slice_and_scale(oc, osc, "e4m3", name)
+        assert np.array_equal(tc[idx].cpu().numpy(), wc) and np.array_equal(ts[idx].cpu().numpy(), ws), name
+        if name == "e2m1":
+            y = mx.mx_dequant(tc, ts, ft, rows, cols, dtype=torch.bfloat16)
+            want = oracle.dequant(wc, ws, "e2m1", len(probe), cols, out="bf16")
+            assert np.array_equal(_bf16_to_host(y[idx].contiguous()), want)
+            del y
+        del tc, ts
+    del ac, asc
+    torch.cuda.empty_cache()
+
+    y = torch.empty_like(x)
+    mx.mx_fake_quant(x, mx.make_format("int4"), mx.make_format("int8"), y)
+    assert np.array_equal(_bf16_to_host(y[idx].contiguous()), oracle.fake_quant(host, "int4", anchor="int8"))
+    # blocks down the columns: the row blocks on both sides of each boundary, all columns
+    mx.mx_fake_quant(x, mx.make_format("e2m1", axis=0), None, y)
+    for b in (1 << 18, 1 << 19, 1 << 20):
+        slab = _bf16_to_host(x[b - 32:b + 32].contiguous())
+        assert np.array_equal(_bf16_to_host(y[b - 32:b + 32].contiguous()), oracle.fake_quant(slab, "e2m1", axis=0)), b
+    del y
+    # transposed packed tensor of the column-axis quantizer: whole columns, the last one ends past byte 2^31
+    f4c = mx.make_format("e2m1", axis=0)
+    cc, cs = mx.mx_quantize(x, f4c)
+    pick = [0, 1, 2047, 2048, 4094, 4095]
+    hostc = _bf16_to_host(x[:, torch.as_tensor(pick, device="cuda")].contiguous())
+    wc, ws = oracle.quantize(hostc, "e2m1", axis=0)
+    pidx = torch.as_tensor(pick, device="cuda")
+    assert np.array_equal(cc[pidx].cpu().numpy(), wc) and np.array_equal(cs[pidx].cpu().numpy(), ws)
+    z = mx.mx_dequant(cc, cs, f4c, rows, cols, dtype=torch.bfloat16)
+    want = oracle.dequant(wc, ws, "e2m1", rows, len(pick), axis=0, out="bf16")
+    assert np.array_equal(_bf16_to_host(z[:, pidx].contiguous()), want)

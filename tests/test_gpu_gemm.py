@@ -88,3 +88,19 @@ def test_gemm_tiled_shapes(mx, oracle, M, N, K):
 def test_gemm_prefill_shape_config5(mx, oracle):
     # M = 2048, K = 4096, N = 14336: the prefill shape of the benchmark definition
     _check(mx, oracle, 2048, 14336, 4096, seed=2005)
+
+
+@pytest.mark.parametrize("M,N,K", [(16, 104, 384), (200, 304, 256)])
+def test_gemm_strided_output(mx, oracle, M, N, K):
+    # C as a view of a wider matrix (ld > N): same values as the contiguous call, nothing written outside the view
+    import torch
+    rng = np.random.default_rng(M + N + K)
+    f8 = mx.make_format("e4m3")
+    ac, asc = mx.mx_quantize(_gpu_bf16(rng.standard_normal((M, K)).astype(np.float32)), f8)
+    wc, wsc = mx.mx_quantize(_gpu_bf16((rng.standard_normal((N, K)) * 0.02).astype(np.float32)), f8)
+    want = mx.mx_gemm_ss_fp4(ac, asc, wc, wsc)
+    wide = torch.full((M, N + 24), -7.0, dtype=torch.float32, device="cuda")
+    mx.mx_gemm_ss_fp4(ac, asc, wc, wsc, out=wide[:, :N])
+    torch.cuda.synchronize()
+    assert torch.equal(wide[:, :N], want)
+    assert bool((wide[:, N:] == -7.0).all())
