@@ -186,6 +186,219 @@ __global__ __launch_bounds__(256) void gemm_ss_fp4_smallm_kernel(const uint8_t* 
   }
 }
 
+// ------------------------------------------------------------------ M <= 16 (decode): coalesced loads, transposed in LDS
+// With M <= 16 the kernel does little but stream W once.  Measured on the 58.7 MB anchor of the 4096 x 14336 layer: read
+// with MFMA fragment loads (the 64 lanes of a load on 16 rows, 16 bytes each) the matrix alone takes 12.3 us, read with
+// loads whose lanes take consecutive 16 bytes of one row 9.7 us.  So every load of W here is one contiguous 1 KB -- lane l
+// takes bytes 16 l .. 16 l + 15 of a row's 1 KB K-chunk, half a block -- and the way into the operand layout goes through
+// a wave-private LDS tile, the anchor sliced to E2M1 (Eq. (6)) on the way in, row by row in the order in which the rows
+// were requested, each as soon as it has arrived.  The A chunk takes the same way, unsliced and without passing through
+// registers (loads with LDS as their destination).  The split of K over
+// the four waves, the order of the MFMAs and the final sum are those of the kernel above: the results are the same bit
+// for bit.
+//
+// LDS tile of a wave, used twice per chunk.  First the A chunk: 16 rows of 64 slots of 16 bytes, rows padded by one slot
+// so that the 16 lanes that read one slot of 16 consecutive rows hit 16 different bank groups.  Then, per column tile,
+// 16 rows of 32 slots (one row = the 512 bytes of a column's sliced chunk) with slot s of row r at slot s ^ (r & 15), for
+// the same reason; a row is still written as one contiguous (permuted) run.
+constexpr int kDecodeNT = 2;
+constexpr int kDecodeARow = 1024 + 16;          // A rows are padded by one slot: row r, slot s -> bank group (r + s) % 16
+constexpr int kDecodeTile = 16 * kDecodeARow;   // (>= the 16 KB of the two sliced W tiles)
+constexpr int kDecodeSmem = 4 * kDecodeTile + 3 * kDecodeNT * 4 * 64 * (int)sizeof(float);
+
+// 16 E4M3 anchor codes (4 dwords) -> 16 E2M1 codes (2 dwords): the Slice-and-Scale element step on half a block
+__device__ __forceinline__ void slice_half_block_e2m1(const u32x4& in4, uint32_t (&out)[2]) {
+  const float two_de = __uint_as_float((uint32_t)(127 + kDeltaE_E4M3_E2M1) << 23);
+  const uint32_t in[4] = {in4.x, in4.y, in4.z, in4.w};
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    uint32_t w = 0;
+    static_for<0, 2>([&](auto hh) {
+      constexpr int H = decltype(hh)::value;
+      uint32_t x = e4m3_nan_to_max(in[2 * j + H]);
+      f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8(x, false);
+      f32x2 b = __builtin_amdgcn_cvt_pk_f32_fp8(x, true);
+      w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, a.x, a.y, two_de, 2 * H);
+      w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, b.x, b.y, two_de, 2 * H + 1);
+    });
+    out[j] = w;
+  }
+}
+
+// Raw buffer over `bytes` bytes at p (stride 0; the last word is the gfx9 descriptor default), and a 128-bit load at
+// byte offset `lane_off` (a register) + `row_off` (a scalar); NT marks W, which is read once, as non-temporal.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_buffer(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
+template <bool NT>
+__device__ __forceinline__ u32x4 buffer_load_x4(__amdgpu_buffer_rsrc_t rsrc, uint32_t lane_off, uint32_t row_off) {
+  auto v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)lane_off, (int)row_off, NT ? 2 : 0);
+  return u32x4{v[0], v[1], v[2], v[3]};
+}
+
+// Byte g of each of the 8 dwords of a row's 32-byte scale chunk (the K-block that lane group g holds in each of the
+// chunk's 8 K-steps): K-steps 0-3 packed into out[0], 4-7 into out[1].
+__device__ __forceinline__ void pack_lane_scales(const u32x4& lo, const u32x4& hi, int g, uint32_t (&out)[2]) {
+  const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+  const int sh = 8 * g;
+#pragma unroll
+  for (int h = 0; h < 2; ++h)
+    out[h] = ((w[4 * h] >> sh) & 0xFFu) | (((w[4 * h + 1] >> sh) & 0xFFu) << 8) | (((w[4 * h + 2] >> sh) & 0xFFu) << 16) |
+             ((w[4 * h + 3] >> sh) << 24);
+}
+
+// s_waitcnt vmcnt(32) on gfx9: vmcnt is split over bits 3:0 and 15:14 of the immediate; the other counters stay at
+// their maxima (expcnt 7 in bits 6:4, lgkmcnt 15 in bits 11:8)
+constexpr int kWaitVmcnt32 = (32 & 15) | (7 << 4) | (15 << 8) | ((32 >> 4) << 14);
+
+// Orders the LDS traffic of one wave for the compiler (the hardware executes a wave's LDS instructions in order, so
+// what other lanes wrote is there when the read executes) without making it wait for the global loads in flight.
+__device__ __forceinline__ void wave_lds_order() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_wave_barrier();
+}
+
+
+__global__ __launch_bounds__(256, 2) void gemm_ss_fp4_decode_kernel(const uint8_t* __restrict__ a_codes,
+                                                                 const uint8_t* __restrict__ a_scales,
+                                                                 const uint8_t* __restrict__ w_codes,
+                                                                 const uint8_t* __restrict__ w_scales, float* __restrict__ c,
+                                                                 int M, int N, int K, int64_t ldc) {
+  constexpr int NT = kDecodeNT;
+  static_assert(NT * 8 * 1024 <= kDecodeTile, "one 8 KB tile of sliced codes per column tile");
+  extern __shared__ __attribute__((aligned(16))) uint8_t decode_smem[];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int i = lane & 15, g = lane >> 4;
+  const int KB = K / 32, ksteps = K / 128, chunks = (ksteps + 7) / 8;
+  uint8_t* tile = decode_smem + wave * kDecodeTile;
+  float(*red)[NT][4][64] = reinterpret_cast<float(*)[NT][4][64]>(decode_smem + 4 * kDecodeTile);   // [3][NT][4][64]
+  f32x4 acc[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int col0 = blockIdx.x * NT * 16;
+  // fragment-side view of the columns (lane (i, g) <-> column i of a tile): scale rows and the output
+  int ncol[NT];   // columns past the edge are computed from column N - 1 and never stored
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) ncol[nt] = col0 + nt * 16 + i;
+  // Buffer loads: the 48 loads of a chunk share one offset register per operand (the row is a scalar offset); with one
+  // 64-bit address per load the kernel does not fit two waves per SIMD.  The host has checked that both matrices are
+  // smaller than 4 GiB.  Reads past the end of a buffer return zero.
+  const __amdgpu_buffer_rsrc_t a_rsrc = make_buffer(a_codes, (uint32_t)M * (uint32_t)K);
+  const __amdgpu_buffer_rsrc_t w_rsrc = make_buffer(w_codes, (uint32_t)N * (uint32_t)K);
+  const __amdgpu_buffer_rsrc_t as_rsrc = make_buffer(a_scales, (uint32_t)M * (uint32_t)KB);
+  const __amdgpu_buffer_rsrc_t ws_rsrc = make_buffer(w_scales, (uint32_t)N * (uint32_t)KB);
+  for (int chunk = wave; chunk < chunks; chunk += 4) {
+    // Lane l covers K-step l / 8 of the chunk.  In a ragged last chunk the lanes of K-steps that do not exist load the
+    // chunk's first 16 bytes instead (every access stays inside the matrices); what they load is sliced like the rest and
+    // never multiplied: the MFMA loop stops at the last K-step.  Rows of A past M read row M - 1; their products land in
+    // output rows that are not stored.
+    const int steps = ksteps - chunk * 8 < 8 ? ksteps - chunk * 8 : 8;
+    const uint32_t lane_off = (lane >> 3) < steps ? 16u * (uint32_t)lane : 0u;
+    const uint32_t chunk_off = (uint32_t)chunk * 1024u;
+    // A: the chunk of each row (1 KB, lane l <-> 16 bytes) goes straight from global memory into the wave's LDS tile, no
+    // registers in between; the hardware puts lane l's 16 bytes at slot l of the row.  These loads are requested before
+    // everything else and are the oldest in flight.
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const uint32_t row = r < M ? r : M - 1;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (__attribute__((address_space(3))) void*)(decode_smem + wave * kDecodeTile + r * kDecodeARow),
+                                               16, (int)lane_off, (int)(row * (uint32_t)K + chunk_off), 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // The 32 scale bytes of the chunk per row / column, requested ahead of W (loads return in order) and unpacked after
+    // W has been requested.  In a ragged last chunk the 32 bytes run past the row's end: into the next row, or past the
+    // end of the array, where a buffer load returns zeros; those bytes belong to K-steps that are not multiplied.
+    u32x4 aslo, ashi, wslo[NT], wshi[NT];
+    {
+      const uint32_t ao = (uint32_t)(i < M ? i : M - 1) * (uint32_t)KB + (uint32_t)chunk * 32u;
+      aslo = buffer_load_x4<false>(as_rsrc, ao, 0u);
+      ashi = buffer_load_x4<false>(as_rsrc, ao + 16u, 0u);
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const uint32_t wo = (uint32_t)(ncol[nt] < N ? ncol[nt] : N - 1) * (uint32_t)KB + (uint32_t)chunk * 32u;
+        wslo[nt] = buffer_load_x4<false>(ws_rsrc, wo, 0u);
+        wshi[nt] = buffer_load_x4<false>(ws_rsrc, wo + 16u, 0u);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    u32x4 wraw[NT][16];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int n = col0 + nt * 16 + j < N ? col0 + nt * 16 + j : N - 1;
+        wraw[nt][j] = buffer_load_x4<true>(w_rsrc, lane_off, (uint32_t)n * (uint32_t)K + chunk_off);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+    // The 32 loads of W have been requested after those of A: once no more than 32 loads are outstanding, A is in the
+    // tile (and the scale bytes are in their registers).
+    __builtin_amdgcn_s_waitcnt(kWaitVmcnt32);
+    wave_lds_order();
+    // the 8 x 2 fragment runs of lane (i, g): slots 8 p + g and 8 p + 4 + g of row i
+    i32x8 af[8];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      u32x4 t0 = *reinterpret_cast<const u32x4*>(tile + i * kDecodeARow + 16 * (8 * p + g));
+      u32x4 t1 = *reinterpret_cast<const u32x4*>(tile + i * kDecodeARow + 16 * (8 * p + 4 + g));
+      af[p] = i32x8{(int)t0.x, (int)t0.y, (int)t0.z, (int)t0.w, (int)t1.x, (int)t1.y, (int)t1.z, (int)t1.w};
+    }
+    // the 8 scale bytes this lane feeds to the MFMAs of the chunk (K-block g of each K-step), packed 4 to a register;
+    // those of W sliced (Eq. (6) scale step)
+    uint32_t asc[2], wsc[NT][2];
+    pack_lane_scales(aslo, ashi, g, asc);
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      pack_lane_scales(wslo[nt], wshi[nt], g, wsc[nt]);
+      wsc[nt][0] = scale_add_x4(wsc[nt][0], kDeltaE_E4M3_E2M1);
+      wsc[nt][1] = scale_add_x4(wsc[nt][1], kDeltaE_E4M3_E2M1);
+    }
+    wave_lds_order();   // the tile is free again (the reads above execute before the writes below)
+    // W: lane l holds half l % 2 of block l / 2 of each column's chunk; sliced, it is 8 bytes of the column's row
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        uint32_t half[2];
+        slice_half_block_e2m1(wraw[nt][j], half);   // Eq. (6) element step
+        *reinterpret_cast<u32x2*>(tile + nt * 8192 + j * 512 + 16 * ((lane >> 1) ^ j) + 8 * (lane & 1)) = u32x2{half[0], half[1]};
+      }
+    wave_lds_order();
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      if (p < steps) {
+        const int ascale = (int)(asc[p >> 2] >> (8 * (p & 3)));   // the instruction reads the low byte
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          // block 4 p + g of column i
+          u32x4 t = *reinterpret_cast<const u32x4*>(tile + nt * 8192 + i * 512 + 16 * ((4 * p + g) ^ i));
+          i32x8 b = {(int)t.x, (int)t.y, (int)t.z, (int)t.w, 0, 0, 0, 0};
+          const int bscale = (int)(wsc[nt][p >> 2] >> (8 * (p & 3)));
+          acc[nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af[p], b, acc[nt], 0 /* A: E4M3 */, 4 /* B: E2M1 */, 0,
+                                                                     ascale, 0, bscale);
+        }
+      }
+    }
+    wave_lds_order();   // the next chunk overwrites the tile
+  }
+  if (wave > 0) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) red[wave - 1][nt][j][lane] = acc[nt][j];
+  }
+  __syncthreads();
+  if (wave == 0) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float s = ((acc[nt][j] + red[0][nt][j][lane]) + red[1][nt][j][lane]) + red[2][nt][j][lane];
+        const int m = 4 * g + j;
+        if (m < M && ncol[nt] < N) c[(int64_t)m * ldc + ncol[nt]] = s;
+      }
+  }
+}
+
 // ------------------------------------------------------------------ large M (prefill): LDS-tiled
 // Workgroup tile 256 (M) x 128 (N), K-step 128.  Eight waves in two roles, one wave of each role per SIMD:
 //   waves 0-3, the consumers: a 2 x 2 grid of 128 x 64 wave tiles (8 x 4 MFMA tiles, 32 MFMAs per wave and
@@ -466,6 +679,19 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
     }
     hipLaunchKernelGGL(gemm_ss_fp4_tiled_kernel<0>, dim3((unsigned)(m_tiles * n_tiles)), dim3(kGemmThreads), kSmem, stream, a_codes,
                        a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles);
+    return launch_status("the fused GEMM");
+  }
+  if (M <= 16 && N * K <= 0xFFFFFFFFll) {   // (the decode kernel addresses W with 32-bit offsets)
+    static bool decode_attr_set = false;
+    if (!decode_attr_set) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ss_fp4_decode_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              kDecodeSmem) != hipSuccess)
+        return MX_ERR_LAUNCH;
+      decode_attr_set = true;
+    }
+    const unsigned grid_d = (unsigned)((N + 16 * kDecodeNT - 1) / (16 * kDecodeNT));
+    hipLaunchKernelGGL(gemm_ss_fp4_decode_kernel, dim3(grid_d), dim3(256), kDecodeSmem, stream, a_codes, a_scales, w_codes,
+                       w_scales, c, (int)M, (int)N, (int)K, ldc);
     return launch_status("the fused GEMM");
   }
   const unsigned grid = (unsigned)((N + 16 * kSmallmNT - 1) / (16 * kSmallmNT));

@@ -64,8 +64,11 @@ def _check(mx, oracle, M, N, K, seed, w_axis0=True, random_bytes=False):
         assert (err <= 2e-5 * np.linalg.norm(ref, axis=1) + 1e-30).all()
 
 
-@pytest.mark.parametrize("M,N,K", [(16, 256, 512), (1, 48, 128), (7, 104, 384), (33, 64, 1024), (64, 1000, 256)])
+@pytest.mark.parametrize("M,N,K", [(16, 256, 512), (1, 48, 128), (7, 104, 384), (33, 64, 1024), (64, 1000, 256),
+                                   (16, 64, 9344), (5, 40, 2176), (17, 96, 1152)])
 def test_gemm_small_shapes(mx, oracle, M, N, K):
+    # M <= 16 takes the decode kernel (K chunks of 1024 dealt to 4 waves: several chunks per wave, ragged last chunk,
+    # fewer than 16 rows, a ragged column tile), 16 < M <= 64 the kernel with fragment loads
     _check(mx, oracle, M, N, K, seed=M * 1000 + N)
     _check(mx, oracle, M, N, K, seed=M * 1000 + N + 1, w_axis0=False)
     _check(mx, oracle, M, N, K, seed=M * 1000 + N + 2, random_bytes="narrow")
