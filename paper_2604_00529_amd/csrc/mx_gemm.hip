@@ -403,21 +403,19 @@ __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_decode_kernel(const uint8_
 // Workgroup tile 256 (M) x 128 (N), K-step 128.  Eight waves in two roles, one wave of each role per SIMD:
 //   waves 0-3, the consumers: a 2 x 2 grid of 128 x 64 wave tiles (8 x 4 MFMA tiles, 32 MFMAs per wave and
 //     K-step); they read fragments from LDS and issue the MFMAs, nothing else;
-//   waves 4-7, the producers: they load the A tile (E4M3, 32 KB per K-step) and the anchor tile of W (16 KB)
-//     several K-steps ahead into registers, slice the anchor to E2M1 (Eq. (6)) on its way into LDS -- once per
-//     workgroup instead of once per wave; the tall tile is what amortizes the slicing (about 2.5 vector
-//     instructions per element) against the matrix work -- and stage the scale bytes.
+//   waves 4-7, the producers: they request the A tile (E4M3, 32 KB per K-step) two K-steps ahead with loads that
+//     have LDS as their destination, load the anchor tile of W (16 KB) two K-steps ahead into registers and slice it
+//     to E2M1 (Eq. (6)) on its way into LDS -- once per workgroup instead of once per wave; the tall tile is what
+//     amortizes the slicing (about 2.5 vector instructions per element) against the matrix work -- and stage the
+//     scale bytes.
 // The SIMD's scheduler interleaves the producer's loads and vector work with the consumer's MFMAs; with a
 // single role per wave the same work ran back to back (measured: 308 us against 52 us of pure MFMA time).
-// LDS is double-buffered, one barrier per K-step.  Row strides are padded (144 B / 80 B) so that the 16 lanes
-// of a lane group hit different banks.
+// LDS holds three K-steps (the one being multiplied, the one being completed, the one being requested), one
+// barrier per K-step.  The 16-byte chunks of a row are XOR-swizzled so that the 16 lanes of a lane group hit
+// different banks.
 constexpr int kGemmBM = 256, kGemmBN = 128, kGemmBK = 128;
 constexpr int kGemmMT = 8, kGemmNT = 4;      // MFMA tiles per consumer wave
 constexpr int kGemmLdA = 128, kGemmLdB = 64;   // unpadded rows; 16-byte chunks are XOR-swizzled (see GemmStage)
-#ifndef MX_GEMM_PREFETCH
-#define MX_GEMM_PREFETCH 2
-#endif
-constexpr int kGemmPrefetch = MX_GEMM_PREFETCH;   // K-steps of global loads in flight per producer thread
 constexpr int kGemmAChunks = kGemmBM * kGemmBK / 16 / 256;   // 16-byte A chunks per producer thread and K-step (8)
 constexpr int kGemmThreads = 512;
 #ifndef MX_GEMM_GROUP
@@ -435,10 +433,14 @@ struct GemmStage {
   uint32_t bs[kGemmBN];            // 4 sliced scale bytes per column
 };
 
+// s_waitcnt lgkmcnt(0) alone (gfx9 immediate: vmcnt 63 in bits 3:0 and 15:14, expcnt 7 in bits 6:4, lgkmcnt in bits 11:8)
+constexpr int kWaitLgkmcnt0 = 15 | (7 << 4) | (0 << 8) | (3 << 14);
+// A workgroup barrier that is only the instruction; the "memory" clobber keeps the compiler from moving memory
+// operations across it.
+__device__ __forceinline__ void producer_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
 // SKIP is 0 in the library; a tuning harness instantiates other values to take parts of the kernel out
-// (1: no slicing, 2: no producer work after the prologue, 4: no MFMA, 8: no global loads after the prologue,
-// 16: consumers read their fragments from LDS only in the first K-step, 32: no LDS stores after the prologue,
-// 64 / 128: no loads of W / of A after the first K-steps, 256: non-temporal loads of W).
+// (1: no slicing, 4: no MFMA).
 template <int SKIP>
 __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const uint8_t* __restrict__ a_codes,
                                                                          const uint8_t* __restrict__ a_scales,
@@ -461,21 +463,29 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   // The two roles run separate loops (so that a wave's registers hold either the accumulators or the prefetched
   // tiles, not both) with the same number of barriers: one after the prologue, one per K-step.
   if (wave >= 4) {
-    // ---- producers: per-thread slots of the global -> LDS copies
-    //   A: chunk q = tid + 256 j (j < 8): row q / 8, 16-byte column q % 8
-    //   B: block q = tid + 256 j (j < 2): column q / 4, K-block q % 4 (32 anchor bytes -> 16 bytes of E2M1)
+    // ---- producers
+    //   A: 16-byte chunk q = tid + 256 j (j < 8) of the tile: row q / 8, position q % 8 in that row of the LDS tile.
+    //      Loaded with LDS as the destination (no registers, no LDS store instruction): the hardware puts lane l's 16
+    //      bytes at byte 16 l of the wave's 1 KB block, so the lane fetches the chunk that the swizzle puts there.
+    //   B: block q = tid + 256 j (j < 2): column q / 4, K-block q % 4 (32 anchor bytes -> 16 bytes of E2M1), through
+    //      registers, because it is sliced on the way
     //   scales: thread t one row of A (4 bytes); thread t < 128 also one column of W
     // Rows / columns past the edge are clamped to the last valid one instead of branched around: their products
     // land in outputs that are never stored, and straight-line code lets the loads of several K-steps stay in
     // flight (the compiler counts outstanding loads exactly only without control flow).
-    constexpr int D = kGemmPrefetch;
-    const uint8_t* pa[kGemmAChunks];
+    //
+    // During K-step k the consumers read stage k % 3.  The producers request A of step k + 2 into stage (k + 2) % 3 --
+    // the stage of step k - 1, which every consumer left at the last barrier -- then W and the scales of step k + 2
+    // into registers, and they slice W of step k + 1 into stage (k + 1) % 3.  Loads return in order: when W of step
+    // k + 1 is in its registers, A of step k + 1, requested just before it, is in its stage.
+    const __amdgpu_buffer_rsrc_t a_rsrc = make_buffer(a_codes, (uint32_t)M * (uint32_t)K);   // (the host checks M K < 2^32)
+    uint32_t a_voff[kGemmAChunks];
     const uint8_t* pw[2];
 #pragma unroll
     for (int j = 0; j < kGemmAChunks; ++j) {
-      int q = tid + 256 * j, row = q >> 3, col = q & 7;
-      int m = m0 + row < M ? m0 + row : M - 1;
-      pa[j] = a_codes + (int64_t)m * K + 16 * col;
+      const int q = tid + 256 * j, row = q >> 3, pos = q & 7;
+      const int m = m0 + row < M ? m0 + row : M - 1;
+      a_voff[j] = (uint32_t)m * (uint32_t)K + 16u * (uint32_t)(pos ^ ((row >> 1) & 7));
     }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -485,39 +495,35 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
     }
     const uint8_t* psa = a_scales + (int64_t)(m0 + tid < M ? m0 + tid : M - 1) * KB;
     const uint8_t* psw = w_scales + (int64_t)(n0 + (tid & 127) < N ? n0 + (tid & 127) : N - 1) * KB;
+    const int a_block = (wave - 4) * 1024;   // this wave's 1 KB of each 4 KB that one j covers
 
-    // R = D + 1 register slots: the loads of K-step k + 1 + D are issued first in K-step k, into the slot that
-    // step k's data left, so that the memory pipe works on them while this wave writes LDS and slices
-    constexpr int R = D + 1;
-    u32x4 ra[R][kGemmAChunks], rb[R][2][2];
-    uint32_t rsa[R], rsw[R];
-    auto load_global = [&](int ks, auto slot_c) {
+    u32x4 rb[2][2][2];
+    uint32_t rsa[2], rsw[2];
+    // K-steps past the end are clamped to the last one: loaded again, never used
+    const int last = ksteps - 1;
+    auto clamp_ks = [&](int ks) { return ks < last ? ks : last; };
+    auto load_step = [&](int ks, int stage_i, auto slot_c) {
       constexpr int S = decltype(slot_c)::value;
-      const int k0 = ks * kGemmBK;
-      if (!(SKIP & 128) || ks < D) {
+      const int k0 = clamp_ks(ks) * kGemmBK;
 #pragma unroll
-        for (int j = 0; j < kGemmAChunks; ++j) ra[S][j] = *reinterpret_cast<const u32x4*>(pa[j] + k0);
-      }
-      if (!(SKIP & 64) || ks < D) {
+      for (int j = 0; j < kGemmAChunks; ++j)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            a_rsrc, (__attribute__((address_space(3))) void*)(gemm_smem + stage_i * (int)sizeof(GemmStage) + j * 4096 + a_block), 16,
+            (int)a_voff[j], k0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);   // A first: what follows is younger than it
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const u32x4* p = reinterpret_cast<const u32x4*>(pw[j] + k0);
-          // plain loads: the 8 workgroups that share this W tile run on 8 different XCDs at about the same time,
-          // and non-temporal loads made each of them fetch it from HBM (269 us against 196 us for the kernel)
-          if constexpr (SKIP & 256) { rb[S][j][0] = __builtin_nontemporal_load(p); rb[S][j][1] = __builtin_nontemporal_load(p + 1); }
-          else { rb[S][j][0] = p[0]; rb[S][j][1] = p[1]; }
-        }
+      for (int j = 0; j < 2; ++j) {
+        // plain loads: the 8 workgroups that share this W tile run on 8 different XCDs at about the same time,
+        // and non-temporal loads made each of them fetch it from HBM (269 us against 196 us for the kernel)
+        const u32x4* p = reinterpret_cast<const u32x4*>(pw[j] + k0);
+        rb[S][j][0] = p[0];
+        rb[S][j][1] = p[1];
       }
-      rsa[S] = *reinterpret_cast<const uint32_t*>(psa + ks * 4);
-      rsw[S] = *reinterpret_cast<const uint32_t*>(psw + ks * 4);
+      rsa[S] = *reinterpret_cast<const uint32_t*>(psa + clamp_ks(ks) * 4);
+      rsw[S] = *reinterpret_cast<const uint32_t*>(psw + clamp_ks(ks) * 4);
     };
     auto store_lds = [&](GemmStage& st, auto slot_c) {
       constexpr int S = decltype(slot_c)::value;
-#pragma unroll
-      for (int j = 0; j < kGemmAChunks; ++j) {
-        int q = tid + 256 * j, row = q >> 3, col = q & 7;
-        *reinterpret_cast<u32x4*>(&st.a[row * kGemmLdA + 16 * (col ^ ((row >> 1) & 7))]) = ra[S][j];
-      }
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         int q = tid + 256 * j, col = q >> 2, kb = q & 3;
@@ -533,38 +539,31 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
       st.as[tid] = rsa[S];
       if (tid < kGemmBN) st.bs[tid] = scale_add_x4(rsw[S], kDeltaE_E4M3_E2M1);   // Eq. (6) scale step
     };
-    // Software pipeline without branches around the loads (a branch makes the compiler wait for ALL outstanding
-    // loads): K-steps past the end are clamped to the last one, their data is loaded again and never used.
-    const int last = ksteps - 1;
-    auto clamp_ks = [&](int ks) { return ks < last ? ks : last; };
-    // prologue: K-steps 0 .. D in flight, step 0 staged
-    static_for<0, R>([&](auto d) { load_global(clamp_ks(decltype(d)::value), d); });
+    // prologue: steps 0 and 1 requested, step 0 staged (its W registers are younger than its A)
+    load_step(0, 0, std::integral_constant<int, 0>{});
+    load_step(1, 1, std::integral_constant<int, 1>{});
     store_lds(stage[0], std::integral_constant<int, 0>{});
     __syncthreads();
-    // during K-step k: loads of step k + 1 + D (slot k % R, free since step k was staged), then step k + 1 (slot
-    // (k + 1) % R) goes into the other stage
-    const int rounds = ksteps / R;
-    for (int r = 0; r < rounds; ++r) {
-      static_for<0, R>([&](auto d) {
-        constexpr int DD = decltype(d)::value;
-        constexpr int NEXT = (DD + 1) % R;
-        const int k = r * R + DD;
-        if constexpr (!(SKIP & 2)) {
-          if constexpr (!(SKIP & 8)) load_global(clamp_ks(k + 1 + D), d);
-          if constexpr (!(SKIP & 32)) store_lds(stage[(k + 1) & 1], std::integral_constant<int, NEXT>{});
-        }
-        __syncthreads();
-      });
+    int s1 = 1, s2 = 2;   // (k + 1) % 3, (k + 2) % 3
+    auto k_step = [&](int k, auto slot_c) {
+      constexpr int S = decltype(slot_c)::value;   // k % 2: the slot that step k left, now of step k + 2
+      load_step(k + 2, s2, slot_c);
+      store_lds(stage[s1], std::integral_constant<int, S ^ 1>{});
+      const int t = s1; s1 = s2; s2 = t == 0 ? 2 : t - 1;   // (0, 1, 2 rotate: the stage before s1 is the new s2)
+      // The barrier of K-step k, without the fence of __syncthreads(): that would wait for A of step k + 2, just
+      // requested.  What the consumers read next is in place: the LDS stores above have completed (the wait below),
+      // and A of step k + 1 arrived before the W registers that those stores were made from.
+      __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);
+      producer_barrier();
+    };
+    int k = 0;
+    for (; k + 2 <= ksteps; k += 2) {
+      k_step(k, std::integral_constant<int, 0>{});
+      k_step(k + 1, std::integral_constant<int, 1>{});
     }
-    // the K-steps left over when their number is not a multiple of R (at most R - 1; no more loads are needed)
-    static_for<0, R - 1>([&](auto d) {
-      constexpr int DD = decltype(d)::value;
-      const int k = rounds * R + DD;
-      if (k < ksteps) {
-        store_lds(stage[(k + 1) & 1], std::integral_constant<int, (DD + 1) % R>{});
-        __syncthreads();
-      }
-    });
+    if (k < ksteps) k_step(k, std::integral_constant<int, 0>{});
+    // the loads with LDS as their destination must have landed before the workgroup's LDS is given back
+    __builtin_amdgcn_s_waitcnt(0);
     return;
   }
 
@@ -592,20 +591,26 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   i32x8 bf[kGemmNT];
 #pragma unroll
   for (int nt = 0; nt < kGemmNT; ++nt) bf[nt] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
+  // Scale bytes are read with byte loads (the instruction takes the low byte of its scale register; a dword load
+  // would need a shift that waits for the read).  Every LDS read of the loop is issued as one piece between two
+  // MFMAs: bunched in front of a group of MFMAs they leave the matrix pipe idle while they issue.
   auto read_b = [&](const GemmStage& st, int nt) {
     u32x4 t = *reinterpret_cast<const u32x4*>(&st.b[b_off + nt * 16 * kGemmLdB]);
     bf[nt][0] = (int)t.x; bf[nt][1] = (int)t.y; bf[nt][2] = (int)t.z; bf[nt][3] = (int)t.w;
-    sb[nt] = st.bs[wn * 64 + nt * 16 + i] >> (8 * g);   // the instruction reads the low byte
+    sb[nt] = reinterpret_cast<const uint8_t*>(st.bs)[(wn * 64 + nt * 16 + i) * 4 + g];
   };
-  auto read_a = [&](const GemmStage& st, auto group_c) {
-    constexpr int G = decltype(group_c)::value, SET = G & 1;
-#pragma unroll
-    for (int m = 0; m < GM; ++m) {
-      const int mt = G * GM + m;
-      u32x4 t0 = *reinterpret_cast<const u32x4*>(&st.a[a_off + mt * 16 * kGemmLdA]);
-      u32x4 t1 = *reinterpret_cast<const u32x4*>(&st.a[(a_off ^ 64) + mt * 16 * kGemmLdA]);
-      af[SET][m] = i32x8{(int)t0.x, (int)t0.y, (int)t0.z, (int)t0.w, (int)t1.x, (int)t1.y, (int)t1.z, (int)t1.w};
-      sa[SET][m] = st.as[wm * 128 + mt * 16 + i] >> (8 * g);   // the instruction reads the low byte
+  // piece 3 m + q of group G: q = 0 / 1 the two 16-byte runs of row tile m, q = 2 its scale byte
+  auto read_a_piece = [&](const GemmStage& st, auto group_c, auto piece_c) {
+    constexpr int G = decltype(group_c)::value, SET = G & 1, P = decltype(piece_c)::value, m = P / 3, q = P % 3;
+    constexpr int mt = G * GM + m;
+    if constexpr (q == 0) {
+      u32x4 t = *reinterpret_cast<const u32x4*>(&st.a[a_off + mt * 16 * kGemmLdA]);
+      af[SET][m][0] = (int)t.x; af[SET][m][1] = (int)t.y; af[SET][m][2] = (int)t.z; af[SET][m][3] = (int)t.w;
+    } else if constexpr (q == 1) {
+      u32x4 t = *reinterpret_cast<const u32x4*>(&st.a[(a_off ^ 64) + mt * 16 * kGemmLdA]);
+      af[SET][m][4] = (int)t.x; af[SET][m][5] = (int)t.y; af[SET][m][6] = (int)t.z; af[SET][m][7] = (int)t.w;
+    } else {
+      sa[SET][m] = reinterpret_cast<const uint8_t*>(st.as)[(wm * 128 + mt * 16 + i) * 4 + g];
     }
   };
   auto mfma_one = [&](auto group_c, int m, int nt) {
@@ -619,35 +624,44 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
                                                                      0, (int)sb[nt]);
     }
   };
+  constexpr int kPieces = 3 * GM;   // reads of one group of A fragments
+  static_assert(kPieces <= GM * kGemmNT, "one read per MFMA of a group");
   __syncthreads();   // stage 0 is filled
 #pragma unroll
   for (int nt = 0; nt < kGemmNT; ++nt) read_b(stage[0], nt);
-  read_a(stage[0], std::integral_constant<int, 0>{});
+  static_for<0, kPieces>([&](auto pc) { read_a_piece(stage[0], std::integral_constant<int, 0>{}, pc); });
   __builtin_amdgcn_sched_barrier(0);
+  int cur_i = 0;   // k % 3
   for (int k = 0; k < ksteps; ++k) {
-    const GemmStage& cur = stage[(SKIP & 16) ? 0 : (k & 1)];
-    const GemmStage& nxt = stage[(SKIP & 16) ? 0 : ((k + 1) & 1)];
+    const int nxt_i = cur_i == 2 ? 0 : cur_i + 1;
+    const GemmStage& cur = stage[cur_i];
+    const GemmStage& nxt = stage[nxt_i];
+    cur_i = nxt_i;
     static_for<0, NG - 1>([&](auto gc) {
       constexpr int G = decltype(gc)::value;
-      read_a(cur, std::integral_constant<int, G + 1>{});
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int m = 0; m < GM; ++m)
-#pragma unroll
-        for (int nt = 0; nt < kGemmNT; ++nt) mfma_one(gc, m, nt);
-      __builtin_amdgcn_sched_barrier(0);
+      // MFMAs of group G, row tile by row tile; after each of the first 12 the next piece of group G + 1
+      static_for<0, GM * kGemmNT>([&](auto xc) {
+        constexpr int X = decltype(xc)::value;
+        mfma_one(gc, X / kGemmNT, X % kGemmNT);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (X < kPieces) {
+          read_a_piece(cur, std::integral_constant<int, G + 1>{}, xc);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      });
     });
     __syncthreads();   // every read of this stage has landed; the producers have filled the other stage
-    read_a(nxt, std::integral_constant<int, 0>{});   // (after the last K-step: a read of stale data that nothing uses)
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int nt = 0; nt < kGemmNT; ++nt) {
-#pragma unroll
-      for (int m = 0; m < GM; ++m) mfma_one(std::integral_constant<int, NG - 1>{}, m, nt);
+    // last group, column tile by column tile: after each MFMA a piece of the next K-step's first group, after the
+    // last MFMA of a column tile also that tile's next B fragment (after the last K-step: reads of stale data that
+    // nothing uses)
+    static_for<0, GM * kGemmNT>([&](auto xc) {
+      constexpr int X = decltype(xc)::value, nt = X / GM, m = X % GM;
+      mfma_one(std::integral_constant<int, NG - 1>{}, m, nt);
       __builtin_amdgcn_sched_barrier(0);
-      read_b(nxt, nt);
+      if constexpr (X < kPieces) read_a_piece(nxt, std::integral_constant<int, 0>{}, xc);
+      if constexpr (m == GM - 1) read_b(nxt, nt);
       __builtin_amdgcn_sched_barrier(0);
-    }
+    });
   }
 #pragma unroll
   for (int mt = 0; mt < kGemmMT; ++mt)
@@ -668,8 +682,9 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
   if (M > 64) {
     const int64_t m_tiles = (M + kGemmBM - 1) / kGemmBM, n_tiles = (N + kGemmBN - 1) / kGemmBN;
     if (m_tiles * n_tiles > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-    // 2 stages x 41.5 KB: above the 64 KB a kernel gets by default, so the dynamic size is requested explicitly
-    constexpr int kSmem = 2 * (int)sizeof(GemmStage);
+    if (M * K > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;   // the kernel addresses A with 32-bit offsets
+    // 3 stages x 41.5 KB: above the 64 KB a kernel gets by default, so the dynamic size is requested explicitly
+    constexpr int kSmem = 3 * (int)sizeof(GemmStage);
     static bool attr_set = false;
     if (!attr_set) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ss_fp4_tiled_kernel<0>),
