@@ -418,6 +418,10 @@ constexpr int kGemmMT = 8, kGemmNT = 4;      // MFMA tiles per consumer wave
 constexpr int kGemmLdA = 128, kGemmLdB = 64;   // unpadded rows; 16-byte chunks are XOR-swizzled (see GemmStage)
 constexpr int kGemmAChunks = kGemmBM * kGemmBK / 16 / 256;   // 16-byte A chunks per producer thread and K-step (8)
 constexpr int kGemmThreads = 512;
+#ifndef MX_GEMM_WDEPTH
+#define MX_GEMM_WDEPTH 3
+#endif
+constexpr int kGemmWDepth = MX_GEMM_WDEPTH;   // K-steps of W in flight per producer thread
 #ifndef MX_GEMM_GROUP
 #define MX_GEMM_GROUP 4
 #endif
@@ -435,12 +439,21 @@ struct GemmStage {
 
 // s_waitcnt lgkmcnt(0) alone (gfx9 immediate: vmcnt 63 in bits 3:0 and 15:14, expcnt 7 in bits 6:4, lgkmcnt in bits 11:8)
 constexpr int kWaitLgkmcnt0 = 15 | (7 << 4) | (0 << 8) | (3 << 14);
+constexpr int kWaitLgkmcnt0Vmcnt8 = 8 | (7 << 4) | (0 << 8) | (0 << 14);   // s_waitcnt vmcnt(8) lgkmcnt(0)
 // A workgroup barrier that is only the instruction; the "memory" clobber keeps the compiler from moving memory
 // operations across it.
 __device__ __forceinline__ void producer_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
 // SKIP is 0 in the library; a tuning harness instantiates other values to take parts of the kernel out
-// (1: no slicing, 4: no MFMA).
+// (1: no slicing, 4: no MFMA, 8 / 64: A / W requested only for the first K-steps, 16: no LDS reads in the consumer loop,
+// 512 / 1024: every workgroup loads the first tile of W / of A).
+#ifdef MX_GEMM_TIMING
+__device__ long long g_gemm_times[4096][4];   // tuning harness only: clock readings of consumer wave 0 of each workgroup
+#define MX_GEMM_STAMP(slot) \
+  if (wave == 0 && lane == 0 && blockIdx.x < 4096) g_gemm_times[blockIdx.x][slot] = (long long)wall_clock64();
+#else
+#define MX_GEMM_STAMP(slot)
+#endif
 template <int SKIP>
 __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const uint8_t* __restrict__ a_codes,
                                                                          const uint8_t* __restrict__ a_scales,
@@ -462,108 +475,93 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
 
   // The two roles run separate loops (so that a wave's registers hold either the accumulators or the prefetched
   // tiles, not both) with the same number of barriers: one after the prologue, one per K-step.
+  // Loads return in order within a wave, so the two operands are requested by different waves: W, which comes from HBM
+  // or the last-level cache, by the producers, kWDepth K-steps ahead through registers; A, which sits in L2, by the
+  // consumers, two K-steps ahead, straight into LDS.  A wave that waits for its A tile then never waits behind a load of
+  // W (measured: with both in the producers, the loads of W cost 56 us of the kernel's 194).
+  //
+  // During K-step k the consumers read stage k % 3 and request A of step k + 2 into stage (k + 2) % 3 -- the stage of
+  // step k - 1, which every consumer left at the last barrier; the producers slice W of step k + 1 into stage
+  // (k + 1) % 3.  A consumer arrives at the barrier of step k when its reads of stage k have landed and its part of A
+  // of step k + 1 is in LDS; a producer when its LDS stores have completed.
   if (wave >= 4) {
     // ---- producers
-    //   A: 16-byte chunk q = tid + 256 j (j < 8) of the tile: row q / 8, position q % 8 in that row of the LDS tile.
-    //      Loaded with LDS as the destination (no registers, no LDS store instruction): the hardware puts lane l's 16
-    //      bytes at byte 16 l of the wave's 1 KB block, so the lane fetches the chunk that the swizzle puts there.
-    //   B: block q = tid + 256 j (j < 2): column q / 4, K-block q % 4 (32 anchor bytes -> 16 bytes of E2M1), through
-    //      registers, because it is sliced on the way
+    //   B: 16-byte piece q = tid + 256 j (j < 4) of the anchor tile: column q / 8, half q % 2 of K-block (q % 8) / 2
+    //      (16 anchor bytes -> 8 bytes of E2M1), through registers, because it is sliced on the way.  The lanes of a
+    //      load read consecutive 16 bytes (8 lanes one 128-byte row).
     //   scales: thread t one row of A (4 bytes); thread t < 128 also one column of W
     // Rows / columns past the edge are clamped to the last valid one instead of branched around: their products
     // land in outputs that are never stored, and straight-line code lets the loads of several K-steps stay in
     // flight (the compiler counts outstanding loads exactly only without control flow).
-    //
-    // During K-step k the consumers read stage k % 3.  The producers request A of step k + 2 into stage (k + 2) % 3 --
-    // the stage of step k - 1, which every consumer left at the last barrier -- then W and the scales of step k + 2
-    // into registers, and they slice W of step k + 1 into stage (k + 1) % 3.  Loads return in order: when W of step
-    // k + 1 is in its registers, A of step k + 1, requested just before it, is in its stage.
-    const __amdgpu_buffer_rsrc_t a_rsrc = make_buffer(a_codes, (uint32_t)M * (uint32_t)K);   // (the host checks M K < 2^32)
-    uint32_t a_voff[kGemmAChunks];
-    const uint8_t* pw[2];
+    constexpr int R = kGemmWDepth;   // register slots: slot s % R holds K-step s from its request until it is staged
+    const uint8_t* pw[4];
 #pragma unroll
-    for (int j = 0; j < kGemmAChunks; ++j) {
-      const int q = tid + 256 * j, row = q >> 3, pos = q & 7;
-      const int m = m0 + row < M ? m0 + row : M - 1;
-      a_voff[j] = (uint32_t)m * (uint32_t)K + 16u * (uint32_t)(pos ^ ((row >> 1) & 7));
-    }
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      int q = tid + 256 * j, col = q >> 2, kb = q & 3;
-      int n = n0 + col < N ? n0 + col : N - 1;
-      pw[j] = w_codes + (int64_t)n * K + 32 * kb;
+    for (int j = 0; j < 4; ++j) {
+      int q = tid + 256 * j, col = q >> 3, piece = q & 7;
+      const int n0l = (SKIP & 512) ? 0 : n0;
+      int n = n0l + col < N ? n0l + col : N - 1;
+      pw[j] = w_codes + (int64_t)n * K + 16 * piece;
     }
     const uint8_t* psa = a_scales + (int64_t)(m0 + tid < M ? m0 + tid : M - 1) * KB;
     const uint8_t* psw = w_scales + (int64_t)(n0 + (tid & 127) < N ? n0 + (tid & 127) : N - 1) * KB;
-    const int a_block = (wave - 4) * 1024;   // this wave's 1 KB of each 4 KB that one j covers
-
-    u32x4 rb[2][2][2];
-    uint32_t rsa[2], rsw[2];
+    u32x4 rb[R][4];
+    uint32_t rsa[R], rsw[R];
     // K-steps past the end are clamped to the last one: loaded again, never used
     const int last = ksteps - 1;
-    auto clamp_ks = [&](int ks) { return ks < last ? ks : last; };
-    auto load_step = [&](int ks, int stage_i, auto slot_c) {
+    auto load_step = [&](int ks_raw, auto slot_c) {
       constexpr int S = decltype(slot_c)::value;
-      const int k0 = clamp_ks(ks) * kGemmBK;
+      const int ks = ks_raw < last ? ks_raw : last;
+      const int k0 = ks * kGemmBK;
 #pragma unroll
-      for (int j = 0; j < kGemmAChunks; ++j)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            a_rsrc, (__attribute__((address_space(3))) void*)(gemm_smem + stage_i * (int)sizeof(GemmStage) + j * 4096 + a_block), 16,
-            (int)a_voff[j], k0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);   // A first: what follows is younger than it
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
+      for (int j = 0; j < 4; ++j) {
         // plain loads: the 8 workgroups that share this W tile run on 8 different XCDs at about the same time,
         // and non-temporal loads made each of them fetch it from HBM (269 us against 196 us for the kernel)
-        const u32x4* p = reinterpret_cast<const u32x4*>(pw[j] + k0);
-        rb[S][j][0] = p[0];
-        rb[S][j][1] = p[1];
+        if (!(SKIP & 64) || ks_raw < R) rb[S][j] = *reinterpret_cast<const u32x4*>(pw[j] + k0);
       }
-      rsa[S] = *reinterpret_cast<const uint32_t*>(psa + clamp_ks(ks) * 4);
-      rsw[S] = *reinterpret_cast<const uint32_t*>(psw + clamp_ks(ks) * 4);
+      rsa[S] = *reinterpret_cast<const uint32_t*>(psa + ks * 4);
+      rsw[S] = *reinterpret_cast<const uint32_t*>(psw + ks * 4);
     };
     auto store_lds = [&](GemmStage& st, auto slot_c) {
       constexpr int S = decltype(slot_c)::value;
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        int q = tid + 256 * j, col = q >> 2, kb = q & 3;
-        uint32_t b4[4];
+      for (int j = 0; j < 4; ++j) {
+        int q = tid + 256 * j, col = q >> 3, kb = (q & 7) >> 1, half = q & 1;
+        uint32_t b2[2];
         if constexpr (SKIP & 1) {
-          b4[0] = rb[S][j][0].x ^ rb[S][j][1].x; b4[1] = rb[S][j][0].y ^ rb[S][j][1].y;
-          b4[2] = rb[S][j][0].z ^ rb[S][j][1].z; b4[3] = rb[S][j][0].w ^ rb[S][j][1].w;
+          b2[0] = rb[S][j].x ^ rb[S][j].y; b2[1] = rb[S][j].z ^ rb[S][j].w;
         } else {
-          slice_block_e2m1(rb[S][j][0], rb[S][j][1], b4);   // Eq. (6) element step, once per workgroup and K-step
+          slice_half_block_e2m1(rb[S][j], b2);   // Eq. (6) element step, once per workgroup and K-step
         }
-        *reinterpret_cast<u32x4*>(&st.b[col * kGemmLdB + 16 * (kb ^ ((col >> 2) & 3))]) = u32x4{b4[0], b4[1], b4[2], b4[3]};
+        *reinterpret_cast<u32x2*>(&st.b[col * kGemmLdB + 16 * (kb ^ ((col >> 2) & 3)) + 8 * half]) = u32x2{b2[0], b2[1]};
       }
       st.as[tid] = rsa[S];
       if (tid < kGemmBN) st.bs[tid] = scale_add_x4(rsw[S], kDeltaE_E4M3_E2M1);   // Eq. (6) scale step
     };
-    // prologue: steps 0 and 1 requested, step 0 staged (its W registers are younger than its A)
-    load_step(0, 0, std::integral_constant<int, 0>{});
-    load_step(1, 1, std::integral_constant<int, 1>{});
+    // prologue: steps 0 .. R - 1 requested, step 0 staged
+    static_for<0, R>([&](auto d) { load_step(decltype(d)::value, d); });
     store_lds(stage[0], std::integral_constant<int, 0>{});
     __syncthreads();
-    int s1 = 1, s2 = 2;   // (k + 1) % 3, (k + 2) % 3
-    auto k_step = [&](int k, auto slot_c) {
-      constexpr int S = decltype(slot_c)::value;   // k % 2: the slot that step k left, now of step k + 2
-      load_step(k + 2, s2, slot_c);
-      store_lds(stage[s1], std::integral_constant<int, S ^ 1>{});
-      const int t = s1; s1 = s2; s2 = t == 0 ? 2 : t - 1;   // (0, 1, 2 rotate: the stage before s1 is the new s2)
-      // The barrier of K-step k, without the fence of __syncthreads(): that would wait for A of step k + 2, just
-      // requested.  What the consumers read next is in place: the LDS stores above have completed (the wait below),
-      // and A of step k + 1 arrived before the W registers that those stores were made from.
-      __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);
-      producer_barrier();
-    };
-    int k = 0;
-    for (; k + 2 <= ksteps; k += 2) {
-      k_step(k, std::integral_constant<int, 0>{});
-      k_step(k + 1, std::integral_constant<int, 1>{});
+    // K-step k: step k + R is requested into the slot that step k left (staged in step k - 1), step k + 1 is staged
+    int s1 = 1;   // (k + 1) % 3
+    const int rounds = ksteps / R;
+    for (int r = 0; r < rounds; ++r) {
+      static_for<0, R>([&](auto d) {
+        constexpr int DD = decltype(d)::value;
+        load_step(r * R + DD + R, d);
+        store_lds(stage[s1], std::integral_constant<int, (DD + 1) % R>{});
+        s1 = s1 == 2 ? 0 : s1 + 1;
+        __syncthreads();
+      });
     }
-    if (k < ksteps) k_step(k, std::integral_constant<int, 0>{});
-    // the loads with LDS as their destination must have landed before the workgroup's LDS is given back
-    __builtin_amdgcn_s_waitcnt(0);
+    // the K-steps left over when their number is not a multiple of R (no more loads are needed)
+    static_for<0, R - 1>([&](auto d) {
+      constexpr int DD = decltype(d)::value;
+      if (rounds * R + DD < ksteps) {
+        store_lds(stage[s1], std::integral_constant<int, (DD + 1) % R>{});
+        s1 = s1 == 2 ? 0 : s1 + 1;
+        __syncthreads();
+      }
+    });
     return;
   }
 
@@ -626,14 +624,46 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   };
   constexpr int kPieces = 3 * GM;   // reads of one group of A fragments
   static_assert(kPieces <= GM * kGemmNT, "one read per MFMA of a group");
-  __syncthreads();   // stage 0 is filled
+  // A: 16-byte chunk q = tid + 256 j (j < 8) of the tile: row q / 8, position q % 8 in that row of the LDS tile.
+  // Requested with LDS as the destination (no registers, no LDS store instruction): the hardware puts lane l's 16
+  // bytes at byte 16 l of the wave's 1 KB block, so the lane fetches the chunk that the swizzle puts there.  Rows past
+  // the edge read the last valid row.  (The host checks M K < 2^32.)
+  const __amdgpu_buffer_rsrc_t a_rsrc = make_buffer(a_codes, (uint32_t)M * (uint32_t)K);
+  uint32_t a_voff[kGemmAChunks];
+#pragma unroll
+  for (int j = 0; j < kGemmAChunks; ++j) {
+    const int q = tid + 256 * j, row = q >> 3, pos = q & 7;
+    const int m0l = (SKIP & 1024) ? 0 : m0;
+    const int m = m0l + row < M ? m0l + row : M - 1;
+    a_voff[j] = (uint32_t)m * (uint32_t)K + 16u * (uint32_t)(pos ^ ((row >> 1) & 7));
+  }
+  const int last = ksteps - 1;
+  auto request_a = [&](int ks_raw, int stage_i, auto jc) {   // (K-steps past the end: the last one again, never used)
+    constexpr int J = decltype(jc)::value;
+    if (!(SKIP & 8) || ks_raw < 2)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(
+          a_rsrc, (__attribute__((address_space(3))) void*)(gemm_smem + stage_i * (int)sizeof(GemmStage) + J * 4096 + wave * 1024), 16,
+          (int)a_voff[J], (ks_raw < last ? ks_raw : last) * kGemmBK, 0, 0);
+  };
+  // the barrier of a K-step for a consumer: its LDS reads have landed (the producers overwrite that stage two steps
+  // on, the consumers' own requests one step on) and of its requests only the 8 youngest, of the step after next, are
+  // still in flight; no fence -- that would wait for those too
+  auto consumer_barrier = [&] {
+    __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0Vmcnt8);
+    producer_barrier();
+  };
+  MX_GEMM_STAMP(0)
+  static_for<0, kGemmAChunks>([&](auto jc) { request_a(0, 0, jc); });
+  static_for<0, kGemmAChunks>([&](auto jc) { request_a(1, 1, jc); });
+  consumer_barrier();   // stage 0 is filled
+  MX_GEMM_STAMP(1)
 #pragma unroll
   for (int nt = 0; nt < kGemmNT; ++nt) read_b(stage[0], nt);
   static_for<0, kPieces>([&](auto pc) { read_a_piece(stage[0], std::integral_constant<int, 0>{}, pc); });
   __builtin_amdgcn_sched_barrier(0);
   int cur_i = 0;   // k % 3
   for (int k = 0; k < ksteps; ++k) {
-    const int nxt_i = cur_i == 2 ? 0 : cur_i + 1;
+    const int nxt_i = cur_i == 2 ? 0 : cur_i + 1, req_i = cur_i == 0 ? 2 : cur_i - 1;   // (k + 1) % 3, (k + 2) % 3
     const GemmStage& cur = stage[cur_i];
     const GemmStage& nxt = stage[nxt_i];
     cur_i = nxt_i;
@@ -644,13 +674,20 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
         constexpr int X = decltype(xc)::value;
         mfma_one(gc, X / kGemmNT, X % kGemmNT);
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (X < kPieces) {
+        if constexpr (X < kPieces && !(SKIP & 16)) {
           read_a_piece(cur, std::integral_constant<int, G + 1>{}, xc);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (G == 0 && X >= GM * kGemmNT - kGemmAChunks / 2) {
+          // the requests of A for the step after next, two behind each of the last MFMAs of the first group
+          constexpr int J = 2 * (X - (GM * kGemmNT - kGemmAChunks / 2));
+          request_a(k + 2, req_i, std::integral_constant<int, J>{});
+          request_a(k + 2, req_i, std::integral_constant<int, J + 1>{});
           __builtin_amdgcn_sched_barrier(0);
         }
       });
     });
-    __syncthreads();   // every read of this stage has landed; the producers have filled the other stage
+    consumer_barrier();   // every read of this stage has landed; the next stage is complete
     // last group, column tile by column tile: after each MFMA a piece of the next K-step's first group, after the
     // last MFMA of a column tile also that tile's next B fragment (after the last K-step: reads of stale data that
     // nothing uses)
@@ -658,11 +695,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
       constexpr int X = decltype(xc)::value, nt = X / GM, m = X % GM;
       mfma_one(std::integral_constant<int, NG - 1>{}, m, nt);
       __builtin_amdgcn_sched_barrier(0);
-      if constexpr (X < kPieces) read_a_piece(nxt, std::integral_constant<int, 0>{}, xc);
-      if constexpr (m == GM - 1) read_b(nxt, nt);
+      if constexpr (X < kPieces && !(SKIP & 16)) read_a_piece(nxt, std::integral_constant<int, 0>{}, xc);
+      if constexpr (m == GM - 1 && !(SKIP & 16)) read_b(nxt, nt);
       __builtin_amdgcn_sched_barrier(0);
     });
   }
+  __builtin_amdgcn_s_waitcnt(0);   // the last requests (of steps that do not exist) must land before the LDS is given back
+  MX_GEMM_STAMP(2)
 #pragma unroll
   for (int mt = 0; mt < kGemmMT; ++mt)
 #pragma unroll
@@ -674,6 +713,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
         if (m < M && n < N) c[(int64_t)m * ldc + n] = acc[mt][nt][j];
       }
     }
+  MX_GEMM_STAMP(3)
 }
 
 mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
