@@ -400,31 +400,29 @@ __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_decode_kernel(const uint8_
 }
 
 // ------------------------------------------------------------------ large M (prefill): LDS-tiled
-// Workgroup tile 256 (M) x 128 (N), K-step 128.  Eight waves in two roles, one wave of each role per SIMD:
-//   waves 0-3, the consumers: a 2 x 2 grid of 128 x 64 wave tiles (8 x 4 MFMA tiles, 32 MFMAs per wave and
-//     K-step); they read fragments from LDS and issue the MFMAs, nothing else;
-//   waves 4-7, the producers: they request the A tile (E4M3, 32 KB per K-step) two K-steps ahead with loads that
-//     have LDS as their destination, load the anchor tile of W (16 KB) two K-steps ahead into registers and slice it
-//     to E2M1 (Eq. (6)) on its way into LDS -- once per workgroup instead of once per wave; the tall tile is what
-//     amortizes the slicing (about 2.5 vector instructions per element) against the matrix work -- and stage the
-//     scale bytes.
+// Workgroup tile 256 (M) x 16 NTW (N; NTW = 8, 7 or 6), K-step 128.  Eight waves in two roles, one wave of each role
+// per SIMD:
+//   waves 0-3, the consumers: each owns 64 rows and all columns of the tile (4 x NTW MFMA tiles); they read
+//     fragments from LDS, issue the MFMAs and request the A tile (E4M3, 32 KB per K-step) two K-steps ahead with loads
+//     that have LDS as their destination;
+//   waves 4-7, the producers: they load the anchor tile of W (up to 16 KB) kGemmWDepth K-steps ahead into registers
+//     and slice it to E2M1 (Eq. (6)) on its way into LDS -- once per workgroup instead of once per wave; the tall
+//     tile is what amortizes the slicing (about 2.5 vector instructions per element) against the matrix work -- and
+//     stage the scale bytes.
 // The SIMD's scheduler interleaves the producer's loads and vector work with the consumer's MFMAs; with a
 // single role per wave the same work ran back to back (measured: 308 us against 52 us of pure MFMA time).
 // LDS holds three K-steps (the one being multiplied, the one being completed, the one being requested), one
 // barrier per K-step.  The 16-byte chunks of a row are XOR-swizzled so that the 16 lanes of a lane group hit
 // different banks.
 constexpr int kGemmBM = 256, kGemmBN = 128, kGemmBK = 128;
-constexpr int kGemmMT = 8, kGemmNT = 4;      // MFMA tiles per consumer wave
 constexpr int kGemmLdA = 128, kGemmLdB = 64;   // unpadded rows; 16-byte chunks are XOR-swizzled (see GemmStage)
 constexpr int kGemmAChunks = kGemmBM * kGemmBK / 16 / 256;   // 16-byte A chunks per producer thread and K-step (8)
 constexpr int kGemmThreads = 512;
 #ifndef MX_GEMM_WDEPTH
-#define MX_GEMM_WDEPTH 3
+#define MX_GEMM_WDEPTH 6
 #endif
-constexpr int kGemmWDepth = MX_GEMM_WDEPTH;   // K-steps of W in flight per producer thread
-#ifndef MX_GEMM_GROUP
-#define MX_GEMM_GROUP 4
-#endif
+constexpr int kGemmWDepth = MX_GEMM_WDEPTH;   // K-steps of W in flight per producer thread (weights streaming from HBM:
+                                              // 3 -> 182 us, 6 -> 176 us, 10 -> 189 us for 2048 x 14336 x 4096)
 
 // LDS layout of one K-step.  The 16-byte chunk c of row r of A lives at chunk c ^ ((r >> 1) & 7) of that row, chunk c
 // of column n of B at chunk c ^ ((n >> 2) & 3): with 64 banks of 4 bytes, the 16 lanes of a 128-bit access then hit 64
@@ -454,7 +452,7 @@ __device__ long long g_gemm_times[4096][4];   // tuning harness only: clock read
 #else
 #define MX_GEMM_STAMP(slot)
 #endif
-template <int SKIP>
+template <int NTW, int SKIP>
 __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const uint8_t* __restrict__ a_codes,
                                                                          const uint8_t* __restrict__ a_scales,
                                                                          const uint8_t* __restrict__ w_codes,
@@ -470,7 +468,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   // consecutive workgroups walk the M tiles of one N tile: with round-robin dispatch over the 8 XCDs each XCD
   // keeps re-using the same few A tiles from its L2 while the W tile streams through
   const int tm = blockIdx.x % m_tiles, tn = blockIdx.x / m_tiles;
-  const int m0 = tm * kGemmBM, n0 = tn * kGemmBN;
+  constexpr int BN = 16 * NTW;   // columns of the workgroup tile
+  const int m0 = tm * kGemmBM, n0 = tn * BN;
   const int KB = K / 32, ksteps = K / kGemmBK;
 
   // The two roles run separate loops (so that a wave's registers hold either the accumulators or the prefetched
@@ -498,12 +497,14 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       int q = tid + 256 * j, col = q >> 3, piece = q & 7;
+      if (col > BN - 1) col = BN - 1;   // a tile narrower than 128 columns: the spare threads repeat its last column
       const int n0l = (SKIP & 512) ? 0 : n0;
       int n = n0l + col < N ? n0l + col : N - 1;
       pw[j] = w_codes + (int64_t)n * K + 16 * piece;
     }
     const uint8_t* psa = a_scales + (int64_t)(m0 + tid < M ? m0 + tid : M - 1) * KB;
-    const uint8_t* psw = w_scales + (int64_t)(n0 + (tid & 127) < N ? n0 + (tid & 127) : N - 1) * KB;
+    const int scol = (tid & 127) < BN ? (tid & 127) : BN - 1;
+    const uint8_t* psw = w_scales + (int64_t)(n0 + scol < N ? n0 + scol : N - 1) * KB;
     u32x4 rb[R][4];
     uint32_t rsa[R], rsw[R];
     // K-steps past the end are clamped to the last one: loaded again, never used
@@ -526,6 +527,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         int q = tid + 256 * j, col = q >> 3, kb = (q & 7) >> 1, half = q & 1;
+        if (col > BN - 1) col = BN - 1;
         uint32_t b2[2];
         if constexpr (SKIP & 1) {
           b2[0] = rb[S][j].x ^ rb[S][j].y; b2[1] = rb[S][j].z ^ rb[S][j].w;
@@ -535,7 +537,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
         *reinterpret_cast<u32x2*>(&st.b[col * kGemmLdB + 16 * (kb ^ ((col >> 2) & 3)) + 8 * half]) = u32x2{b2[0], b2[1]};
       }
       st.as[tid] = rsa[S];
-      if (tid < kGemmBN) st.bs[tid] = scale_add_x4(rsw[S], kDeltaE_E4M3_E2M1);   // Eq. (6) scale step
+      if (tid < BN) st.bs[tid] = scale_add_x4(rsw[S], kDeltaE_E4M3_E2M1);   // Eq. (6) scale step
     };
     // prologue: steps 0 .. R - 1 requested, step 0 staged
     static_for<0, R>([&](auto d) { load_step(decltype(d)::value, d); });
@@ -565,65 +567,61 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
     return;
   }
 
-  // ---- consumers
-  // A K-step is worked in groups of GM row tiles, with two sets of A-fragment registers: the reads of the next
-  // group are in flight while the MFMAs of the current one run, across the barrier too -- the barrier of K-step k
-  // sits before the MFMAs of its last group, when the last read of stage k & 1 has landed, and the first group
-  // of step k + 1 is read right after it.  The B fragments (single set) are replaced column tile by column tile
-  // inside the last group, as soon as the MFMAs that use them have been issued.  Scheduling barriers keep the
-  // compiler from moving the reads back to their uses.
-  const int wm = wave >> 1, wn = wave & 1;
-  constexpr int GM = MX_GEMM_GROUP, NG = kGemmMT / GM;
-  static_assert(NG % 2 == 0, "the two register sets must alternate with period one K-step");
-  f32x4 acc[kGemmMT][kGemmNT];
+  // ---- consumers: wave w owns rows m0 + 64 w + [0, 64) and all 16 NTW columns of the tile (4 x NTW MFMA tiles).
+  // A K-step goes column tile by column tile, 4 MFMAs each (one per row tile), and every other instruction of the loop
+  // sits between two MFMAs -- bunched in front of a group of MFMAs they leave the matrix pipe idle while they issue:
+  //   - the B fragments come from LDS through a ring of 4 register sets; the set that a column tile leaves takes the
+  //     fragment 4 column tiles further on (of the next K-step, behind the barrier, for the last 4);
+  //   - the A fragments of the next K-step (two register sets alternate) are read behind the barrier;
+  //   - the requests of A for the step after next go out behind the first MFMAs.
+  // The barrier of the step sits where the read-ahead first reaches into the next stage.  Scale bytes are read with
+  // byte loads (the instruction takes the low byte of its scale register; a dword load would need a shift that waits
+  // for the read).  Scheduling barriers keep the compiler from moving anything back to its use.
+  constexpr int MTW = 4, RING = 4;
+  static_assert(NTW >= RING && NTW <= kGemmBN / 16, "column tiles per wave");
+  f32x4 acc[MTW][NTW];
 #pragma unroll
-  for (int mt = 0; mt < kGemmMT; ++mt)
+  for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
-    for (int nt = 0; nt < kGemmNT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  // (the tile offsets wm * 128, mt * 16, wn * 64, nt * 16 do not change the swizzle term of a lane)
-  const int a_off = (wm * 128 + i) * kGemmLdA + 16 * (g ^ ((i >> 1) & 7));   // + mt * 16 rows; second run of K: ^ 64
-  const int b_off = (wn * 64 + i) * kGemmLdB + 16 * (g ^ ((i >> 2) & 3));    // + nt * 16 columns
-  i32x8 af[2][GM];   // two 16-byte runs of K per lane
-  uint32_t sa[2][GM], sb[kGemmNT];
+    for (int nt = 0; nt < NTW; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // (the tile offsets 64 w, 16 mt, 16 nt do not change the swizzle term of a lane)
+  const int a_off = (wave * 64 + i) * kGemmLdA + 16 * (g ^ ((i >> 1) & 7));   // + mt * 16 rows; second run of K: ^ 64
+  const int b_off = i * kGemmLdB + 16 * (g ^ ((i >> 2) & 3));                 // + nt * 16 columns
+  i32x8 af[2][MTW];   // two 16-byte runs of K per lane
   // B operands: only the low 4 dwords carry FP4 codes; the upper 4 stay zero for the whole kernel
-  i32x8 bf[kGemmNT];
+  i32x8 bf[RING];
+  uint32_t sa[2][MTW], sb[RING];
 #pragma unroll
-  for (int nt = 0; nt < kGemmNT; ++nt) bf[nt] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
-  // Scale bytes are read with byte loads (the instruction takes the low byte of its scale register; a dword load
-  // would need a shift that waits for the read).  Every LDS read of the loop is issued as one piece between two
-  // MFMAs: bunched in front of a group of MFMAs they leave the matrix pipe idle while they issue.
-  auto read_b = [&](const GemmStage& st, int nt) {
-    u32x4 t = *reinterpret_cast<const u32x4*>(&st.b[b_off + nt * 16 * kGemmLdB]);
-    bf[nt][0] = (int)t.x; bf[nt][1] = (int)t.y; bf[nt][2] = (int)t.z; bf[nt][3] = (int)t.w;
-    sb[nt] = reinterpret_cast<const uint8_t*>(st.bs)[(wn * 64 + nt * 16 + i) * 4 + g];
+  for (int r = 0; r < RING; ++r) bf[r] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
+  auto read_b = [&](const GemmStage& st, auto nt_c, auto slot_c) {
+    constexpr int NT = decltype(nt_c)::value, R = decltype(slot_c)::value;
+    u32x4 t = *reinterpret_cast<const u32x4*>(&st.b[b_off + NT * 16 * kGemmLdB]);
+    bf[R][0] = (int)t.x; bf[R][1] = (int)t.y; bf[R][2] = (int)t.z; bf[R][3] = (int)t.w;
+    sb[R] = reinterpret_cast<const uint8_t*>(st.bs)[(NT * 16 + i) * 4 + g];
   };
-  // piece 3 m + q of group G: q = 0 / 1 the two 16-byte runs of row tile m, q = 2 its scale byte
-  auto read_a_piece = [&](const GemmStage& st, auto group_c, auto piece_c) {
-    constexpr int G = decltype(group_c)::value, SET = G & 1, P = decltype(piece_c)::value, m = P / 3, q = P % 3;
-    constexpr int mt = G * GM + m;
+  // piece 3 mt + q of a K-step's A fragments: q = 0 / 1 the two 16-byte runs of row tile mt, q = 2 its scale byte
+  auto read_a_piece = [&](const GemmStage& st, auto set_c, auto piece_c) {
+    constexpr int SET = decltype(set_c)::value, P = decltype(piece_c)::value, mt = P / 3, q = P % 3;
     if constexpr (q == 0) {
       u32x4 t = *reinterpret_cast<const u32x4*>(&st.a[a_off + mt * 16 * kGemmLdA]);
-      af[SET][m][0] = (int)t.x; af[SET][m][1] = (int)t.y; af[SET][m][2] = (int)t.z; af[SET][m][3] = (int)t.w;
+      af[SET][mt][0] = (int)t.x; af[SET][mt][1] = (int)t.y; af[SET][mt][2] = (int)t.z; af[SET][mt][3] = (int)t.w;
     } else if constexpr (q == 1) {
       u32x4 t = *reinterpret_cast<const u32x4*>(&st.a[(a_off ^ 64) + mt * 16 * kGemmLdA]);
-      af[SET][m][4] = (int)t.x; af[SET][m][5] = (int)t.y; af[SET][m][6] = (int)t.z; af[SET][m][7] = (int)t.w;
+      af[SET][mt][4] = (int)t.x; af[SET][mt][5] = (int)t.y; af[SET][mt][6] = (int)t.z; af[SET][mt][7] = (int)t.w;
     } else {
-      sa[SET][m] = reinterpret_cast<const uint8_t*>(st.as)[(wm * 128 + mt * 16 + i) * 4 + g];
+      sa[SET][mt] = reinterpret_cast<const uint8_t*>(st.as)[(wave * 64 + mt * 16 + i) * 4 + g];
     }
   };
-  auto mfma_one = [&](auto group_c, int m, int nt) {
-    constexpr int G = decltype(group_c)::value, SET = G & 1;
-    const int mt = G * GM + m;
+  auto mfma_one = [&](auto set_c, auto slot_c, auto mt_c, auto nt_c) {
+    constexpr int SET = decltype(set_c)::value, R = decltype(slot_c)::value, MT = decltype(mt_c)::value, NT = decltype(nt_c)::value;
     if constexpr (SKIP & 4) {
-      acc[mt][nt][0] += __int_as_float(af[SET][m][0] ^ bf[nt][0] ^ (int)sa[SET][m]);
-      acc[mt][nt][1] += __int_as_float(af[SET][m][7] ^ bf[nt][3] ^ (int)sb[nt]);
+      acc[MT][NT][0] += __int_as_float(af[SET][MT][0] ^ bf[R][0] ^ (int)sa[SET][MT]);
+      acc[MT][NT][1] += __int_as_float(af[SET][MT][7] ^ bf[R][3] ^ (int)sb[R]);
     } else {
-      acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af[SET][m], bf[nt], acc[mt][nt], 0, 4, 0, (int)sa[SET][m],
-                                                                     0, (int)sb[nt]);
+      acc[MT][NT] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af[SET][MT], bf[R], acc[MT][NT], 0, 4, 0, (int)sa[SET][MT], 0,
+                                                                     (int)sb[R]);
     }
   };
-  constexpr int kPieces = 3 * GM;   // reads of one group of A fragments
-  static_assert(kPieces <= GM * kGemmNT, "one read per MFMA of a group");
   // A: 16-byte chunk q = tid + 256 j (j < 8) of the tile: row q / 8, position q % 8 in that row of the LDS tile.
   // Requested with LDS as the destination (no registers, no LDS store instruction): the hardware puts lane l's 16
   // bytes at byte 16 l of the wave's 1 KB block, so the lane fetches the chunk that the swizzle puts there.  Rows past
@@ -649,70 +647,80 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   // on, the consumers' own requests one step on) and of its requests only the 8 youngest, of the step after next, are
   // still in flight; no fence -- that would wait for those too
   auto consumer_barrier = [&] {
-    __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0Vmcnt8);
+    if constexpr (SKIP & 2048) __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);   // (timing only: does not wait for A)
+    else __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0Vmcnt8);
     producer_barrier();
+  };
+  constexpr int kPieces = 3 * MTW;
+  // K-step k with the A fragments in register set SET and B fragment nt in ring slot (PHASE + nt) % RING
+  auto k_step = [&](int k, int cur_i, auto set_c, auto phase_c) {
+    constexpr int SET = decltype(set_c)::value, PHASE = decltype(phase_c)::value;
+    using NSET = std::integral_constant<int, SET ^ 1>;
+    const int nxt_i = cur_i == 2 ? 0 : cur_i + 1, req_i = cur_i == 0 ? 2 : cur_i - 1;   // (k + 1) % 3, (k + 2) % 3
+    const GemmStage& cur = stage[cur_i];
+    const GemmStage& nxt = stage[nxt_i];
+    static_for<0, NTW * MTW>([&](auto xc) {
+      constexpr int X = decltype(xc)::value, NT = X / MTW, MT = X % MTW;
+      using SLOT = std::integral_constant<int, (PHASE + NT) % RING>;
+      constexpr int kBarrierX = (NTW - RING) * MTW + MTW - 1;   // the MFMA after which the ring first needs the next stage
+      mfma_one(set_c, SLOT{}, std::integral_constant<int, MT>{}, std::integral_constant<int, NT>{});
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (X < kGemmAChunks) {
+        request_a(k + 2, req_i, xc);   // A of the step after next, into the stage that every consumer left a step ago
+      }
+      if constexpr (X == kBarrierX) consumer_barrier();   // every read of this stage has landed; the next one is complete
+      if constexpr (!(SKIP & 16)) {
+        if constexpr (MT == MTW - 1) {
+          // the ring set of this column tile is free: fragment NT + RING, of this K-step or of the next
+          if constexpr (NT + RING < NTW) read_b(cur, std::integral_constant<int, NT + RING>{}, SLOT{});
+          else read_b(nxt, std::integral_constant<int, NT + RING - NTW>{}, SLOT{});
+        }
+        if constexpr (X >= kBarrierX) {
+          // behind the barrier: the A fragments of the next K-step, spread over the remaining MFMAs
+          constexpr int kLeft = NTW * MTW - kBarrierX;                  // MFMA slots from here on (13)
+          constexpr int P0 = (X - kBarrierX) * kPieces / kLeft, P1 = (X - kBarrierX + 1) * kPieces / kLeft;
+          static_for<P0, P1>([&](auto pc) { read_a_piece(nxt, NSET{}, pc); });
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
   };
   MX_GEMM_STAMP(0)
   static_for<0, kGemmAChunks>([&](auto jc) { request_a(0, 0, jc); });
   static_for<0, kGemmAChunks>([&](auto jc) { request_a(1, 1, jc); });
   consumer_barrier();   // stage 0 is filled
   MX_GEMM_STAMP(1)
-#pragma unroll
-  for (int nt = 0; nt < kGemmNT; ++nt) read_b(stage[0], nt);
   static_for<0, kPieces>([&](auto pc) { read_a_piece(stage[0], std::integral_constant<int, 0>{}, pc); });
+  static_for<0, RING>([&](auto rc) { read_b(stage[0], rc, rc); });
   __builtin_amdgcn_sched_barrier(0);
-  int cur_i = 0;   // k % 3
-  for (int k = 0; k < ksteps; ++k) {
-    const int nxt_i = cur_i == 2 ? 0 : cur_i + 1, req_i = cur_i == 0 ? 2 : cur_i - 1;   // (k + 1) % 3, (k + 2) % 3
-    const GemmStage& cur = stage[cur_i];
-    const GemmStage& nxt = stage[nxt_i];
-    cur_i = nxt_i;
-    static_for<0, NG - 1>([&](auto gc) {
-      constexpr int G = decltype(gc)::value;
-      // MFMAs of group G, row tile by row tile; after each of the first 12 the next piece of group G + 1
-      static_for<0, GM * kGemmNT>([&](auto xc) {
-        constexpr int X = decltype(xc)::value;
-        mfma_one(gc, X / kGemmNT, X % kGemmNT);
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (X < kPieces && !(SKIP & 16)) {
-          read_a_piece(cur, std::integral_constant<int, G + 1>{}, xc);
-          __builtin_amdgcn_sched_barrier(0);
-        }
-        if constexpr (G == 0 && X >= GM * kGemmNT - kGemmAChunks / 2) {
-          // the requests of A for the step after next, two behind each of the last MFMAs of the first group
-          constexpr int J = 2 * (X - (GM * kGemmNT - kGemmAChunks / 2));
-          request_a(k + 2, req_i, std::integral_constant<int, J>{});
-          request_a(k + 2, req_i, std::integral_constant<int, J + 1>{});
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      });
-    });
-    consumer_barrier();   // every read of this stage has landed; the next stage is complete
-    // last group, column tile by column tile: after each MFMA a piece of the next K-step's first group, after the
-    // last MFMA of a column tile also that tile's next B fragment (after the last K-step: reads of stale data that
-    // nothing uses)
-    static_for<0, GM * kGemmNT>([&](auto xc) {
-      constexpr int X = decltype(xc)::value, nt = X / GM, m = X % GM;
-      mfma_one(std::integral_constant<int, NG - 1>{}, m, nt);
-      __builtin_amdgcn_sched_barrier(0);
-      if constexpr (X < kPieces && !(SKIP & 16)) read_a_piece(nxt, std::integral_constant<int, 0>{}, xc);
-      if constexpr (m == GM - 1 && !(SKIP & 16)) read_b(nxt, nt);
-      __builtin_amdgcn_sched_barrier(0);
-    });
+  // The ring slot of a K-step's first fragment moves on by NTW % RING per step and the A register sets alternate:
+  // four K-steps bring both back, so the loop is unrolled by four with the slots as compile-time constants.
+  constexpr int PH = NTW % RING;
+  int cur_i = 0, k = 0;   // cur_i = k % 3
+  auto advance = [&] { cur_i = cur_i == 2 ? 0 : cur_i + 1; ++k; };
+  for (; k + 4 <= ksteps;) {
+    k_step(k, cur_i, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}); advance();
+    k_step(k, cur_i, std::integral_constant<int, 1>{}, std::integral_constant<int, PH % RING>{}); advance();
+    k_step(k, cur_i, std::integral_constant<int, 0>{}, std::integral_constant<int, (2 * PH) % RING>{}); advance();
+    k_step(k, cur_i, std::integral_constant<int, 1>{}, std::integral_constant<int, (3 * PH) % RING>{}); advance();
   }
+  if (k < ksteps) { k_step(k, cur_i, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}); advance(); }
+  if (k < ksteps) { k_step(k, cur_i, std::integral_constant<int, 1>{}, std::integral_constant<int, PH % RING>{}); advance(); }
+  if (k < ksteps) { k_step(k, cur_i, std::integral_constant<int, 0>{}, std::integral_constant<int, (2 * PH) % RING>{}); advance(); }
   __builtin_amdgcn_s_waitcnt(0);   // the last requests (of steps that do not exist) must land before the LDS is given back
   MX_GEMM_STAMP(2)
+  {
+    float* ct = c + (int64_t)(m0 + wave * 64 + 4 * g) * ldc + n0 + i;
+    const bool inside = m0 + kGemmBM <= M && n0 + 16 * NTW <= N;   // the whole tile lies in C: no per-element tests
 #pragma unroll
-  for (int mt = 0; mt < kGemmMT; ++mt)
+    for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
-    for (int nt = 0; nt < kGemmNT; ++nt) {
-      const int n = n0 + wn * 64 + nt * 16 + i;
+      for (int nt = 0; nt < NTW; ++nt)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int m = m0 + wm * 128 + mt * 16 + 4 * g + j;
-        if (m < M && n < N) c[(int64_t)m * ldc + n] = acc[mt][nt][j];
-      }
-    }
+        for (int j = 0; j < 4; ++j)
+          if (inside || (m0 + wave * 64 + mt * 16 + 4 * g + j < M && n0 + nt * 16 + i < N))
+            ct[(int64_t)(mt * 16 + j) * ldc + nt * 16] = acc[mt][nt][j];
+  }
   MX_GEMM_STAMP(3)
 }
 
@@ -720,20 +728,40 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
                                const uint8_t* w_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
                                hipStream_t stream) {
   if (M > 64) {
-    const int64_t m_tiles = (M + kGemmBM - 1) / kGemmBM, n_tiles = (N + kGemmBN - 1) / kGemmBN;
-    if (m_tiles * n_tiles > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
     if (M * K > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;   // the kernel addresses A with 32-bit offsets
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        cus <= 0)
+      return MX_ERR_LAUNCH;
+    // Tile width: one workgroup fills a CU, so the tiles run in rounds of `cus`; the narrower tiles trade work per
+    // tile for a last round that is less empty.  Cost ~ rounds x width (896 tiles of 128 columns on 256 CUs are 4
+    // rounds of which the last is half empty; 1024 tiles of 112 columns are 4 full rounds of 7/8 the work).
+    const int64_t m_tiles = (M + kGemmBM - 1) / kGemmBM;
+    int ntw = 8;
+    int64_t best = -1;
+    for (int cand = 8; cand >= 6; --cand) {
+      const int64_t tiles_c = m_tiles * ((N + 16 * cand - 1) / (16 * cand));
+      const int64_t cost = (tiles_c + cus - 1) / cus * cand;
+      if (best < 0 || cost < best) { best = cost; ntw = cand; }
+    }
+    const int64_t n_tiles = (N + 16 * ntw - 1) / (16 * ntw);
+    if (m_tiles * n_tiles > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
     // 3 stages x 41.5 KB: above the 64 KB a kernel gets by default, so the dynamic size is requested explicitly
     constexpr int kSmem = 3 * (int)sizeof(GemmStage);
-    static bool attr_set = false;
-    if (!attr_set) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ss_fp4_tiled_kernel<0>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) != hipSuccess)
-        return MX_ERR_LAUNCH;
-      attr_set = true;
-    }
-    hipLaunchKernelGGL(gemm_ss_fp4_tiled_kernel<0>, dim3((unsigned)(m_tiles * n_tiles)), dim3(kGemmThreads), kSmem, stream, a_codes,
-                       a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles);
+#define MX_GEMM_TILED(NTW)                                                                                                  \
+  if (ntw == NTW) {                                                                                                         \
+    static bool attr_set = false;                                                                                           \
+    if (!attr_set) {                                                                                                        \
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ss_fp4_tiled_kernel<NTW, 0>),                              \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) != hipSuccess)                             \
+        return MX_ERR_LAUNCH;                                                                                               \
+      attr_set = true;                                                                                                      \
+    }                                                                                                                       \
+    hipLaunchKernelGGL((gemm_ss_fp4_tiled_kernel<NTW, 0>), dim3((unsigned)(m_tiles * n_tiles)), dim3(kGemmThreads), kSmem,  \
+                       stream, a_codes, a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles);         \
+  }
+    MX_GEMM_TILED(8) MX_GEMM_TILED(7) MX_GEMM_TILED(6)
+#undef MX_GEMM_TILED
     return launch_status("the fused GEMM");
   }
   if (M <= 16 && N * K <= 0xFFFFFFFFll) {   // (the decode kernel addresses W with 32-bit offsets)

@@ -80,9 +80,12 @@ def test_gemm_decode_shape_config5(mx, oracle):
     _check(mx, oracle, 16, 14336, 4096, seed=1005)
 
 
-@pytest.mark.parametrize("M,N,K", [(128, 128, 128), (65, 16, 256), (200, 304, 256), (384, 136, 1024)])
+@pytest.mark.parametrize("M,N,K", [(128, 128, 128), (65, 16, 256), (200, 304, 256), (384, 136, 1024), (512, 16384, 640),
+                                   (300, 3600, 896)])
 def test_gemm_tiled_shapes(mx, oracle, M, N, K):
-    # M > 64 takes the LDS-tiled kernel; ragged M and N tiles
+    # M > 64 takes the LDS-tiled kernel; ragged M and N tiles; the launcher picks tiles of 96, 112 or 128 columns by the
+    # number of rounds they need on the GPU (the large shapes here take 128 and 112), and the K loop is unrolled by 4
+    # (1, 2, 5, 7 and 8 K-steps here)
     _check(mx, oracle, M, N, K, seed=M + N)
     _check(mx, oracle, M, N, K, seed=M + N + 1, random_bytes="narrow")
     _check(mx, oracle, M, N, K, seed=M + N + 2, random_bytes="wide")
