@@ -444,7 +444,7 @@ __device__ __forceinline__ void producer_barrier() { asm volatile("s_barrier" ::
 
 // SKIP is 0 in the library; a tuning harness instantiates other values to take parts of the kernel out
 // (1: no slicing, 4: no MFMA, 8 / 64: A / W requested only for the first K-steps, 16: no LDS reads in the consumer loop,
-// 512 / 1024: every workgroup loads the first tile of W / of A).
+// 512 / 1024: every workgroup loads the first tile of W / of A, 2048: the consumers' barrier does not wait for A).
 #ifdef MX_GEMM_TIMING
 __device__ long long g_gemm_times[4096][4];   // tuning harness only: clock readings of consumer wave 0 of each workgroup
 #define MX_GEMM_STAMP(slot) \
