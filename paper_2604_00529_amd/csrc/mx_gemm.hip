@@ -526,15 +526,15 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
       constexpr int S = decltype(slot_c)::value;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        int q = tid + 256 * j, col = q >> 3, kb = (q & 7) >> 1, half = q & 1;
-        if (col > BN - 1) col = BN - 1;
+        const int q = tid + 256 * j, col = q >> 3, kb = (q & 7) >> 1, half = q & 1;
         uint32_t b2[2];
         if constexpr (SKIP & 1) {
           b2[0] = rb[S][j].x ^ rb[S][j].y; b2[1] = rb[S][j].z ^ rb[S][j].w;
         } else {
           slice_half_block_e2m1(rb[S][j], b2);   // Eq. (6) element step, once per workgroup and K-step
         }
-        *reinterpret_cast<u32x2*>(&st.b[col * kGemmLdB + 16 * (kb ^ ((col >> 2) & 3)) + 8 * half]) = u32x2{b2[0], b2[1]};
+        // (a tile narrower than 128 columns: the spare threads, which loaded its last column again, store nothing)
+        if (col < BN) *reinterpret_cast<u32x2*>(&st.b[col * kGemmLdB + 16 * (kb ^ ((col >> 2) & 3)) + 8 * half]) = u32x2{b2[0], b2[1]};
       }
       st.as[tid] = rsa[S];
       if (tid < BN) st.bs[tid] = scale_add_x4(rsw[S], kDeltaE_E4M3_E2M1);   // Eq. (6) scale step
