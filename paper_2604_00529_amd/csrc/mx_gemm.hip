@@ -729,10 +729,16 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
                                hipStream_t stream) {
   if (M > 64) {
     if (M * K > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;   // the kernel addresses A with 32-bit offsets
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-        cus <= 0)
-      return MX_ERR_LAUNCH;
+    // compute units of the current device (asked once per device)
+    static int cu_count[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MX_ERR_LAUNCH;
+    if (cu_count[dev] == 0) {
+      int n = 0;
+      if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return MX_ERR_LAUNCH;
+      cu_count[dev] = n;
+    }
+    const int cus = cu_count[dev];
     // Tile width: one workgroup fills a CU, so the tiles run in rounds of `cus`; the narrower tiles trade work per
     // tile for a last round that is less empty.  Cost ~ rounds x width (896 tiles of 128 columns on 256 CUs are 4
     // rounds of which the last is half empty; 1024 tiles of 112 columns are 4 full rounds of 7/8 the work).
