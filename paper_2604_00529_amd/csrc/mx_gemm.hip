@@ -452,26 +452,48 @@ __device__ long long g_gemm_times[4096][4];   // tuning harness only: clock read
 #else
 #define MX_GEMM_STAMP(slot)
 #endif
+// Position of a role in a workgroup's sequence of K-steps: tile coordinates and K-step, advanced without branches;
+// past the last step it stays there (such steps load valid data again that nothing uses).
+struct GemmCursor {
+  int k, tm, tn, tiles_left;
+};
+__device__ __forceinline__ void gemm_advance(GemmCursor& cur, int ksteps, int m_tiles, int step_tm, int step_tn) {
+  const bool last_k = cur.k == ksteps - 1;
+  const bool next_tile = last_k && cur.tiles_left > 1;
+  int tm = cur.tm + step_tm, tn = cur.tn + step_tn;
+  if (tm >= m_tiles) { tm -= m_tiles; tn += 1; }
+  cur.k = next_tile ? 0 : (last_k ? cur.k : cur.k + 1);
+  cur.tm = next_tile ? tm : cur.tm;
+  cur.tn = next_tile ? tn : cur.tn;
+  cur.tiles_left -= next_tile ? 1 : 0;
+}
+
 template <int NTW, int SKIP>
 __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const uint8_t* __restrict__ a_codes,
                                                                          const uint8_t* __restrict__ a_scales,
                                                                          const uint8_t* __restrict__ w_codes,
                                                                          const uint8_t* __restrict__ w_scales,
                                                                          float* __restrict__ c, int M, int N, int K,
-                                                                         int64_t ldc, int m_tiles) {
+                                                                         int64_t ldc, int m_tiles, int tiles) {
   extern __shared__ __attribute__((aligned(16))) uint8_t gemm_smem[];
   GemmStage* stage = reinterpret_cast<GemmStage*>(gemm_smem);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // a scalar: the role branch is uniform
   const int tid = threadIdx.x & 255;   // index inside the role's 256 threads
   const int i = lane & 15, g = lane >> 4;
-  // consecutive workgroups walk the M tiles of one N tile: with round-robin dispatch over the 8 XCDs each XCD
-  // keeps re-using the same few A tiles from its L2 while the W tile streams through
-  const int tm = blockIdx.x % m_tiles, tn = blockIdx.x / m_tiles;
   constexpr int BN = 16 * NTW;   // columns of the workgroup tile
-  const int m0 = tm * kGemmBM, n0 = tn * BN;
   const int KB = K / 32, ksteps = K / kGemmBK;
-
+  // The kernel is persistent: workgroup b works the tiles b, b + gridDim.x, ... and both roles run ONE software pipeline
+  // over all K-steps of all their tiles: the operands of the next tile's first K-steps are in flight while the current
+  // tile is finished, and a consumer goes on to the next tile's MFMAs as soon as it has issued the stores of the
+  // finished one.  (A workgroup fills a CU, so with one tile per workgroup nothing overlaps the 4-6 us until a tile's
+  // first operands arrive, nor the 4 us in which its stores drain.)  Consecutive tiles walk the M tiles of one N
+  // tile: with round-robin dispatch over the 8 XCDs and a grid that is a multiple of 8 each XCD keeps re-using the same
+  // few A tiles from its L2 while the W tiles stream through.
+  const int my_tiles = (tiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;   // >= 1: the grid is <= tiles
+  const int total = my_tiles * ksteps;                                                     // K-steps of this workgroup
+  const int step_tm = (int)gridDim.x % m_tiles, step_tn = (int)gridDim.x / m_tiles;
+  const GemmCursor first = {0, (int)blockIdx.x % m_tiles, (int)blockIdx.x / m_tiles, my_tiles};
   // The two roles run separate loops (so that a wave's registers hold either the accumulators or the prefetched
   // tiles, not both) with the same number of barriers: one after the prologue, one per K-step.
   // Loads return in order within a wave, so the two operands are requested by different waves: W, which comes from HBM
@@ -493,36 +515,35 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
     // land in outputs that are never stored, and straight-line code lets the loads of several K-steps stay in
     // flight (the compiler counts outstanding loads exactly only without control flow).
     constexpr int R = kGemmWDepth;   // register slots: slot s % R holds K-step s from its request until it is staged
-    const uint8_t* pw[4];
+    // per-thread parts of the addresses that do not depend on the tile
+    int w_col[4], w_piece[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      int q = tid + 256 * j, col = q >> 3, piece = q & 7;
-      if (col > BN - 1) col = BN - 1;   // a tile narrower than 128 columns: the spare threads repeat its last column
-      const int n0l = (SKIP & 512) ? 0 : n0;
-      int n = n0l + col < N ? n0l + col : N - 1;
-      pw[j] = w_codes + (int64_t)n * K + 16 * piece;
+      const int q = tid + 256 * j;
+      w_col[j] = (q >> 3) < BN ? (q >> 3) : BN - 1;   // a tile narrower than 128 columns: the spare threads repeat its last column
+      w_piece[j] = 16 * (q & 7);
     }
-    const uint8_t* psa = a_scales + (int64_t)(m0 + tid < M ? m0 + tid : M - 1) * KB;
     const int scol = (tid & 127) < BN ? (tid & 127) : BN - 1;
-    const uint8_t* psw = w_scales + (int64_t)(n0 + scol < N ? n0 + scol : N - 1) * KB;
     u32x4 rb[R][4];
     uint32_t rsa[R], rsw[R];
-    // K-steps past the end are clamped to the last one: loaded again, never used
-    const int last = ksteps - 1;
-    auto load_step = [&](int ks_raw, auto slot_c) {
+    GemmCursor ld = first;   // the K-step that the next call of load_step requests
+    auto load_step = [&](auto slot_c) __attribute__((always_inline)) {
       constexpr int S = decltype(slot_c)::value;
-      const int ks = ks_raw < last ? ks_raw : last;
-      const int k0 = ks * kGemmBK;
+      const int m0 = ld.tm * kGemmBM, n0 = (SKIP & 512) ? 0 : ld.tn * BN;
+      const int k0 = ld.k * kGemmBK;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         // plain loads: the 8 workgroups that share this W tile run on 8 different XCDs at about the same time,
         // and non-temporal loads made each of them fetch it from HBM (269 us against 196 us for the kernel)
-        if (!(SKIP & 64) || ks_raw < R) rb[S][j] = *reinterpret_cast<const u32x4*>(pw[j] + k0);
+        const int n = n0 + w_col[j] < N ? n0 + w_col[j] : N - 1;
+        rb[S][j] = *reinterpret_cast<const u32x4*>(w_codes + (int64_t)n * K + k0 + w_piece[j]);
       }
-      rsa[S] = *reinterpret_cast<const uint32_t*>(psa + ks * 4);
-      rsw[S] = *reinterpret_cast<const uint32_t*>(psw + ks * 4);
+      const int ms = m0 + tid < M ? m0 + tid : M - 1, ns = n0 + scol < N ? n0 + scol : N - 1;
+      rsa[S] = *reinterpret_cast<const uint32_t*>(a_scales + (int64_t)ms * KB + ld.k * 4);
+      rsw[S] = *reinterpret_cast<const uint32_t*>(w_scales + (int64_t)ns * KB + ld.k * 4);
+      gemm_advance(ld, ksteps, m_tiles, step_tm, step_tn);
     };
-    auto store_lds = [&](GemmStage& st, auto slot_c) {
+    auto store_lds = [&](GemmStage& st, auto slot_c) __attribute__((always_inline)) {
       constexpr int S = decltype(slot_c)::value;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -540,16 +561,16 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
       if (tid < BN) st.bs[tid] = scale_add_x4(rsw[S], kDeltaE_E4M3_E2M1);   // Eq. (6) scale step
     };
     // prologue: steps 0 .. R - 1 requested, step 0 staged
-    static_for<0, R>([&](auto d) { load_step(decltype(d)::value, d); });
+    static_for<0, R>([&](auto d) { load_step(d); });
     store_lds(stage[0], std::integral_constant<int, 0>{});
     __syncthreads();
-    // K-step k: step k + R is requested into the slot that step k left (staged in step k - 1), step k + 1 is staged
-    int s1 = 1;   // (k + 1) % 3
-    const int rounds = ksteps / R;
+    // K-step s: step s + R is requested into the slot that step s left (staged in step s - 1), step s + 1 is staged
+    int s1 = 1;   // (s + 1) % 3
+    const int rounds = total / R;
     for (int r = 0; r < rounds; ++r) {
       static_for<0, R>([&](auto d) {
         constexpr int DD = decltype(d)::value;
-        load_step(r * R + DD + R, d);
+        load_step(d);
         store_lds(stage[s1], std::integral_constant<int, (DD + 1) % R>{});
         s1 = s1 == 2 ? 0 : s1 + 1;
         __syncthreads();
@@ -558,7 +579,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
     // the K-steps left over when their number is not a multiple of R (no more loads are needed)
     static_for<0, R - 1>([&](auto d) {
       constexpr int DD = decltype(d)::value;
-      if (rounds * R + DD < ksteps) {
+      if (rounds * R + DD < total) {
         store_lds(stage[s1], std::integral_constant<int, (DD + 1) % R>{});
         s1 = s1 == 2 ? 0 : s1 + 1;
         __syncthreads();
@@ -618,30 +639,38 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
       acc[MT][NT][0] += __int_as_float(af[SET][MT][0] ^ bf[R][0] ^ (int)sa[SET][MT]);
       acc[MT][NT][1] += __int_as_float(af[SET][MT][7] ^ bf[R][3] ^ (int)sb[R]);
     } else {
-      acc[MT][NT] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af[SET][MT], bf[R], acc[MT][NT], 0, 4, 0, (int)sa[SET][MT], 0,
-                                                                     (int)sb[R]);
+      // W is the instruction's first operand, so a lane's four results are four consecutive COLUMNS of one row of C
+      // (one 16-byte store): acc[MT][NT][j] = C[row 16 MT + i][column 16 NT + 4 g + j] of the wave's part of the tile
+      acc[MT][NT] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bf[R], af[SET][MT], acc[MT][NT], 4, 0, 0, (int)sb[R], 0,
+                                                                     (int)sa[SET][MT]);
+      // (an MFMA has no side effect, so the compiler may move it down into the block of its next use, across the
+      // scheduling barriers; the empty statement, which it must not move, holds the result where it is)
+      asm volatile("" : "+v"(acc[MT][NT]));
     }
   };
   // A: 16-byte chunk q = tid + 256 j (j < 8) of the tile: row q / 8, position q % 8 in that row of the LDS tile.
   // Requested with LDS as the destination (no registers, no LDS store instruction): the hardware puts lane l's 16
-  // bytes at byte 16 l of the wave's 1 KB block, so the lane fetches the chunk that the swizzle puts there.  Rows past
-  // the edge read the last valid row.  (The host checks M K < 2^32.)
-  const __amdgpu_buffer_rsrc_t a_rsrc = make_buffer(a_codes, (uint32_t)M * (uint32_t)K);
-  uint32_t a_voff[kGemmAChunks];
-#pragma unroll
-  for (int j = 0; j < kGemmAChunks; ++j) {
-    const int q = tid + 256 * j, row = q >> 3, pos = q & 7;
-    const int m0l = (SKIP & 1024) ? 0 : m0;
-    const int m = m0l + row < M ? m0l + row : M - 1;
-    a_voff[j] = (uint32_t)m * (uint32_t)K + 16u * (uint32_t)(pos ^ ((row >> 1) & 7));
-  }
-  const int last = ksteps - 1;
-  auto request_a = [&](int ks_raw, int stage_i, auto jc) {   // (K-steps past the end: the last one again, never used)
+  // bytes at byte 16 l of the wave's 1 KB block, so the lane fetches the chunk that the swizzle puts there.  The
+  // buffer descriptor covers the valid rows of ONE tile of A and the lane offsets are the same for every tile; a row
+  // past the edge of A is out of the descriptor's range, which the hardware answers with zeros instead of a read.
+  // (The host checks 256 K < 2^32.)
+  // (Chunk j lies 32 j rows below chunk 0, so one register holds the lane's part and the rest of the offset --
+  // 32 j K and the K-step -- is scalar; it is added into the lane offset, not passed as the instruction's scalar
+  // offset, because the range check looks at the lane offset only.)
+  const uint32_t a_lane = (uint32_t)(tid >> 3) * (uint32_t)K + 16u * (uint32_t)((tid & 7) ^ ((tid >> 4) & 7));
+  auto a_tile = [&](const GemmCursor& cur) {
+    const int m0 = (SKIP & 1024) ? 0 : cur.tm * kGemmBM;
+    const int rows = M - m0 < kGemmBM ? M - m0 : kGemmBM;
+    return make_buffer(a_codes + (int64_t)m0 * K, (uint32_t)rows * (uint32_t)K);
+  };
+  // K-step ks of the tile behind descriptor rsrc (a step past the end of K: the last one again, which nothing uses)
+  auto request_a = [&](__amdgpu_buffer_rsrc_t rsrc, int ks, int stage_i, auto jc) __attribute__((always_inline)) {
     constexpr int J = decltype(jc)::value;
-    if (!(SKIP & 8) || ks_raw < 2)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(
-          a_rsrc, (__attribute__((address_space(3))) void*)(gemm_smem + stage_i * (int)sizeof(GemmStage) + J * 4096 + wave * 1024), 16,
-          (int)a_voff[J], (ks_raw < last ? ks_raw : last) * kGemmBK, 0, 0);
+    if constexpr ((SKIP & 8) != 0) { if (ks > 3) return; }
+    const int kc = ks < ksteps ? ks : ksteps - 1;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+        rsrc, (__attribute__((address_space(3))) void*)(gemm_smem + stage_i * (int)sizeof(GemmStage) + J * 4096 + wave * 1024), 16,
+        (int)(a_lane + (uint32_t)(32 * J) * (uint32_t)K + (uint32_t)(kc * kGemmBK)), 0, 0, 0);
   };
   // the barrier of a K-step for a consumer: its LDS reads have landed (the producers overwrite that stage two steps
   // on, the consumers' own requests one step on) and of its requests only the 8 youngest, of the step after next, are
@@ -653,7 +682,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   };
   constexpr int kPieces = 3 * MTW;
   // K-step k with the A fragments in register set SET and B fragment nt in ring slot (PHASE + nt) % RING
-  auto k_step = [&](int k, int cur_i, auto set_c, auto phase_c) {
+  auto k_step = [&](int cur_i, auto set_c, auto phase_c, __amdgpu_buffer_rsrc_t req_rsrc, int req_k) __attribute__((always_inline)) {
     constexpr int SET = decltype(set_c)::value, PHASE = decltype(phase_c)::value;
     using NSET = std::integral_constant<int, SET ^ 1>;
     const int nxt_i = cur_i == 2 ? 0 : cur_i + 1, req_i = cur_i == 0 ? 2 : cur_i - 1;   // (k + 1) % 3, (k + 2) % 3
@@ -666,7 +695,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
       mfma_one(set_c, SLOT{}, std::integral_constant<int, MT>{}, std::integral_constant<int, NT>{});
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (X < kGemmAChunks) {
-        request_a(k + 2, req_i, xc);   // A of the step after next, into the stage that every consumer left a step ago
+        request_a(req_rsrc, req_k, req_i, xc);   // A of the step after next, into the stage that every consumer left a step ago
       }
       if constexpr (X == kBarrierX) consumer_barrier();   // every read of this stage has landed; the next one is complete
       if constexpr (!(SKIP & 16)) {
@@ -685,42 +714,105 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
       __builtin_amdgcn_sched_barrier(0);
     });
   };
+  // The ring slot of a K-step's first fragment moves on by NTW % RING per step and the A register sets alternate:
+  // four K-steps bring both back, so the loop runs in rounds of four with the slots as compile-time constants.
+  // Everything that depends on the tile changes BETWEEN rounds: a tile's last K-step is the fourth of a round when K
+  // is a multiple of 512, and only then does the host give a workgroup more than one tile.  (Inside a round there
+  // must be no control flow at all: the compiler is free to move an MFMA, which has no side effect, down into the
+  // block of its next use, and did -- all MFMAs of a round in one clump, their operands spilled.)
+  GemmCursor at = first;   // the round being multiplied (k = its first K-step)
+  GemmCursor nx = first;   // the round after it
+  auto next_round = [&](GemmCursor& cur) {
+    const bool tile_done = cur.k + 4 >= ksteps;
+    if (!tile_done) {
+      cur.k += 4;
+    } else if (cur.tiles_left > 1) {
+      cur.k = 0;
+      cur.tm += step_tm; cur.tn += step_tn;
+      if (cur.tm >= m_tiles) { cur.tm -= m_tiles; cur.tn += 1; }
+      cur.tiles_left -= 1;
+    }   // else: the workgroup's last round; the cursor stays (its requests repeat valid loads that nothing uses)
+  };
+  next_round(nx);
+  __amdgpu_buffer_rsrc_t rs_at = a_tile(at), rs_nx = a_tile(nx);
   MX_GEMM_STAMP(0)
-  static_for<0, kGemmAChunks>([&](auto jc) { request_a(0, 0, jc); });
-  static_for<0, kGemmAChunks>([&](auto jc) { request_a(1, 1, jc); });
+  static_for<0, kGemmAChunks>([&](auto jc) { request_a(rs_at, 0, 0, jc); });
+  static_for<0, kGemmAChunks>([&](auto jc) { request_a(rs_at, 1, 1, jc); });
   consumer_barrier();   // stage 0 is filled
   MX_GEMM_STAMP(1)
   static_for<0, kPieces>([&](auto pc) { read_a_piece(stage[0], std::integral_constant<int, 0>{}, pc); });
   static_for<0, RING>([&](auto rc) { read_b(stage[0], rc, rc); });
   __builtin_amdgcn_sched_barrier(0);
-  // The ring slot of a K-step's first fragment moves on by NTW % RING per step and the A register sets alternate:
-  // four K-steps bring both back, so the loop is unrolled by four with the slots as compile-time constants.
+  // Stores go through a buffer descriptor that starts at the tile's first element: a lane keeps ONE offset register,
+  // (i ldc + 4 g) floats, and the place of each of the 4 NTW row / column tiles is a scalar offset, so the stores
+  // need no address registers while the fragments of the next K-step are already held.  (The host checks
+  // 256 ldc < 2^30.)
+  typedef uint32_t u32v4 __attribute__((ext_vector_type(4)));
+  const uint32_t c_lane = ((uint32_t)i * (uint32_t)ldc + (uint32_t)(4 * g)) * 4u;
+  auto store_tile = [&]() __attribute__((always_inline)) {
+    const int m0 = at.tm * kGemmBM, n0 = at.tn * BN;
+    const int rows = M - m0 < kGemmBM ? M - m0 : kGemmBM, cols = N - n0 < BN ? N - n0 : BN;   // the part of the tile inside C
+    const __amdgpu_buffer_rsrc_t c_rsrc =
+        make_buffer(c + (int64_t)m0 * ldc + n0, ((uint32_t)(rows - 1) * (uint32_t)ldc + (uint32_t)cols) * 4u);
+    const int g4 = 4 * g;
+    if (rows == kGemmBM && cols == BN) {   // the whole tile lies in C: 16 bytes per lane, no tests
+#pragma unroll
+      for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) {
+          const f32x4 v = acc[mt][nt];
+          __builtin_amdgcn_raw_buffer_store_b128(u32v4{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])},
+                                                 c_rsrc, (int)c_lane, (int)(((uint32_t)(wave * 64 + mt * 16) * (uint32_t)ldc + (uint32_t)(nt * 16)) * 4u), 0);
+        }
+    } else {   // a tile on the edge: element by element (lane part against a scalar)
+#pragma unroll
+      for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) {
+          const f32x4 v = acc[mt][nt];
+          const bool row_ok = i < rows - (wave * 64 + mt * 16);
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (row_ok && g4 < cols - (nt * 16 + j))
+              __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v[j]), c_rsrc, (int)c_lane,
+                                                    (int)(((uint32_t)(wave * 64 + mt * 16) * (uint32_t)ldc + (uint32_t)(nt * 16 + j)) * 4u), 0);
+        }
+    }
+  };
   constexpr int PH = NTW % RING;
-  int cur_i = 0, k = 0;   // cur_i = k % 3
-  auto advance = [&] { cur_i = cur_i == 2 ? 0 : cur_i + 1; ++k; };
-  for (; k + 4 <= ksteps;) {
-    k_step(k, cur_i, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}); advance();
-    k_step(k, cur_i, std::integral_constant<int, 1>{}, std::integral_constant<int, PH % RING>{}); advance();
-    k_step(k, cur_i, std::integral_constant<int, 0>{}, std::integral_constant<int, (2 * PH) % RING>{}); advance();
-    k_step(k, cur_i, std::integral_constant<int, 1>{}, std::integral_constant<int, (3 * PH) % RING>{}); advance();
-  }
-  if (k < ksteps) { k_step(k, cur_i, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}); advance(); }
-  if (k < ksteps) { k_step(k, cur_i, std::integral_constant<int, 1>{}, std::integral_constant<int, PH % RING>{}); advance(); }
-  if (k < ksteps) { k_step(k, cur_i, std::integral_constant<int, 0>{}, std::integral_constant<int, (2 * PH) % RING>{}); advance(); }
-  __builtin_amdgcn_s_waitcnt(0);   // the last requests (of steps that do not exist) must land before the LDS is given back
-  MX_GEMM_STAMP(2)
-  {
-    float* ct = c + (int64_t)(m0 + wave * 64 + 4 * g) * ldc + n0 + i;
-    const bool inside = m0 + kGemmBM <= M && n0 + 16 * NTW <= N;   // the whole tile lies in C: no per-element tests
+  using C0 = std::integral_constant<int, 0>;
+  using C1 = std::integral_constant<int, 1>;
+  int cur_i = 0, s = 0;   // cur_i = s % 3
+  auto step_done = [&] { cur_i = cur_i == 2 ? 0 : cur_i + 1; ++s; };
+  while (s + 4 <= total) {
+    // (requests: two K-steps ahead -- the third and fourth of this round, then the first two of the next)
+    k_step(cur_i, C0{}, std::integral_constant<int, 0>{}, rs_at, at.k + 2); step_done();
+    k_step(cur_i, C1{}, std::integral_constant<int, PH % RING>{}, rs_at, at.k + 3); step_done();
+    k_step(cur_i, C0{}, std::integral_constant<int, (2 * PH) % RING>{}, rs_nx, nx.k); step_done();
+    k_step(cur_i, C1{}, std::integral_constant<int, (3 * PH) % RING>{}, rs_nx, nx.k + 1); step_done();
+    // a finished tile: stored (the stores drain while the next tile's MFMAs run), and the next one starts from zero.
+    // The accumulators are cleared by selects, not inside the branch, so that they stay in place: 128 selects in
+    // four K-steps are nothing beside 512 MFMAs.
+    const bool done = at.k + 4 == ksteps;
+    if (done) store_tile();
 #pragma unroll
     for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
       for (int nt = 0; nt < NTW; ++nt)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-          if (inside || (m0 + wave * 64 + mt * 16 + 4 * g + j < M && n0 + nt * 16 + i < N))
-            ct[(int64_t)(mt * 16 + j) * ldc + nt * 16] = acc[mt][nt][j];
+        for (int j = 0; j < 4; ++j) acc[mt][nt][j] = done ? 0.f : acc[mt][nt][j];
+    at = nx; rs_at = rs_nx;
+    next_round(nx);
+    rs_nx = a_tile(nx);
   }
+  if (s < total) {   // the last one to three K-steps of a K that is not a multiple of 512 (the workgroup's only tile)
+    k_step(cur_i, C0{}, std::integral_constant<int, 0>{}, rs_at, at.k + 2); step_done();
+    if (s < total) { k_step(cur_i, C1{}, std::integral_constant<int, PH % RING>{}, rs_at, at.k + 3); step_done(); }
+    if (s < total) { k_step(cur_i, C0{}, std::integral_constant<int, (2 * PH) % RING>{}, rs_at, at.k + 4); step_done(); }
+    store_tile();
+  }
+  MX_GEMM_STAMP(2)
+  __builtin_amdgcn_s_waitcnt(0);   // the last requests (of steps that do not exist) must land before the LDS is given back
   MX_GEMM_STAMP(3)
 }
 
@@ -728,7 +820,7 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
                                const uint8_t* w_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
                                hipStream_t stream) {
   if (M > 64) {
-    if (M * K > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;   // the kernel addresses A with 32-bit offsets
+    if (kGemmBM * K > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;   // the kernel addresses a tile of A with 32-bit offsets
     // compute units of the current device (asked once per device)
     static int cu_count[64] = {};
     int dev = 0;
@@ -751,7 +843,13 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
       if (best < 0 || cost < best) { best = cost; ntw = cand; }
     }
     const int64_t n_tiles = (N + 16 * ntw - 1) / (16 * ntw);
-    if (m_tiles * n_tiles > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+    const int64_t tiles = m_tiles * n_tiles;
+    if (tiles > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+    // one persistent workgroup per CU (its LDS and registers fill the CU), fewer when there are fewer tiles; the kernel
+    // counts the K-steps of a workgroup in an int
+    const int64_t grid_wgs = (tiles < cus || K % (4 * kGemmBK) != 0) ? tiles : cus;   // (the kernel takes several tiles only in rounds of four K-steps)
+    if ((tiles + grid_wgs - 1) / grid_wgs * (K / kGemmBK) > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+    if (ldc * kGemmBM >= ((int64_t)1 << 30)) return MX_ERR_UNSUPPORTED;   // a tile of C is addressed with 32-bit byte offsets
     // 3 stages x 41.5 KB: above the 64 KB a kernel gets by default, so the dynamic size is requested explicitly
     constexpr int kSmem = 3 * (int)sizeof(GemmStage);
 #define MX_GEMM_TILED(NTW)                                                                                                  \
@@ -763,8 +861,8 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
         return MX_ERR_LAUNCH;                                                                                               \
       attr_set = true;                                                                                                      \
     }                                                                                                                       \
-    hipLaunchKernelGGL((gemm_ss_fp4_tiled_kernel<NTW, 0>), dim3((unsigned)(m_tiles * n_tiles)), dim3(kGemmThreads), kSmem,  \
-                       stream, a_codes, a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles);         \
+    hipLaunchKernelGGL((gemm_ss_fp4_tiled_kernel<NTW, 0>), dim3((unsigned)grid_wgs), dim3(kGemmThreads), kSmem, stream,     \
+                       a_codes, a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles, (int)tiles);     \
   }
     MX_GEMM_TILED(8) MX_GEMM_TILED(7) MX_GEMM_TILED(6)
 #undef MX_GEMM_TILED
