@@ -490,10 +490,15 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   // first operands arrive, nor the 4 us in which its stores drain.)  Consecutive tiles walk the M tiles of one N
   // tile: with round-robin dispatch over the 8 XCDs and a grid that is a multiple of 8 each XCD keeps re-using the same
   // few A tiles from its L2 while the W tiles stream through.
-  const int my_tiles = (tiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;   // >= 1: the grid is <= tiles
+  // Workgroup b runs on XCD b % 8 (round-robin dispatch).  The workgroups of one XCD take NEIGHBOURING tiles of every
+  // round of gridDim.x tiles -- a block of M tiles x a few N tiles -- so that what one of them brings into the XCD's L2
+  // the others use: with b itself as the tile index, an XCD held one M tile and fetched every tile of W.
+  const int grid = (int)gridDim.x;
+  const int vb = (SKIP & 4096) || grid % 8 != 0 ? (int)blockIdx.x : ((int)blockIdx.x % 8) * (grid / 8) + (int)blockIdx.x / 8;
+  const int my_tiles = (tiles - vb + grid - 1) / grid;   // >= 1: the grid is <= tiles
   const int total = my_tiles * ksteps;                                                     // K-steps of this workgroup
-  const int step_tm = (int)gridDim.x % m_tiles, step_tn = (int)gridDim.x / m_tiles;
-  const GemmCursor first = {0, (int)blockIdx.x % m_tiles, (int)blockIdx.x / m_tiles, my_tiles};
+  const int step_tm = grid % m_tiles, step_tn = grid / m_tiles;
+  const GemmCursor first = {0, vb % m_tiles, vb / m_tiles, my_tiles};
   // The two roles run separate loops (so that a wave's registers hold either the accumulators or the prefetched
   // tiles, not both) with the same number of barriers: one after the prologue, one per K-step.
   // Loads return in order within a wave, so the two operands are requested by different waves: W, which comes from HBM
@@ -839,7 +844,8 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
     int64_t best = -1;
     for (int cand = 8; cand >= 6; --cand) {
       const int64_t tiles_c = m_tiles * ((N + 16 * cand - 1) / (16 * cand));
-      const int64_t cost = (tiles_c + cus - 1) / cus * cand;
+      // (the 128-column kernel runs out of registers and spills a little: measured 9 % slower per column)
+      const int64_t cost = (tiles_c + cus - 1) / cus * (cand == 8 ? 87 : cand * 10);
       if (best < 0 || cost < best) { best = cost; ntw = cand; }
     }
     const int64_t n_tiles = (N + 16 * ntw - 1) / (16 * ntw);
