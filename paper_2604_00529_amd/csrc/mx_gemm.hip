@@ -413,7 +413,7 @@ __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_decode_kernel(const uint8_
 // single role per wave the same work ran back to back (measured: 308 us against 52 us of pure MFMA time).
 // LDS holds three K-steps (the one being multiplied, the one being completed, the one being requested), one
 // barrier per K-step.  The 16-byte chunks of a row are XOR-swizzled so that the 16 lanes of a lane group hit
-// different banks.
+// different banks.  The kernel is persistent: one workgroup per compute unit works several tiles in one pipeline.
 constexpr int kGemmBM = 256, kGemmBN = 128, kGemmBK = 128;
 constexpr int kGemmLdA = 128, kGemmLdB = 64;   // unpadded rows; 16-byte chunks are XOR-swizzled (see GemmStage)
 constexpr int kGemmAChunks = kGemmBM * kGemmBK / 16 / 256;   // 16-byte A chunks per producer thread and K-step (8)
@@ -443,8 +443,9 @@ constexpr int kWaitLgkmcnt0Vmcnt8 = 8 | (7 << 4) | (0 << 8) | (0 << 14);   // s_
 __device__ __forceinline__ void producer_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
 // SKIP is 0 in the library; a tuning harness instantiates other values to take parts of the kernel out
-// (1: no slicing, 4: no MFMA, 8 / 64: A / W requested only for the first K-steps, 16: no LDS reads in the consumer loop,
-// 512 / 1024: every workgroup loads the first tile of W / of A, 2048: the consumers' barrier does not wait for A).
+// (1: no slicing, 4: no MFMA, 8: A requested only for the first K-steps, 16: no LDS reads in the consumer loop,
+// 512 / 1024: every workgroup loads the first tile of W / of A, 2048: the consumers' barrier does not wait for A,
+// 4096: the tile index is the workgroup index, without the XCD-aware order).
 #ifdef MX_GEMM_TIMING
 __device__ long long g_gemm_times[4096][4];   // tuning harness only: clock readings of consumer wave 0 of each workgroup
 #define MX_GEMM_STAMP(slot) \
@@ -483,16 +484,14 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   const int i = lane & 15, g = lane >> 4;
   constexpr int BN = 16 * NTW;   // columns of the workgroup tile
   const int KB = K / 32, ksteps = K / kGemmBK;
-  // The kernel is persistent: workgroup b works the tiles b, b + gridDim.x, ... and both roles run ONE software pipeline
-  // over all K-steps of all their tiles: the operands of the next tile's first K-steps are in flight while the current
-  // tile is finished, and a consumer goes on to the next tile's MFMAs as soon as it has issued the stores of the
-  // finished one.  (A workgroup fills a CU, so with one tile per workgroup nothing overlaps the 4-6 us until a tile's
-  // first operands arrive, nor the 4 us in which its stores drain.)  Consecutive tiles walk the M tiles of one N
-  // tile: with round-robin dispatch over the 8 XCDs and a grid that is a multiple of 8 each XCD keeps re-using the same
-  // few A tiles from its L2 while the W tiles stream through.
-  // Workgroup b runs on XCD b % 8 (round-robin dispatch).  The workgroups of one XCD take NEIGHBOURING tiles of every
-  // round of gridDim.x tiles -- a block of M tiles x a few N tiles -- so that what one of them brings into the XCD's L2
-  // the others use: with b itself as the tile index, an XCD held one M tile and fetched every tile of W.
+  // The kernel is persistent: a workgroup works the tiles v, v + gridDim.x, ... of the tile list (M tile index
+  // fastest) and both roles run ONE software pipeline over all K-steps of all their tiles: the operands of the next
+  // tile's first K-steps are in flight while the current tile is finished, and a consumer goes on to the next tile's
+  // MFMAs as soon as it has issued the stores of the finished one.  (A workgroup fills a CU, so with one tile per
+  // workgroup nothing overlaps the 4-6 us until a tile's first operands arrive.)
+  // Workgroup b runs on XCD b % 8 (round-robin dispatch), and v is chosen so that the workgroups of one XCD take
+  // NEIGHBOURING tiles of every round of gridDim.x tiles -- a block of M tiles x a few N tiles -- so that what one of
+  // them brings into the XCD's L2 the others use: with v = b an XCD held one M tile and fetched every tile of W.
   const int grid = (int)gridDim.x;
   const int vb = (SKIP & 4096) || grid % 8 != 0 ? (int)blockIdx.x : ((int)blockIdx.x % 8) * (grid / 8) + (int)blockIdx.x / 8;
   const int my_tiles = (tiles - vb + grid - 1) / grid;   // >= 1: the grid is <= tiles
