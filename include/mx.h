@@ -159,7 +159,7 @@ mx_status_t mx_dequant(const mx_format_t* f, const mx_packed_t* src, const mx_de
  *   w_anchor: MXFP8 E4M3 anchor of the weight, K-contiguous: outer = N, nblocks = K / 32 (mx_quantize of
  *             W[N, K] along axis 1, or of W[K, N] along axis 0).
  *   c: dense fp32 [M, N], written (not accumulated into).
- * K must be a multiple of 128.  MX_ERR_UNSUPPORTED for shapes this build has no kernel for (for M > 64: K >= 2^24
+ * K must be a multiple of 128.  MX_ERR_UNSUPPORTED for shapes this build has no kernel for (for M > 48: K >= 2^24
  * or a row stride of c of 2^22 elements or more).  Each output is an
  * fp32 sum over K in a fixed order (results are reproducible run to run). */
 mx_status_t mx_gemm_ss_fp4(const mx_packed_t* a, const mx_packed_t* w_anchor, const mx_dense_t* c, void* stream);

@@ -49,6 +49,7 @@ __device__ __forceinline__ uint32_t slice_scale(uint32_t byte) {
 // slices its own B fragments (Eq. (6)) and multiplies them with MT row tiles of A; the loads of 4 K-steps are in
 // flight together.  The four partial sums are added in a fixed order through LDS (deterministic).
 constexpr int kSmallmNT = 2;
+constexpr int kSmallmMaxM = 48;   // above it the LDS-tiled kernel is faster (measured, N = 14336, K = 4096: 30.7 against 31.3 us at M = 40, 36.1 against 31.9 us at M = 56)
 
 // scale byte of K-step p (0..7) of a chunk for lane group g, out of the chunk's 32 bytes
 __device__ __forceinline__ uint32_t chunk_scale(const u32x4& lo, const u32x4& hi, int p, int g) {
@@ -437,7 +438,7 @@ struct GemmStage {
 
 // s_waitcnt lgkmcnt(0) alone (gfx9 immediate: vmcnt 63 in bits 3:0 and 15:14, expcnt 7 in bits 6:4, lgkmcnt in bits 11:8)
 constexpr int kWaitLgkmcnt0 = 15 | (7 << 4) | (0 << 8) | (3 << 14);
-constexpr int kWaitLgkmcnt0Vmcnt8 = 8 | (7 << 4) | (0 << 8) | (0 << 14);   // s_waitcnt vmcnt(8) lgkmcnt(0)
+constexpr int wait_lgkmcnt0_vmcnt(int v) { return (v & 15) | (7 << 4) | (0 << 8) | ((v >> 4) << 14); }   // s_waitcnt vmcnt(v) lgkmcnt(0)
 // A workgroup barrier that is only the instruction; the "memory" clobber keeps the compiler from moving memory
 // operations across it.
 __device__ __forceinline__ void producer_barrier() { asm volatile("s_barrier" ::: "memory"); }
@@ -679,9 +680,14 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   // the barrier of a K-step for a consumer: its LDS reads have landed (the producers overwrite that stage two steps
   // on, the consumers' own requests one step on) and of its requests only the 8 youngest, of the step after next, are
   // still in flight; no fence -- that would wait for those too
-  auto consumer_barrier = [&] {
+  // (`younger`: how many of this wave's requests were issued after those that must have landed -- the ones of the
+  // step after next that precede the barrier in the K-step: all 8, or the first 4 with the 64-column tile, whose
+  // barrier comes after the fourth MFMA)
+  constexpr int kBarrierX = (NTW - RING) * MTW + MTW - 1;   // the MFMA after which the ring first needs the next stage
+  constexpr int kYoungerInStep = kBarrierX + 1 < kGemmAChunks ? kBarrierX + 1 : kGemmAChunks;
+  auto consumer_barrier = [&](auto younger_c) {
     if constexpr (SKIP & 2048) __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);   // (timing only: does not wait for A)
-    else __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0Vmcnt8);
+    else __builtin_amdgcn_s_waitcnt(wait_lgkmcnt0_vmcnt(decltype(younger_c)::value));
     producer_barrier();
   };
   constexpr int kPieces = 3 * MTW;
@@ -695,13 +701,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
     static_for<0, NTW * MTW>([&](auto xc) {
       constexpr int X = decltype(xc)::value, NT = X / MTW, MT = X % MTW;
       using SLOT = std::integral_constant<int, (PHASE + NT) % RING>;
-      constexpr int kBarrierX = (NTW - RING) * MTW + MTW - 1;   // the MFMA after which the ring first needs the next stage
       mfma_one(set_c, SLOT{}, std::integral_constant<int, MT>{}, std::integral_constant<int, NT>{});
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (X < kGemmAChunks) {
         request_a(req_rsrc, req_k, req_i, xc);   // A of the step after next, into the stage that every consumer left a step ago
       }
-      if constexpr (X == kBarrierX) consumer_barrier();   // every read of this stage has landed; the next one is complete
+      if constexpr (X == kBarrierX) consumer_barrier(std::integral_constant<int, kYoungerInStep>{});   // every read of this stage has landed; the next one is complete
       if constexpr (!(SKIP & 16)) {
         if constexpr (MT == MTW - 1) {
           // the ring set of this column tile is free: fragment NT + RING, of this K-step or of the next
@@ -742,7 +747,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   MX_GEMM_STAMP(0)
   static_for<0, kGemmAChunks>([&](auto jc) { request_a(rs_at, 0, 0, jc); });
   static_for<0, kGemmAChunks>([&](auto jc) { request_a(rs_at, 1, 1, jc); });
-  consumer_barrier();   // stage 0 is filled
+  consumer_barrier(std::integral_constant<int, kGemmAChunks>{});   // stage 0 is filled (the requests of stage 1 may be in flight)
   MX_GEMM_STAMP(1)
   static_for<0, kPieces>([&](auto pc) { read_a_piece(stage[0], std::integral_constant<int, 0>{}, pc); });
   static_for<0, RING>([&](auto rc) { read_b(stage[0], rc, rc); });
@@ -823,7 +828,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
 mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                                const uint8_t* w_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
                                hipStream_t stream) {
-  if (M > 64) {
+  if (M > kSmallmMaxM) {
     if (kGemmBM * K > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;   // the kernel addresses a tile of A with 32-bit offsets
     // compute units of the current device (asked once per device)
     static int cu_count[64] = {};
@@ -836,15 +841,18 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
     }
     const int cus = cu_count[dev];
     // Tile width: one workgroup fills a CU, so the tiles run in rounds of `cus`; the narrower tiles trade work per
-    // tile for a last round that is less empty.  Cost ~ rounds x width (896 tiles of 128 columns on 256 CUs are 4
-    // rounds of which the last is half empty; 1024 tiles of 112 columns are 4 full rounds of 7/8 the work).
+    // tile for a last round that is less empty, or for more workgroups when M is small.  A tile costs a fixed part (its
+    // A tile and the latencies of a K-step do not shrink with the width) plus a part per column: measured 19 us + 0.26 us
+    // per column for K = 4096, hence cost ~ rounds x (5 + width / 16).  (896 tiles of 128 columns on 256 CUs are 4
+    // rounds of which the last is half empty; 1024 tiles of 112 columns are 4 full rounds of 7/8 the work.  M = 128:
+    // 224 tiles of 64 columns take 36 us, 128 tiles of 112 columns 48 us.)
     const int64_t m_tiles = (M + kGemmBM - 1) / kGemmBM;
     int ntw = 8;
     int64_t best = -1;
-    for (int cand = 8; cand >= 6; --cand) {
+    for (int cand = 8; cand >= 4; --cand) {
       const int64_t tiles_c = m_tiles * ((N + 16 * cand - 1) / (16 * cand));
       // (the 128-column kernel runs out of registers and spills a little: measured 9 % slower per column)
-      const int64_t cost = (tiles_c + cus - 1) / cus * (cand == 8 ? 87 : cand * 10);
+      const int64_t cost = (tiles_c + cus - 1) / cus * (50 + (cand == 8 ? 87 : cand * 10));
       if (best < 0 || cost < best) { best = cost; ntw = cand; }
     }
     const int64_t n_tiles = (N + 16 * ntw - 1) / (16 * ntw);
@@ -869,7 +877,7 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
     hipLaunchKernelGGL((gemm_ss_fp4_tiled_kernel<NTW, 0>), dim3((unsigned)grid_wgs), dim3(kGemmThreads), kSmem, stream,     \
                        a_codes, a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles, (int)tiles);     \
   }
-    MX_GEMM_TILED(8) MX_GEMM_TILED(7) MX_GEMM_TILED(6)
+    MX_GEMM_TILED(8) MX_GEMM_TILED(7) MX_GEMM_TILED(6) MX_GEMM_TILED(5) MX_GEMM_TILED(4)
 #undef MX_GEMM_TILED
     return launch_status("the fused GEMM");
   }
@@ -893,7 +901,7 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
     hipLaunchKernelGGL((gemm_ss_fp4_smallm_kernel<MT>), dim3(grid), dim3(256), 0, stream, a_codes, a_scales, w_codes,     \
                        w_scales, c, (int)M, (int)N, (int)K, ldc);                                                         \
   }
-  MX_GEMM_CASE(1) MX_GEMM_CASE(2) MX_GEMM_CASE(3) MX_GEMM_CASE(4)
+  MX_GEMM_CASE(1) MX_GEMM_CASE(2) MX_GEMM_CASE(3)
 #undef MX_GEMM_CASE
   return launch_status("the fused GEMM");
 }

@@ -70,7 +70,7 @@ def _check(mx, oracle, M, N, K, seed, w_axis0=True, random_bytes=False):
                                    (16, 64, 9344), (5, 40, 2176), (17, 96, 1152)])
 def test_gemm_small_shapes(mx, oracle, M, N, K):
     # M <= 16 takes the decode kernel (K chunks of 1024 dealt to 4 waves: several chunks per wave, ragged last chunk,
-    # fewer than 16 rows, a ragged column tile), 16 < M <= 64 the kernel with fragment loads
+    # fewer than 16 rows, a ragged column tile), 16 < M <= 48 the kernel with fragment loads, M = 64 the tiled kernel
     _check(mx, oracle, M, N, K, seed=M * 1000 + N)
     _check(mx, oracle, M, N, K, seed=M * 1000 + N + 1, w_axis0=False)
     _check(mx, oracle, M, N, K, seed=M * 1000 + N + 2, random_bytes="narrow")
@@ -85,8 +85,8 @@ def test_gemm_decode_shape_config5(mx, oracle):
 @pytest.mark.parametrize("M,N,K", [(128, 128, 128), (65, 16, 256), (200, 304, 256), (384, 136, 1024), (512, 16384, 640),
                                    (300, 3600, 896)])
 def test_gemm_tiled_shapes(mx, oracle, M, N, K):
-    # M > 64 takes the LDS-tiled kernel; ragged M and N tiles; the launcher picks tiles of 96, 112 or 128 columns by the
-    # number of rounds they need on the GPU (the large shapes here take 128 and 112), and the K loop is unrolled by 4
+    # M > 48 takes the LDS-tiled kernel; ragged M and N tiles; the launcher picks tiles of 64 to 128 columns by the
+    # number of rounds they need on the GPU (the small shapes here take 64, the large ones 112), and the K loop is unrolled by 4
     # (1, 2, 5, 7 and 8 K-steps here)
     _check(mx, oracle, M, N, K, seed=M + N)
     _check(mx, oracle, M, N, K, seed=M + N + 1, random_bytes="narrow")
@@ -96,7 +96,7 @@ def test_gemm_tiled_shapes(mx, oracle, M, N, K):
 @pytest.mark.parametrize("M,N,K", [(1000, 9000, 512), (600, 16384, 512), (2048, 8192, 512), (520, 12000, 1024)])
 def test_gemm_several_tiles_per_workgroup(mx, oracle, M, N, K):
     # more tiles than compute units and K a multiple of 512: a workgroup works several tiles in one pipeline (tiles of
-    # 96, 112 and 128 columns here; ragged last M and N tiles; a number of M tiles that does not divide the grid, so
+    # 80, 112 and 128 columns here; ragged last M and N tiles; a number of M tiles that does not divide the grid, so
     # that a workgroup's walk over the tiles wraps around)
     _check(mx, oracle, M, N, K, seed=M + N + K)
     _check(mx, oracle, M, N, K, seed=M + N + K + 1, random_bytes="narrow")

@@ -23,7 +23,7 @@ def test_graph_replays_match_eager_and_oracle(mx, oracle):
     nblocks = sum(int(s.numel()) for _, s in anchors)
     ws = torch.empty(mx.binding.lib().mx_slice_and_scale_batched_workspace(len(anchors), nblocks), dtype=torch.uint8, device="cuda")
     fq = [torch.empty_like(d) for d in dense]
-    # the fused GEMM too (its tiled kernel: M > 64): activations = tensor 2 (128 x 2048), weight = its first 48 rows
+    # the fused GEMM too (its tiled kernel: M > 48): activations = tensor 2 (128 x 2048), weight = its first 48 rows
     c_out = torch.empty((128, 48), dtype=torch.float32, device="cuda")
     batch4 = mx.SsBatch(anchors, fa, ft, t4, ws)
     batch46 = mx.SsBatch(anchors, fa, [f6, ft], [[t6[i], t4[i]] for i in range(len(anchors))], ws)
