@@ -1,0 +1,117 @@
+"""Pins of the oracle's reference for the fused consumer GEMM (Sec. 3.5: the model runs with W_t = Q_{A->t}(W_A);
+Eq. (6) for the conversion, Sec. 3.3 for the reconstruction V^ = X * P): exact rational arithmetic written out here
+from the value tables, and cases with a closed form.  A transposed operand, a scale taken from the wrong block, a
+forgotten or doubled 2^De, or the anchor multiplied instead of its slice each fail at least one of them."""
+from fractions import Fraction
+
+import numpy as np
+
+import defs
+
+DE = 6   # e_max(E4M3) - e_max(E2M1) = 8 - 2 (Sec. 3.3, Eq. (6))
+
+
+def _tables():
+    e4m3 = dict(defs.value_table("e4m3"))
+    e2m1 = dict(defs.value_table("e2m1"))
+    return e4m3, e2m1
+
+
+def _exact_product(a_codes, a_scales, w_codes, w_scales):
+    """C[m][n] as Fractions, every step spelled out: activation value = 2^(byte - 127) * value(code); weight code
+    sliced with the exhaustive nearest-value search on value / 2^De, its scale byte raised by De."""
+    e4m3, e2m1 = _tables()
+    M, KB, k = a_codes.shape
+    N = w_codes.shape[0]
+    out = [[Fraction(0) for _ in range(N)] for _ in range(M)]
+    for m in range(M):
+        for n in range(N):
+            acc = Fraction(0)
+            for b in range(KB):
+                xa = Fraction(2) ** (int(a_scales[m, b]) - 127)
+                xw = Fraction(2) ** (int(w_scales[n, b]) + DE - 127)
+                for j in range(k):
+                    av = e4m3[int(a_codes[m, b, j])]
+                    wv = e4m3[int(w_codes[n, b, j])]
+                    wt = e2m1[defs.nearest_code("e2m1", wv / 2 ** DE, negative_zero=bool(w_codes[n, b, j] & 0x80))]
+                    acc += (xa * av) * (xw * wt)
+            out[m][n] = acc
+    return out
+
+
+def _random_operands(rng, M, N, KB):
+    a_codes = rng.integers(0, 256, size=(M, KB, 32), dtype=np.uint8)
+    w_codes = rng.integers(0, 256, size=(N, KB, 32), dtype=np.uint8)
+    a_codes[(a_codes & 0x7F) == 0x7F] = 0x3A      # no NaN codes: their reading has a pin of its own
+    w_codes[(w_codes & 0x7F) == 0x7F] = 0x6B
+    a_scales = rng.integers(120, 134, size=(M, KB), dtype=np.uint8)
+    w_scales = rng.integers(115, 128, size=(N, KB), dtype=np.uint8)
+    return a_codes, a_scales, w_codes, w_scales
+
+
+def test_gemm_reference_against_exact_rationals(oracle):
+    rng = np.random.default_rng(20260401)
+    for M, N, KB in [(3, 4, 2), (1, 5, 1), (4, 2, 3)]:
+        a_codes, a_scales, w_codes, w_scales = _random_operands(rng, M, N, KB)
+        # large anchor codes in some columns, so that the slice is not zero almost everywhere
+        w_codes[:, :, ::3] |= 0x60
+        w_codes[(w_codes & 0x7F) == 0x7F] = 0x7E
+        got, got_abs = oracle.gemm_ss_reference(a_codes, a_scales, w_codes, w_scales, with_abs=True)
+        want = _exact_product(a_codes, a_scales, w_codes, w_scales)
+        assert got.shape == (M, N)
+        for m in range(M):
+            for n in range(N):
+                w = float(want[m][n])
+                assert abs(got[m, n] - w) <= 1e-12 * max(abs(w), float(got_abs[m, n])), (M, N, KB, m, n)
+        assert (got_abs >= np.abs(got) * (1 - 1e-12)).all()
+
+
+def test_gemm_reference_one_hot_activations_read_the_sliced_weight(oracle):
+    # A[m] = 1.0 at position p(m) only (code 0x38, scale byte 127): C[m][n] is the dequantized SLICED weight at
+    # [n][p(m)] -- not the anchor's value, and not the weight of another row, block or position
+    e4m3, e2m1 = _tables()
+    rng = np.random.default_rng(7)
+    M, N, KB = 5, 6, 2
+    _, _, w_codes, w_scales = _random_operands(rng, M, N, KB)
+    w_codes |= 0x50                                # magnitudes of 2^3 and more: most slices are non-zero
+    w_codes[(w_codes & 0x7F) == 0x7F] = 0x7E
+    a_codes = np.zeros((M, KB, 32), dtype=np.uint8)
+    a_scales = np.full((M, KB), 127, dtype=np.uint8)
+    pos = [(0, 0), (0, 31), (1, 0), (1, 17), (0, 5)]
+    for m, (b, j) in enumerate(pos):
+        a_codes[m, b, j] = 0x38
+    got = oracle.gemm_ss_reference(a_codes, a_scales, w_codes, w_scales)
+    differs_from_anchor = 0
+    for m, (b, j) in enumerate(pos):
+        for n in range(N):
+            wv = e4m3[int(w_codes[n, b, j])]
+            wt = e2m1[defs.nearest_code("e2m1", wv / 2 ** DE, negative_zero=bool(w_codes[n, b, j] & 0x80))]
+            want = Fraction(2) ** (int(w_scales[n, b]) + DE - 127) * wt
+            assert got[m, n] == float(want), (m, n)
+            differs_from_anchor += want != Fraction(2) ** (int(w_scales[n, b]) - 127) * wv
+    assert differs_from_anchor > 0                 # the case can tell the slice from the anchor
+
+
+def test_gemm_reference_closed_forms(oracle):
+    # constant operands: every activation 1.5 * 2^2, every weight anchor 384 * 2^-3 (code 0x7C; 384 / 64 = 6 is E2M1's
+    # largest value, kept exactly): C = K * 6 * 48 for every output
+    M, N, KB = 2, 3, 4
+    a_codes = np.full((M, KB, 32), 0x3C, dtype=np.uint8)
+    a_scales = np.full((M, KB), 129, dtype=np.uint8)
+    w_codes = np.full((N, KB, 32), 0x7C, dtype=np.uint8)
+    w_scales = np.full((N, KB), 124, dtype=np.uint8)
+    got = oracle.gemm_ss_reference(a_codes, a_scales, w_codes, w_scales)
+    assert (got == KB * 32 * 6.0 * 48.0).all()
+    # anchor values below half of E2M1's smallest magnitude times 2^De (0.25 * 64 = 16) slice to zero: C = 0;
+    # exactly 16 is a tie between 0 and 0.5 and goes to the even code, 0
+    w_codes[:] = 0x58                              # 16
+    assert (oracle.gemm_ss_reference(a_codes, a_scales, w_codes, w_scales) == 0).all()
+    w_codes[:] = 0x59                              # 18 -> 0.5 * 64 = 32
+    assert (oracle.gemm_ss_reference(a_codes, a_scales, w_codes, w_scales) == KB * 32 * 6.0 * 4.0).all()
+    # the sign of the weight carries through the slice; a row of activations with alternating signs cancels
+    a_codes[:, :, 1::2] ^= 0x80
+    assert (oracle.gemm_ss_reference(a_codes, a_scales, w_codes, w_scales) == 0).all()
+    # scaling one block's activation scale byte by +1 adds that block's share once more
+    a_codes[:, :, 1::2] ^= 0x80
+    a_scales[:, 2] += 1
+    assert (oracle.gemm_ss_reference(a_codes, a_scales, w_codes, w_scales) == (KB + 1) * 32 * 6.0 * 4.0).all()
