@@ -510,26 +510,97 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   // step k - 1, which every consumer left at the last barrier; the producers slice W of step k + 1 into stage
   // (k + 1) % 3.  A consumer arrives at the barrier of step k when its reads of stage k have landed and its part of A
   // of step k + 1 is in LDS; a producer when its LDS stores have completed.
+  // Tiles of 128 columns leave a consumer no register for the requests of A (it spilled, 20 % slower): there a fifth
+  // wave, the loader, requests A and the other three producer waves share W.  The narrower tiles keep the requests in
+  // the consumers and four producer waves, which is 2 % faster for them.
+  constexpr bool kLoader = NTW == 8;
+  if constexpr (kLoader) {
+    if (wave == 4) {
+      // ---- the A loader: one wave requests the whole A tile (E4M3 codes, 32 KB) and its scale bytes (1 KB) of K-step
+      // s + 2 with loads that have LDS as their destination (no registers, no LDS store instructions), waits until
+      // those of step s + 1 have landed and arrives at the barrier.  A wave that issues MFMAs never waits for the CU's
+      // memory pipe this way (a request held a consumer for ~80 cycles), and the stores of a finished tile share no
+      // in-order queue with requests that somebody waits for.
+      //   codes: request J (J < 32) is the 1 KB of 16-byte chunks q = lane + 64 J of the tile: row q / 8, position q % 8
+      //     in that row of the LDS tile; the hardware puts lane l's 16 bytes at byte 16 l of the block, so the lane
+      //     fetches the chunk that the swizzle puts there.
+      //   scales: request j (j < 4) is the scale dword of rows 64 j + lane.
+      // The buffer descriptors cover the valid rows of ONE tile and the lane offsets are the same for every tile; a row
+      // past the edge of A is out of the descriptor's range, which the hardware answers with zeros instead of a read.
+      // The whole offset is in the lane register, because the range check looks at that only.  (The host checks
+      // 256 K < 2^32.)
+      constexpr int kRequests = kGemmBM * kGemmBK / 1024 + kGemmBM / 64;   // 32 + 4 per K-step
+      const uint32_t a_lane = (uint32_t)(lane >> 3) * (uint32_t)K + 16u * (uint32_t)((lane & 7) ^ (lane >> 4));
+      const uint32_t s_lane = (uint32_t)lane * (uint32_t)KB;
+      GemmCursor rq = first;   // the K-step requested next
+      int issued = 0;
+      auto request_step = [&](int stage_i) __attribute__((always_inline)) {
+        const int m0 = (SKIP & 1024) ? 0 : rq.tm * kGemmBM;
+        const int rows = M - m0 < kGemmBM ? M - m0 : kGemmBM;
+        const __amdgpu_buffer_rsrc_t c_rsrc = make_buffer(a_codes + (int64_t)m0 * K, (uint32_t)rows * (uint32_t)K);
+        const __amdgpu_buffer_rsrc_t s_rsrc = make_buffer(a_scales + (int64_t)m0 * KB, (uint32_t)rows * (uint32_t)KB);
+        uint8_t* st = gemm_smem + stage_i * (int)sizeof(GemmStage);
+        const uint32_t k_off = (uint32_t)(rq.k * kGemmBK), ks_off = (uint32_t)(rq.k * 4);
+        const bool skip = (SKIP & 8) && issued >= 4;   // (timing only)
+        if (!skip) {
+          static_for<0, kGemmBM * kGemmBK / 1024>([&](auto jc) {
+            constexpr int J = decltype(jc)::value;
+            // rows 8 J + lane / 8; their swizzle term (row / 2) % 8 = lane / 16 + 4 (J % 2)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(c_rsrc, (__attribute__((address_space(3))) void*)(st + J * 1024), 16,
+                                                     (int)((a_lane ^ (64u * (J & 1))) + (uint32_t)(8 * J) * (uint32_t)K + k_off), 0, 0, 0);
+          });
+          static_for<0, kGemmBM / 64>([&](auto jc) {
+            constexpr int J = decltype(jc)::value;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(s_rsrc, (__attribute__((address_space(3))) void*)(st + offsetof(GemmStage, as) + J * 256), 4,
+                                                     (int)(s_lane + (uint32_t)(64 * J) * (uint32_t)KB + ks_off), 0, 0, 0);
+          });
+        }
+        ++issued;
+        gemm_advance(rq, ksteps, m_tiles, step_tm, step_tn);
+      };
+      // arrive at a barrier when everything but the `kRequests` youngest requests has landed (vector memory operations
+      // of a wave complete in the order of issue); no fence, which would wait for those too
+      auto arrive = [&] {
+        if constexpr (SKIP & 8) __builtin_amdgcn_s_waitcnt(0);
+        else __builtin_amdgcn_s_waitcnt(wait_lgkmcnt0_vmcnt(kRequests));
+        producer_barrier();
+      };
+      request_step(0);
+      request_step(1);
+      arrive();   // stage 0 is complete
+      int st2 = 2;   // (s + 2) % 3: the stage that every consumer left at the last barrier
+      for (int s = 0; s < total; ++s) {
+        request_step(st2);
+        st2 = st2 == 2 ? 0 : st2 + 1;
+        arrive();   // step s + 1 is complete
+      }
+      __builtin_amdgcn_s_waitcnt(0);   // the last requests (of steps that do not exist) must land before the LDS is given back
+      return;
+    }
+  }
   if (wave >= 4) {
     // ---- producers
-    //   B: 16-byte piece q = tid + 256 j (j < 4) of the anchor tile: column q / 8, half q % 2 of K-block (q % 8) / 2
+    //   B: 16-byte piece q = t + PT j (j < WP; PT = 256 producer threads, 192 beside a loader wave) of the anchor tile: column q / 8, half q % 2 of K-block (q % 8) / 2
     //      (16 anchor bytes -> 8 bytes of E2M1), through registers, because it is sliced on the way.  The lanes of a
     //      load read consecutive 16 bytes (8 lanes one 128-byte row).
-    //   scales: thread t one row of A (4 bytes); thread t < 128 also one column of W
+    //   scales: thread t one row of A (4 bytes; not beside a loader wave); thread t < 16 NTW also one column of W
     // Rows / columns past the edge are clamped to the last valid one instead of branched around: their products
     // land in outputs that are never stored, and straight-line code lets the loads of several K-steps stay in
     // flight (the compiler counts outstanding loads exactly only without control flow).
     constexpr int R = kGemmWDepth;   // register slots: slot s % R holds K-step s from its request until it is staged
     // per-thread parts of the addresses that do not depend on the tile
-    int w_col[4], w_piece[4];
+    constexpr int PT = kLoader ? 192 : 256;        // producer threads
+    constexpr int WP = (8 * BN + PT - 1) / PT;     // 16-byte pieces per thread and K-step
+    const int pt = kLoader ? (int)threadIdx.x - 320 : tid;
+    int w_col[WP], w_piece[WP];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int q = tid + 256 * j;
-      w_col[j] = (q >> 3) < BN ? (q >> 3) : BN - 1;   // a tile narrower than 128 columns: the spare threads repeat its last column
+    for (int j = 0; j < WP; ++j) {
+      const int q = pt + PT * j;
+      w_col[j] = (q >> 3) < BN ? (q >> 3) : BN - 1;   // the spare threads of the last piece repeat the tile's last column
       w_piece[j] = 16 * (q & 7);
     }
-    const int scol = (tid & 127) < BN ? (tid & 127) : BN - 1;
-    u32x4 rb[R][4];
+    const int scol = pt < BN ? pt : BN - 1;
+    u32x4 rb[R][WP];
     uint32_t rsa[R], rsw[R];
     GemmCursor ld = first;   // the K-step that the next call of load_step requests
     auto load_step = [&](auto slot_c) __attribute__((always_inline)) {
@@ -537,33 +608,36 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
       const int m0 = ld.tm * kGemmBM, n0 = (SKIP & 512) ? 0 : ld.tn * BN;
       const int k0 = ld.k * kGemmBK;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        // plain loads: the 8 workgroups that share this W tile run on 8 different XCDs at about the same time,
+      for (int j = 0; j < WP; ++j) {
+        // plain loads: the workgroups that share this W tile run at about the same time, partly on different XCDs,
         // and non-temporal loads made each of them fetch it from HBM (269 us against 196 us for the kernel)
         const int n = n0 + w_col[j] < N ? n0 + w_col[j] : N - 1;
         rb[S][j] = *reinterpret_cast<const u32x4*>(w_codes + (int64_t)n * K + k0 + w_piece[j]);
       }
-      const int ms = m0 + tid < M ? m0 + tid : M - 1, ns = n0 + scol < N ? n0 + scol : N - 1;
-      rsa[S] = *reinterpret_cast<const uint32_t*>(a_scales + (int64_t)ms * KB + ld.k * 4);
+      if constexpr (!kLoader) {   // (with a loader wave the scale bytes of A come with its codes)
+        const int ms = m0 + pt < M ? m0 + pt : M - 1;
+        rsa[S] = *reinterpret_cast<const uint32_t*>(a_scales + (int64_t)ms * KB + ld.k * 4);
+      }
+      const int ns = n0 + scol < N ? n0 + scol : N - 1;
       rsw[S] = *reinterpret_cast<const uint32_t*>(w_scales + (int64_t)ns * KB + ld.k * 4);
       gemm_advance(ld, ksteps, m_tiles, step_tm, step_tn);
     };
     auto store_lds = [&](GemmStage& st, auto slot_c) __attribute__((always_inline)) {
       constexpr int S = decltype(slot_c)::value;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int q = tid + 256 * j, col = q >> 3, kb = (q & 7) >> 1, half = q & 1;
+      for (int j = 0; j < WP; ++j) {
+        const int q = pt + PT * j, col = q >> 3, kb = (q & 7) >> 1, half = q & 1;
         uint32_t b2[2];
         if constexpr (SKIP & 1) {
           b2[0] = rb[S][j].x ^ rb[S][j].y; b2[1] = rb[S][j].z ^ rb[S][j].w;
         } else {
           slice_half_block_e2m1(rb[S][j], b2);   // Eq. (6) element step, once per workgroup and K-step
         }
-        // (a tile narrower than 128 columns: the spare threads, which loaded its last column again, store nothing)
+        // (the spare threads of the last piece, which loaded the tile's last column again, store nothing)
         if (col < BN) *reinterpret_cast<u32x2*>(&st.b[col * kGemmLdB + 16 * (kb ^ ((col >> 2) & 3)) + 8 * half]) = u32x2{b2[0], b2[1]};
       }
-      st.as[tid] = rsa[S];
-      if (tid < BN) st.bs[tid] = scale_add_x4(rsw[S], kDeltaE_E4M3_E2M1);   // Eq. (6) scale step
+      if constexpr (!kLoader) st.as[pt] = rsa[S];
+      if (pt < BN) st.bs[pt] = scale_add_x4(rsw[S], kDeltaE_E4M3_E2M1);   // Eq. (6) scale step
     };
     // prologue: steps 0 .. R - 1 requested, step 0 staged
     static_for<0, R>([&](auto d) { load_step(d); });
@@ -671,6 +745,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   // K-step ks of the tile behind descriptor rsrc (a step past the end of K: the last one again, which nothing uses)
   auto request_a = [&](__amdgpu_buffer_rsrc_t rsrc, int ks, int stage_i, auto jc) __attribute__((always_inline)) {
     constexpr int J = decltype(jc)::value;
+    if constexpr (kLoader) return;   // (the loader wave requests A)
     if constexpr ((SKIP & 8) != 0) { if (ks > 3) return; }
     const int kc = ks < ksteps ? ks : ksteps - 1;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(
@@ -686,7 +761,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   constexpr int kBarrierX = (NTW - RING) * MTW + MTW - 1;   // the MFMA after which the ring first needs the next stage
   constexpr int kYoungerInStep = kBarrierX + 1 < kGemmAChunks ? kBarrierX + 1 : kGemmAChunks;
   auto consumer_barrier = [&](auto younger_c) {
-    if constexpr (SKIP & 2048) __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);   // (timing only: does not wait for A)
+    if constexpr (kLoader || (SKIP & 2048)) __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);   // (the loader waits for A; 2048: timing only)
     else __builtin_amdgcn_s_waitcnt(wait_lgkmcnt0_vmcnt(decltype(younger_c)::value));
     producer_barrier();
   };
@@ -851,8 +926,7 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
     int64_t best = -1;
     for (int cand = 8; cand >= 4; --cand) {
       const int64_t tiles_c = m_tiles * ((N + 16 * cand - 1) / (16 * cand));
-      // (the 128-column kernel runs out of registers and spills a little: measured 9 % slower per column)
-      const int64_t cost = (tiles_c + cus - 1) / cus * (50 + (cand == 8 ? 87 : cand * 10));
+      const int64_t cost = (tiles_c + cus - 1) / cus * (50 + cand * 10);
       if (best < 0 || cost < best) { best = cost; ntw = cand; }
     }
     const int64_t n_tiles = (N + 16 * ntw - 1) / (16 * ntw);
