@@ -145,6 +145,19 @@ def test_validation_returns_codes_without_launching(mx):
     # dequant
     assert L.mx_dequant(ref(f), ref(B.MxPacked(P, P, 32, 3)), ref(s2), None) == 3
     assert L.mx_dequant(ref(f), None, ref(s2), None) == 1
+    # fused GEMM: A [M, K / 32 blocks], W anchor [N, K / 32 blocks], C fp32 [M, N]
+    ga, gw = B.MxPacked(P, P, 16, 8), B.MxPacked(P, P, 64, 8)
+    gc = B.MxDense(P, B.MX_F32, 16, 64, 64)
+    assert L.mx_gemm_ss_fp4(None, ref(gw), ref(gc), None) == 1
+    assert L.mx_gemm_ss_fp4(ref(ga), ref(gw), None, None) == 1
+    assert L.mx_gemm_ss_fp4(ref(ga), ref(B.MxPacked(P, None, 64, 8)), ref(gc), None) == 1
+    assert L.mx_gemm_ss_fp4(ref(ga), ref(gw), ref(B.MxDense(P, B.MX_BF16, 16, 64, 64)), None) == 5   # C is fp32 only
+    assert L.mx_gemm_ss_fp4(ref(ga), ref(B.MxPacked(P, P, 64, 12)), ref(gc), None) == 3              # K differs
+    assert L.mx_gemm_ss_fp4(ref(ga), ref(gw), ref(B.MxDense(P, B.MX_F32, 16, 32, 32)), None) == 3    # N differs
+    assert L.mx_gemm_ss_fp4(ref(ga), ref(gw), ref(B.MxDense(P, B.MX_F32, 8, 64, 64)), None) == 3     # M differs
+    assert L.mx_gemm_ss_fp4(ref(ga), ref(gw), ref(B.MxDense(P + 4, B.MX_F32, 16, 64, 64)), None) == 4
+    assert L.mx_gemm_ss_fp4(ref(B.MxPacked(P, P, 16, 6)), ref(B.MxPacked(P, P, 64, 6)), ref(gc), None) == 5   # K = 192
+    assert L.mx_gemm_ss_fp4(ref(B.MxPacked(None, None, 0, 8)), ref(gw), ref(B.MxDense(None, B.MX_F32, 0, 64, 64)), None) == 0
     for code in range(8):
         assert mx.binding.status_str(code) not in ("", "unknown status")
     assert mx.binding.status_str(42) == "unknown status"
