@@ -202,10 +202,9 @@ __global__ __launch_bounds__(256) void gemm_ss_fp4_smallm_kernel(const uint8_t* 
 // so that the 16 lanes that read one slot of 16 consecutive rows hit 16 different bank groups.  Then, per column tile,
 // 16 rows of 32 slots (one row = the 512 bytes of a column's sliced chunk) with slot s of row r at slot s ^ (r & 15), for
 // the same reason; a row is still written as one contiguous (permuted) run.
-constexpr int kDecodeNT = 2;
 constexpr int kDecodeARow = 1024 + 16;          // A rows are padded by one slot: row r, slot s -> bank group (r + s) % 16
-constexpr int kDecodeTile = 16 * kDecodeARow;   // (>= the 16 KB of the two sliced W tiles)
-constexpr int kDecodeSmem = 4 * kDecodeTile + 3 * kDecodeNT * 4 * 64 * (int)sizeof(float);
+constexpr int kDecodeTile = 16 * kDecodeARow;   // (>= the 16 KB of two sliced W tiles)
+constexpr int decode_smem_bytes(int nt) { return 4 * kDecodeTile + 3 * nt * 4 * 64 * (int)sizeof(float); }
 
 // 16 E4M3 anchor codes (4 dwords) -> 16 E2M1 codes (2 dwords): the Slice-and-Scale element step on half a block
 __device__ __forceinline__ void slice_half_block_e2m1(const u32x4& in4, uint32_t (&out)[2]) {
@@ -260,12 +259,13 @@ __device__ __forceinline__ void wave_lds_order() {
 }
 
 
+// NT column tiles of 16 per workgroup: 2, or 1 when that is what it takes to give every compute unit a workgroup
+template <int NT>
 __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_decode_kernel(const uint8_t* __restrict__ a_codes,
                                                                  const uint8_t* __restrict__ a_scales,
                                                                  const uint8_t* __restrict__ w_codes,
                                                                  const uint8_t* __restrict__ w_scales, float* __restrict__ c,
                                                                  int M, int N, int K, int64_t ldc) {
-  constexpr int NT = kDecodeNT;
   static_assert(NT * 8 * 1024 <= kDecodeTile, "one 8 KB tile of sliced codes per column tile");
   extern __shared__ __attribute__((aligned(16))) uint8_t decode_smem[];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -908,21 +908,26 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   MX_GEMM_STAMP(3)
 }
 
+// compute units of the current device (asked once per device); 0 on failure
+static int device_compute_units() {
+  static int cu_count[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+  if (cu_count[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 0;
+    cu_count[dev] = n;
+  }
+  return cu_count[dev];
+}
+
 mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                                const uint8_t* w_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
                                hipStream_t stream) {
   if (M > kSmallmMaxM) {
     if (kGemmBM * K > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;   // the kernel addresses a tile of A with 32-bit offsets
-    // compute units of the current device (asked once per device)
-    static int cu_count[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MX_ERR_LAUNCH;
-    if (cu_count[dev] == 0) {
-      int n = 0;
-      if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return MX_ERR_LAUNCH;
-      cu_count[dev] = n;
-    }
-    const int cus = cu_count[dev];
+    const int cus = device_compute_units();
+    if (cus <= 0) return MX_ERR_LAUNCH;
     // Tile width: one workgroup fills a CU, so the tiles run in rounds of `cus`; the narrower tiles trade work per
     // tile for a last round that is less empty, or for more workgroups when M is small.  A tile costs a fixed part (its
     // A tile and the latencies of a K-step do not shrink with the width) plus a part per column: measured 19 us + 0.26 us
@@ -964,16 +969,24 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
     return launch_status("the fused GEMM");
   }
   if (M <= 16 && N * K <= 0xFFFFFFFFll) {   // (the decode kernel addresses W with 32-bit offsets)
-    static bool decode_attr_set = false;
-    if (!decode_attr_set) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ss_fp4_decode_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              kDecodeSmem) != hipSuccess)
-        return MX_ERR_LAUNCH;
-      decode_attr_set = true;
-    }
-    const unsigned grid_d = (unsigned)((N + 16 * kDecodeNT - 1) / (16 * kDecodeNT));
-    hipLaunchKernelGGL(gemm_ss_fp4_decode_kernel, dim3(grid_d), dim3(256), kDecodeSmem, stream, a_codes, a_scales, w_codes,
-                       w_scales, c, (int)M, (int)N, (int)K, ldc);
+    // 32 columns per workgroup; 16 when 32 would leave compute units without one (N = 4096, K = 14336: 27 us with 128
+    // workgroups of 32 columns)
+    const int cus = device_compute_units();
+    if (cus <= 0) return MX_ERR_LAUNCH;
+#define MX_GEMM_DECODE(NT)                                                                                                  \
+  {                                                                                                                         \
+    static bool attr_set = false;                                                                                           \
+    if (!attr_set) {                                                                                                        \
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ss_fp4_decode_kernel<NT>),                                 \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, decode_smem_bytes(NT)) != hipSuccess)            \
+        return MX_ERR_LAUNCH;                                                                                               \
+      attr_set = true;                                                                                                      \
+    }                                                                                                                       \
+    hipLaunchKernelGGL(gemm_ss_fp4_decode_kernel<NT>, dim3((unsigned)((N + 16 * NT - 1) / (16 * NT))), dim3(256),           \
+                       decode_smem_bytes(NT), stream, a_codes, a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc); \
+  }
+    if ((N + 31) / 32 >= cus) MX_GEMM_DECODE(2) else MX_GEMM_DECODE(1)
+#undef MX_GEMM_DECODE
     return launch_status("the fused GEMM");
   }
   const unsigned grid = (unsigned)((N + 16 * kSmallmNT - 1) / (16 * kSmallmNT));
