@@ -19,173 +19,7 @@ typedef int i32x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kDeltaE_E4M3_E2M1 = Elem<MX_FP8_E4M3>::emax - Elem<MX_FP4_E2M1>::emax;  // 6
 
-// 32 E4M3 anchor codes (8 dwords) -> 32 E2M1 codes (4 dwords): the Slice-and-Scale element step
-__device__ __forceinline__ void slice_block_e2m1(const u32x4& lo, const u32x4& hi, uint32_t (&out)[4]) {
-  const float two_de = __uint_as_float((uint32_t)(127 + kDeltaE_E4M3_E2M1) << 23);
-  const uint32_t in[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    uint32_t w = 0;
-    static_for<0, 2>([&](auto hh) {
-      constexpr int H = decltype(hh)::value;
-      uint32_t x = e4m3_nan_to_max(in[2 * j + H]);
-      f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8(x, false);
-      f32x2 b = __builtin_amdgcn_cvt_pk_f32_fp8(x, true);
-      w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, a.x, a.y, two_de, 2 * H);
-      w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, b.x, b.y, two_de, 2 * H + 1);
-    });
-    out[j] = w;
-  }
-}
-
-__device__ __forceinline__ uint32_t slice_scale(uint32_t byte) {
-  return byte == 255u ? 255u : (byte + kDeltaE_E4M3_E2M1 > 254u ? 254u : byte + kDeltaE_E4M3_E2M1);
-}
-
-// ------------------------------------------------------------------ small M (decode): no LDS tiling
-// One workgroup of 4 waves per 16 * NT output columns.  K is cut into chunks of 8 K-steps (a K-step is 128
-// elements = 4 blocks, one per lane group; a chunk is 1024 elements) dealt round-robin to the waves, so a wave
-// reads, per row, 1 KB of contiguous codes and the chunk's 32 scale bytes with two 128-bit loads.  Every wave
-// slices its own B fragments (Eq. (6)) and multiplies them with MT row tiles of A; the loads of 4 K-steps are in
-// flight together.  The four partial sums are added in a fixed order through LDS (deterministic).
-constexpr int kSmallmNT = 2;
-constexpr int kSmallmMaxM = 48;   // above it the LDS-tiled kernel is faster (measured, N = 14336, K = 4096: 30.7 against 31.3 us at M = 40, 36.1 against 31.9 us at M = 56)
-
-// scale byte of K-step p (0..7) of a chunk for lane group g, out of the chunk's 32 bytes
-__device__ __forceinline__ uint32_t chunk_scale(const u32x4& lo, const u32x4& hi, int p, int g) {
-  const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-  return (w[p] >> (8 * g)) & 0xFFu;
-}
-
-// the 32 scale bytes of chunk `chunk` of one row (KB bytes long); a ragged last chunk is read byte by byte
-__device__ __forceinline__ void load_chunk_scales(const uint8_t* row, int chunk, int KB, u32x4& lo, u32x4& hi) {
-  const int b0 = chunk * 32;
-  if (b0 + 32 <= KB) {
-    lo = *reinterpret_cast<const u32x4*>(row + b0);
-    hi = *reinterpret_cast<const u32x4*>(row + b0 + 16);
-  } else {
-    uint32_t w[8];
-#pragma unroll
-    for (int d = 0; d < 8; ++d) {
-      w[d] = 0x7F7F7F7Fu;
-      if (b0 + 4 * d + 4 <= KB) w[d] = *reinterpret_cast<const uint32_t*>(row + b0 + 4 * d);
-    }
-    lo = u32x4{w[0], w[1], w[2], w[3]};
-    hi = u32x4{w[4], w[5], w[6], w[7]};
-  }
-}
-
-template <int MT>
-__global__ __launch_bounds__(256) void gemm_ss_fp4_smallm_kernel(const uint8_t* __restrict__ a_codes,
-                                                                 const uint8_t* __restrict__ a_scales,
-                                                                 const uint8_t* __restrict__ w_codes,
-                                                                 const uint8_t* __restrict__ w_scales, float* __restrict__ c,
-                                                                 int M, int N, int K, int64_t ldc) {
-  constexpr int NT = kSmallmNT, PF = 4;
-  __shared__ float red[3][MT][NT][4][64];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int i = lane & 15, g = lane >> 4;
-  const int KB = K / 32, ksteps = K / 128, chunks = (ksteps + 7) / 8;
-  f32x4 acc[MT][NT];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  int ncol[NT];
-  bool n_ok[NT];
-  const uint8_t* wrow[NT];
-  const uint8_t* wsrow[NT];
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    ncol[nt] = (blockIdx.x * NT + nt) * 16 + i;
-    n_ok[nt] = ncol[nt] < N;
-    wrow[nt] = w_codes + (int64_t)(n_ok[nt] ? ncol[nt] : 0) * K;
-    wsrow[nt] = w_scales + (int64_t)(n_ok[nt] ? ncol[nt] : 0) * KB;
-  }
-  for (int chunk = wave; chunk < chunks; chunk += 4) {
-    u32x4 wslo[NT], wshi[NT], aslo[MT], ashi[MT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) load_chunk_scales(wsrow[nt], chunk, KB, wslo[nt], wshi[nt]);
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int m = mt * 16 + i;
-      aslo[mt] = ashi[mt] = u32x4{0x7F7F7F7Fu, 0x7F7F7F7Fu, 0x7F7F7F7Fu, 0x7F7F7F7Fu};
-      if (m < M) load_chunk_scales(a_scales + (int64_t)m * KB, chunk, KB, aslo[mt], ashi[mt]);
-    }
-#pragma unroll
-    for (int half = 0; half < 8 / PF; ++half) {
-      u32x4 wlo[PF][NT], whi[PF][NT], a0[PF][MT], a1[PF][MT];
-#pragma unroll
-      for (int p = 0; p < PF; ++p) {
-        const int ks = chunk * 8 + half * PF + p;
-        const bool live = ks < ksteps;
-        const int kb = (live ? ks : 0) * 4 + g;
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          const u32x4* wp = reinterpret_cast<const u32x4*>(wrow[nt] + (int64_t)kb * 32);
-          wlo[p][nt] = __builtin_nontemporal_load(wp);
-          whi[p][nt] = __builtin_nontemporal_load(wp + 1);
-        }
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          const int m = mt * 16 + i;
-          a0[p][mt] = a1[p][mt] = u32x4{0, 0, 0, 0};
-          if (m < M && live) {
-            const uint8_t* ap = a_codes + (int64_t)m * K + ks * 128 + 16 * g;
-            a0[p][mt] = *reinterpret_cast<const u32x4*>(ap);
-            a1[p][mt] = *reinterpret_cast<const u32x4*>(ap + 64);
-          }
-        }
-      }
-#pragma unroll
-      for (int p = 0; p < PF; ++p) {
-        const bool live = chunk * 8 + half * PF + p < ksteps;
-        i32x8 b[NT];
-        int bscale[NT];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          // B: anchor block (n, kb), sliced in registers (Eq. (6)); dead steps and columns multiply zeros
-          uint32_t b4[4];
-          slice_block_e2m1(wlo[p][nt], whi[p][nt], b4);
-          bscale[nt] = (int)slice_scale(chunk_scale(wslo[nt], wshi[nt], half * PF + p, g));
-          b[nt] = i32x8{(int)b4[0], (int)b4[1], (int)b4[2], (int)b4[3], 0, 0, 0, 0};
-          if (!n_ok[nt] || !live) { b[nt] = i32x8{0, 0, 0, 0, 0, 0, 0, 0}; bscale[nt] = 127; }
-        }
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          i32x8 a = {(int)a0[p][mt].x, (int)a0[p][mt].y, (int)a0[p][mt].z, (int)a0[p][mt].w,
-                     (int)a1[p][mt].x, (int)a1[p][mt].y, (int)a1[p][mt].z, (int)a1[p][mt].w};
-          int ascale = (int)chunk_scale(aslo[mt], ashi[mt], half * PF + p, g);
-#pragma unroll
-          for (int nt = 0; nt < NT; ++nt)
-            acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b[nt], acc[mt][nt], 0 /* A: E4M3 */,
-                                                                           4 /* B: E2M1 */, 0, ascale, 0, bscale[nt]);
-        }
-      }
-    }
-  }
-  if (wave > 0) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) red[wave - 1][mt][nt][j][lane] = acc[mt][nt][j];
-  }
-  __syncthreads();
-  if (wave == 0) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          float s = ((acc[mt][nt][j] + red[0][mt][nt][j][lane]) + red[1][mt][nt][j][lane]) + red[2][mt][nt][j][lane];
-          const int m = mt * 16 + 4 * g + j;
-          if (m < M && n_ok[nt]) c[(int64_t)m * ldc + ncol[nt]] = s;
-        }
-  }
-}
+constexpr int kMidmMaxM = 48;     // 16 < M <= 48: the streaming kernel with fragment loads for A (at M = 64 the tiled kernel is faster: 25 against 30 us)
 
 // ------------------------------------------------------------------ M <= 16 (decode): coalesced loads, transposed in LDS
 // With M <= 16 the kernel does little but stream W once.  Measured on the 58.7 MB anchor of the 4096 x 14336 layer: read
@@ -194,9 +28,9 @@ __global__ __launch_bounds__(256) void gemm_ss_fp4_smallm_kernel(const uint8_t* 
 // takes bytes 16 l .. 16 l + 15 of a row's 1 KB K-chunk, half a block -- and the way into the operand layout goes through
 // a wave-private LDS tile, the anchor sliced to E2M1 (Eq. (6)) on the way in, row by row in the order in which the rows
 // were requested, each as soon as it has arrived.  The A chunk takes the same way, unsliced and without passing through
-// registers (loads with LDS as their destination).  The split of K over
-// the four waves, the order of the MFMAs and the final sum are those of the kernel above: the results are the same bit
-// for bit.
+// registers (loads with LDS as their destination).  One workgroup of 4 waves per 16 NT output columns; K is cut into
+// chunks of 8 K-steps (a K-step is 128 elements = 4 blocks, one per lane group; a chunk is 1024 elements) dealt
+// round-robin to the waves, and the four partial sums are added in a fixed order through LDS (deterministic).
 //
 // LDS tile of a wave, used twice per chunk.  First the A chunk: 16 rows of 64 slots of 16 bytes, rows padded by one slot
 // so that the 16 lanes that read one slot of 16 consecutive rows hit 16 different bank groups.  Then, per column tile,
@@ -397,6 +231,177 @@ __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_decode_kernel(const uint8_
         const int m = 4 * g + j;
         if (m < M && ncol[nt] < N) c[(int64_t)m * ldc + ncol[nt]] = s;
       }
+  }
+}
+
+// ------------------------------------------------------------------ 16 < M <= 48: W as in the decode kernel, A as fragments
+// The same stream of W (coalesced 1 KB loads, sliced on arrival, a wave-private swizzled LDS tile on the way into the
+// operand layout) multiplied with MT row tiles of A.  MT chunks of A do not fit the LDS beside the W tiles, so A comes
+// as MFMA operand fragments straight from global memory (it is small and stays in L2; the lanes of such a load sit on 16
+// rows, which costs the memory pipe 4 x the time of a coalesced one -- affordable for A, not for W), in groups of
+// kGroup K-steps: the first group is requested ahead of W, the second half-way through the slicing, when half of W's
+// registers are free, the others (MT > 2) behind the MFMAs of the group whose registers they take.  K is split over
+// the four waves in chunks of 1024 as in the decode kernel, and the partial sums are added in the same order.
+template <int MT, int NT>
+__global__ __launch_bounds__(256, 2) void gemm_ss_fp4_midm_kernel(const uint8_t* __restrict__ a_codes,
+                                                               const uint8_t* __restrict__ a_scales,
+                                                               const uint8_t* __restrict__ w_codes,
+                                                               const uint8_t* __restrict__ w_scales, float* __restrict__ c,
+                                                               int M, int N, int K, int64_t ldc) {
+  constexpr int kGroups = MT <= 2 ? 2 : 4, kGroup = 8 / kGroups;   // (NT column tiles of 16 per workgroup, as in the decode kernel)
+  constexpr int kTile = NT * 8192;   // sliced codes of a chunk: 16 columns x 512 bytes per column tile
+  static_assert(3 * MT * NT * 4 * 64 * (int)sizeof(float) <= 4 * kTile, "the partial sums reuse the W tiles");
+  extern __shared__ __attribute__((aligned(16))) uint8_t midm_smem[];   // 4 x kTile
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int i = lane & 15, g = lane >> 4;
+  const int KB = K / 32, ksteps = K / 128, chunks = (ksteps + 7) / 8;
+  uint8_t* tile = midm_smem + wave * kTile;
+  f32x4 acc[MT][NT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int col0 = blockIdx.x * NT * 16;
+  int ncol[NT];   // columns past the edge are computed from column N - 1 and never stored
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) ncol[nt] = col0 + nt * 16 + i;
+  // fragment side of A: lane (i, g) <-> row 16 mt + i (rows past M read row M - 1; their products are not stored),
+  // bytes 16 g .. and 64 + 16 g .. of each K-step
+  const uint8_t* arow[MT];
+  uint32_t as_off[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int m = mt * 16 + i < M ? mt * 16 + i : M - 1;
+    arow[mt] = a_codes + (int64_t)m * K + 16 * g;
+    as_off[mt] = (uint32_t)m * (uint32_t)KB;
+  }
+  // (the host has checked that W is smaller than 4 GiB; reads past the end of a buffer return zero)
+  const __amdgpu_buffer_rsrc_t w_rsrc = make_buffer(w_codes, (uint32_t)N * (uint32_t)K);
+  const __amdgpu_buffer_rsrc_t as_rsrc = make_buffer(a_scales, (uint32_t)M * (uint32_t)KB);
+  const __amdgpu_buffer_rsrc_t ws_rsrc = make_buffer(w_scales, (uint32_t)N * (uint32_t)KB);
+  for (int chunk = wave; chunk < chunks; chunk += 4) {
+    const int steps = ksteps - chunk * 8 < 8 ? ksteps - chunk * 8 : 8;
+    const uint32_t lane_off = (lane >> 3) < steps ? 16u * (uint32_t)lane : 0u;   // (as in the decode kernel)
+    const uint32_t chunk_off = (uint32_t)chunk * 1024u;
+    // the fragments of A of K-steps kGroup q .. kGroup q + kGroup - 1 of the chunk (a K-step that does not exist: the
+    // chunk's last one again, which is not multiplied)
+    u32x4 a0[2][kGroup][MT], a1[2][kGroup][MT];
+    auto load_a_group = [&](auto qc) __attribute__((always_inline)) {
+      constexpr int Q = decltype(qc)::value;
+#pragma unroll
+      for (int pp = 0; pp < kGroup; ++pp) {
+        const int p = Q * kGroup + pp < steps ? Q * kGroup + pp : steps - 1;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const uint8_t* ap = arow[mt] + (int64_t)chunk * 1024 + p * 128;
+          a0[Q & 1][pp][mt] = *reinterpret_cast<const u32x4*>(ap);
+          a1[Q & 1][pp][mt] = *reinterpret_cast<const u32x4*>(ap + 64);
+        }
+      }
+    };
+    // scale bytes (32 per row / column and chunk; in a ragged last chunk they run into the next row or past the end of
+    // the array, where a buffer load returns zeros: bytes of K-steps that are not multiplied)
+    u32x4 aslo[MT], ashi[MT], wslo[NT], wshi[NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      aslo[mt] = buffer_load_x4<false>(as_rsrc, as_off[mt] + (uint32_t)chunk * 32u, 0u);
+      ashi[mt] = buffer_load_x4<false>(as_rsrc, as_off[mt] + (uint32_t)chunk * 32u + 16u, 0u);
+    }
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const uint32_t wo = (uint32_t)(ncol[nt] < N ? ncol[nt] : N - 1) * (uint32_t)KB + (uint32_t)chunk * 32u;
+      wslo[nt] = buffer_load_x4<false>(ws_rsrc, wo, 0u);
+      wshi[nt] = buffer_load_x4<false>(ws_rsrc, wo + 16u, 0u);
+    }
+    load_a_group(std::integral_constant<int, 0>{});
+    __builtin_amdgcn_sched_barrier(0);
+    u32x4 wraw[NT][16];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int n = col0 + nt * 16 + j < N ? col0 + nt * 16 + j : N - 1;
+        wraw[nt][j] = buffer_load_x4<true>(w_rsrc, lane_off, (uint32_t)n * (uint32_t)K + chunk_off);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+    uint32_t asc[MT][2], wsc[NT][2];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) pack_lane_scales(aslo[mt], ashi[mt], g, asc[mt]);
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      pack_lane_scales(wslo[nt], wshi[nt], g, wsc[nt]);
+      wsc[nt][0] = scale_add_x4(wsc[nt][0], kDeltaE_E4M3_E2M1);   // Eq. (6) scale step
+      wsc[nt][1] = scale_add_x4(wsc[nt][1], kDeltaE_E4M3_E2M1);
+    }
+    // W: lane l holds half l % 2 of block l / 2 of each column's chunk; sliced, it is 8 bytes of the column's row
+    static_for<0, NT>([&](auto ntc) {
+      constexpr int nt = decltype(ntc)::value;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        uint32_t half[2];
+        slice_half_block_e2m1(wraw[nt][j], half);   // Eq. (6) element step
+        *reinterpret_cast<u32x2*>(tile + nt * 8192 + j * 512 + 16 * ((lane >> 1) ^ j) + 8 * (lane & 1)) = u32x2{half[0], half[1]};
+      }
+      if constexpr (nt == 0) {
+        __builtin_amdgcn_sched_barrier(0);
+        load_a_group(std::integral_constant<int, 1>{});   // half of W's registers are free now
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    });
+    wave_lds_order();
+    static_for<0, kGroups>([&](auto qc) {
+      constexpr int Q = decltype(qc)::value;
+#pragma unroll
+      for (int pp = 0; pp < kGroup; ++pp) {
+        const int p = Q * kGroup + pp;
+        if (p < steps) {
+          i32x8 b[NT];
+          int bscale[NT];
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            u32x4 t = *reinterpret_cast<const u32x4*>(tile + nt * 8192 + i * 512 + 16 * ((4 * p + g) ^ i));   // block 4 p + g of column i
+            b[nt] = i32x8{(int)t.x, (int)t.y, (int)t.z, (int)t.w, 0, 0, 0, 0};
+            bscale[nt] = (int)(wsc[nt][p >> 2] >> (8 * (p & 3)));   // the instruction reads the low byte
+          }
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            const u32x4 lo = a0[Q & 1][pp][mt], hi = a1[Q & 1][pp][mt];
+            const i32x8 a = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+            const int ascale = (int)(asc[mt][p >> 2] >> (8 * (p & 3)));
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+              acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b[nt], acc[mt][nt], 0 /* A: E4M3 */,
+                                                                             4 /* B: E2M1 */, 0, ascale, 0, bscale[nt]);
+          }
+        }
+      }
+      // the group after next takes this group's registers
+      if constexpr (Q + 2 < kGroups) load_a_group(std::integral_constant<int, Q + 2>{});
+    });
+    wave_lds_order();   // the next chunk overwrites the tile
+  }
+  __syncthreads();   // every wave is done with its W tile: the partial sums go where the tiles were
+  float(*red)[MT][NT][4][64] = reinterpret_cast<float(*)[MT][NT][4][64]>(midm_smem);   // [3][MT][NT][4][64]
+  if (wave > 0) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) red[wave - 1][mt][nt][j][lane] = acc[mt][nt][j];
+  }
+  __syncthreads();
+  if (wave == 0) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float s = ((acc[mt][nt][j] + red[0][mt][nt][j][lane]) + red[1][mt][nt][j][lane]) + red[2][mt][nt][j][lane];
+          const int m = mt * 16 + 4 * g + j;
+          if (m < M && ncol[nt] < N) c[(int64_t)m * ldc + ncol[nt]] = s;
+        }
   }
 }
 
@@ -924,7 +929,29 @@ static int device_compute_units() {
 mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                                const uint8_t* w_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
                                hipStream_t stream) {
-  if (M > kSmallmMaxM) {
+  const bool w_fits_32_bits = N * K <= 0xFFFFFFFFll;   // (the streaming kernels address W with 32-bit offsets)
+  if (M > 16 && M <= kMidmMaxM && w_fits_32_bits) {
+    const int cus = device_compute_units();
+    if (cus <= 0) return MX_ERR_LAUNCH;
+    const int mt_mid = (int)((M + 15) / 16), nt_mid = (N + 31) / 32 >= cus ? 2 : 1;   // (16 columns per workgroup when 32 leave compute units idle)
+#define MX_GEMM_MIDM(MT, NT)                                                                                               \
+  if (mt_mid == MT && nt_mid == NT) {                                                                                      \
+    constexpr int kSmem = 4 * NT * 8192;                                                                                   \
+    static bool attr_set = false;                                                                                          \
+    if (!attr_set) {                                                                                                       \
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ss_fp4_midm_kernel<MT, NT>),                              \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) != hipSuccess)                            \
+        return MX_ERR_LAUNCH;                                                                                              \
+      attr_set = true;                                                                                                     \
+    }                                                                                                                      \
+    hipLaunchKernelGGL((gemm_ss_fp4_midm_kernel<MT, NT>), dim3((unsigned)((N + 16 * NT - 1) / (16 * NT))), dim3(256),      \
+                       kSmem, stream, a_codes, a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc);              \
+  }
+    MX_GEMM_MIDM(2, 2) MX_GEMM_MIDM(3, 2) MX_GEMM_MIDM(2, 1) MX_GEMM_MIDM(3, 1)
+#undef MX_GEMM_MIDM
+    return launch_status("the fused GEMM");
+  }
+  if (M > kMidmMaxM || !w_fits_32_bits) {   // (the tiled kernel takes any M; below 49 rows only when W has 4 GiB or more)
     if (kGemmBM * K > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;   // the kernel addresses a tile of A with 32-bit offsets
     const int cus = device_compute_units();
     if (cus <= 0) return MX_ERR_LAUNCH;
@@ -968,7 +995,7 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
 #undef MX_GEMM_TILED
     return launch_status("the fused GEMM");
   }
-  if (M <= 16 && N * K <= 0xFFFFFFFFll) {   // (the decode kernel addresses W with 32-bit offsets)
+  if (M <= 16 && w_fits_32_bits) {
     // 32 columns per workgroup; 16 when 32 would leave compute units without one (N = 4096, K = 14336: 27 us with 128
     // workgroups of 32 columns)
     const int cus = device_compute_units();
@@ -989,16 +1016,7 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
 #undef MX_GEMM_DECODE
     return launch_status("the fused GEMM");
   }
-  const unsigned grid = (unsigned)((N + 16 * kSmallmNT - 1) / (16 * kSmallmNT));
-  const int mt = (int)((M + 15) / 16);
-#define MX_GEMM_CASE(MT)                                                                                                  \
-  if (mt == MT) {                                                                                                         \
-    hipLaunchKernelGGL((gemm_ss_fp4_smallm_kernel<MT>), dim3(grid), dim3(256), 0, stream, a_codes, a_scales, w_codes,     \
-                       w_scales, c, (int)M, (int)N, (int)K, ldc);                                                         \
-  }
-  MX_GEMM_CASE(1) MX_GEMM_CASE(2) MX_GEMM_CASE(3)
-#undef MX_GEMM_CASE
-  return launch_status("the fused GEMM");
+  return MX_ERR_UNSUPPORTED;   // (not reached: every shape is taken above)
 }
 
 }  // namespace mx

@@ -67,10 +67,13 @@ def _check(mx, oracle, M, N, K, seed, w_axis0=True, random_bytes=False):
 
 
 @pytest.mark.parametrize("M,N,K", [(16, 256, 512), (1, 48, 128), (7, 104, 384), (33, 64, 1024), (64, 1000, 256),
-                                   (16, 64, 9344), (5, 40, 2176), (17, 96, 1152)])
+                                   (16, 64, 9344), (5, 40, 2176), (17, 96, 1152), (48, 208, 2048), (40, 136, 3072),
+                                   (64, 96, 8192), (32, 4096, 512), (32, 8192, 256), (64, 8200, 1152), (40, 8208, 1024)])
 def test_gemm_small_shapes(mx, oracle, M, N, K):
     # M <= 16 takes the decode kernel (K chunks of 1024 dealt to 4 waves: several chunks per wave, ragged last chunk,
-    # fewer than 16 rows, a ragged column tile), 16 < M <= 48 the kernel with fragment loads, M = 64 the tiled kernel
+    # fewer than 16 rows, a ragged column tile), 16 < M <= 48 the same stream of W against 2 or 3 row tiles of A read
+    # as fragments (groups of 4 or 2 K-steps; ragged last chunk and ragged last row tile); a workgroup takes 32 columns
+    # when that gives every compute unit one (N >= 8192 on 256 CUs), else 16; M = 64 takes the tiled kernel
     _check(mx, oracle, M, N, K, seed=M * 1000 + N)
     _check(mx, oracle, M, N, K, seed=M * 1000 + N + 1, w_axis0=False)
     _check(mx, oracle, M, N, K, seed=M * 1000 + N + 2, random_bytes="narrow")
