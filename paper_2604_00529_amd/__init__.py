@@ -15,14 +15,35 @@ __all__ = ["mx_quantize", "mx_slice_and_scale", "mx_slice_and_scale_batched", "m
            "packed_shape", "SsBatch"]
 
 
+_torch_module = None
+
+
 def _torch():
-    import torch
-    return torch
+    global _torch_module
+    if _torch_module is None:
+        import torch
+        _torch_module = torch
+    return _torch_module
 
 
 def _stream(t):
+    """The current HIP stream of t's device as a void pointer (the raw handle: building a torch Stream object for it
+    costs 2 us per call, a fifth of what a small call costs on the CPU)."""
     torch = _torch()
+    raw = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+    if raw is not None:
+        return ctypes.c_void_p(raw(t.device.index if t.device.index is not None else torch.cuda.current_device()))
     return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+_ELEM_BITS = {}
+
+
+def _elem_bits(elem):
+    b = _ELEM_BITS.get(elem)
+    if b is None:
+        b = _ELEM_BITS[elem] = binding.lib().mx_elem_bits(elem)
+    return b
 
 
 def _dense(t):
@@ -69,7 +90,7 @@ def mx_packed_bytes(fmt, rows, cols):
 def packed_shape(fmt, rows, cols):
     """(outer, nblocks, bytes_per_block) of a [rows, cols] tensor in format fmt."""
     outer, ext = (rows, cols) if fmt.axis == 1 else (cols, rows)
-    return outer, ext // fmt.block, fmt.block * binding.lib().mx_elem_bits(fmt.elem) // 8
+    return outer, ext // fmt.block, fmt.block * _elem_bits(fmt.elem) // 8
 
 
 def _alloc_packed(fmt, rows, cols, device):
@@ -83,9 +104,11 @@ def _alloc_packed(fmt, rows, cols, device):
 def mx_quantize(src, fmt, codes=None, scales=None):
     """Q_f (Eq. (1), (2)): dense [rows, cols] -> (codes[outer, nblocks, bytes], scales[outer, nblocks])."""
     rows, cols = src.shape
+    outer, nblocks, bb = packed_shape(fmt, rows, cols)
     if codes is None:
-        codes, scales = _alloc_packed(fmt, rows, cols, src.device)
-    outer, nblocks, _ = packed_shape(fmt, rows, cols)
+        torch = _torch()
+        codes = torch.empty((outer, nblocks, bb), dtype=torch.uint8, device=src.device)
+        scales = torch.empty((outer, nblocks), dtype=torch.uint8, device=src.device)
     d = _dense(src)
     p = _packed(codes, scales, outer, nblocks)
     binding.check(binding.lib().mx_quantize(ctypes.byref(fmt), ctypes.byref(d), ctypes.byref(p), _stream(src)), "mx_quantize")
@@ -96,7 +119,7 @@ def mx_slice_and_scale(codes, scales, fa, ft, out_codes=None, out_scales=None):
     """Q_{A->t} (Eq. (4), (6)) on a packed anchor; returns (codes, scales) of the target format."""
     torch = _torch()
     nb = scales.numel()
-    bb = ft.block * binding.lib().mx_elem_bits(ft.elem) // 8
+    bb = ft.block * _elem_bits(ft.elem) // 8
     if out_codes is None:
         out_codes = torch.empty(tuple(scales.shape) + (bb,), dtype=torch.uint8, device=codes.device)
         out_scales = torch.empty_like(scales)
@@ -174,8 +197,7 @@ class SsBatch:
         self._dev = anchors[0][0].device
 
     def run(self):
-        torch = _torch()
-        stream = ctypes.c_void_p(torch.cuda.current_stream(self._dev).cuda_stream)
+        stream = _stream(self.workspace)
         binding.check(binding.lib().mx_slice_and_scale_multi_batched(
             ctypes.byref(self.fa), self.nt, self._F, self.n, self._A, self._T,
             ctypes.c_void_p(self.workspace.data_ptr()), self.workspace.numel(), stream), "mx_slice_and_scale_multi_batched")
