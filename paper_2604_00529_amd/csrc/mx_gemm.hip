@@ -929,7 +929,8 @@ static int device_compute_units() {
 mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                                const uint8_t* w_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
                                hipStream_t stream) {
-  const bool w_fits_32_bits = N * K <= 0xFFFFFFFFll;   // (the streaming kernels address W with 32-bit offsets)
+  // (the streaming kernels address W, and the decode kernel its up to 16 rows of A, with 32-bit offsets)
+  const bool w_fits_32_bits = N * K <= 0xFFFFFFFFll && 16 * K <= 0xFFFFFFFFll;
   if (M > 16 && M <= kMidmMaxM && w_fits_32_bits) {
     const int cus = device_compute_units();
     if (cus <= 0) return MX_ERR_LAUNCH;
