@@ -25,6 +25,9 @@ def test_graph_replays_match_eager_and_oracle(mx, oracle):
     fq = [torch.empty_like(d) for d in dense]
     # the fused GEMM too (its tiled kernel: M > 48): activations = tensor 2 (128 x 2048), weight = its first 48 rows
     c_out = torch.empty((128, 48), dtype=torch.float32, device="cuda")
+    # and its streaming kernels: 33 x 512 activations (tensor 1) against 32 of its rows, 16 rows of tensor 0 against 64
+    c_mid = torch.empty((33, 32), dtype=torch.float32, device="cuda")
+    c_dec = torch.empty((16, 64), dtype=torch.float32, device="cuda")
     batch4 = mx.SsBatch(anchors, fa, ft, t4, ws)
     batch46 = mx.SsBatch(anchors, fa, [f6, ft], [[t6[i], t4[i]] for i in range(len(anchors))], ws)
 
@@ -36,6 +39,8 @@ def test_graph_replays_match_eager_and_oracle(mx, oracle):
         for d, o in zip(dense, fq):
             mx.mx_fake_quant(d, ft, fa, o)                                 # Eq. (7)
         mx.mx_gemm_ss_fp4(anchors[2][0], anchors[2][1], anchors[2][0][:48], anchors[2][1][:48], c_out)
+        mx.mx_gemm_ss_fp4(anchors[1][0], anchors[1][1], anchors[1][0][:32], anchors[1][1][:32], c_mid)
+        mx.mx_gemm_ss_fp4(anchors[0][0][:16], anchors[0][1][:16], anchors[0][0], anchors[0][1], c_dec)
 
     work()                                                                 # eager once (also sets kernel attributes)
     torch.cuda.synchronize()
@@ -52,9 +57,12 @@ def test_graph_replays_match_eager_and_oracle(mx, oracle):
             t[0].fill_(0xA5)
             t[1].fill_(0xA5)
         c_out.zero_()
+        c_mid.zero_()
+        c_dec.zero_()
         g.replay()
         torch.cuda.synchronize()
-        got = [(to_host(a), to_host(b)) for a, b in t4], [(to_host(a), to_host(b)) for a, b in t6], [to_host(o) for o in fq], to_host(c_out)
+        got = ([(to_host(a), to_host(b)) for a, b in t4], [(to_host(a), to_host(b)) for a, b in t6], [to_host(o) for o in fq], to_host(c_out),
+               to_host(c_mid), to_host(c_dec))
         for i, h in enumerate(host):
             wc, wsc = oracle.quantize(h, "e4m3")
             assert np.array_equal(to_host(anchors[i][0]), wc) and np.array_equal(to_host(anchors[i][1]), wsc), (rep, i)
@@ -67,5 +75,8 @@ def test_graph_replays_match_eager_and_oracle(mx, oracle):
         work()
         torch.cuda.synchronize()
         assert np.array_equal(to_host(c_out).view(np.uint32), got[3].view(np.uint32)), rep
+        assert np.array_equal(to_host(c_mid).view(np.uint32), got[4].view(np.uint32)), rep
+        assert np.array_equal(to_host(c_dec).view(np.uint32), got[5].view(np.uint32)), rep
+        assert np.abs(got[4]).max() > 0 and np.abs(got[5]).max() > 0
         for i in range(len(anchors)):
             assert np.array_equal(to_host(t4[i][0]), got[0][i][0]) and np.array_equal(to_host(t6[i][0]), got[1][i][0])
