@@ -228,11 +228,18 @@ def mx_dequant(codes, scales, fmt, rows, cols, dtype=None, out=None):
     return out
 
 
-def mx_gemm_ss_fp4(a_codes, a_scales, w_codes, w_scales, out=None):
-    """C[M, N] = DQ(A) @ DQ(SS(W_anchor -> E2M1)).T with the anchor sliced in registers (scaled MX MFMA, fp32 out).
+GEMM_HOIST_MIN_ROWS = 512   # MX_GEMM_HOIST_MIN_ROWS of mx.h
 
-    a_*: MXFP8 E4M3 activations [M, K/32, 32] / [M, K/32]; w_*: E4M3 anchor, K-contiguous [N, K/32, 32] / [N, K/32]."""
+
+def mx_gemm_ss_fp4(a_codes, a_scales, w_codes, w_scales, out=None, workspace=None):
+    """C[M, N] = DQ(A) @ DQ(SS(W_anchor -> E2M1)).T (scaled MX MFMA, fp32 out).
+
+    a_*: MXFP8 E4M3 activations [M, K/32, 32] / [M, K/32]; w_*: E4M3 anchor, K-contiguous [N, K/32, 32] / [N, K/32].
+    With fewer than 512 rows the anchor is sliced in registers on its way into the product.  From 512 rows on it is
+    sliced once per call into `workspace` (uint8, mx_gemm_ss_fp4_workspace(N, K) bytes; allocated here when not given;
+    workspace=False keeps the on-the-fly kernel) and multiplied from there; the results are the same bit for bit."""
     torch = _torch()
+    L = binding.lib()
     M, KB = a_scales.shape
     N = w_scales.shape[0]
     if out is None:
@@ -240,8 +247,14 @@ def mx_gemm_ss_fp4(a_codes, a_scales, w_codes, w_scales, out=None):
     a = _packed(a_codes, a_scales, M, KB)
     w = _packed(w_codes, w_scales, N, w_scales.shape[1])
     c = _dense(out)
-    binding.check(binding.lib().mx_gemm_ss_fp4(ctypes.byref(a), ctypes.byref(w), ctypes.byref(c), _stream(a_codes)),
-                  "mx_gemm_ss_fp4")
+    if M >= GEMM_HOIST_MIN_ROWS and workspace is not False:
+        need = L.mx_gemm_ss_fp4_workspace(N, KB * 32)
+        if workspace is None:
+            workspace = torch.empty(max(16, need), dtype=torch.uint8, device=a_codes.device)
+        binding.check(L.mx_gemm_ss_fp4_ws(ctypes.byref(a), ctypes.byref(w), ctypes.byref(c), ctypes.c_void_p(workspace.data_ptr()),
+                                          workspace.numel(), _stream(a_codes)), "mx_gemm_ss_fp4_ws")
+        return out
+    binding.check(L.mx_gemm_ss_fp4(ctypes.byref(a), ctypes.byref(w), ctypes.byref(c), _stream(a_codes)), "mx_gemm_ss_fp4")
     return out
 
 

@@ -290,6 +290,35 @@ mx_status_t mx_gemm_ss_fp4(const mx_packed_t* a, const mx_packed_t* w_anchor, co
                                 static_cast<hipStream_t>(stream));
 }
 
+size_t mx_gemm_ss_fp4_workspace(int64_t n, int64_t k) {
+  if (n <= 0 || k <= 0 || k % 32 != 0) return 0;
+  return (size_t)n * (size_t)k / 2 + (size_t)n * (size_t)k / 32;   // E2M1 codes, then their scale bytes
+}
+
+mx_status_t mx_gemm_ss_fp4_ws(const mx_packed_t* a, const mx_packed_t* w_anchor, const mx_dense_t* c, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  mx_status_t st;
+  if ((st = check_packed(a)) != MX_OK) return st;
+  if ((st = check_packed(w_anchor)) != MX_OK) return st;
+  if ((st = check_dense(c)) != MX_OK) return st;
+  // few rows, too few tiles to fill the GPU, or no workspace: the kernels that slice on the fly
+  if (!workspace || c->rows < MX_GEMM_HOIST_MIN_ROWS || !mx::gemm_hoist_pays(c->rows, c->cols)) return mx_gemm_ss_fp4(a, w_anchor, c, stream);
+  if (c->dtype != MX_F32) return MX_ERR_UNSUPPORTED;
+  if (a->nblocks != w_anchor->nblocks || c->rows != a->outer || c->cols != w_anchor->outer) return MX_ERR_SHAPE;
+  if (c->cols == 0) return MX_OK;
+  const int64_t K = a->nblocks * 32, N = w_anchor->outer;
+  if (K == 0 || K % 128 != 0 || K > 0x7FFFFFFF || c->rows > 0x7FFFFFFF || N > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+  if (!aligned16(workspace)) return MX_ERR_ALIGN;
+  if (workspace_bytes < mx_gemm_ss_fp4_workspace(N, K)) return MX_ERR_WORKSPACE;
+  // W_t = Q_{A->t}(W_A) (Eq. (6)) once, by the Slice-and-Scale kernel, then the product
+  uint8_t* w4 = static_cast<uint8_t*>(workspace);
+  const mx_format_t fa = {MX_FP8_E4M3, MX_SCALE_E8M0, 32, 1, MX_ROUND_DEFAULT}, ft = {MX_FP4_E2M1, MX_SCALE_E8M0, 32, 1, MX_ROUND_DEFAULT};
+  const mx_packed_t wt = {w4, w4 + (size_t)N * (size_t)K / 2, N, K / 32};
+  if ((st = mx_slice_and_scale(&fa, w_anchor, &ft, &wt, stream)) != MX_OK) return st;
+  return mx::gemm_fp8_fp4_launch(static_cast<const uint8_t*>(a->codes), a->scales, w4, wt.scales, static_cast<float*>(c->data),
+                                 c->rows, N, K, c->ld, static_cast<hipStream_t>(stream));
+}
+
 const char* mx_status_str(mx_status_t status) {
   switch (status) {
     case MX_OK: return "ok";

@@ -913,6 +913,158 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   MX_GEMM_STAMP(3)
 }
 
+// ------------------------------------------------------------------ large M, W already sliced: 256 x 256 tiles, four waves
+// C = DQ(A) * DQ(W_t)^T with W_t = Q_{A->t}(W_A) taken from a workspace (MXFP4 E2M1 codes, K-contiguous, and their
+// scale bytes): for large M the conversion is hoisted out of the product -- in the fused kernel above every workgroup
+// slices every tile of W it touches, M / 256 times in all, and the slicing waves take half of the CU's registers.
+// Without them a workgroup is four waves of 512 registers, one per SIMD: a wave owns 128 x 128 outputs (64 MFMA tiles,
+// exactly its 256 accumulation registers), the workgroup 256 x 256, and a K-step brings 50 KB into the CU for 256
+// MFMAs where the fused kernel brings 46 KB for 112: the matrix pipe, not the CU's memory pipe, is the longer one.
+// Both operands and their scale bytes are requested straight into LDS (no registers, no LDS stores), two K-steps
+// ahead, 14 requests per wave and K-step spread between the MFMAs; LDS holds three K-steps; one barrier per K-step
+// (no fence: "all but the 14 youngest requests have landed").  A wave goes through its 8 x 8 MFMA tiles row by row:
+// the 8 B fragments of a K-step stay in registers, the A fragments pass through two register sets.  The sum over K
+// of every output runs in the order of the fused kernel: the results are the same bit for bit.
+struct BigStage {
+  uint8_t a[256 * 128];   // E4M3 codes, row r: 128 bytes of K, 16-byte chunk c at c ^ ((r >> 1) & 7)
+  uint8_t b[256 * 64];    // E2M1 codes, column n: 64 bytes, chunk c at c ^ ((n >> 2) & 3)
+  uint32_t as[256];       // 4 scale bytes per row (one per K-block of the step)
+  uint32_t bs[256];       // 4 scale bytes per column
+};
+constexpr int kBigRequests = 8 + 4 + 1 + 1;   // per wave and K-step: 8 KB of A, 4 KB of B, 64 scale dwords of each
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_fp8_fp4_tile256_kernel(
+    const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales, const uint8_t* __restrict__ w4_codes,
+    const uint8_t* __restrict__ w4_scales, float* __restrict__ c, int M, int N, int K, int64_t ldc, int m_tiles, int tiles) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t big_smem[];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int i = lane & 15, g = lane >> 4;
+  const int wm = wave & 1, wn = wave >> 1;   // the wave's quarter of the tile
+  const int KB = K / 32, K2 = K / 2, ksteps = K / 128;
+  // tile order as in the fused kernel: bands of 8 M tiles, and the workgroups of one XCD (blockIdx % 8) take neighbours
+  const int grid = (int)gridDim.x;
+  const int vb = grid % 8 != 0 ? (int)blockIdx.x : ((int)blockIdx.x % 8) * (grid / 8) + (int)blockIdx.x / 8;
+  const GemmTileShape shape = {m_tiles, tiles / m_tiles, grid};
+  int tm, tn;
+  gemm_tile_coords(vb, shape, tm, tn);
+  const int m0 = tm * 256, n0 = tn * 256;
+  const int rows = M - m0 < 256 ? M - m0 : 256, cols = N - n0 < 256 ? N - n0 : 256;   // the part of the tile inside C
+  // descriptors over the valid rows / columns of this tile: what lies past the edge is out of range and reads as zeros
+  const __amdgpu_buffer_rsrc_t a_rsrc = make_buffer(a_codes + (int64_t)m0 * K, (uint32_t)rows * (uint32_t)K);
+  const __amdgpu_buffer_rsrc_t b_rsrc = make_buffer(w4_codes + (int64_t)n0 * K2, (uint32_t)cols * (uint32_t)K2);
+  const __amdgpu_buffer_rsrc_t as_rsrc = make_buffer(a_scales + (int64_t)m0 * KB, (uint32_t)rows * (uint32_t)KB);
+  const __amdgpu_buffer_rsrc_t bs_rsrc = make_buffer(w4_scales + (int64_t)n0 * KB, (uint32_t)cols * (uint32_t)KB);
+  // lane parts of the offsets (the hardware puts lane l's bytes at 16 l, or 4 l, of the request's LDS block, so the lane
+  // fetches the chunk that the swizzle puts there); the whole offset goes into the lane register, which is what the
+  // range check looks at
+  const uint32_t a_lane = (uint32_t)(lane >> 3) * (uint32_t)K + 16u * (uint32_t)((lane & 7) ^ (lane >> 4));
+  const uint32_t b_lane = (uint32_t)(lane >> 2) * (uint32_t)K2 + 16u * (uint32_t)((lane & 3) ^ (lane >> 4));
+  const uint32_t s_lane = (uint32_t)(64 * wave + lane) * (uint32_t)KB;
+  auto request_one = [&](int kc, uint8_t* st, auto rc) __attribute__((always_inline)) {
+    constexpr int R = decltype(rc)::value;
+    if constexpr (R < 8) {
+      const int J = wave * 8 + R;   // rows 8 J + lane / 8; their swizzle term (row / 2) % 8 = lane / 16 + 4 (J % 2)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (__attribute__((address_space(3))) void*)(st + J * 1024), 16,
+                                               (int)((a_lane ^ (64u * (R & 1))) + (uint32_t)(8 * J) * (uint32_t)K + (uint32_t)(kc * 128)), 0, 0, 0);
+    } else if constexpr (R < 12) {
+      const int J = wave * 4 + (R - 8);   // columns 16 J + lane / 4; their swizzle term (column / 4) % 4 = lane / 16
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (__attribute__((address_space(3))) void*)(st + offsetof(BigStage, b) + J * 1024), 16,
+                                               (int)(b_lane + (uint32_t)(16 * J) * (uint32_t)K2 + (uint32_t)(kc * 64)), 0, 0, 0);
+    } else if constexpr (R == 12) {   // rows 64 wave + lane
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(as_rsrc, (__attribute__((address_space(3))) void*)(st + offsetof(BigStage, as) + wave * 256), 4,
+                                               (int)(s_lane + (uint32_t)(kc * 4)), 0, 0, 0);
+    } else {                          // columns 64 wave + lane
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(bs_rsrc, (__attribute__((address_space(3))) void*)(st + offsetof(BigStage, bs) + wave * 256), 4,
+                                               (int)(s_lane + (uint32_t)(kc * 4)), 0, 0, 0);
+    }
+  };
+  // (a K-step past the end of K: the last one again, which nothing uses)
+  auto request_step = [&](int ks, int stage_i) __attribute__((always_inline)) {
+    const int kc = ks < ksteps ? ks : ksteps - 1;
+    uint8_t* st = big_smem + stage_i * (int)sizeof(BigStage);
+    static_for<0, kBigRequests>([&](auto rc) { request_one(kc, st, rc); });
+  };
+  // my LDS reads have landed (the stage is free) and all requests but those of the youngest K-step too
+  auto arrive = [&] {
+    __builtin_amdgcn_s_waitcnt(wait_lgkmcnt0_vmcnt(kBigRequests));
+    producer_barrier();
+  };
+  f32x4 acc[8][8];
+#pragma unroll
+  for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // (the tile offsets 128 wm, 16 mt, 128 wn, 16 nt do not change the swizzle term of a lane)
+  const int a_off = (wm * 128 + i) * 128 + 16 * (g ^ ((i >> 1) & 7));   // + mt * 16 rows; second run of K: ^ 64
+  const int b_off = (wn * 128 + i) * 64 + 16 * (g ^ ((i >> 2) & 3));    // + nt * 16 columns
+  request_step(0, 0);
+  request_step(1, 1);
+  arrive();   // stage 0 is complete
+  int cur_i = 0;
+  for (int k = 0; k < ksteps; ++k) {
+    const int req_i = cur_i == 0 ? 2 : cur_i - 1;   // (k + 2) % 3: the stage that every wave left at the last barrier
+    const int kc = k + 2 < ksteps ? k + 2 : ksteps - 1;
+    uint8_t* rst = big_smem + req_i * (int)sizeof(BigStage);
+    const BigStage& st = *reinterpret_cast<const BigStage*>(big_smem + cur_i * (int)sizeof(BigStage));
+    i32x8 bf[8];   // only the low 4 dwords carry FP4 codes
+    uint32_t sb[8];
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt) bf[nt] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
+    auto read_b = [&](auto ntc) __attribute__((always_inline)) {
+      constexpr int NT = decltype(ntc)::value;
+      u32x4 t = *reinterpret_cast<const u32x4*>(&st.b[b_off + NT * 16 * 64]);
+      bf[NT][0] = (int)t.x; bf[NT][1] = (int)t.y; bf[NT][2] = (int)t.z; bf[NT][3] = (int)t.w;
+      sb[NT] = reinterpret_cast<const uint8_t*>(st.bs)[(wn * 128 + NT * 16 + i) * 4 + g];
+    };
+    i32x8 af[2];
+    uint32_t sa[2];
+    auto read_a = [&](auto mtc) __attribute__((always_inline)) {
+      constexpr int MT = decltype(mtc)::value;
+      u32x4 t0 = *reinterpret_cast<const u32x4*>(&st.a[a_off + MT * 16 * 128]);
+      u32x4 t1 = *reinterpret_cast<const u32x4*>(&st.a[(a_off ^ 64) + MT * 16 * 128]);
+      af[MT & 1] = i32x8{(int)t0.x, (int)t0.y, (int)t0.z, (int)t0.w, (int)t1.x, (int)t1.y, (int)t1.z, (int)t1.w};
+      sa[MT & 1] = reinterpret_cast<const uint8_t*>(st.as)[(wm * 128 + MT * 16 + i) * 4 + g];
+    };
+    read_a(std::integral_constant<int, 0>{});
+    read_b(std::integral_constant<int, 0>{});
+    read_b(std::integral_constant<int, 1>{});
+    read_b(std::integral_constant<int, 2>{});
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<0, 64>([&](auto xc) {
+      constexpr int X = decltype(xc)::value, MT = X / 8, NT = X % 8;
+      // W_t is the instruction's first operand: a lane's four results are four consecutive columns of one row of C
+      acc[MT][NT] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bf[NT], af[MT & 1], acc[MT][NT], 4 /* E2M1 */, 0 /* E4M3 */, 0,
+                                                                     (int)sb[NT], 0, (int)sa[MT & 1]);
+      asm volatile("" : "+a"(acc[MT][NT]));   // (keeps the result in its accumulation register and the MFMA in its place)
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (MT == 0 && NT + 3 < 8) read_b(std::integral_constant<int, NT + 3>{});   // B fragments run three MFMAs ahead in the first row
+      if constexpr (NT == 1 && MT + 1 < 8) read_a(std::integral_constant<int, MT + 1>{});   // the next row tile of A, into the other register set
+      if constexpr (X >= 10 && X < 10 + 2 * kBigRequests && (X - 10) % 2 == 0)               // one request behind every other MFMA
+        request_one(kc, rst, std::integral_constant<int, (X - 10) / 2>{});
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    arrive();   // K-step k + 1 is complete
+    cur_i = cur_i == 2 ? 0 : cur_i + 1;
+  }
+  __builtin_amdgcn_s_waitcnt(0);   // the last requests (of steps that do not exist) must land before the LDS is given back
+  // acc[mt][nt][j] = C[row 16 mt + i][column 16 nt + 4 g + j] of the wave's quarter
+  float* ct = c + (int64_t)(m0 + wm * 128 + i) * ldc + n0 + wn * 128 + 4 * g;
+  if (rows == 256 && cols == 256) {
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < 8; ++nt) *reinterpret_cast<f32x4*>(ct + (int64_t)(mt * 16) * ldc + nt * 16) = acc[mt][nt];
+  } else {
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < 8; ++nt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (wm * 128 + mt * 16 + i < rows && wn * 128 + nt * 16 + 4 * g + j < cols) ct[(int64_t)(mt * 16) * ldc + nt * 16 + j] = acc[mt][nt][j];
+  }
+}
+
 // compute units of the current device (asked once per device); 0 on failure
 static int device_compute_units() {
   static int cu_count[64] = {};
@@ -1018,6 +1170,34 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
     return launch_status("the fused GEMM");
   }
   return MX_ERR_UNSUPPORTED;   // (not reached: every shape is taken above)
+}
+
+// Is the product with W sliced beforehand the faster one?  Its 256 x 256 tiles must fill the GPU: measured on 256 CUs,
+// 192 tiles win (2048 x 6144 x 4096: 60 against 68 us), 128 and 112 tiles lose (2048 x 4096 x 4096: 56 against 48 us;
+// 512 x 14336 x 4096: 67 against 46 us).
+bool gemm_hoist_pays(int64_t M, int64_t N) {
+  const int cus = device_compute_units();
+  return cus > 0 && 4 * (((M + 255) / 256) * ((N + 255) / 256)) >= 3 * (int64_t)cus;
+}
+
+// The product with W already sliced (E2M1 codes [N][K / 2] and scale bytes [N][K / 32] in a workspace).
+mx_status_t gemm_fp8_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w4_codes,
+                                const uint8_t* w4_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
+                                hipStream_t stream) {
+  if (256 * K > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;   // a tile is addressed with 32-bit offsets
+  const int64_t m_tiles = (M + 255) / 256, tiles = m_tiles * ((N + 255) / 256);
+  if (tiles > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+  constexpr int kSmem = 3 * (int)sizeof(BigStage);
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_fp8_fp4_tile256_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            kSmem) != hipSuccess)
+      return MX_ERR_LAUNCH;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(gemm_fp8_fp4_tile256_kernel, dim3((unsigned)tiles), dim3(256), kSmem, stream, a_codes, a_scales, w4_codes,
+                     w4_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles, (int)tiles);
+  return launch_status("the MXFP8 x MXFP4 GEMM");
 }
 
 }  // namespace mx

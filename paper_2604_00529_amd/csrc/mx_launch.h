@@ -77,5 +77,9 @@ mx_status_t fake_quant_launch(int target, int anchor /* -1: none */, int axis, i
 mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                                const uint8_t* w_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
                                hipStream_t stream);
+bool gemm_hoist_pays(int64_t M, int64_t N);
+mx_status_t gemm_fp8_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w4_codes,
+                                const uint8_t* w4_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
+                                hipStream_t stream);
 
 }  // namespace mx

@@ -45,6 +45,12 @@ def _check(mx, oracle, M, N, K, seed, w_axis0=True, random_bytes=False):
             wc, wsc = mx.mx_quantize(_gpu_bf16(w), f8)
     c = mx.mx_gemm_ss_fp4(ac, asc, wc, wsc)
     torch.cuda.synchronize()
+    if M >= mx.GEMM_HOIST_MIN_ROWS:
+        # the call above sliced W once into a workspace and multiplied from there; the kernel that slices on the fly
+        # must give the same bits (every output's sum over K runs in the same order)
+        c_fly = mx.mx_gemm_ss_fp4(ac, asc, wc, wsc, workspace=False)
+        torch.cuda.synchronize()
+        assert torch.equal(c.view(torch.int32), c_fly.view(torch.int32))
     ref, ref_abs = oracle.gemm_ss_reference(ac.cpu().numpy(), asc.cpu().numpy(), wc.cpu().numpy(), wsc.cpu().numpy(),
                                             with_abs=True)
     got = c.cpu().numpy().astype(np.float64)
@@ -96,11 +102,13 @@ def test_gemm_tiled_shapes(mx, oracle, M, N, K):
     _check(mx, oracle, M, N, K, seed=M + N + 2, random_bytes="wide")
 
 
-@pytest.mark.parametrize("M,N,K", [(1000, 9000, 512), (600, 16384, 512), (2048, 8192, 512), (520, 12000, 1024)])
+@pytest.mark.parametrize("M,N,K", [(1000, 9000, 512), (600, 16384, 512), (2048, 8192, 512), (520, 12000, 1024),
+                                   (1000, 13000, 256), (2304, 5400, 384)])
 def test_gemm_several_tiles_per_workgroup(mx, oracle, M, N, K):
     # more tiles than compute units and K a multiple of 512: a workgroup works several tiles in one pipeline (tiles of
     # 80, 112 and 128 columns here; ragged last M and N tiles; a number of M tiles that does not divide the grid, so
-    # that a workgroup's walk over the tiles wraps around)
+    # that a workgroup's walk over the tiles wraps around).  Where C has 192 or more tiles of 256 x 256 (the second,
+    # third and the last two shapes) the default call slices W into a workspace first and _check compares both ways.
     _check(mx, oracle, M, N, K, seed=M + N + K)
     _check(mx, oracle, M, N, K, seed=M + N + K + 1, random_bytes="narrow")
 
@@ -110,7 +118,7 @@ def test_gemm_prefill_shape_config5(mx, oracle):
     _check(mx, oracle, 2048, 14336, 4096, seed=2005)
 
 
-@pytest.mark.parametrize("M,N,K", [(16, 104, 384), (200, 304, 256)])
+@pytest.mark.parametrize("M,N,K", [(16, 104, 384), (200, 304, 256), (600, 304, 256), (1024, 12400, 128)])
 def test_gemm_strided_output(mx, oracle, M, N, K):
     # C as a view of a wider matrix (ld > N): same values as the contiguous call, nothing written outside the view
     import torch
