@@ -132,3 +132,47 @@ def test_gemm_strided_output(mx, oracle, M, N, K):
     torch.cuda.synchronize()
     assert torch.equal(wide[:, :N], want)
     assert bool((wide[:, N:] == -7.0).all())
+
+
+def test_gemm_workspace_entry_point(mx, oracle):
+    # mx_gemm_ss_fp4_ws through the C ABI: size function, a workspace that is too small, a misaligned one, and a shape
+    # with too few tiles for the hoisted conversion (served by the on-the-fly kernels, workspace untouched)
+    import ctypes
+    import torch
+    B, L = mx.binding, mx.binding.lib()
+    assert L.mx_gemm_ss_fp4_workspace(64, 256) == 64 * 256 // 2 + 64 * 256 // 32
+    assert L.mx_gemm_ss_fp4_workspace(0, 256) == 0 and L.mx_gemm_ss_fp4_workspace(64, 48) == 0
+    M, N, K = 768, 16384, 128                                     # 3 x 64 tiles of 256 x 256: hoisted on 256 CUs
+    rng = np.random.default_rng(5)
+    f8 = mx.make_format("e4m3")
+    ac, asc = mx.mx_quantize(_gpu_bf16(rng.standard_normal((M, K)).astype(np.float32)), f8)
+    wc, wsc = mx.mx_quantize(_gpu_bf16((rng.standard_normal((N, K)) * 0.02).astype(np.float32)), f8)
+    out = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    a, w, c = mx._packed(ac, asc, M, K // 32), mx._packed(wc, wsc, N, K // 32), mx._dense(out)
+    need = L.mx_gemm_ss_fp4_workspace(N, K)
+    ws = torch.full((need + 64,), 0x5A, dtype=torch.uint8, device="cuda")
+    ref = ctypes.byref
+    assert L.mx_gemm_ss_fp4_ws(ref(a), ref(w), ref(c), ctypes.c_void_p(ws.data_ptr()), need - 1, None) == 7
+    assert L.mx_gemm_ss_fp4_ws(ref(a), ref(w), ref(c), ctypes.c_void_p(ws.data_ptr() + 4), need, None) == 4
+    assert L.mx_gemm_ss_fp4_ws(ref(a), None, ref(c), ctypes.c_void_p(ws.data_ptr()), need, None) == 1
+    assert L.mx_gemm_ss_fp4_ws(ref(a), ref(w), ref(c), ctypes.c_void_p(ws.data_ptr()), need, None) == 0
+    torch.cuda.synchronize()
+    assert bool((ws[need:] == 0x5A).all())                        # nothing written past the stated size
+    want = mx.mx_gemm_ss_fp4(ac, asc, wc, wsc, workspace=False)
+    assert torch.equal(out.view(torch.int32), want.view(torch.int32))
+    # the workspace holds W_t: the Slice-and-Scale of the anchor (Eq. (6)), codes then scale bytes
+    tc, ts = oracle.slice_and_scale(wc.cpu().numpy(), wsc.cpu().numpy(), "e4m3", "e2m1")
+    got = ws.cpu().numpy()
+    assert np.array_equal(got[:N * K // 2], tc.reshape(-1)) and np.array_equal(got[N * K // 2:need], ts.reshape(-1))
+    # NULL workspace, or few tiles: the on-the-fly kernels; a small workspace is then no error
+    out.zero_()
+    assert L.mx_gemm_ss_fp4_ws(ref(a), ref(w), ref(c), None, 0, None) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int32), want.view(torch.int32))
+    a2, w2 = mx._packed(ac[:512], asc[:512], 512, K // 32), mx._packed(wc[:256], wsc[:256], 256, K // 32)
+    out2 = torch.empty((512, 256), dtype=torch.float32, device="cuda")
+    ws.fill_(0x5A)
+    assert L.mx_gemm_ss_fp4_ws(ref(a2), ref(w2), ref(mx._dense(out2)), ctypes.c_void_p(ws.data_ptr()), 16, None) == 0
+    torch.cuda.synchronize()
+    assert bool((ws == 0x5A).all())
+    assert torch.equal(out2.view(torch.int32), want[:512, :256].contiguous().view(torch.int32))
