@@ -933,6 +933,9 @@ struct BigStage {
 };
 constexpr int kBigRequests = 8 + 4 + 1 + 1;   // per wave and K-step: 8 KB of A, 4 KB of B, 64 scale dwords of each
 
+// NTW column tiles of 16 per wave: the workgroup tile is 256 x 32 NTW (256 or 224 columns; the launcher takes the width
+// whose tiles fill the GPU's rounds better)
+template <int NTW>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_fp8_fp4_tile256_kernel(
     const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales, const uint8_t* __restrict__ w4_codes,
     const uint8_t* __restrict__ w4_scales, float* __restrict__ c, int M, int N, int K, int64_t ldc, int m_tiles, int tiles) {
@@ -947,8 +950,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const GemmTileShape shape = {m_tiles, tiles / m_tiles, grid};
   int tm, tn;
   gemm_tile_coords(vb, shape, tm, tn);
-  const int m0 = tm * 256, n0 = tn * 256;
-  const int rows = M - m0 < 256 ? M - m0 : 256, cols = N - n0 < 256 ? N - n0 : 256;   // the part of the tile inside C
+  constexpr int BN = 32 * NTW;   // columns of the workgroup tile
+  const int m0 = tm * 256, n0 = tn * BN;
+  const int rows = M - m0 < 256 ? M - m0 : 256, cols = N - n0 < BN ? N - n0 : BN;   // the part of the tile inside C
   // descriptors over the valid rows / columns of this tile: what lies past the edge is out of range and reads as zeros
   const __amdgpu_buffer_rsrc_t a_rsrc = make_buffer(a_codes + (int64_t)m0 * K, (uint32_t)rows * (uint32_t)K);
   const __amdgpu_buffer_rsrc_t b_rsrc = make_buffer(w4_codes + (int64_t)n0 * K2, (uint32_t)cols * (uint32_t)K2);
@@ -967,7 +971,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (__attribute__((address_space(3))) void*)(st + J * 1024), 16,
                                                (int)((a_lane ^ (64u * (R & 1))) + (uint32_t)(8 * J) * (uint32_t)K + (uint32_t)(kc * 128)), 0, 0, 0);
     } else if constexpr (R < 12) {
-      const int J = wave * 4 + (R - 8);   // columns 16 J + lane / 4; their swizzle term (column / 4) % 4 = lane / 16
+      const int J = wave * 4 + (R - 8);   // columns 16 J + lane / 4 (past the tile's width: out of range, zeros); their swizzle term (column / 4) % 4 = lane / 16
       __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (__attribute__((address_space(3))) void*)(st + offsetof(BigStage, b) + J * 1024), 16,
                                                (int)(b_lane + (uint32_t)(16 * J) * (uint32_t)K2 + (uint32_t)(kc * 64)), 0, 0, 0);
     } else if constexpr (R == 12) {   // rows 64 wave + lane
@@ -989,14 +993,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     __builtin_amdgcn_s_waitcnt(wait_lgkmcnt0_vmcnt(kBigRequests));
     producer_barrier();
   };
-  f32x4 acc[8][8];
+  f32x4 acc[8][NTW];
 #pragma unroll
   for (int mt = 0; mt < 8; ++mt)
 #pragma unroll
-    for (int nt = 0; nt < 8; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  // (the tile offsets 128 wm, 16 mt, 128 wn, 16 nt do not change the swizzle term of a lane)
+    for (int nt = 0; nt < NTW; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // (the tile offsets 128 wm, 16 mt, 16 NTW wn, 16 nt do not change the swizzle term of a lane: 16 NTW / 4 is a multiple of 4)
+  static_assert((16 * NTW / 4) % 4 == 0, "swizzle term of the second column half");
   const int a_off = (wm * 128 + i) * 128 + 16 * (g ^ ((i >> 1) & 7));   // + mt * 16 rows; second run of K: ^ 64
-  const int b_off = (wn * 128 + i) * 64 + 16 * (g ^ ((i >> 2) & 3));    // + nt * 16 columns
+  const int b_off = (wn * 16 * NTW + i) * 64 + 16 * (g ^ ((i >> 2) & 3));    // + nt * 16 columns
   request_step(0, 0);
   request_step(1, 1);
   arrive();   // stage 0 is complete
@@ -1006,15 +1011,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int kc = k + 2 < ksteps ? k + 2 : ksteps - 1;
     uint8_t* rst = big_smem + req_i * (int)sizeof(BigStage);
     const BigStage& st = *reinterpret_cast<const BigStage*>(big_smem + cur_i * (int)sizeof(BigStage));
-    i32x8 bf[8];   // only the low 4 dwords carry FP4 codes
-    uint32_t sb[8];
+    i32x8 bf[NTW];   // only the low 4 dwords carry FP4 codes
+    uint32_t sb[NTW];
 #pragma unroll
-    for (int nt = 0; nt < 8; ++nt) bf[nt] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
+    for (int nt = 0; nt < NTW; ++nt) bf[nt] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
     auto read_b = [&](auto ntc) __attribute__((always_inline)) {
       constexpr int NT = decltype(ntc)::value;
       u32x4 t = *reinterpret_cast<const u32x4*>(&st.b[b_off + NT * 16 * 64]);
       bf[NT][0] = (int)t.x; bf[NT][1] = (int)t.y; bf[NT][2] = (int)t.z; bf[NT][3] = (int)t.w;
-      sb[NT] = reinterpret_cast<const uint8_t*>(st.bs)[(wn * 128 + NT * 16 + i) * 4 + g];
+      sb[NT] = reinterpret_cast<const uint8_t*>(st.bs)[(wn * 16 * NTW + NT * 16 + i) * 4 + g];
     };
     i32x8 af[2];
     uint32_t sa[2];
@@ -1030,14 +1035,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     read_b(std::integral_constant<int, 1>{});
     read_b(std::integral_constant<int, 2>{});
     __builtin_amdgcn_sched_barrier(0);
-    static_for<0, 64>([&](auto xc) {
-      constexpr int X = decltype(xc)::value, MT = X / 8, NT = X % 8;
+    static_for<0, 8 * NTW>([&](auto xc) {
+      constexpr int X = decltype(xc)::value, MT = X / NTW, NT = X % NTW;
       // W_t is the instruction's first operand: a lane's four results are four consecutive columns of one row of C
       acc[MT][NT] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bf[NT], af[MT & 1], acc[MT][NT], 4 /* E2M1 */, 0 /* E4M3 */, 0,
                                                                      (int)sb[NT], 0, (int)sa[MT & 1]);
       asm volatile("" : "+a"(acc[MT][NT]));   // (keeps the result in its accumulation register and the MFMA in its place)
       __builtin_amdgcn_sched_barrier(0);
-      if constexpr (MT == 0 && NT + 3 < 8) read_b(std::integral_constant<int, NT + 3>{});   // B fragments run three MFMAs ahead in the first row
+      if constexpr (MT == 0 && NT + 3 < NTW) read_b(std::integral_constant<int, NT + 3>{});   // B fragments run three MFMAs ahead in the first row
       if constexpr (NT == 1 && MT + 1 < 8) read_a(std::integral_constant<int, MT + 1>{});   // the next row tile of A, into the other register set
       if constexpr (X >= 10 && X < 10 + 2 * kBigRequests && (X - 10) % 2 == 0)               // one request behind every other MFMA
         request_one(kc, rst, std::integral_constant<int, (X - 10) / 2>{});
@@ -1048,20 +1053,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   }
   __builtin_amdgcn_s_waitcnt(0);   // the last requests (of steps that do not exist) must land before the LDS is given back
   // acc[mt][nt][j] = C[row 16 mt + i][column 16 nt + 4 g + j] of the wave's quarter
-  float* ct = c + (int64_t)(m0 + wm * 128 + i) * ldc + n0 + wn * 128 + 4 * g;
-  if (rows == 256 && cols == 256) {
+  float* ct = c + (int64_t)(m0 + wm * 128 + i) * ldc + n0 + wn * 16 * NTW + 4 * g;
+  if (rows == 256 && cols == BN) {
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt)
 #pragma unroll
-      for (int nt = 0; nt < 8; ++nt) *reinterpret_cast<f32x4*>(ct + (int64_t)(mt * 16) * ldc + nt * 16) = acc[mt][nt];
+      for (int nt = 0; nt < NTW; ++nt) *reinterpret_cast<f32x4*>(ct + (int64_t)(mt * 16) * ldc + nt * 16) = acc[mt][nt];
   } else {
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt)
 #pragma unroll
-      for (int nt = 0; nt < 8; ++nt)
+      for (int nt = 0; nt < NTW; ++nt)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-          if (wm * 128 + mt * 16 + i < rows && wn * 128 + nt * 16 + 4 * g + j < cols) ct[(int64_t)(mt * 16) * ldc + nt * 16 + j] = acc[mt][nt][j];
+          if (wm * 128 + mt * 16 + i < rows && wn * 16 * NTW + nt * 16 + 4 * g + j < cols) ct[(int64_t)(mt * 16) * ldc + nt * 16 + j] = acc[mt][nt][j];
   }
 }
 
@@ -1185,18 +1190,30 @@ mx_status_t gemm_fp8_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales,
                                 const uint8_t* w4_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
                                 hipStream_t stream) {
   if (256 * K > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;   // a tile is addressed with 32-bit offsets
-  const int64_t m_tiles = (M + 255) / 256, tiles = m_tiles * ((N + 255) / 256);
+  const int cus = device_compute_units();
+  if (cus <= 0) return MX_ERR_LAUNCH;
+  // tile width 256 or 224: rounds on the GPU x width (2048 x 14336: 448 tiles of 256 columns are 1.75 rounds that take 2,
+  // 512 tiles of 224 columns two full rounds of 7/8 the work)
+  const int64_t m_tiles = (M + 255) / 256;
+  const int64_t t8 = m_tiles * ((N + 255) / 256), t7 = m_tiles * ((N + 223) / 224);
+  const bool narrow = (t7 + cus - 1) / cus * 7 < (t8 + cus - 1) / cus * 8;
+  const int64_t tiles = narrow ? t7 : t8;
   if (tiles > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
   constexpr int kSmem = 3 * (int)sizeof(BigStage);
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_fp8_fp4_tile256_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            kSmem) != hipSuccess)
-      return MX_ERR_LAUNCH;
-    attr_set = true;
+#define MX_GEMM_TILE256(NTW)                                                                                                \
+  {                                                                                                                         \
+    static bool attr_set = false;                                                                                           \
+    if (!attr_set) {                                                                                                        \
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_fp8_fp4_tile256_kernel<NTW>),                              \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) != hipSuccess)                             \
+        return MX_ERR_LAUNCH;                                                                                               \
+      attr_set = true;                                                                                                      \
+    }                                                                                                                       \
+    hipLaunchKernelGGL(gemm_fp8_fp4_tile256_kernel<NTW>, dim3((unsigned)tiles), dim3(256), kSmem, stream, a_codes, a_scales, \
+                       w4_codes, w4_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles, (int)tiles);                      \
   }
-  hipLaunchKernelGGL(gemm_fp8_fp4_tile256_kernel, dim3((unsigned)tiles), dim3(256), kSmem, stream, a_codes, a_scales, w4_codes,
-                     w4_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles, (int)tiles);
+  if (narrow) MX_GEMM_TILE256(7) else MX_GEMM_TILE256(8)
+#undef MX_GEMM_TILE256
   return launch_status("the MXFP8 x MXFP4 GEMM");
 }
 
