@@ -913,7 +913,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   MX_GEMM_STAMP(3)
 }
 
-// ------------------------------------------------------------------ large M, W already sliced: 256 x 256 tiles, four waves
+// ------------------------------------------------------------------ large M, W already sliced: 256 x 256 (or 224) tiles, four waves
 // C = DQ(A) * DQ(W_t)^T with W_t = Q_{A->t}(W_A) taken from a workspace (MXFP4 E2M1 codes, K-contiguous, and their
 // scale bytes): for large M the conversion is hoisted out of the product -- in the fused kernel above every workgroup
 // slices every tile of W it touches, M / 256 times in all, and the slicing waves take half of the CU's registers.
@@ -924,7 +924,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
 // ahead, 14 requests per wave and K-step spread between the MFMAs; LDS holds three K-steps; one barrier per K-step
 // (no fence: "all but the 14 youngest requests have landed").  A wave goes through its 8 x 8 MFMA tiles row by row:
 // the 8 B fragments of a K-step stay in registers, the A fragments pass through two register sets.  The sum over K
-// of every output runs in the order of the fused kernel: the results are the same bit for bit.
+// of every output runs in the order of the fused kernel: the results are the same bit for bit.  NTW = 7 makes the
+// tile 224 columns wide (a wave owns 128 x 112); the launcher takes it when the grid's rounds then hold fewer MFMAs.
 struct BigStage {
   uint8_t a[256 * 128];   // E4M3 codes, row r: 128 bytes of K, 16-byte chunk c at c ^ ((r >> 1) & 7)
   uint8_t b[256 * 64];    // E2M1 codes, column n: 64 bytes, chunk c at c ^ ((n >> 2) & 3)
