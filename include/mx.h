@@ -164,14 +164,22 @@ mx_status_t mx_dequant(const mx_format_t* f, const mx_packed_t* src, const mx_de
  * fp32 sum over K in a fixed order (results are reproducible run to run). */
 mx_status_t mx_gemm_ss_fp4(const mx_packed_t* a, const mx_packed_t* w_anchor, const mx_dense_t* c, void* stream);
 
-/* The same product for callers that can lend a workspace.  From MX_GEMM_HOIST_MIN_ROWS rows of A on, and when C has
- * enough tiles of 256 x 256 to fill the GPU, W_t (Eq. (6)) is generated once per call into the workspace -- MXFP4 codes and scale bytes, mx_gemm_ss_fp4_workspace(N, K) =
- * N K / 2 + N K / 32 bytes, device memory, 16-byte aligned, borrowed for the duration of the enqueued work -- and
- * multiplied from there by a kernel that has the whole compute unit for the product (the on-the-fly kernels slice
- * every tile of W once per 256 rows of A).  Otherwise, or with workspace == NULL, this is mx_gemm_ss_fp4.  The
- * results of the two entry points are identical bit for bit.  MX_ERR_WORKSPACE when the workspace is too small. */
+/* The same product for callers that can lend a workspace of mx_gemm_ss_fp4_workspace(N, K) = N K / 2 + N K / 32 bytes
+ * (device memory, 16-byte aligned, borrowed for the duration of the enqueued work; MX_ERR_ALIGN / MX_ERR_WORKSPACE when
+ * it is misaligned or smaller).  Two things are done with it.
+ *   From MX_GEMM_HOIST_MIN_ROWS rows of A on, and when C has enough tiles of 256 x 256 to fill the GPU, W_t (Eq. (6))
+ *   is generated once per call into the workspace -- MXFP4 codes and scale bytes -- and multiplied from there by a
+ *   kernel that has the whole compute unit for the product (the on-the-fly kernels slice every tile of W once per 256
+ *   rows of A).  The results are those of mx_gemm_ss_fp4 bit for bit.
+ *   Otherwise, from 49 rows on, when the tiles of C leave most compute units without one (a narrow N), K is split over
+ *   2, 4 or 8 workgroups per tile whose partial sums go through the workspace and are added in the order of the slices:
+ *   still a fixed order (reproducible run to run), but not mx_gemm_ss_fp4's, so the two results differ by fp32 rounding.
+ * In every other case, and with workspace == NULL, this is mx_gemm_ss_fp4. */
 #define MX_GEMM_HOIST_MIN_ROWS 512
 size_t mx_gemm_ss_fp4_workspace(int64_t n, int64_t k);
+/* The number of K slices mx_gemm_ss_fp4_ws works with for an [m, k] x [n, k] product and a workspace of that size on the
+ * current device: 1 when its result is mx_gemm_ss_fp4's bit for bit, 2 / 4 / 8 when partial sums are added afterwards. */
+int mx_gemm_ss_fp4_ws_slices(int64_t m, int64_t n, int64_t k, size_t workspace_bytes);
 mx_status_t mx_gemm_ss_fp4_ws(const mx_packed_t* a, const mx_packed_t* w_anchor, const mx_dense_t* c, void* workspace,
                               size_t workspace_bytes, void* stream);
 

@@ -229,15 +229,18 @@ def mx_dequant(codes, scales, fmt, rows, cols, dtype=None, out=None):
 
 
 GEMM_HOIST_MIN_ROWS = 512   # MX_GEMM_HOIST_MIN_ROWS of mx.h
+GEMM_WORKSPACE_MIN_ROWS = 49   # below, the streaming kernels run whatever the caller lends
 
 
 def mx_gemm_ss_fp4(a_codes, a_scales, w_codes, w_scales, out=None, workspace=None):
     """C[M, N] = DQ(A) @ DQ(SS(W_anchor -> E2M1)).T (scaled MX MFMA, fp32 out).
 
     a_*: MXFP8 E4M3 activations [M, K/32, 32] / [M, K/32]; w_*: E4M3 anchor, K-contiguous [N, K/32, 32] / [N, K/32].
-    With fewer than 512 rows the anchor is sliced in registers on its way into the product.  From 512 rows on it is
-    sliced once per call into `workspace` (uint8, mx_gemm_ss_fp4_workspace(N, K) bytes; allocated here when not given;
-    workspace=False keeps the on-the-fly kernel) and multiplied from there; the results are the same bit for bit."""
+    The anchor is sliced in registers on its way into the product, or, from 512 rows on when C has enough tiles, once
+    per call into `workspace` (uint8, mx_gemm_ss_fp4_workspace(N, K) bytes; allocated here when not given) and
+    multiplied from there, with the same results bit for bit.  From 49 rows on the workspace also lets shapes with few
+    tiles split K over several workgroups (partial sums added in a fixed order of their own).  workspace=False keeps
+    the on-the-fly kernels without a workspace."""
     torch = _torch()
     L = binding.lib()
     M, KB = a_scales.shape
@@ -247,7 +250,7 @@ def mx_gemm_ss_fp4(a_codes, a_scales, w_codes, w_scales, out=None, workspace=Non
     a = _packed(a_codes, a_scales, M, KB)
     w = _packed(w_codes, w_scales, N, w_scales.shape[1])
     c = _dense(out)
-    if M >= GEMM_HOIST_MIN_ROWS and workspace is not False:
+    if M >= GEMM_WORKSPACE_MIN_ROWS and workspace is not False:
         need = L.mx_gemm_ss_fp4_workspace(N, KB * 32)
         if workspace is None:
             workspace = torch.empty(max(16, need), dtype=torch.uint8, device=a_codes.device)

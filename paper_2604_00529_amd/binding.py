@@ -78,6 +78,8 @@ def lib():
         L.mx_slice_and_scale_multi_batched.restype = st
         L.mx_gemm_ss_fp4_workspace.argtypes = [ctypes.c_int64, ctypes.c_int64]
         L.mx_gemm_ss_fp4_workspace.restype = ctypes.c_size_t
+        L.mx_gemm_ss_fp4_ws_slices.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_size_t]
+        L.mx_gemm_ss_fp4_ws_slices.restype = ctypes.c_int
         L.mx_gemm_ss_fp4_ws.argtypes = [P(MxPacked), P(MxPacked), P(MxDense), vp, ctypes.c_size_t, vp]
         L.mx_gemm_ss_fp4_ws.restype = st
         L.mx_fake_quant.argtypes = [P(MxFormat), P(MxFormat), P(MxDense), P(MxDense), vp]

@@ -295,21 +295,37 @@ size_t mx_gemm_ss_fp4_workspace(int64_t n, int64_t k) {
   return (size_t)n * (size_t)k / 2 + (size_t)n * (size_t)k / 32;   // E2M1 codes, then their scale bytes
 }
 
+int mx_gemm_ss_fp4_ws_slices(int64_t m, int64_t n, int64_t k, size_t workspace_bytes) {
+  if (m <= 0 || n <= 0 || k <= 0 || k % 128 != 0 || k > 0x7FFFFFFF || m > 0x7FFFFFFF || n > 0x7FFFFFFF) return 1;
+  if (workspace_bytes < mx_gemm_ss_fp4_workspace(n, k)) return 1;
+  if (m >= MX_GEMM_HOIST_MIN_ROWS && mx::gemm_hoist_pays(m, n)) return 1;
+  return mx::gemm_splitk_slices(m, n, k, workspace_bytes, nullptr);
+}
+
 mx_status_t mx_gemm_ss_fp4_ws(const mx_packed_t* a, const mx_packed_t* w_anchor, const mx_dense_t* c, void* workspace,
                               size_t workspace_bytes, void* stream) {
   mx_status_t st;
   if ((st = check_packed(a)) != MX_OK) return st;
   if ((st = check_packed(w_anchor)) != MX_OK) return st;
   if ((st = check_dense(c)) != MX_OK) return st;
-  // few rows, too few tiles to fill the GPU, or no workspace: the kernels that slice on the fly
-  if (!workspace || c->rows < MX_GEMM_HOIST_MIN_ROWS || !mx::gemm_hoist_pays(c->rows, c->cols)) return mx_gemm_ss_fp4(a, w_anchor, c, stream);
+  if (!workspace) return mx_gemm_ss_fp4(a, w_anchor, c, stream);
   if (c->dtype != MX_F32) return MX_ERR_UNSUPPORTED;
   if (a->nblocks != w_anchor->nblocks || c->rows != a->outer || c->cols != w_anchor->outer) return MX_ERR_SHAPE;
-  if (c->cols == 0) return MX_OK;
+  if (c->rows == 0 || c->cols == 0) return MX_OK;
   const int64_t K = a->nblocks * 32, N = w_anchor->outer;
   if (K == 0 || K % 128 != 0 || K > 0x7FFFFFFF || c->rows > 0x7FFFFFFF || N > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
   if (!aligned16(workspace)) return MX_ERR_ALIGN;
   if (workspace_bytes < mx_gemm_ss_fp4_workspace(N, K)) return MX_ERR_WORKSPACE;
+  if (c->rows < MX_GEMM_HOIST_MIN_ROWS || !mx::gemm_hoist_pays(c->rows, c->cols)) {
+    // Few rows or too few tiles to fill the GPU: the kernels that slice on the fly -- with K split over several
+    // workgroups per tile, their partial sums in the workspace, when the tiles alone leave most of the GPU idle.
+    drop_stale_error();
+    if (mx::gemm_ss_fp4_splitk(static_cast<const uint8_t*>(a->codes), a->scales, static_cast<const uint8_t*>(w_anchor->codes),
+                               w_anchor->scales, static_cast<float*>(c->data), c->rows, N, K, c->ld, workspace, workspace_bytes,
+                               static_cast<hipStream_t>(stream), &st))
+      return st;
+    return mx_gemm_ss_fp4(a, w_anchor, c, stream);
+  }
   // W_t = Q_{A->t}(W_A) (Eq. (6)) once, by the Slice-and-Scale kernel, then the product
   uint8_t* w4 = static_cast<uint8_t*>(workspace);
   const mx_format_t fa = {MX_FP8_E4M3, MX_SCALE_E8M0, 32, 1, MX_ROUND_DEFAULT}, ft = {MX_FP4_E2M1, MX_SCALE_E8M0, 32, 1, MX_ROUND_DEFAULT};

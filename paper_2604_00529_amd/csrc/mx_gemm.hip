@@ -494,15 +494,24 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
                                                                          const uint8_t* __restrict__ w_codes,
                                                                          const uint8_t* __restrict__ w_scales,
                                                                          float* __restrict__ c, int M, int N, int K,
-                                                                         int64_t ldc, int m_tiles, int tiles) {
+                                                                         int64_t ldc, int m_tiles, int tiles, int k_len,
+                                                                         int64_t c_slice) {
   extern __shared__ __attribute__((aligned(16))) uint8_t gemm_smem[];
   GemmStage* stage = reinterpret_cast<GemmStage*>(gemm_smem);
+  // K can be split over gridDim.y: slice y multiplies the K elements [y k_len, (y + 1) k_len) of every row (K stays
+  // the row stride) and writes its partial sums to c + y c_slice.  One slice (k_len = K) is the whole product.
+  const uint32_t k_skip = (uint32_t)blockIdx.y * (uint32_t)k_len;
+  a_codes += k_skip;
+  w_codes += k_skip;
+  a_scales += k_skip / 32;
+  w_scales += k_skip / 32;
+  c += (int64_t)blockIdx.y * c_slice;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // a scalar: the role branch is uniform
   const int tid = threadIdx.x & 255;   // index inside the role's 256 threads
   const int i = lane & 15, g = lane >> 4;
   constexpr int BN = 16 * NTW;   // columns of the workgroup tile
-  const int KB = K / 32, ksteps = K / kGemmBK;
+  const int KB = K / 32, ksteps = k_len / kGemmBK;
   // The kernel is persistent: a workgroup works the tiles v, v + gridDim.x, ... of the tile list (bands of 8 M
   // tiles, M tile index fastest inside a band) and both roles run ONE software pipeline over all K-steps of all their tiles: the operands of the next
   // tile's first K-steps are in flight while the current tile is finished, and a consumer goes on to the next tile's
@@ -556,8 +565,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
       auto request_step = [&](int stage_i) __attribute__((always_inline)) {
         const int m0 = (SKIP & 1024) ? 0 : rq.tm * kGemmBM;
         const int rows = M - m0 < kGemmBM ? M - m0 : kGemmBM;
-        const __amdgpu_buffer_rsrc_t c_rsrc = make_buffer(a_codes + (int64_t)m0 * K, (uint32_t)rows * (uint32_t)K);
-        const __amdgpu_buffer_rsrc_t s_rsrc = make_buffer(a_scales + (int64_t)m0 * KB, (uint32_t)rows * (uint32_t)KB);
+        // (the bases are k_skip bytes into row m0, so the descriptors end that much earlier: at the end of the last valid row)
+        const __amdgpu_buffer_rsrc_t c_rsrc = make_buffer(a_codes + (int64_t)m0 * K, (uint32_t)rows * (uint32_t)K - k_skip);
+        const __amdgpu_buffer_rsrc_t s_rsrc = make_buffer(a_scales + (int64_t)m0 * KB, (uint32_t)rows * (uint32_t)KB - k_skip / 32);
         uint8_t* st = gemm_smem + stage_i * (int)sizeof(GemmStage);
         const uint32_t k_off = (uint32_t)(rq.k * kGemmBK), ks_off = (uint32_t)(rq.k * 4);
         const bool skip = (SKIP & 8) && issued >= 4;   // (timing only)
@@ -759,7 +769,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   auto a_tile = [&](const GemmCursor& cur) {
     const int m0 = (SKIP & 1024) ? 0 : cur.tm * kGemmBM;
     const int rows = M - m0 < kGemmBM ? M - m0 : kGemmBM;
-    return make_buffer(a_codes + (int64_t)m0 * K, (uint32_t)rows * (uint32_t)K);
+    return make_buffer(a_codes + (int64_t)m0 * K, (uint32_t)rows * (uint32_t)K - k_skip);   // (ends with the last valid row)
   };
   // K-step ks of the tile behind descriptor rsrc (a step past the end of K: the last one again, which nothing uses)
   auto request_a = [&](__amdgpu_buffer_rsrc_t rsrc, int ks, int stage_i, auto jc) __attribute__((always_inline)) {
@@ -1148,7 +1158,8 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
       attr_set = true;                                                                                                      \
     }                                                                                                                       \
     hipLaunchKernelGGL((gemm_ss_fp4_tiled_kernel<NTW, 0>), dim3((unsigned)grid_wgs), dim3(kGemmThreads), kSmem, stream,     \
-                       a_codes, a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles, (int)tiles);     \
+                       a_codes, a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles, (int)tiles,      \
+                       (int)K, (int64_t)0);                                                                                \
   }
     MX_GEMM_TILED(8) MX_GEMM_TILED(7) MX_GEMM_TILED(6) MX_GEMM_TILED(5) MX_GEMM_TILED(4)
 #undef MX_GEMM_TILED
@@ -1176,6 +1187,104 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
     return launch_status("the fused GEMM");
   }
   return MX_ERR_UNSUPPORTED;   // (not reached: every shape is taken above)
+}
+
+// C = the K slices' partial sums added in the order of the slices: thread q takes 4 consecutive columns of one row.
+// (The partial sums lie in S slices of M x ldp floats, ldp = N rounded up to 4; the padding columns are never written
+// by the product and never stored here.)
+__global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(const float* __restrict__ p, float* __restrict__ c, int M,
+                                                                 int N, int ldp, int64_t ldc, int64_t slice, int S) {
+  const int quads = ldp / 4;
+  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (q >= (int64_t)M * quads) return;
+  const int m = (int)(q / quads), n = (int)(q - (int64_t)m * quads) * 4;
+  const float* src = p + (int64_t)m * ldp + n;
+  f32x4 sum = *reinterpret_cast<const f32x4*>(src);
+  for (int s = 1; s < S; ++s) {
+    const f32x4 v = *reinterpret_cast<const f32x4*>(src + (int64_t)s * slice);
+    sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
+  }
+  float* dst = c + (int64_t)m * ldc + n;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    if (n + j < N) dst[j] = sum[j];
+}
+
+// The tiled kernel with K split over several workgroups per tile, for shapes whose tiles leave most compute units
+// without one (49 <= M and a narrow N: 64 x 4096 x 14336 is 64 tiles of 112 K-steps each on 256 CUs).  Slice s of a
+// tile sums its K / S elements in the usual order into a buffer of partial sums in the workspace; a second kernel
+// adds the S partial sums of every output in the order of the slices -- a fixed order, but not the one of the
+// unsplit kernels.  gemm_splitk_slices is the plan (1: no split, because it does not pay or does not fit);
+// gemm_ss_fp4_splitk returns false, with nothing enqueued, when the plan is 1.
+int gemm_splitk_slices(int64_t M, int64_t N, int64_t K, size_t workspace_bytes, int* ntw_out) {
+  if (M <= kMidmMaxM) return 1;   // (the streaming kernels split K inside a workgroup)
+  if (kGemmBM * K > 0xFFFFFFFFll) return 1;
+  const int cus = device_compute_units();
+  if (cus <= 0) return 1;
+  const int64_t ksteps = K / kGemmBK, m_tiles = (M + kGemmBM - 1) / kGemmBM, ldp = (N + 3) & ~(int64_t)3;
+  if (ldp * kGemmBM >= ((int64_t)1 << 30)) return 1;
+  // The split pays when the narrowest tiles still leave half of the compute units without one: with more workgroups
+  // than that the unsplit launch is already bound by the stream of W (64 x 14336 x 4096, 224 tiles of 64 columns: 25.7
+  // us unsplit, 28.8 us in two slices), with fewer it is bound by the K-steps one workgroup makes in sequence
+  // (64 x 4096 x 14336, 64 tiles: 71 us unsplit, 33 us in eight slices).
+  if (m_tiles * ((N + 63) / 64) > cus / 2) return 1;
+  // cost of a launch in units of ~12 ns: a K-step of a tile of 16 w columns takes (50 + 10 w) (the model of the
+  // unsplit launch), a workgroup's launch, way to its first operands and last stores ~750 (9 us measured), the second
+  // kernel and the gap in front of it ~420 (5 us)
+  int best_s = 1, best_ntw = 0;
+  int64_t best = -1;
+  for (int cand = 8; cand >= 4; --cand) {
+    const int64_t tiles_c = m_tiles * ((N + 16 * cand - 1) / (16 * cand));
+    const int64_t cost = (tiles_c + cus - 1) / cus * ksteps * (50 + cand * 10) + 750;
+    if (best < 0 || cost < best) { best = cost; best_ntw = cand; }
+  }
+  for (int S = 2; S <= 8; S *= 2) {
+    if (ksteps % S != 0 || ksteps / S < 8) continue;                                     // equal slices of eight K-steps and more
+    if ((uint64_t)S * (uint64_t)M * (uint64_t)ldp * 4u > (uint64_t)workspace_bytes) continue;
+    for (int cand = 8; cand >= 4; --cand) {
+      const int64_t tiles_c = m_tiles * ((N + 16 * cand - 1) / (16 * cand));
+      if (tiles_c * S > cus) continue;                                                   // one round
+      const int64_t cost = ksteps / S * (50 + cand * 10) + 750 + 420;
+      if (cost < best) { best = cost; best_s = S; best_ntw = cand; }
+    }
+  }
+  if (ntw_out) *ntw_out = best_ntw;
+  return best_s;
+}
+
+bool gemm_ss_fp4_splitk(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes, const uint8_t* w_scales,
+                        float* c, int64_t M, int64_t N, int64_t K, int64_t ldc, void* workspace, size_t workspace_bytes,
+                        hipStream_t stream, mx_status_t* status) {
+  int ntw = 0;
+  const int S = gemm_splitk_slices(M, N, K, workspace_bytes, &ntw);
+  if (S == 1) return false;
+  const int64_t m_tiles = (M + kGemmBM - 1) / kGemmBM, ldp = (N + 3) & ~(int64_t)3;
+  const int64_t tiles = m_tiles * ((N + 16 * ntw - 1) / (16 * ntw));
+  const int64_t k_len = K / S, slice = M * ldp;
+  float* partial = static_cast<float*>(workspace);
+  constexpr int kSmem = 3 * (int)sizeof(GemmStage);
+  *status = MX_ERR_LAUNCH;
+#define MX_GEMM_TILED_SPLIT(NTW)                                                                                            \
+  if (ntw == NTW) {                                                                                                         \
+    static bool attr_set = false;                                                                                           \
+    if (!attr_set) {                                                                                                        \
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ss_fp4_tiled_kernel<NTW, 0>),                              \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) != hipSuccess)                             \
+        return true;                                                                                                        \
+      attr_set = true;                                                                                                      \
+    }                                                                                                                       \
+    hipLaunchKernelGGL((gemm_ss_fp4_tiled_kernel<NTW, 0>), dim3((unsigned)tiles, (unsigned)S), dim3(kGemmThreads), kSmem,   \
+                       stream, a_codes, a_scales, w_codes, w_scales, partial, (int)M, (int)N, (int)K, ldp, (int)m_tiles,    \
+                       (int)tiles, (int)k_len, slice);                                                                      \
+  }
+  MX_GEMM_TILED_SPLIT(8) MX_GEMM_TILED_SPLIT(7) MX_GEMM_TILED_SPLIT(6) MX_GEMM_TILED_SPLIT(5) MX_GEMM_TILED_SPLIT(4)
+#undef MX_GEMM_TILED_SPLIT
+  if ((*status = launch_status("the fused GEMM (K slices)")) != MX_OK) return true;
+  const int64_t quads = M * (ldp / 4);
+  hipLaunchKernelGGL(gemm_splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, partial, c, (int)M,
+                     (int)N, (int)ldp, ldc, slice, S);
+  *status = launch_status("the sum of the fused GEMM's K slices");
+  return true;
 }
 
 // Is the product with W sliced beforehand the faster one?  Its 256 x 256 tiles must fill the GPU: measured on 256 CUs,

@@ -78,6 +78,10 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
                                const uint8_t* w_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
                                hipStream_t stream);
 bool gemm_hoist_pays(int64_t M, int64_t N);
+int gemm_splitk_slices(int64_t M, int64_t N, int64_t K, size_t workspace_bytes, int* ntw_out);
+bool gemm_ss_fp4_splitk(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes, const uint8_t* w_scales,
+                        float* c, int64_t M, int64_t N, int64_t K, int64_t ldc, void* workspace, size_t workspace_bytes,
+                        hipStream_t stream, mx_status_t* status);
 mx_status_t gemm_fp8_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w4_codes,
                                 const uint8_t* w4_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
                                 hipStream_t stream);

@@ -22,7 +22,7 @@ def _gpu_bf16(a):
     return torch.from_numpy(synth.f32_to_bf16_bits(a).view(np.int16).copy()).view(torch.bfloat16).cuda()
 
 
-def _check(mx, oracle, M, N, K, seed, w_axis0=True, random_bytes=False):
+def _check(mx, oracle, M, N, K, seed, w_axis0=True, random_bytes=False, want_slices=None):
     import torch
     rng = np.random.default_rng(seed)
     f8 = mx.make_format("e4m3")
@@ -45,16 +45,26 @@ def _check(mx, oracle, M, N, K, seed, w_axis0=True, random_bytes=False):
             wc, wsc = mx.mx_quantize(_gpu_bf16(w), f8)
     c = mx.mx_gemm_ss_fp4(ac, asc, wc, wsc)
     torch.cuda.synchronize()
-    if M >= mx.GEMM_HOIST_MIN_ROWS:
-        # the call above sliced W once into a workspace and multiplied from there; the kernel that slices on the fly
+    c_fly, slices = None, 1
+    if M >= mx.GEMM_WORKSPACE_MIN_ROWS:
+        # the call above lent a workspace: W sliced once into it and multiplied from there (large M, many tiles), or
+        # the partial sums of K slices (few tiles), or nothing.  Unless K was split, the kernels that slice on the fly
         # must give the same bits (every output's sum over K runs in the same order)
+        L = mx.binding.lib()
+        slices = L.mx_gemm_ss_fp4_ws_slices(M, N, K, max(16, L.mx_gemm_ss_fp4_workspace(N, K)))
         c_fly = mx.mx_gemm_ss_fp4(ac, asc, wc, wsc, workspace=False)
         torch.cuda.synchronize()
-        assert torch.equal(c.view(torch.int32), c_fly.view(torch.int32))
+        if slices == 1:
+            assert torch.equal(c.view(torch.int32), c_fly.view(torch.int32))
+        if want_slices is not None:
+            assert slices == want_slices
     ref, ref_abs = oracle.gemm_ss_reference(ac.cpu().numpy(), asc.cpu().numpy(), wc.cpu().numpy(), wsc.cpu().numpy(),
                                             with_abs=True)
     got = c.cpu().numpy().astype(np.float64)
     assert got.shape == (M, N)
+    if slices > 1:
+        # K slices: the same products grouped differently -- a few fp32 roundings of the partial sums apart
+        assert (np.abs(got - c_fly.cpu().numpy().astype(np.float64)) <= 1e-6 * ref_abs + 1e-30).all()
     # Error on the scale of sum |products| (holds under any cancellation).  The matrix instruction adds the 128
     # products of one step after aligning them to the largest one, so blocks whose scales differ by many powers of
     # two lose the low bits of the small products: the bound is looser for the wide-range adversarial operands.
@@ -113,14 +123,47 @@ def test_gemm_several_tiles_per_workgroup(mx, oracle, M, N, K):
     _check(mx, oracle, M, N, K, seed=M + N + K + 1, random_bytes="narrow")
 
 
+@pytest.mark.parametrize("M,N,K,S", [(64, 1024, 4096, 4), (100, 520, 2048, 2), (130, 1000, 4096, 4), (300, 776, 8192, 2),
+                                     (64, 96, 8192, 8), (49, 4096, 3584, 2)])
+def test_gemm_k_slices(mx, oracle, M, N, K, S):
+    # few tiles and a long K: with a workspace, K is split over S workgroups per tile (on 256 compute units) and the
+    # partial sums are added by a second kernel; ragged M and N tiles, two M tiles, the fewest rows that take this way
+    _check(mx, oracle, M, N, K, seed=M + N + K, want_slices=S)
+    _check(mx, oracle, M, N, K, seed=M + N + K + 1, random_bytes="narrow", want_slices=S)
+    _check(mx, oracle, M, N, K, seed=M + N + K + 2, random_bytes="wide", want_slices=S)
+
+
+def test_gemm_k_slices_columns_not_a_multiple_of_4(mx, oracle):
+    # N = 522 (C is a view of a matrix with a row stride of 528): the rows of partial sums are padded to 524 columns
+    import torch
+    M, N, K = 100, 522, 2048
+    rng = np.random.default_rng(522)
+    f8 = mx.make_format("e4m3")
+    ac, asc = mx.mx_quantize(_gpu_bf16(rng.standard_normal((M, K)).astype(np.float32)), f8)
+    wc, wsc = mx.mx_quantize(_gpu_bf16((rng.standard_normal((N, K)) * 0.02).astype(np.float32)), f8)
+    L = mx.binding.lib()
+    assert L.mx_gemm_ss_fp4_ws_slices(M, N, K, L.mx_gemm_ss_fp4_workspace(N, K)) == 2
+    wide = torch.full((M, 528), -7.0, dtype=torch.float32, device="cuda")
+    mx.mx_gemm_ss_fp4(ac, asc, wc, wsc, out=wide[:, :N])
+    fly = torch.full((M, 528), -7.0, dtype=torch.float32, device="cuda")
+    mx.mx_gemm_ss_fp4(ac, asc, wc, wsc, out=fly[:, :N], workspace=False)
+    torch.cuda.synchronize()
+    assert bool((wide[:, N:] == -7.0).all()) and bool((fly[:, N:] == -7.0).all())
+    ref, ref_abs = oracle.gemm_ss_reference(ac.cpu().numpy(), asc.cpu().numpy(), wc.cpu().numpy(), wsc.cpu().numpy(), with_abs=True)
+    got = wide[:, :N].cpu().numpy().astype(np.float64)
+    assert (np.abs(got - ref) <= 2e-5 * ref_abs).all()
+    assert (np.abs(got - fly[:, :N].cpu().numpy()) <= 1e-6 * ref_abs).all()
+
+
 def test_gemm_prefill_shape_config5(mx, oracle):
     # M = 2048, K = 4096, N = 14336: the prefill shape of the benchmark definition
     _check(mx, oracle, 2048, 14336, 4096, seed=2005)
 
 
-@pytest.mark.parametrize("M,N,K", [(16, 104, 384), (200, 304, 256), (600, 304, 256), (1024, 12400, 128)])
+@pytest.mark.parametrize("M,N,K", [(16, 104, 384), (200, 304, 256), (600, 304, 256), (1024, 12400, 128), (100, 520, 2048)])
 def test_gemm_strided_output(mx, oracle, M, N, K):
     # C as a view of a wider matrix (ld > N): same values as the contiguous call, nothing written outside the view
+    # (the last shape goes through K slices)
     import torch
     rng = np.random.default_rng(M + N + K)
     f8 = mx.make_format("e4m3")
@@ -164,15 +207,33 @@ def test_gemm_workspace_entry_point(mx, oracle):
     tc, ts = oracle.slice_and_scale(wc.cpu().numpy(), wsc.cpu().numpy(), "e4m3", "e2m1")
     got = ws.cpu().numpy()
     assert np.array_equal(got[:N * K // 2], tc.reshape(-1)) and np.array_equal(got[N * K // 2:need], ts.reshape(-1))
-    # NULL workspace, or few tiles: the on-the-fly kernels; a small workspace is then no error
+    # NULL workspace, or few tiles and a short K: the on-the-fly kernels, the workspace untouched
     out.zero_()
     assert L.mx_gemm_ss_fp4_ws(ref(a), ref(w), ref(c), None, 0, None) == 0
     torch.cuda.synchronize()
     assert torch.equal(out.view(torch.int32), want.view(torch.int32))
     a2, w2 = mx._packed(ac[:512], asc[:512], 512, K // 32), mx._packed(wc[:256], wsc[:256], 256, K // 32)
     out2 = torch.empty((512, 256), dtype=torch.float32, device="cuda")
+    need2 = L.mx_gemm_ss_fp4_workspace(256, K)
+    assert L.mx_gemm_ss_fp4_ws_slices(512, 256, K, need2) == 1
     ws.fill_(0x5A)
-    assert L.mx_gemm_ss_fp4_ws(ref(a2), ref(w2), ref(mx._dense(out2)), ctypes.c_void_p(ws.data_ptr()), 16, None) == 0
+    assert L.mx_gemm_ss_fp4_ws(ref(a2), ref(w2), ref(mx._dense(out2)), ctypes.c_void_p(ws.data_ptr()), need2 - 1, None) == 7
+    assert L.mx_gemm_ss_fp4_ws(ref(a2), ref(w2), ref(mx._dense(out2)), ctypes.c_void_p(ws.data_ptr()), need2, None) == 0
     torch.cuda.synchronize()
     assert bool((ws == 0x5A).all())
     assert torch.equal(out2.view(torch.int32), want[:512, :256].contiguous().view(torch.int32))
+    # K slices through the C ABI: the partial sums stay inside the stated size
+    M3, N3, K3 = 64, 520, 2048
+    ac3, asc3 = mx.mx_quantize(_gpu_bf16(rng.standard_normal((M3, K3)).astype(np.float32)), f8)
+    wc3, wsc3 = mx.mx_quantize(_gpu_bf16((rng.standard_normal((N3, K3)) * 0.02).astype(np.float32)), f8)
+    need3 = L.mx_gemm_ss_fp4_workspace(N3, K3)
+    assert L.mx_gemm_ss_fp4_ws_slices(M3, N3, K3, need3) == 2
+    assert L.mx_gemm_ss_fp4_ws_slices(M3, N3, K3, need3 - 1) == 1 and L.mx_gemm_ss_fp4_ws_slices(48, N3, K3, need3) == 1
+    ws3 = torch.full((need3 + 64,), 0x5A, dtype=torch.uint8, device="cuda")
+    out3 = torch.empty((M3, N3), dtype=torch.float32, device="cuda")
+    assert L.mx_gemm_ss_fp4_ws(ref(mx._packed(ac3, asc3, M3, K3 // 32)), ref(mx._packed(wc3, wsc3, N3, K3 // 32)), ref(mx._dense(out3)),
+                               ctypes.c_void_p(ws3.data_ptr()), need3, None) == 0
+    torch.cuda.synchronize()
+    assert bool((ws3[need3:] == 0x5A).all()) and not bool((ws3[:2 * M3 * N3 * 4] == 0x5A).all())
+    ref3 = oracle.gemm_ss_reference(ac3.cpu().numpy(), asc3.cpu().numpy(), wc3.cpu().numpy(), wsc3.cpu().numpy())
+    assert np.abs(out3.cpu().numpy() - ref3).max() <= 2e-5 * np.linalg.norm(ref3, axis=1).max()
