@@ -272,30 +272,33 @@ def gemm_rows(torch, mx, synth, rows):
     # sliced to E2M1 in registers, scaled MX MFMA.  Decode (M = 16) is bound by reading the anchor: 8 weights are
     # rotated (484 MB) so that they stream from HBM; prefill (M = 2048) is bound by the matrix cores (operand A is
     # FP8, so the FP8 dense peak applies).
-    Kg, Ng = 4096, 14336
     f8 = mx.make_format("e4m3")
     wlist = []
     for i in range(8):
-        w = synth.torch_config3_weight(3000 + i, Ng, Kg)
+        w = synth.torch_config3_weight(3000 + i, 14336, 4096)
         wlist.append(mx.mx_quantize(w, f8))
         del w
-    for Mg in (16, 2048):
+    # third row: a down_proj shape with few rows (M = 64, N = 4096, K = 14336; the same anchors' bytes read as
+    # [4096, 14336]): few tiles and a long K, which the library splits over several workgroups per tile
+    for Mg, Ng, Kg, name in ((16, 14336, 4096, "gemm_ss_fp4_M16"), (2048, 14336, 4096, "gemm_ss_fp4_M2048"),
+                             (64, 4096, 14336, "gemm_ss_fp4_M64_N4096_K14336")):
         a = torch.randn((Mg, Kg), device="cuda", dtype=torch.float32, generator=torch.Generator(device="cuda").manual_seed(1005)).to(torch.bfloat16)
         ac, asc = mx.mx_quantize(a, f8)
         cbuf = torch.empty((Mg, Ng), dtype=torch.float32, device="cuda")
+        ws = [(c.view(Ng, Kg // 32, 32), sc.view(Ng, Kg // 32)) for c, sc in wlist]
         st = {"i": 0}
 
         def gemm():
             i = st["i"] = (st["i"] + 1) % 8
-            mx.mx_gemm_ss_fp4(ac, asc, wlist[i][0], wlist[i][1], cbuf)
+            mx.mx_gemm_ss_fp4(ac, asc, ws[i][0], ws[i][1], cbuf)
         m, _, _ = time_region(torch, gemm, 24, 8, WARM_MS)
         flops = 2.0 * Mg * Ng * Kg
         nbytes_g = Ng * Kg + Ng * Kg // 32 + Mg * Kg + Mg * Kg // 32 + Mg * Ng * 4
-        rows["gemm_ss_fp4_M%d" % Mg] = {"ms": round(m, 4), "TFLOP/s": round(flops / (m * 1e-3) / 1e12, 1),
-                                        "frac_fp8_mfma_peak": round(flops / (m * 1e-3) / 5.0e15, 4),
-                                        "GB/s": round(nbytes_g / (m * 1e-3) / 1e9, 1),
-                                        "frac_hbm_peak": round(nbytes_g / (m * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-        del a, ac, asc, cbuf
+        rows[name] = {"ms": round(m, 4), "TFLOP/s": round(flops / (m * 1e-3) / 1e12, 1),
+                      "frac_fp8_mfma_peak": round(flops / (m * 1e-3) / 5.0e15, 4),
+                      "GB/s": round(nbytes_g / (m * 1e-3) / 1e9, 1),
+                      "frac_hbm_peak": round(nbytes_g / (m * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del a, ac, asc, cbuf, ws
     del wlist
 
 
