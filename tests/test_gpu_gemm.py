@@ -133,6 +133,12 @@ def test_gemm_k_slices(mx, oracle, M, N, K, S):
     _check(mx, oracle, M, N, K, seed=M + N + K + 2, random_bytes="wide", want_slices=S)
 
 
+def test_gemm_few_rows_down_proj_shape(mx, oracle):
+    # M = 64, N = 4096, K = 14336: the few-tiles row of the bench, in the configuration it times (eight slices of K on
+    # 256 compute units, default call with a workspace)
+    _check(mx, oracle, 64, 4096, 14336, seed=3005, w_axis0=False, want_slices=8)
+
+
 def test_gemm_k_slices_columns_not_a_multiple_of_4(mx, oracle):
     # N = 522 (C is a view of a matrix with a row stride of 528): the rows of partial sums are padded to 524 columns
     import torch
