@@ -23,11 +23,20 @@ def test_graph_replays_match_eager_and_oracle(mx, oracle):
     nblocks = sum(int(s.numel()) for _, s in anchors)
     ws = torch.empty(mx.binding.lib().mx_slice_and_scale_batched_workspace(len(anchors), nblocks), dtype=torch.uint8, device="cuda")
     fq = [torch.empty_like(d) for d in dense]
-    # the fused GEMM too (its tiled kernel: M > 48): activations = tensor 2 (128 x 2048), weight = its first 48 rows
+    # the fused GEMM too (its tiled kernel: M > 48; one tile and 16 K-steps, so with the workspace that the binding
+    # allocates -- from torch's pool of the graph while capturing -- K goes in two slices and a second kernel adds them):
+    # activations = tensor 2 (128 x 2048), weight = its first 48 rows
     c_out = torch.empty((128, 48), dtype=torch.float32, device="cuda")
     # and its streaming kernels: 33 x 512 activations (tensor 1) against 32 of its rows, 16 rows of tensor 0 against 64
     c_mid = torch.empty((33, 32), dtype=torch.float32, device="cuda")
     c_dec = torch.empty((16, 64), dtype=torch.float32, device="cuda")
+    # and its workspace path (W sliced into a lent workspace, then the 256-row-tile kernel): 768 x 16384 x 128, operands
+    # quantized once outside the graph
+    big_a = mx.mx_quantize(to_gpu(rng.standard_normal((768, 128)).astype(np.float32)), fa)
+    big_w = mx.mx_quantize(to_gpu((rng.standard_normal((16384, 128)) * 0.02).astype(np.float32)), fa)
+    big_ws = torch.empty(mx.binding.lib().mx_gemm_ss_fp4_workspace(16384, 128), dtype=torch.uint8, device="cuda")
+    c_big = torch.empty((768, 16384), dtype=torch.float32, device="cuda")
+    c_big_fly = mx.mx_gemm_ss_fp4(big_a[0], big_a[1], big_w[0], big_w[1], workspace=False)
     batch4 = mx.SsBatch(anchors, fa, ft, t4, ws)
     batch46 = mx.SsBatch(anchors, fa, [f6, ft], [[t6[i], t4[i]] for i in range(len(anchors))], ws)
 
@@ -41,6 +50,7 @@ def test_graph_replays_match_eager_and_oracle(mx, oracle):
         mx.mx_gemm_ss_fp4(anchors[2][0], anchors[2][1], anchors[2][0][:48], anchors[2][1][:48], c_out)
         mx.mx_gemm_ss_fp4(anchors[1][0], anchors[1][1], anchors[1][0][:32], anchors[1][1][:32], c_mid)
         mx.mx_gemm_ss_fp4(anchors[0][0][:16], anchors[0][1][:16], anchors[0][0], anchors[0][1], c_dec)
+        mx.mx_gemm_ss_fp4(big_a[0], big_a[1], big_w[0], big_w[1], c_big, workspace=big_ws)
 
     work()                                                                 # eager once (also sets kernel attributes)
     torch.cuda.synchronize()
@@ -59,10 +69,13 @@ def test_graph_replays_match_eager_and_oracle(mx, oracle):
         c_out.zero_()
         c_mid.zero_()
         c_dec.zero_()
+        c_big.zero_()
+        big_ws.fill_(0x5A)
         g.replay()
         torch.cuda.synchronize()
         got = ([(to_host(a), to_host(b)) for a, b in t4], [(to_host(a), to_host(b)) for a, b in t6], [to_host(o) for o in fq], to_host(c_out),
                to_host(c_mid), to_host(c_dec))
+        assert torch.equal(c_big.view(torch.int32), c_big_fly.view(torch.int32)), rep   # (bit-identical to the on-the-fly kernels)
         for i, h in enumerate(host):
             wc, wsc = oracle.quantize(h, "e4m3")
             assert np.array_equal(to_host(anchors[i][0]), wc) and np.array_equal(to_host(anchors[i][1]), wsc), (rep, i)
