@@ -3,7 +3,12 @@
 // (E4M3) activations and W_A is the stored MXFP8 (E4M3) anchor, both blocked by 32 along K.  The anchor
 // is sliced to E2M1 in registers (Eq. (6)) and fed, with the E8M0 block scales (Eq. (6) scale step), to
 // the CDNA4 scaled MFMA v_mfma_scale_f32_16x16x128_f8f6f4; accumulation is fp32.  W_t never exists in
-// memory.
+// memory -- unless the caller lends a workspace: then, for large M, W_t is written there once per call and
+// multiplied by a kernel without slicing waves (last part of this file), and shapes with few tiles of C
+// split K over several workgroups whose partial sums pass through it.
+//
+// Kernels by shape: M <= 16 decode (streams W once), 16 < M <= 48 the same stream against two or three row
+// tiles of A, M > 48 the LDS-tiled persistent kernel with producer and consumer waves.
 //
 // Operand layout of that instruction, established by one-hot probes on the GPU:
 //   lane l = (i = l % 16, g = l / 16).  An FP4 operand lane holds the 32 codes of K-block g of row /
