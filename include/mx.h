@@ -172,13 +172,13 @@ mx_status_t mx_gemm_ss_fp4(const mx_packed_t* a, const mx_packed_t* w_anchor, co
  *   kernel that has the whole compute unit for the product (the on-the-fly kernels slice every tile of W once per 256
  *   rows of A).  The results are those of mx_gemm_ss_fp4 bit for bit.
  *   Otherwise, from 49 rows on, when the tiles of C leave most compute units without one (a narrow N), K is split over
- *   2, 4 or 8 workgroups per tile whose partial sums go through the workspace and are added in the order of the slices:
+ *   2 to 8 workgroups per tile whose partial sums go through the workspace and are added in the order of the slices:
  *   still a fixed order (reproducible run to run), but not mx_gemm_ss_fp4's, so the two results differ by fp32 rounding.
  * In every other case, and with workspace == NULL, this is mx_gemm_ss_fp4. */
 #define MX_GEMM_HOIST_MIN_ROWS 512
 size_t mx_gemm_ss_fp4_workspace(int64_t n, int64_t k);
 /* The number of K slices mx_gemm_ss_fp4_ws works with for an [m, k] x [n, k] product and a workspace of that size on the
- * current device: 1 when its result is mx_gemm_ss_fp4's bit for bit, 2 / 4 / 8 when partial sums are added afterwards. */
+ * current device: 1 when its result is mx_gemm_ss_fp4's bit for bit, 2 .. 8 when partial sums are added afterwards. */
 int mx_gemm_ss_fp4_ws_slices(int64_t m, int64_t n, int64_t k, size_t workspace_bytes);
 mx_status_t mx_gemm_ss_fp4_ws(const mx_packed_t* a, const mx_packed_t* w_anchor, const mx_dense_t* c, void* workspace,
                               size_t workspace_bytes, void* stream);

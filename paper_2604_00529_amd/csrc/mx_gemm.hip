@@ -503,8 +503,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
                                                                          int64_t c_slice) {
   extern __shared__ __attribute__((aligned(16))) uint8_t gemm_smem[];
   GemmStage* stage = reinterpret_cast<GemmStage*>(gemm_smem);
-  // K can be split over gridDim.y: slice y multiplies the K elements [y k_len, (y + 1) k_len) of every row (K stays
-  // the row stride) and writes its partial sums to c + y c_slice.  One slice (k_len = K) is the whole product.
+  // K can be split over gridDim.y: slice y multiplies the K elements [y k_len, (y + 1) k_len) of every row -- the
+  // last slice what is left of K, at least one K-step -- (K stays the row stride) and writes its partial sums to
+  // c + y c_slice.  One slice (k_len = K) is the whole product.
   const uint32_t k_skip = (uint32_t)blockIdx.y * (uint32_t)k_len;
   a_codes += k_skip;
   w_codes += k_skip;
@@ -516,7 +517,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   const int tid = threadIdx.x & 255;   // index inside the role's 256 threads
   const int i = lane & 15, g = lane >> 4;
   constexpr int BN = 16 * NTW;   // columns of the workgroup tile
-  const int KB = K / 32, ksteps = k_len / kGemmBK;
+  const int KB = K / 32, ksteps = (K - (int)k_skip < k_len ? K - (int)k_skip : k_len) / kGemmBK;
   // The kernel is persistent: a workgroup works the tiles v, v + gridDim.x, ... of the tile list (bands of 8 M
   // tiles, M tile index fastest inside a band) and both roles run ONE software pipeline over all K-steps of all their tiles: the operands of the next
   // tile's first K-steps are in flight while the current tile is finished, and a consumer goes on to the next tile's
@@ -1243,13 +1244,14 @@ int gemm_splitk_slices(int64_t M, int64_t N, int64_t K, size_t workspace_bytes, 
     const int64_t cost = (tiles_c + cus - 1) / cus * ksteps * (50 + cand * 10) + 750;
     if (best < 0 || cost < best) { best = cost; best_ntw = cand; }
   }
-  for (int S = 2; S <= 8; S *= 2) {
-    if (ksteps % S != 0 || ksteps / S < 8) continue;                                     // equal slices of eight K-steps and more
+  for (int S = 2; S <= 8; ++S) {
+    const int64_t per = (ksteps + S - 1) / S;                                            // K-steps of a slice; the last one takes the rest
+    if (per < 8 || (S - 1) * per >= ksteps) continue;                                    // slices of eight K-steps and more, none empty
     if ((uint64_t)S * (uint64_t)M * (uint64_t)ldp * 4u > (uint64_t)workspace_bytes) continue;
     for (int cand = 8; cand >= 4; --cand) {
       const int64_t tiles_c = m_tiles * ((N + 16 * cand - 1) / (16 * cand));
       if (tiles_c * S > cus) continue;                                                   // one round
-      const int64_t cost = ksteps / S * (50 + cand * 10) + 750 + 420;
+      const int64_t cost = per * (20 + cand * 15) + 750 + 420;   // (with every CU at work a wide tile's K-step costs more: 256 x 4096 x 14336 in 7 slices of 128 columns 42 us, in 4 of 64 columns 39 us)
       if (cost < best) { best = cost; best_s = S; best_ntw = cand; }
     }
   }
@@ -1265,7 +1267,7 @@ bool gemm_ss_fp4_splitk(const uint8_t* a_codes, const uint8_t* a_scales, const u
   if (S == 1) return false;
   const int64_t m_tiles = (M + kGemmBM - 1) / kGemmBM, ldp = (N + 3) & ~(int64_t)3;
   const int64_t tiles = m_tiles * ((N + 16 * ntw - 1) / (16 * ntw));
-  const int64_t k_len = K / S, slice = M * ldp;
+  const int64_t k_len = (K / kGemmBK + S - 1) / S * kGemmBK, slice = M * ldp;
   float* partial = static_cast<float*>(workspace);
   constexpr int kSmem = 3 * (int)sizeof(GemmStage);
   *status = MX_ERR_LAUNCH;

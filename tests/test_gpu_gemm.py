@@ -123,14 +123,34 @@ def test_gemm_several_tiles_per_workgroup(mx, oracle, M, N, K):
     _check(mx, oracle, M, N, K, seed=M + N + K + 1, random_bytes="narrow")
 
 
-@pytest.mark.parametrize("M,N,K,S", [(64, 1024, 4096, 4), (100, 520, 2048, 2), (130, 1000, 4096, 4), (300, 776, 8192, 2),
-                                     (64, 96, 8192, 8), (49, 4096, 3584, 2)])
+@pytest.mark.parametrize("M,N,K,S", [(64, 1024, 4096, 4), (100, 520, 2048, 2), (130, 1000, 4096, 4), (300, 776, 8192, 3),
+                                     (64, 96, 8192, 8), (49, 4096, 3584, 3), (101, 1008, 11136, 8), (64, 256, 2944, 3)])
 def test_gemm_k_slices(mx, oracle, M, N, K, S):
     # few tiles and a long K: with a workspace, K is split over S workgroups per tile (on 256 compute units) and the
-    # partial sums are added by a second kernel; ragged M and N tiles, two M tiles, the fewest rows that take this way
+    # partial sums are added by a second kernel; ragged M and N tiles, two M tiles, the fewest rows that take this way,
+    # slices of unequal length (87 K-steps in 8 slices: 7 of 11 and one of 10; 23 in 3: 8, 8 and 7)
     _check(mx, oracle, M, N, K, seed=M + N + K, want_slices=S)
     _check(mx, oracle, M, N, K, seed=M + N + K + 1, random_bytes="narrow", want_slices=S)
     _check(mx, oracle, M, N, K, seed=M + N + K + 2, random_bytes="wide", want_slices=S)
+
+
+def test_gemm_seeded_sweep_of_shapes(mx, oracle):
+    # 28 shapes drawn from a seeded generator: every kernel and every way through the workspace (none, K slices,
+    # hoisted conversion) gets ragged tiles and K-step counts that nobody picked by hand
+    rng = np.random.default_rng(20260402)
+    L = mx.binding.lib()
+    seen = set()
+    for case in range(28):
+        M = int(rng.choice([rng.integers(1, 17), rng.integers(17, 49), rng.integers(49, 300), rng.integers(300, 1400)]))
+        K = 128 * int(rng.choice([rng.integers(1, 9), rng.integers(9, 40), rng.integers(40, 113)]))
+        n_max = max(16, min(6000, int(3e9 // (M * K))))
+        N = 8 * int(rng.integers(1, n_max // 8 + 1))
+        kind = case % 3
+        slices = L.mx_gemm_ss_fp4_ws_slices(M, N, K, max(16, L.mx_gemm_ss_fp4_workspace(N, K)))
+        seen.add("slices" if slices > 1 else "decode" if M <= 16 else "mid" if M <= 48 else "tiled")
+        print("case %d: M %d N %d K %d, %d slice(s)" % (case, M, N, K, slices), flush=True)
+        _check(mx, oracle, M, N, K, seed=7000 + case, w_axis0=kind == 0, random_bytes="narrow" if kind == 2 else False)
+    assert seen == {"slices", "decode", "mid", "tiled"}
 
 
 def test_gemm_few_rows_down_proj_shape(mx, oracle):
