@@ -948,11 +948,12 @@ struct BigStage {
   uint32_t as[256];       // 4 scale bytes per row (one per K-block of the step)
   uint32_t bs[256];       // 4 scale bytes per column
 };
-constexpr int kBigRequests = 8 + 4 + 1 + 1;   // per wave and K-step: 8 KB of A, 4 KB of B, 64 scale dwords of each
 
-// NTW column tiles of 16 per wave: the workgroup tile is 256 x 32 NTW (256 or 224 columns; the launcher takes the width
-// whose tiles fill the GPU's rounds better)
-template <int NTW>
+// NTW column tiles of 16 per wave: the workgroup tile is 32 NTW columns wide (256 or 224; the launcher takes the width
+// whose tiles fill the GPU's rounds better).  MTW row tiles of 16 per wave: the workgroup tile is 32 MTW rows high --
+// 256, or 128 for shapes whose 256-row tiles would leave compute units without one (the stage keeps its size; half of
+// its A part is then unused).
+template <int NTW, int MTW>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_fp8_fp4_tile256_kernel(
     const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales, const uint8_t* __restrict__ w4_codes,
     const uint8_t* __restrict__ w4_scales, float* __restrict__ c, int M, int N, int K, int64_t ldc, int m_tiles, int tiles) {
@@ -968,8 +969,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   int tm, tn;
   gemm_tile_coords(vb, shape, tm, tn);
   constexpr int BN = 32 * NTW;   // columns of the workgroup tile
-  const int m0 = tm * 256, n0 = tn * BN;
-  const int rows = M - m0 < 256 ? M - m0 : 256, cols = N - n0 < BN ? N - n0 : BN;   // the part of the tile inside C
+  constexpr int BM = 32 * MTW;   // rows of the workgroup tile
+  constexpr int kBigRequests = MTW + 4 + 1 + 1;   // per wave and K-step: MTW KB of A, 4 KB of B, 64 scale dwords of each
+  constexpr int kRequestX0 = MTW == 8 ? 10 : 4;   // the MFMA behind which the first request of a K-step goes out
+  static_assert(MTW == 8 || MTW == 4, "rows per wave");
+  static_assert(kRequestX0 + 2 * kBigRequests <= MTW * NTW + 1, "the requests of a K-step fit between its MFMAs");
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int rows = M - m0 < BM ? M - m0 : BM, cols = N - n0 < BN ? N - n0 : BN;   // the part of the tile inside C
   // descriptors over the valid rows / columns of this tile: what lies past the edge is out of range and reads as zeros
   const __amdgpu_buffer_rsrc_t a_rsrc = make_buffer(a_codes + (int64_t)m0 * K, (uint32_t)rows * (uint32_t)K);
   const __amdgpu_buffer_rsrc_t b_rsrc = make_buffer(w4_codes + (int64_t)n0 * K2, (uint32_t)cols * (uint32_t)K2);
@@ -983,15 +989,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const uint32_t s_lane = (uint32_t)(64 * wave + lane) * (uint32_t)KB;
   auto request_one = [&](int kc, uint8_t* st, auto rc) __attribute__((always_inline)) {
     constexpr int R = decltype(rc)::value;
-    if constexpr (R < 8) {
-      const int J = wave * 8 + R;   // rows 8 J + lane / 8; their swizzle term (row / 2) % 8 = lane / 16 + 4 (J % 2)
+    if constexpr (R < MTW) {
+      const int J = wave * MTW + R;   // rows 8 J + lane / 8; their swizzle term (row / 2) % 8 = lane / 16 + 4 (J % 2)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (__attribute__((address_space(3))) void*)(st + J * 1024), 16,
                                                (int)((a_lane ^ (64u * (R & 1))) + (uint32_t)(8 * J) * (uint32_t)K + (uint32_t)(kc * 128)), 0, 0, 0);
-    } else if constexpr (R < 12) {
-      const int J = wave * 4 + (R - 8);   // columns 16 J + lane / 4 (past the tile's width: out of range, zeros); their swizzle term (column / 4) % 4 = lane / 16
+    } else if constexpr (R < MTW + 4) {
+      const int J = wave * 4 + (R - MTW);   // columns 16 J + lane / 4 (past the tile's width: out of range, zeros); their swizzle term (column / 4) % 4 = lane / 16
       __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (__attribute__((address_space(3))) void*)(st + offsetof(BigStage, b) + J * 1024), 16,
                                                (int)(b_lane + (uint32_t)(16 * J) * (uint32_t)K2 + (uint32_t)(kc * 64)), 0, 0, 0);
-    } else if constexpr (R == 12) {   // rows 64 wave + lane
+    } else if constexpr (R == MTW + 4) {   // rows 64 wave + lane (past the tile's height: out of range, zeros)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(as_rsrc, (__attribute__((address_space(3))) void*)(st + offsetof(BigStage, as) + wave * 256), 4,
                                                (int)(s_lane + (uint32_t)(kc * 4)), 0, 0, 0);
     } else {                          // columns 64 wave + lane
@@ -1010,14 +1016,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     __builtin_amdgcn_s_waitcnt(wait_lgkmcnt0_vmcnt(kBigRequests));
     producer_barrier();
   };
-  f32x4 acc[8][NTW];
+  f32x4 acc[MTW][NTW];
 #pragma unroll
-  for (int mt = 0; mt < 8; ++mt)
+  for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
     for (int nt = 0; nt < NTW; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  // (the tile offsets 128 wm, 16 mt, 16 NTW wn, 16 nt do not change the swizzle term of a lane: 16 NTW / 4 is a multiple of 4)
+  // (the tile offsets 16 MTW wm, 16 mt, 16 NTW wn, 16 nt do not change the swizzle term of a lane: 16 NTW / 4 is a multiple of 4)
   static_assert((16 * NTW / 4) % 4 == 0, "swizzle term of the second column half");
-  const int a_off = (wm * 128 + i) * 128 + 16 * (g ^ ((i >> 1) & 7));   // + mt * 16 rows; second run of K: ^ 64
+  const int a_off = (wm * 16 * MTW + i) * 128 + 16 * (g ^ ((i >> 1) & 7));   // + mt * 16 rows; second run of K: ^ 64
   const int b_off = (wn * 16 * NTW + i) * 64 + 16 * (g ^ ((i >> 2) & 3));    // + nt * 16 columns
   request_step(0, 0);
   request_step(1, 1);
@@ -1045,14 +1051,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       u32x4 t0 = *reinterpret_cast<const u32x4*>(&st.a[a_off + MT * 16 * 128]);
       u32x4 t1 = *reinterpret_cast<const u32x4*>(&st.a[(a_off ^ 64) + MT * 16 * 128]);
       af[MT & 1] = i32x8{(int)t0.x, (int)t0.y, (int)t0.z, (int)t0.w, (int)t1.x, (int)t1.y, (int)t1.z, (int)t1.w};
-      sa[MT & 1] = reinterpret_cast<const uint8_t*>(st.as)[(wm * 128 + MT * 16 + i) * 4 + g];
+      sa[MT & 1] = reinterpret_cast<const uint8_t*>(st.as)[(wm * 16 * MTW + MT * 16 + i) * 4 + g];
     };
     read_a(std::integral_constant<int, 0>{});
     read_b(std::integral_constant<int, 0>{});
     read_b(std::integral_constant<int, 1>{});
     read_b(std::integral_constant<int, 2>{});
     __builtin_amdgcn_sched_barrier(0);
-    static_for<0, 8 * NTW>([&](auto xc) {
+    static_for<0, MTW * NTW>([&](auto xc) {
       constexpr int X = decltype(xc)::value, MT = X / NTW, NT = X % NTW;
       // W_t is the instruction's first operand: a lane's four results are four consecutive columns of one row of C
       acc[MT][NT] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bf[NT], af[MT & 1], acc[MT][NT], 4 /* E2M1 */, 0 /* E4M3 */, 0,
@@ -1060,9 +1066,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       asm volatile("" : "+a"(acc[MT][NT]));   // (keeps the result in its accumulation register and the MFMA in its place)
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (MT == 0 && NT + 3 < NTW) read_b(std::integral_constant<int, NT + 3>{});   // B fragments run three MFMAs ahead in the first row
-      if constexpr (NT == 1 && MT + 1 < 8) read_a(std::integral_constant<int, MT + 1>{});   // the next row tile of A, into the other register set
-      if constexpr (X >= 10 && X < 10 + 2 * kBigRequests && (X - 10) % 2 == 0)               // one request behind every other MFMA
-        request_one(kc, rst, std::integral_constant<int, (X - 10) / 2>{});
+      if constexpr (NT == 1 && MT + 1 < MTW) read_a(std::integral_constant<int, MT + 1>{});   // the next row tile of A, into the other register set
+      if constexpr (X >= kRequestX0 && X < kRequestX0 + 2 * kBigRequests && (X - kRequestX0) % 2 == 0)   // one request behind every other MFMA
+        request_one(kc, rst, std::integral_constant<int, (X - kRequestX0) / 2>{});
       __builtin_amdgcn_sched_barrier(0);
     });
     arrive();   // K-step k + 1 is complete
@@ -1070,20 +1076,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   }
   __builtin_amdgcn_s_waitcnt(0);   // the last requests (of steps that do not exist) must land before the LDS is given back
   // acc[mt][nt][j] = C[row 16 mt + i][column 16 nt + 4 g + j] of the wave's quarter
-  float* ct = c + (int64_t)(m0 + wm * 128 + i) * ldc + n0 + wn * 16 * NTW + 4 * g;
-  if (rows == 256 && cols == BN) {
+  float* ct = c + (int64_t)(m0 + wm * 16 * MTW + i) * ldc + n0 + wn * 16 * NTW + 4 * g;
+  if (rows == BM && cols == BN) {
 #pragma unroll
-    for (int mt = 0; mt < 8; ++mt)
+    for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
       for (int nt = 0; nt < NTW; ++nt) *reinterpret_cast<f32x4*>(ct + (int64_t)(mt * 16) * ldc + nt * 16) = acc[mt][nt];
   } else {
 #pragma unroll
-    for (int mt = 0; mt < 8; ++mt)
+    for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
       for (int nt = 0; nt < NTW; ++nt)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-          if (wm * 128 + mt * 16 + i < rows && wn * 16 * NTW + nt * 16 + 4 * g + j < cols) ct[(int64_t)(mt * 16) * ldc + nt * 16 + j] = acc[mt][nt][j];
+          if (wm * 16 * MTW + mt * 16 + i < rows && wn * 16 * NTW + nt * 16 + 4 * g + j < cols) ct[(int64_t)(mt * 16) * ldc + nt * 16 + j] = acc[mt][nt][j];
   }
 }
 
@@ -1294,12 +1300,20 @@ bool gemm_ss_fp4_splitk(const uint8_t* a_codes, const uint8_t* a_scales, const u
   return true;
 }
 
-// Is the product with W sliced beforehand the faster one?  Its 256 x 256 tiles must fill the GPU: measured on 256 CUs,
-// 192 tiles win (2048 x 6144 x 4096: 60 against 68 us), 128 and 112 tiles lose (2048 x 4096 x 4096: 56 against 48 us;
-// 512 x 14336 x 4096: 67 against 46 us).
+// Do tiles of 256 rows (256 columns wide) give at least 3/4 of the compute units a workgroup?
+static bool gemm_tall_tiles_fill(int64_t M, int64_t N, int cus) {
+  return 4 * (((M + 255) / 256) * ((N + 255) / 256)) >= 3 * (int64_t)cus;
+}
+
+// Is the product with W sliced beforehand the faster one?  Its tiles must fill the GPU: measured on 256 CUs, 192 tiles
+// of 256 x 256 win (2048 x 6144 x 4096: 60 against 68 us), 128 and 112 such tiles lose (2048 x 4096 x 4096: 56 against
+// 48 us; 512 x 14336 x 4096: 67 against 46 us).  There tiles of 128 rows fill the GPU, with less work per byte of
+// operand; they win from 1024 rows on (2048 x 4096 x 4096: 46 against 48 us, 2048 x 4096 x 14336: 134 against 146 us)
+// and lose below, where the conversion pass is a larger part of the call (512 x 14336 x 4096: 55 against 46 us).
 bool gemm_hoist_pays(int64_t M, int64_t N) {
   const int cus = device_compute_units();
-  return cus > 0 && 4 * (((M + 255) / 256) * ((N + 255) / 256)) >= 3 * (int64_t)cus;
+  if (cus <= 0) return false;
+  return gemm_tall_tiles_fill(M, N, cus) || (M >= 1024 && 4 * (((M + 127) / 128) * ((N + 255) / 256)) >= 3 * (int64_t)cus);
 }
 
 // The product with W already sliced (E2M1 codes [N][K / 2] and scale bytes [N][K / 32] in a workspace).
@@ -1309,27 +1323,34 @@ mx_status_t gemm_fp8_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales,
   if (256 * K > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;   // a tile is addressed with 32-bit offsets
   const int cus = device_compute_units();
   if (cus <= 0) return MX_ERR_LAUNCH;
-  // tile width 256 or 224: rounds on the GPU x width (2048 x 14336: 448 tiles of 256 columns are 1.75 rounds that take 2,
-  // 512 tiles of 224 columns two full rounds of 7/8 the work)
-  const int64_t m_tiles = (M + 255) / 256;
+  // tile height 256, or 128 when tiles of 256 rows would leave a quarter of the compute units or more without one
+  // (2048 x 4096: 128 tiles of 256 x 256, 256 of 128 x 256); tile width 256 or 224: rounds on the GPU x width
+  // (2048 x 14336: 448 tiles of 256 columns are 1.75 rounds that take 2, 512 tiles of 224 columns two full rounds of
+  // 7/8 the work)
+  const bool low = !gemm_tall_tiles_fill(M, N, cus);
+  const int64_t m_tiles = low ? (M + 127) / 128 : (M + 255) / 256;
   const int64_t t8 = m_tiles * ((N + 255) / 256), t7 = m_tiles * ((N + 223) / 224);
   const bool narrow = (t7 + cus - 1) / cus * 7 < (t8 + cus - 1) / cus * 8;
   const int64_t tiles = narrow ? t7 : t8;
   if (tiles > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
   constexpr int kSmem = 3 * (int)sizeof(BigStage);
-#define MX_GEMM_TILE256(NTW)                                                                                                \
+#define MX_GEMM_TILE256(NTW, MTW)                                                                                           \
   {                                                                                                                         \
     static bool attr_set = false;                                                                                           \
     if (!attr_set) {                                                                                                        \
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_fp8_fp4_tile256_kernel<NTW>),                              \
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_fp8_fp4_tile256_kernel<NTW, MTW>),                         \
                               hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) != hipSuccess)                             \
         return MX_ERR_LAUNCH;                                                                                               \
       attr_set = true;                                                                                                      \
     }                                                                                                                       \
-    hipLaunchKernelGGL(gemm_fp8_fp4_tile256_kernel<NTW>, dim3((unsigned)tiles), dim3(256), kSmem, stream, a_codes, a_scales, \
-                       w4_codes, w4_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles, (int)tiles);                      \
+    hipLaunchKernelGGL((gemm_fp8_fp4_tile256_kernel<NTW, MTW>), dim3((unsigned)tiles), dim3(256), kSmem, stream, a_codes,   \
+                       a_scales, w4_codes, w4_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles, (int)tiles);            \
   }
-  if (narrow) MX_GEMM_TILE256(7) else MX_GEMM_TILE256(8)
+  if (low) {
+    if (narrow) MX_GEMM_TILE256(7, 4) else MX_GEMM_TILE256(8, 4)
+  } else {
+    if (narrow) MX_GEMM_TILE256(7, 8) else MX_GEMM_TILE256(8, 8)
+  }
 #undef MX_GEMM_TILE256
   return launch_status("the MXFP8 x MXFP4 GEMM");
 }
