@@ -168,10 +168,9 @@ mx_status_t mx_gemm_ss_fp4(const mx_packed_t* a, const mx_packed_t* w_anchor, co
  * (device memory, 16-byte aligned, borrowed for the duration of the enqueued work; MX_ERR_ALIGN / MX_ERR_WORKSPACE when
  * it is misaligned or smaller).  Two things are done with it.
  *   From MX_GEMM_HOIST_MIN_ROWS rows of A on, and when C has enough tiles of 256 x 256 (from 1024 rows on: of 128 x 256)
- *   to fill the GPU, W_t (Eq. (6))
- *   is generated once per call into the workspace -- MXFP4 codes and scale bytes -- and multiplied from there by a
- *   kernel that has the whole compute unit for the product (the on-the-fly kernels slice every tile of W once per 256
- *   rows of A).  The results are those of mx_gemm_ss_fp4 bit for bit.
+ *   to fill the GPU, W_t (Eq. (6)) is generated once per call into the workspace -- MXFP4 codes and scale bytes -- and
+ *   multiplied from there by a kernel that has the whole compute unit for the product (the on-the-fly kernels slice
+ *   every tile of W once per 256 rows of A).  The results are those of mx_gemm_ss_fp4 bit for bit.
  *   Otherwise, from 49 rows on, when the tiles of C leave most compute units without one (a narrow N), K is split over
  *   2 to 8 workgroups per tile whose partial sums go through the workspace and are added in the order of the slices:
  *   still a fixed order (reproducible run to run), but not mx_gemm_ss_fp4's, so the two results differ by fp32 rounding.
