@@ -942,17 +942,23 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
 // the 8 B fragments of a K-step stay in registers, the A fragments pass through two register sets.  The sum over K
 // of every output runs in the order of the fused kernel: the results are the same bit for bit.  NTW = 7 makes the
 // tile 224 columns wide (a wave owns 128 x 112); the launcher takes it when the grid's rounds then hold fewer MFMAs.
+template <int MTW>
 struct BigStage {
-  uint8_t a[256 * 128];   // E4M3 codes, row r: 128 bytes of K, 16-byte chunk c at c ^ ((r >> 1) & 7)
-  uint8_t b[256 * 64];    // E2M1 codes, column n: 64 bytes, chunk c at c ^ ((n >> 2) & 3)
-  uint32_t as[256];       // 4 scale bytes per row (one per K-block of the step)
-  uint32_t bs[256];       // 4 scale bytes per column
+  uint8_t a[32 * MTW * 128];   // E4M3 codes of the tile's 32 MTW rows, row r: 128 bytes of K, 16-byte chunk c at c ^ ((r >> 1) & 7)
+  uint8_t b[256 * 64];         // E2M1 codes, column n: 64 bytes, chunk c at c ^ ((n >> 2) & 3)
+  uint32_t as[256];            // 4 scale bytes per row (one per K-block of the step)
+  uint32_t bs[256];            // 4 scale bytes per column
 };
+static_assert(sizeof(BigStage<8>) == 51200 && sizeof(BigStage<4>) == 34816, "stage sizes");
+// K-steps held in LDS: three of 50 KB with 256-row tiles; four of 34 KB with 128-row tiles, whose shorter K-steps need
+// their operands requested three steps ahead to cover the same latency
+template <int MTW>
+constexpr int kBigStages = MTW == 8 ? 3 : 4;
 
 // NTW column tiles of 16 per wave: the workgroup tile is 32 NTW columns wide (256 or 224; the launcher takes the width
 // whose tiles fill the GPU's rounds better).  MTW row tiles of 16 per wave: the workgroup tile is 32 MTW rows high --
-// 256, or 128 for shapes whose 256-row tiles would leave compute units without one (the stage keeps its size; half of
-// its A part is then unused).
+// 256, or 128 for shapes whose 256-row tiles would leave compute units without one (the stage
+// is smaller and there is one more of them).
 template <int NTW, int MTW>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_fp8_fp4_tile256_kernel(
     const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales, const uint8_t* __restrict__ w4_codes,
@@ -970,6 +976,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   gemm_tile_coords(vb, shape, tm, tn);
   constexpr int BN = 32 * NTW;   // columns of the workgroup tile
   constexpr int BM = 32 * MTW;   // rows of the workgroup tile
+  using Stage = BigStage<MTW>;
+  constexpr int NS = kBigStages<MTW>;   // stages: K-step s lives in stage s % NS, requested NS - 1 steps ahead
   constexpr int kBigRequests = MTW + 4 + 1 + 1;   // per wave and K-step: MTW KB of A, 4 KB of B, 64 scale dwords of each
   constexpr int kRequestX0 = MTW == 8 ? 10 : 4;   // the MFMA behind which the first request of a K-step goes out
   static_assert(MTW == 8 || MTW == 4, "rows per wave");
@@ -995,25 +1003,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                                                (int)((a_lane ^ (64u * (R & 1))) + (uint32_t)(8 * J) * (uint32_t)K + (uint32_t)(kc * 128)), 0, 0, 0);
     } else if constexpr (R < MTW + 4) {
       const int J = wave * 4 + (R - MTW);   // columns 16 J + lane / 4 (past the tile's width: out of range, zeros); their swizzle term (column / 4) % 4 = lane / 16
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (__attribute__((address_space(3))) void*)(st + offsetof(BigStage, b) + J * 1024), 16,
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (__attribute__((address_space(3))) void*)(st + offsetof(Stage, b) + J * 1024), 16,
                                                (int)(b_lane + (uint32_t)(16 * J) * (uint32_t)K2 + (uint32_t)(kc * 64)), 0, 0, 0);
     } else if constexpr (R == MTW + 4) {   // rows 64 wave + lane (past the tile's height: out of range, zeros)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(as_rsrc, (__attribute__((address_space(3))) void*)(st + offsetof(BigStage, as) + wave * 256), 4,
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(as_rsrc, (__attribute__((address_space(3))) void*)(st + offsetof(Stage, as) + wave * 256), 4,
                                                (int)(s_lane + (uint32_t)(kc * 4)), 0, 0, 0);
     } else {                          // columns 64 wave + lane
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(bs_rsrc, (__attribute__((address_space(3))) void*)(st + offsetof(BigStage, bs) + wave * 256), 4,
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(bs_rsrc, (__attribute__((address_space(3))) void*)(st + offsetof(Stage, bs) + wave * 256), 4,
                                                (int)(s_lane + (uint32_t)(kc * 4)), 0, 0, 0);
     }
   };
   // (a K-step past the end of K: the last one again, which nothing uses)
   auto request_step = [&](int ks, int stage_i) __attribute__((always_inline)) {
     const int kc = ks < ksteps ? ks : ksteps - 1;
-    uint8_t* st = big_smem + stage_i * (int)sizeof(BigStage);
+    uint8_t* st = big_smem + stage_i * (int)sizeof(Stage);
     static_for<0, kBigRequests>([&](auto rc) { request_one(kc, st, rc); });
   };
-  // my LDS reads have landed (the stage is free) and all requests but those of the youngest K-step too
+  // my LDS reads have landed (the stage is free) and all requests but those of the youngest NS - 2 K-steps too
   auto arrive = [&] {
-    __builtin_amdgcn_s_waitcnt(wait_lgkmcnt0_vmcnt(kBigRequests));
+    __builtin_amdgcn_s_waitcnt(wait_lgkmcnt0_vmcnt((NS - 2) * kBigRequests));
     producer_barrier();
   };
   f32x4 acc[MTW][NTW];
@@ -1025,15 +1033,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   static_assert((16 * NTW / 4) % 4 == 0, "swizzle term of the second column half");
   const int a_off = (wm * 16 * MTW + i) * 128 + 16 * (g ^ ((i >> 1) & 7));   // + mt * 16 rows; second run of K: ^ 64
   const int b_off = (wn * 16 * NTW + i) * 64 + 16 * (g ^ ((i >> 2) & 3));    // + nt * 16 columns
-  request_step(0, 0);
-  request_step(1, 1);
+  static_for<0, NS - 1>([&](auto sc) { request_step(decltype(sc)::value, decltype(sc)::value); });
   arrive();   // stage 0 is complete
   int cur_i = 0;
   for (int k = 0; k < ksteps; ++k) {
-    const int req_i = cur_i == 0 ? 2 : cur_i - 1;   // (k + 2) % 3: the stage that every wave left at the last barrier
-    const int kc = k + 2 < ksteps ? k + 2 : ksteps - 1;
-    uint8_t* rst = big_smem + req_i * (int)sizeof(BigStage);
-    const BigStage& st = *reinterpret_cast<const BigStage*>(big_smem + cur_i * (int)sizeof(BigStage));
+    const int req_i = cur_i == 0 ? NS - 1 : cur_i - 1;   // (k + NS - 1) % NS: the stage that every wave left at the last barrier
+    const int kc = k + NS - 1 < ksteps ? k + NS - 1 : ksteps - 1;
+    uint8_t* rst = big_smem + req_i * (int)sizeof(Stage);
+    const Stage& st = *reinterpret_cast<const Stage*>(big_smem + cur_i * (int)sizeof(Stage));
     i32x8 bf[NTW];   // only the low 4 dwords carry FP4 codes
     uint32_t sb[NTW];
 #pragma unroll
@@ -1072,7 +1079,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       __builtin_amdgcn_sched_barrier(0);
     });
     arrive();   // K-step k + 1 is complete
-    cur_i = cur_i == 2 ? 0 : cur_i + 1;
+    cur_i = cur_i == NS - 1 ? 0 : cur_i + 1;
   }
   __builtin_amdgcn_s_waitcnt(0);   // the last requests (of steps that do not exist) must land before the LDS is given back
   // acc[mt][nt][j] = C[row 16 mt + i][column 16 nt + 4 g + j] of the wave's quarter
@@ -1333,9 +1340,9 @@ mx_status_t gemm_fp8_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales,
   const bool narrow = (t7 + cus - 1) / cus * 7 < (t8 + cus - 1) / cus * 8;
   const int64_t tiles = narrow ? t7 : t8;
   if (tiles > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-  constexpr int kSmem = 3 * (int)sizeof(BigStage);
 #define MX_GEMM_TILE256(NTW, MTW)                                                                                           \
   {                                                                                                                         \
+    constexpr int kSmem = kBigStages<MTW> * (int)sizeof(BigStage<MTW>);                                                     \
     static bool attr_set = false;                                                                                           \
     if (!attr_set) {                                                                                                        \
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_fp8_fp4_tile256_kernel<NTW, MTW>),                         \

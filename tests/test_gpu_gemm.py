@@ -113,13 +113,15 @@ def test_gemm_tiled_shapes(mx, oracle, M, N, K):
 
 
 @pytest.mark.parametrize("M,N,K", [(1000, 9000, 512), (600, 16384, 512), (2048, 8192, 512), (520, 12000, 1024),
-                                   (1000, 13000, 256), (2304, 5400, 384), (1100, 6000, 512)])
+                                   (1000, 13000, 256), (2304, 5400, 384), (1100, 6000, 512), (1536, 4000, 640),
+                                   (1030, 6200, 256)])
 def test_gemm_several_tiles_per_workgroup(mx, oracle, M, N, K):
     # more tiles than compute units and K a multiple of 512: a workgroup works several tiles in one pipeline (tiles of
     # 80, 112 and 128 columns here; ragged last M and N tiles; a number of M tiles that does not divide the grid, so
     # that a workgroup's walk over the tiles wraps around).  Where C has 192 or more tiles of 256 x 256 (the second,
     # third, fifth and sixth shape) the default call slices W into a workspace first and _check compares both ways; so it
-    # does for the last shape, where 216 tiles of 128 x 256 stand in for 120 of 256 x 256 (ragged last M tile of 76 rows).
+    # does for the last three shapes, where tiles of 128 x 256 stand in for too few of 256 x 256 (ragged last M tiles of 76
+    # and 6 rows; 5 and 2 K-steps, fewer than the stages of that kernel's pipeline).
     _check(mx, oracle, M, N, K, seed=M + N + K)
     _check(mx, oracle, M, N, K, seed=M + N + K + 1, random_bytes="narrow")
 
