@@ -979,9 +979,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   using Stage = BigStage<MTW>;
   constexpr int NS = kBigStages<MTW>;   // stages: K-step s lives in stage s % NS, requested NS - 1 steps ahead
   constexpr int kBigRequests = MTW + 4 + 1 + 1;   // per wave and K-step: MTW KB of A, 4 KB of B, 64 scale dwords of each
-  constexpr int kRequestX0 = MTW == 8 ? 10 : 4;   // the MFMA behind which the first request of a K-step goes out
+  // The requests of a K-step go out behind every other MFMA from the third on (the fifth with 128-row tiles): early in
+  // the step, because the barrier of the next step waits for what they bring (from the eleventh MFMA on: 121 against
+  // 117-118 us for 2048 x 14336 x 4096; behind every MFMA from the second on: the same).
+  constexpr int kRequestX0 = MTW == 8 ? 2 : 4, kRequestStride = 2;
   static_assert(MTW == 8 || MTW == 4, "rows per wave");
-  static_assert(kRequestX0 + 2 * kBigRequests <= MTW * NTW + 1, "the requests of a K-step fit between its MFMAs");
+  static_assert(kRequestX0 + kRequestStride * (kBigRequests - 1) <= MTW * NTW - 1, "the requests of a K-step fit between its MFMAs");
   const int m0 = tm * BM, n0 = tn * BN;
   const int rows = M - m0 < BM ? M - m0 : BM, cols = N - n0 < BN ? N - n0 : BN;   // the part of the tile inside C
   // descriptors over the valid rows / columns of this tile: what lies past the edge is out of range and reads as zeros
@@ -1074,8 +1077,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (MT == 0 && NT + 3 < NTW) read_b(std::integral_constant<int, NT + 3>{});   // B fragments run three MFMAs ahead in the first row
       if constexpr (NT == 1 && MT + 1 < MTW) read_a(std::integral_constant<int, MT + 1>{});   // the next row tile of A, into the other register set
-      if constexpr (X >= kRequestX0 && X < kRequestX0 + 2 * kBigRequests && (X - kRequestX0) % 2 == 0)   // one request behind every other MFMA
-        request_one(kc, rst, std::integral_constant<int, (X - kRequestX0) / 2>{});
+      if constexpr (X >= kRequestX0 && X < kRequestX0 + kRequestStride * kBigRequests && (X - kRequestX0) % kRequestStride == 0)
+        request_one(kc, rst, std::integral_constant<int, (X - kRequestX0) / kRequestStride>{});
       __builtin_amdgcn_sched_barrier(0);
     });
     arrive();   // K-step k + 1 is complete
