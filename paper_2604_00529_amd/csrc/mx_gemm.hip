@@ -877,19 +877,29 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
           __builtin_amdgcn_raw_buffer_store_b128(u32v4{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])},
                                                  c_rsrc, (int)c_lane, (int)(((uint32_t)(wave * 64 + mt * 16) * (uint32_t)ldc + (uint32_t)(nt * 16)) * 4u), 0);
         }
-    } else {   // a tile on the edge: element by element (lane part against a scalar)
+    } else {   // a tile on the edge: the 16 x 16 pieces that lie inside C whole as above, the others element by element
+               // (lane part against a scalar); pieces wholly outside are skipped
 #pragma unroll
-      for (int mt = 0; mt < MTW; ++mt)
+      for (int mt = 0; mt < MTW; ++mt) {
+        const int rows_left = rows - (wave * 64 + mt * 16);   // rows of C from this piece's first row on (a scalar)
+        if (rows_left <= 0) continue;
 #pragma unroll
         for (int nt = 0; nt < NTW; ++nt) {
           const f32x4 v = acc[mt][nt];
-          const bool row_ok = i < rows - (wave * 64 + mt * 16);
+          const int cols_left = cols - nt * 16;
+          if (cols_left <= 0) continue;
+          const int piece = (int)(((uint32_t)(wave * 64 + mt * 16) * (uint32_t)ldc + (uint32_t)(nt * 16)) * 4u);
+          if (rows_left >= 16 && cols_left >= 16) {
+            __builtin_amdgcn_raw_buffer_store_b128(u32v4{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])},
+                                                   c_rsrc, (int)c_lane, piece, 0);
+          } else {
+            const bool row_ok = i < rows_left;
 #pragma unroll
-          for (int j = 0; j < 4; ++j)
-            if (row_ok && g4 < cols - (nt * 16 + j))
-              __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v[j]), c_rsrc, (int)c_lane,
-                                                    (int)(((uint32_t)(wave * 64 + mt * 16) * (uint32_t)ldc + (uint32_t)(nt * 16 + j)) * 4u), 0);
+            for (int j = 0; j < 4; ++j)
+              if (row_ok && g4 < cols_left - j) __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v[j]), c_rsrc, (int)c_lane, piece + 4 * j, 0);
+          }
         }
+      }
     }
   };
   constexpr int PH = NTW % RING;
