@@ -1102,14 +1102,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
       for (int nt = 0; nt < NTW; ++nt) *reinterpret_cast<f32x4*>(ct + (int64_t)(mt * 16) * ldc + nt * 16) = acc[mt][nt];
-  } else {
+  } else {   // a tile on the edge: the 16 x 16 pieces that lie inside C whole as above, the ragged ones element by element
 #pragma unroll
-    for (int mt = 0; mt < MTW; ++mt)
+    for (int mt = 0; mt < MTW; ++mt) {
+      const int rows_left = rows - (wm * 16 * MTW + mt * 16);   // (scalars: the branches are uniform)
+      if (rows_left <= 0) continue;
 #pragma unroll
-      for (int nt = 0; nt < NTW; ++nt)
+      for (int nt = 0; nt < NTW; ++nt) {
+        const int cols_left = cols - (wn * 16 * NTW + nt * 16);
+        if (cols_left <= 0) continue;
+        float* piece = ct + (int64_t)(mt * 16) * ldc + nt * 16;
+        f32x4 v = acc[mt][nt];
+        asm volatile("" : "+v"(v));   // (one piece leaves its accumulation registers at a time; all 64 at once spill)
+        if (rows_left >= 16 && cols_left >= 16) {
+          *reinterpret_cast<f32x4*>(piece) = v;
+        } else {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-          if (wm * 16 * MTW + mt * 16 + i < rows && wn * 16 * NTW + nt * 16 + 4 * g + j < cols) ct[(int64_t)(mt * 16) * ldc + nt * 16 + j] = acc[mt][nt][j];
+          for (int j = 0; j < 4; ++j)
+            if (i < rows_left && 4 * g + j < cols_left) piece[j] = v[j];
+        }
+      }
+    }
   }
 }
 
