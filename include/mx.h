@@ -12,9 +12,12 @@
  * Conventions common to every entry point
  *   - Every data pointer is a DEVICE pointer owned by the caller (borrowed for the call); the
  *     descriptor structs themselves and the format structs are HOST memory.
- *   - Nothing is allocated, freed or synchronized by the library.  Work is enqueued on the HIP
- *     stream passed as `stream` (a hipStream_t cast to void*; NULL = the default stream) and is
- *     complete when that stream reaches the end of the enqueued work.
+ *   - Nothing is allocated, freed or synchronized by the library, on the device or on the host.
+ *     Work is enqueued on the HIP stream passed as `stream` (a hipStream_t cast to void*; NULL =
+ *     the default stream) and is complete when that stream reaches the end of the enqueued work.
+ *   - The library keeps no state between calls apart from two facts it memoizes per device on
+ *     first use (its number of compute units; that a kernel has been granted its LDS size there);
+ *     calls from several threads are safe.
  *   - All arguments are validated on the host before anything is launched: a call that returns
  *     an error has had no effect on device memory.  Errors are reported by return code only.
  *   - Dense tensors are row-major [rows, cols] with leading dimension `ld` (elements, >= cols).
@@ -100,7 +103,9 @@ mx_status_t mx_packed_bytes(const mx_format_t* f, int64_t rows, int64_t cols, si
 /* Q_f, Eq. (1) and Eq. (2): per block, shared_exp = floor(log2 max|V_i|) - e_max(f), clamped to
  * [-127, 127]; P_i = quantize_f(V_i / 2^shared_exp).  src: dense, read-only.  dst: packed with
  * outer / nblocks matching src and f->axis; dst must not overlap src.  An all-zero block gets
- * scale byte 0; a block holding NaN / Inf gets scale byte 255 and zero codes. */
+ * scale byte 0; a block holding NaN / Inf gets scale byte 255 and zero codes.
+ * Codes are packed in runs of 32: with blocks of 16 and an odd number of blocks in the tensor,
+ * element widths other than 8 and 4 bits are MX_ERR_UNSUPPORTED (here and in mx_dequant). */
 mx_status_t mx_quantize(const mx_format_t* f, const mx_dense_t* src, const mx_packed_t* dst, void* stream);
 
 /* Q_{A->t}, Eq. (4) (SSMXINT) and Eq. (6) (SSMXFP): P_l = quantize_t(P_h / 2^De),

@@ -1,5 +1,5 @@
 // C-ABI layer: argument validation on the host, then dispatch to the kernel launchers.
-// Nothing here allocates, frees or synchronizes; a call that fails validation launches nothing.
+// Nothing here allocates (host or device), frees or synchronizes; a call that fails validation launches nothing.
 #include "mx_device.h"
 #include "mx_launch.h"
 #include <cstdio>
@@ -64,6 +64,13 @@ mx_status_t check_packed(const mx_packed_t* p) {
   if (!aligned16(p->codes) || !aligned16(p->scales)) return MX_ERR_ALIGN;
   if (p->outer > 0 && p->nblocks > ((int64_t)1 << 40) / p->outer) return MX_ERR_UNSUPPORTED;
   return MX_OK;
+}
+
+// Blocks of 16: the row kernels pack and unpack codes in windows of 32, so a tensor with an odd number of such blocks
+// ends in half a window.  Element widths of 8 and 4 bits keep every lane's share of a window inside whole bytes of its
+// own; the other widths share dwords across the lanes of a window and would touch bytes past the end of the codes.
+bool partial_window_unsupported(const mx_format_t* f, const ElemInfo& info, int64_t rows, int64_t cols) {
+  return f->block == 16 && (rows * cols) % 32 != 0 && info.bits != 8 && info.bits != 4;
 }
 
 // The tie rule the kernels implement in hardware conversions: ties to even on an MXFP target.
@@ -134,9 +141,10 @@ mx_status_t mx_quantize(const mx_format_t* f, const mx_dense_t* src, const mx_pa
   if ((st = blocked_shape(f, src->rows, src->cols, &outer, &nblocks)) != MX_OK) return st;
   if (outer != dst->outer || nblocks != dst->nblocks) return MX_ERR_SHAPE;
   if (outer == 0 || nblocks == 0) return MX_OK;
+  if (f->axis == 0 && f->block != 32) return MX_ERR_UNSUPPORTED;   // column blocks: 32 rows only
+  if (partial_window_unsupported(f, info, src->rows, src->cols)) return MX_ERR_UNSUPPORTED;
   mx::DenseArg s{src->data, (int)src->dtype, src->rows, src->cols, src->ld};
   drop_stale_error();
-  if (f->axis == 0 && f->block != 32) return MX_ERR_UNSUPPORTED;   // column blocks: 32 rows only
   return mx::quantize_launch((int)f->elem, f->axis, f->block, (int)f->round, s, dst->codes, dst->scales, static_cast<hipStream_t>(stream));
 }
 
@@ -193,6 +201,21 @@ size_t mx_slice_and_scale_batched_workspace(int32_t n, int64_t total_blocks) {
   return mx::ss_workspace_bytes(n, total_blocks);
 }
 
+// Validation shared by the batched entry points: every descriptor is checked before anything is launched.
+static mx_status_t check_ss_batch(int32_t n_targets, int32_t n, const mx_packed_t* anchors, const mx_packed_t* targets) {
+  mx_status_t st;
+  for (int32_t i = 0; i < n; ++i) {
+    if ((st = check_packed(&anchors[i])) != MX_OK) return st;
+    const int64_t nb = anchors[i].outer * anchors[i].nblocks;
+    for (int32_t q = 0; q < n_targets; ++q) {
+      const mx_packed_t* tq = &targets[(size_t)i * n_targets + q];
+      if ((st = check_packed(tq)) != MX_OK) return st;
+      if (nb != tq->outer * tq->nblocks) return MX_ERR_SHAPE;
+    }
+  }
+  return MX_OK;
+}
+
 mx_status_t mx_slice_and_scale_multi_batched(const mx_format_t* fa, int32_t n_targets, const mx_format_t* fts, int32_t n,
                                              const mx_packed_t* anchors, const mx_packed_t* targets, void* workspace,
                                              size_t workspace_bytes, void* stream) {
@@ -204,23 +227,10 @@ mx_status_t mx_slice_and_scale_multi_batched(const mx_format_t* fa, int32_t n_ta
   if (n == 0) return MX_OK;
   if (!anchors || !targets || !workspace) return MX_ERR_NULL;
   if (!aligned16(workspace)) return MX_ERR_ALIGN;
-  std::vector<mx::SsTensor> t((size_t)n);
-  for (int32_t i = 0; i < n; ++i) {
-    if ((st = check_packed(&anchors[i])) != MX_OK) return st;
-    int64_t nb = anchors[i].outer * anchors[i].nblocks;
-    mx::SsTensor d{};
-    d.codes_h = anchors[i].codes; d.scales_h = anchors[i].scales; d.nblocks = nb;
-    for (int32_t q = 0; q < n_targets; ++q) {
-      const mx_packed_t* tq = &targets[(size_t)i * n_targets + q];
-      if ((st = check_packed(tq)) != MX_OK) return st;
-      if (nb != tq->outer * tq->nblocks) return MX_ERR_SHAPE;
-      d.codes_l[q] = tq->codes; d.scales_l[q] = tq->scales;
-    }
-    t[(size_t)i] = d;
-  }
+  if ((st = check_ss_batch(n_targets, n, anchors, targets)) != MX_OK) return st;
   drop_stale_error();
-  return mx::ss_launch_many((int)fa->elem, tg, hw, n, t.data(), fa->block, workspace, workspace_bytes, (int)fts[0].round,
-                            static_cast<hipStream_t>(stream));
+  return mx::ss_launch_many((int)fa->elem, tg, hw, mx::SsBatch{anchors, targets, n, n_targets}, fa->block, workspace, workspace_bytes,
+                            (int)fts[0].round, static_cast<hipStream_t>(stream));
 }
 
 mx_status_t mx_slice_and_scale_batched(const mx_format_t* fa, const mx_format_t* ft, int32_t n, const mx_packed_t* anchors,
@@ -250,10 +260,10 @@ mx_status_t mx_fake_quant(const mx_format_t* target, const mx_format_t* anchor, 
   int64_t outer, nblocks;
   if ((st = blocked_shape(target, src->rows, src->cols, &outer, &nblocks)) != MX_OK) return st;
   if (outer == 0 || nblocks == 0) return MX_OK;
+  if (target->axis == 0 && target->block != 32) return MX_ERR_UNSUPPORTED;   // column blocks: 32 rows only
   mx::DenseArg s{src->data, (int)src->dtype, src->rows, src->cols, src->ld};
   mx::DenseArg d{dst->data, (int)dst->dtype, dst->rows, dst->cols, dst->ld};
   drop_stale_error();
-  if (target->axis == 0 && target->block != 32) return MX_ERR_UNSUPPORTED;   // column blocks: 32 rows only
   return mx::fake_quant_launch((int)target->elem, anchor_elem, target->axis, target->block, (int)target->round, s, d,
                                static_cast<hipStream_t>(stream));
 }
@@ -268,9 +278,10 @@ mx_status_t mx_dequant(const mx_format_t* f, const mx_packed_t* src, const mx_de
   if ((st = blocked_shape(f, dst->rows, dst->cols, &outer, &nblocks)) != MX_OK) return st;
   if (outer != src->outer || nblocks != src->nblocks) return MX_ERR_SHAPE;
   if (outer == 0 || nblocks == 0) return MX_OK;
+  if (f->axis == 0 && f->block != 32) return MX_ERR_UNSUPPORTED;   // column blocks: 32 rows only
+  if (partial_window_unsupported(f, info, dst->rows, dst->cols)) return MX_ERR_UNSUPPORTED;
   mx::DenseArg d{dst->data, (int)dst->dtype, dst->rows, dst->cols, dst->ld};
   drop_stale_error();
-  if (f->axis == 0 && f->block != 32) return MX_ERR_UNSUPPORTED;   // column blocks: 32 rows only
   return mx::dequant_launch((int)f->elem, f->axis, f->block, src->codes, src->scales, d, static_cast<hipStream_t>(stream));
 }
 

@@ -10,30 +10,17 @@
 #include "mx_device.h"
 #include "mx_launch.h"
 
-#ifndef MX_FQ_THREADS
-#define MX_FQ_THREADS 64
-#endif
-
-#ifndef MX_NT_LOAD
-#define MX_NT_LOAD 1
-#endif
-#ifndef MX_NT_STORE
-#define MX_NT_STORE 1
-#endif
-
 namespace mx {
 
 // Streaming accesses: every input is read once and every output written once per launch.  Non-temporal
 // loads and stores are worth two to five points of HBM bandwidth here, and far more with several chunks per lane.
 template <typename T>
 __device__ __forceinline__ T stream_load(const T* p) {
-  if constexpr (MX_NT_LOAD) return __builtin_nontemporal_load(p);
-  else return *p;
+  return __builtin_nontemporal_load(p);
 }
 template <typename T>
 __device__ __forceinline__ void stream_store(T* p, T v) {
-  if constexpr (MX_NT_STORE) __builtin_nontemporal_store(v, p);
-  else *p = v;
+  __builtin_nontemporal_store(v, p);
 }
 
 // ------------------------------------------------------------------ dense chunks
@@ -683,7 +670,6 @@ __global__ __launch_bounds__(TPB) void fake_quant_cols_kernel(const void* __rest
 }
 
 // ------------------------------------------------------------------ host launchers
-#ifndef MX_DENSE_KERNELS_ONLY   // (a tuning harness can include this file for the kernels alone)
 // Launch shape of the row-axis kernels: chunks per lane and lanes per workgroup.  Which shape streams best
 // depends on the read : write mix and on the arithmetic per element, so it is chosen per element format
 // (measured on 1 GiB bf16 tensors; the figures are percent of the 8 TB/s HBM peak).
@@ -704,7 +690,7 @@ constexpr RowsShape dequant_shape() {
   return RowsShape{1, 64};                                                     // 8-bit: 83
 }
 constexpr int kFqUnroll = 1;                  // fake-quant: one chunk per lane, one wave per workgroup (82 - 83)
-constexpr int kFqThreads = MX_FQ_THREADS;
+constexpr int kFqThreads = 64;
 
 
 // lanes of N elements per block of `block` elements, as a power of two (block = 16 .. 128, N = 4 or 8)
@@ -860,7 +846,5 @@ mx_status_t fake_quant_launch(int target, int anchor, int axis, int block, int t
 #undef X
   return MX_ERR_FORMAT;
 }
-
-#endif  // MX_DENSE_KERNELS_ONLY
 
 }  // namespace mx

@@ -18,6 +18,8 @@
 #include "mx_device.h"
 #include "mx_launch.h"
 
+#include <atomic>
+
 namespace mx {
 
 typedef int i32x8 __attribute__((ext_vector_type(8)));
@@ -429,10 +431,7 @@ constexpr int kGemmBM = 256, kGemmBN = 128, kGemmBK = 128;
 constexpr int kGemmLdA = 128, kGemmLdB = 64;   // unpadded rows; 16-byte chunks are XOR-swizzled (see GemmStage)
 constexpr int kGemmAChunks = kGemmBM * kGemmBK / 16 / 256;   // 16-byte A chunks per producer thread and K-step (8)
 constexpr int kGemmThreads = 512;
-#ifndef MX_GEMM_WDEPTH
-#define MX_GEMM_WDEPTH 6
-#endif
-constexpr int kGemmWDepth = MX_GEMM_WDEPTH;   // K-steps of W in flight per producer thread (weights streaming from HBM:
+constexpr int kGemmWDepth = 6;                // K-steps of W in flight per producer thread (weights streaming from HBM:
                                               // 3 -> 182 us, 6 -> 176 us, 10 -> 189 us for 2048 x 14336 x 4096)
 
 // LDS layout of one K-step.  The 16-byte chunk c of row r of A lives at chunk c ^ ((r >> 1) & 7) of that row, chunk c
@@ -453,17 +452,6 @@ constexpr int wait_lgkmcnt0_vmcnt(int v) { return (v & 15) | (7 << 4) | (0 << 8)
 // operations across it.
 __device__ __forceinline__ void producer_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
-// SKIP is 0 in the library; a tuning harness instantiates other values to take parts of the kernel out
-// (1: no slicing, 4: no MFMA, 8: A requested only for the first K-steps, 16: no LDS reads in the consumer loop,
-// 512 / 1024: every workgroup loads the first tile of W / of A, 2048: the consumers' barrier does not wait for A,
-// 4096: the tile index is the workgroup index, without the XCD-aware order).
-#ifdef MX_GEMM_TIMING
-__device__ long long g_gemm_times[4096][4];   // tuning harness only: clock readings of consumer wave 0 of each workgroup
-#define MX_GEMM_STAMP(slot) \
-  if (wave == 0 && lane == 0 && blockIdx.x < 4096) g_gemm_times[blockIdx.x][slot] = (long long)wall_clock64();
-#else
-#define MX_GEMM_STAMP(slot)
-#endif
 // Order of the tile list: bands of kGemmBandM M tiles; inside a band the M tile index runs fastest.  A run of
 // consecutive list entries is then a block of (up to) 8 M tiles x a few N tiles whatever M is -- with the M tile index
 // fastest over ALL of M, a run of 32 entries of a 32-M-tile problem is 32 different A tiles and one W tile, and A
@@ -493,7 +481,7 @@ __device__ __forceinline__ void gemm_advance(GemmCursor& cur, int ksteps, const 
   else if (cur.tiles_left > 1) gemm_next_tile(cur, sh);
 }
 
-template <int NTW, int SKIP>
+template <int NTW>
 __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const uint8_t* __restrict__ a_codes,
                                                                          const uint8_t* __restrict__ a_scales,
                                                                          const uint8_t* __restrict__ w_codes,
@@ -527,7 +515,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   // NEIGHBOURING tiles of every round of gridDim.x tiles -- a block of 8 M tiles x a few N tiles -- so that what one of
   // them brings into the XCD's L2 the others use: with v = b an XCD held one M tile and fetched every tile of W.
   const int grid = (int)gridDim.x;
-  const int vb = (SKIP & 4096) || grid % 8 != 0 ? (int)blockIdx.x : ((int)blockIdx.x % 8) * (grid / 8) + (int)blockIdx.x / 8;
+  const int vb = grid % 8 != 0 ? (int)blockIdx.x : ((int)blockIdx.x % 8) * (grid / 8) + (int)blockIdx.x / 8;
   const int my_tiles = (tiles - vb + grid - 1) / grid;   // >= 1: the grid is <= tiles
   const int total = my_tiles * ksteps;                                                     // K-steps of this workgroup
   const GemmTileShape shape = {m_tiles, tiles / m_tiles, grid};
@@ -567,37 +555,31 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
       const uint32_t a_lane = (uint32_t)(lane >> 3) * (uint32_t)K + 16u * (uint32_t)((lane & 7) ^ (lane >> 4));
       const uint32_t s_lane = (uint32_t)lane * (uint32_t)KB;
       GemmCursor rq = first;   // the K-step requested next
-      int issued = 0;
       auto request_step = [&](int stage_i) __attribute__((always_inline)) {
-        const int m0 = (SKIP & 1024) ? 0 : rq.tm * kGemmBM;
+        const int m0 = rq.tm * kGemmBM;
         const int rows = M - m0 < kGemmBM ? M - m0 : kGemmBM;
         // (the bases are k_skip bytes into row m0, so the descriptors end that much earlier: at the end of the last valid row)
         const __amdgpu_buffer_rsrc_t c_rsrc = make_buffer(a_codes + (int64_t)m0 * K, (uint32_t)rows * (uint32_t)K - k_skip);
         const __amdgpu_buffer_rsrc_t s_rsrc = make_buffer(a_scales + (int64_t)m0 * KB, (uint32_t)rows * (uint32_t)KB - k_skip / 32);
         uint8_t* st = gemm_smem + stage_i * (int)sizeof(GemmStage);
         const uint32_t k_off = (uint32_t)(rq.k * kGemmBK), ks_off = (uint32_t)(rq.k * 4);
-        const bool skip = (SKIP & 8) && issued >= 4;   // (timing only)
-        if (!skip) {
-          static_for<0, kGemmBM * kGemmBK / 1024>([&](auto jc) {
-            constexpr int J = decltype(jc)::value;
-            // rows 8 J + lane / 8; their swizzle term (row / 2) % 8 = lane / 16 + 4 (J % 2)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(c_rsrc, (__attribute__((address_space(3))) void*)(st + J * 1024), 16,
-                                                     (int)((a_lane ^ (64u * (J & 1))) + (uint32_t)(8 * J) * (uint32_t)K + k_off), 0, 0, 0);
-          });
-          static_for<0, kGemmBM / 64>([&](auto jc) {
-            constexpr int J = decltype(jc)::value;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(s_rsrc, (__attribute__((address_space(3))) void*)(st + offsetof(GemmStage, as) + J * 256), 4,
-                                                     (int)(s_lane + (uint32_t)(64 * J) * (uint32_t)KB + ks_off), 0, 0, 0);
-          });
-        }
-        ++issued;
+        static_for<0, kGemmBM * kGemmBK / 1024>([&](auto jc) {
+          constexpr int J = decltype(jc)::value;
+          // rows 8 J + lane / 8; their swizzle term (row / 2) % 8 = lane / 16 + 4 (J % 2)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(c_rsrc, (__attribute__((address_space(3))) void*)(st + J * 1024), 16,
+                                                   (int)((a_lane ^ (64u * (J & 1))) + (uint32_t)(8 * J) * (uint32_t)K + k_off), 0, 0, 0);
+        });
+        static_for<0, kGemmBM / 64>([&](auto jc) {
+          constexpr int J = decltype(jc)::value;
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(s_rsrc, (__attribute__((address_space(3))) void*)(st + offsetof(GemmStage, as) + J * 256), 4,
+                                                   (int)(s_lane + (uint32_t)(64 * J) * (uint32_t)KB + ks_off), 0, 0, 0);
+        });
         gemm_advance(rq, ksteps, shape);
       };
       // arrive at a barrier when everything but the `kRequests` youngest requests has landed (vector memory operations
       // of a wave complete in the order of issue); no fence, which would wait for those too
       auto arrive = [&] {
-        if constexpr (SKIP & 8) __builtin_amdgcn_s_waitcnt(0);
-        else __builtin_amdgcn_s_waitcnt(wait_lgkmcnt0_vmcnt(kRequests));
+        __builtin_amdgcn_s_waitcnt(wait_lgkmcnt0_vmcnt(kRequests));
         producer_barrier();
       };
       request_step(0);
@@ -640,7 +622,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
     GemmCursor ld = first;   // the K-step that the next call of load_step requests
     auto load_step = [&](auto slot_c) __attribute__((always_inline)) {
       constexpr int S = decltype(slot_c)::value;
-      const int m0 = ld.tm * kGemmBM, n0 = (SKIP & 512) ? 0 : ld.tn * BN;
+      const int m0 = ld.tm * kGemmBM, n0 = ld.tn * BN;
       const int k0 = ld.k * kGemmBK;
 #pragma unroll
       for (int j = 0; j < WP; ++j) {
@@ -663,11 +645,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
       for (int j = 0; j < WP; ++j) {
         const int q = pt + PT * j, col = q >> 3, kb = (q & 7) >> 1, half = q & 1;
         uint32_t b2[2];
-        if constexpr (SKIP & 1) {
-          b2[0] = rb[S][j].x ^ rb[S][j].y; b2[1] = rb[S][j].z ^ rb[S][j].w;
-        } else {
-          slice_half_block_e2m1(rb[S][j], b2);   // Eq. (6) element step, once per workgroup and K-step
-        }
+        slice_half_block_e2m1(rb[S][j], b2);   // Eq. (6) element step, once per workgroup and K-step
         // (the spare threads of the last piece, which loaded the tile's last column again, store nothing)
         if (col < BN) *reinterpret_cast<u32x2*>(&st.b[col * kGemmLdB + 16 * (kb ^ ((col >> 2) & 3)) + 8 * half]) = u32x2{b2[0], b2[1]};
       }
@@ -749,18 +727,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   };
   auto mfma_one = [&](auto set_c, auto slot_c, auto mt_c, auto nt_c) {
     constexpr int SET = decltype(set_c)::value, R = decltype(slot_c)::value, MT = decltype(mt_c)::value, NT = decltype(nt_c)::value;
-    if constexpr (SKIP & 4) {
-      acc[MT][NT][0] += __int_as_float(af[SET][MT][0] ^ bf[R][0] ^ (int)sa[SET][MT]);
-      acc[MT][NT][1] += __int_as_float(af[SET][MT][7] ^ bf[R][3] ^ (int)sb[R]);
-    } else {
-      // W is the instruction's first operand, so a lane's four results are four consecutive COLUMNS of one row of C
-      // (one 16-byte store): acc[MT][NT][j] = C[row 16 MT + i][column 16 NT + 4 g + j] of the wave's part of the tile
-      acc[MT][NT] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bf[R], af[SET][MT], acc[MT][NT], 4, 0, 0, (int)sb[R], 0,
-                                                                     (int)sa[SET][MT]);
-      // (an MFMA has no side effect, so the compiler may move it down into the block of its next use, across the
-      // scheduling barriers; the empty statement, which it must not move, holds the result where it is)
-      asm volatile("" : "+v"(acc[MT][NT]));
-    }
+    // W is the instruction's first operand, so a lane's four results are four consecutive COLUMNS of one row of C
+    // (one 16-byte store): acc[MT][NT][j] = C[row 16 MT + i][column 16 NT + 4 g + j] of the wave's part of the tile
+    acc[MT][NT] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bf[R], af[SET][MT], acc[MT][NT], 4, 0, 0, (int)sb[R], 0,
+                                                                   (int)sa[SET][MT]);
+    // (an MFMA has no side effect, so the compiler may move it down into the block of its next use, across the
+    // scheduling barriers; the empty statement, which it must not move, holds the result where it is)
+    asm volatile("" : "+v"(acc[MT][NT]));
   };
   // A: 16-byte chunk q = tid + 256 j (j < 8) of the tile: row q / 8, position q % 8 in that row of the LDS tile.
   // Requested with LDS as the destination (no registers, no LDS store instruction): the hardware puts lane l's 16
@@ -773,7 +746,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   // offset, because the range check looks at the lane offset only.)
   const uint32_t a_lane = (uint32_t)(tid >> 3) * (uint32_t)K + 16u * (uint32_t)((tid & 7) ^ ((tid >> 4) & 7));
   auto a_tile = [&](const GemmCursor& cur) {
-    const int m0 = (SKIP & 1024) ? 0 : cur.tm * kGemmBM;
+    const int m0 = cur.tm * kGemmBM;
     const int rows = M - m0 < kGemmBM ? M - m0 : kGemmBM;
     return make_buffer(a_codes + (int64_t)m0 * K, (uint32_t)rows * (uint32_t)K - k_skip);   // (ends with the last valid row)
   };
@@ -781,7 +754,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   auto request_a = [&](__amdgpu_buffer_rsrc_t rsrc, int ks, int stage_i, auto jc) __attribute__((always_inline)) {
     constexpr int J = decltype(jc)::value;
     if constexpr (kLoader) return;   // (the loader wave requests A)
-    if constexpr ((SKIP & 8) != 0) { if (ks > 3) return; }
     const int kc = ks < ksteps ? ks : ksteps - 1;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(
         rsrc, (__attribute__((address_space(3))) void*)(gemm_smem + stage_i * (int)sizeof(GemmStage) + J * 4096 + wave * 1024), 16,
@@ -796,7 +768,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   constexpr int kBarrierX = (NTW - RING) * MTW + MTW - 1;   // the MFMA after which the ring first needs the next stage
   constexpr int kYoungerInStep = kBarrierX + 1 < kGemmAChunks ? kBarrierX + 1 : kGemmAChunks;
   auto consumer_barrier = [&](auto younger_c) {
-    if constexpr (kLoader || (SKIP & 2048)) __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);   // (the loader waits for A; 2048: timing only)
+    if constexpr (kLoader) __builtin_amdgcn_s_waitcnt(kWaitLgkmcnt0);   // (the loader waits for A)
     else __builtin_amdgcn_s_waitcnt(wait_lgkmcnt0_vmcnt(decltype(younger_c)::value));
     producer_barrier();
   };
@@ -817,18 +789,16 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
         request_a(req_rsrc, req_k, req_i, xc);   // A of the step after next, into the stage that every consumer left a step ago
       }
       if constexpr (X == kBarrierX) consumer_barrier(std::integral_constant<int, kYoungerInStep>{});   // every read of this stage has landed; the next one is complete
-      if constexpr (!(SKIP & 16)) {
-        if constexpr (MT == MTW - 1) {
-          // the ring set of this column tile is free: fragment NT + RING, of this K-step or of the next
-          if constexpr (NT + RING < NTW) read_b(cur, std::integral_constant<int, NT + RING>{}, SLOT{});
-          else read_b(nxt, std::integral_constant<int, NT + RING - NTW>{}, SLOT{});
-        }
-        if constexpr (X >= kBarrierX) {
-          // behind the barrier: the A fragments of the next K-step, spread over the remaining MFMAs
-          constexpr int kLeft = NTW * MTW - kBarrierX;                  // MFMA slots from here on (13)
-          constexpr int P0 = (X - kBarrierX) * kPieces / kLeft, P1 = (X - kBarrierX + 1) * kPieces / kLeft;
-          static_for<P0, P1>([&](auto pc) { read_a_piece(nxt, NSET{}, pc); });
-        }
+      if constexpr (MT == MTW - 1) {
+        // the ring set of this column tile is free: fragment NT + RING, of this K-step or of the next
+        if constexpr (NT + RING < NTW) read_b(cur, std::integral_constant<int, NT + RING>{}, SLOT{});
+        else read_b(nxt, std::integral_constant<int, NT + RING - NTW>{}, SLOT{});
+      }
+      if constexpr (X >= kBarrierX) {
+        // behind the barrier: the A fragments of the next K-step, spread over the remaining MFMAs
+        constexpr int kLeft = NTW * MTW - kBarrierX;                  // MFMA slots from here on (13)
+        constexpr int P0 = (X - kBarrierX) * kPieces / kLeft, P1 = (X - kBarrierX + 1) * kPieces / kLeft;
+        static_for<P0, P1>([&](auto pc) { read_a_piece(nxt, NSET{}, pc); });
       }
       __builtin_amdgcn_sched_barrier(0);
     });
@@ -848,11 +818,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   };
   next_round(nx);
   __amdgpu_buffer_rsrc_t rs_at = a_tile(at), rs_nx = a_tile(nx);
-  MX_GEMM_STAMP(0)
   static_for<0, kGemmAChunks>([&](auto jc) { request_a(rs_at, 0, 0, jc); });
   static_for<0, kGemmAChunks>([&](auto jc) { request_a(rs_at, 1, 1, jc); });
   consumer_barrier(std::integral_constant<int, kGemmAChunks>{});   // stage 0 is filled (the requests of stage 1 may be in flight)
-  MX_GEMM_STAMP(1)
   static_for<0, kPieces>([&](auto pc) { read_a_piece(stage[0], std::integral_constant<int, 0>{}, pc); });
   static_for<0, RING>([&](auto rc) { read_b(stage[0], rc, rc); });
   __builtin_amdgcn_sched_barrier(0);
@@ -934,9 +902,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
     if (s < total) { k_step(cur_i, C0{}, std::integral_constant<int, (2 * PH) % RING>{}, rs_at, at.k + 4); step_done(); }
     store_tile();
   }
-  MX_GEMM_STAMP(2)
   __builtin_amdgcn_s_waitcnt(0);   // the last requests (of steps that do not exist) must land before the LDS is given back
-  MX_GEMM_STAMP(3)
 }
 
 // ------------------------------------------------------------------ large M, W already sliced: 256 x 256 (or 224) tiles, four waves
@@ -1126,17 +1092,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   }
 }
 
-// compute units of the current device (asked once per device); 0 on failure
-static int device_compute_units() {
-  static int cu_count[64] = {};
+// Two facts about a device are memoized, per device and safely under concurrent callers (atomics; both are
+// properties that never change, and asking or setting twice is harmless): its number of compute units, and that a
+// kernel has been allowed its dynamic LDS size there (hipFuncSetAttribute acts on the current device).
+static int current_device() {
   int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
-  if (cu_count[dev] == 0) {
-    int n = 0;
+  return hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64 ? dev : -1;
+}
+static int device_compute_units() {   // 0 on failure
+  static std::atomic<int> cu_count[64];
+  const int dev = current_device();
+  if (dev < 0) return 0;
+  int n = cu_count[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 0;
-    cu_count[dev] = n;
+    cu_count[dev].store(n, std::memory_order_relaxed);
   }
-  return cu_count[dev];
+  return n;
+}
+template <auto Kernel>
+static bool allow_dynamic_lds(int bytes) {
+  static std::atomic<uint64_t> done{0};   // bit d: set on device d
+  const int dev = current_device();
+  if (dev < 0) return false;
+  if (done.load(std::memory_order_acquire) >> dev & 1u) return true;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+    return false;
+  done.fetch_or((uint64_t)1 << dev, std::memory_order_release);
+  return true;
 }
 
 mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
@@ -1151,13 +1134,7 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
 #define MX_GEMM_MIDM(MT, NT)                                                                                               \
   if (mt_mid == MT && nt_mid == NT) {                                                                                      \
     constexpr int kSmem = 4 * NT * 8192;                                                                                   \
-    static bool attr_set = false;                                                                                          \
-    if (!attr_set) {                                                                                                       \
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ss_fp4_midm_kernel<MT, NT>),                              \
-                              hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) != hipSuccess)                            \
-        return MX_ERR_LAUNCH;                                                                                              \
-      attr_set = true;                                                                                                     \
-    }                                                                                                                      \
+    if (!allow_dynamic_lds<gemm_ss_fp4_midm_kernel<MT, NT>>(kSmem)) return MX_ERR_LAUNCH;                                   \
     hipLaunchKernelGGL((gemm_ss_fp4_midm_kernel<MT, NT>), dim3((unsigned)((N + 16 * NT - 1) / (16 * NT))), dim3(256),      \
                        kSmem, stream, a_codes, a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc);              \
   }
@@ -1195,14 +1172,8 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
     constexpr int kSmem = 3 * (int)sizeof(GemmStage);
 #define MX_GEMM_TILED(NTW)                                                                                                  \
   if (ntw == NTW) {                                                                                                         \
-    static bool attr_set = false;                                                                                           \
-    if (!attr_set) {                                                                                                        \
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ss_fp4_tiled_kernel<NTW, 0>),                              \
-                              hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) != hipSuccess)                             \
-        return MX_ERR_LAUNCH;                                                                                               \
-      attr_set = true;                                                                                                      \
-    }                                                                                                                       \
-    hipLaunchKernelGGL((gemm_ss_fp4_tiled_kernel<NTW, 0>), dim3((unsigned)grid_wgs), dim3(kGemmThreads), kSmem, stream,     \
+    if (!allow_dynamic_lds<gemm_ss_fp4_tiled_kernel<NTW>>(kSmem)) return MX_ERR_LAUNCH;                                     \
+    hipLaunchKernelGGL((gemm_ss_fp4_tiled_kernel<NTW>), dim3((unsigned)grid_wgs), dim3(kGemmThreads), kSmem, stream,     \
                        a_codes, a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles, (int)tiles,      \
                        (int)K, (int64_t)0);                                                                                \
   }
@@ -1217,13 +1188,7 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
     if (cus <= 0) return MX_ERR_LAUNCH;
 #define MX_GEMM_DECODE(NT)                                                                                                  \
   {                                                                                                                         \
-    static bool attr_set = false;                                                                                           \
-    if (!attr_set) {                                                                                                        \
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ss_fp4_decode_kernel<NT>),                                 \
-                              hipFuncAttributeMaxDynamicSharedMemorySize, decode_smem_bytes(NT)) != hipSuccess)            \
-        return MX_ERR_LAUNCH;                                                                                               \
-      attr_set = true;                                                                                                      \
-    }                                                                                                                       \
+    if (!allow_dynamic_lds<gemm_ss_fp4_decode_kernel<NT>>(decode_smem_bytes(NT))) return MX_ERR_LAUNCH;                     \
     hipLaunchKernelGGL(gemm_ss_fp4_decode_kernel<NT>, dim3((unsigned)((N + 16 * NT - 1) / (16 * NT))), dim3(256),           \
                        decode_smem_bytes(NT), stream, a_codes, a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc); \
   }
@@ -1312,14 +1277,8 @@ bool gemm_ss_fp4_splitk(const uint8_t* a_codes, const uint8_t* a_scales, const u
   *status = MX_ERR_LAUNCH;
 #define MX_GEMM_TILED_SPLIT(NTW)                                                                                            \
   if (ntw == NTW) {                                                                                                         \
-    static bool attr_set = false;                                                                                           \
-    if (!attr_set) {                                                                                                        \
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ss_fp4_tiled_kernel<NTW, 0>),                              \
-                              hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) != hipSuccess)                             \
-        return true;                                                                                                        \
-      attr_set = true;                                                                                                      \
-    }                                                                                                                       \
-    hipLaunchKernelGGL((gemm_ss_fp4_tiled_kernel<NTW, 0>), dim3((unsigned)tiles, (unsigned)S), dim3(kGemmThreads), kSmem,   \
+    if (!allow_dynamic_lds<gemm_ss_fp4_tiled_kernel<NTW>>(kSmem)) return true;                                              \
+    hipLaunchKernelGGL((gemm_ss_fp4_tiled_kernel<NTW>), dim3((unsigned)tiles, (unsigned)S), dim3(kGemmThreads), kSmem,   \
                        stream, a_codes, a_scales, w_codes, w_scales, partial, (int)M, (int)N, (int)K, ldp, (int)m_tiles,    \
                        (int)tiles, (int)k_len, slice);                                                                      \
   }
@@ -1369,13 +1328,7 @@ mx_status_t gemm_fp8_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales,
 #define MX_GEMM_TILE256(NTW, MTW)                                                                                           \
   {                                                                                                                         \
     constexpr int kSmem = kBigStages<MTW> * (int)sizeof(BigStage<MTW>);                                                     \
-    static bool attr_set = false;                                                                                           \
-    if (!attr_set) {                                                                                                        \
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_fp8_fp4_tile256_kernel<NTW, MTW>),                         \
-                              hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) != hipSuccess)                             \
-        return MX_ERR_LAUNCH;                                                                                               \
-      attr_set = true;                                                                                                      \
-    }                                                                                                                       \
+    if (!allow_dynamic_lds<gemm_fp8_fp4_tile256_kernel<NTW, MTW>>(kSmem)) return MX_ERR_LAUNCH;                             \
     hipLaunchKernelGGL((gemm_fp8_fp4_tile256_kernel<NTW, MTW>), dim3((unsigned)tiles), dim3(256), kSmem, stream, a_codes,   \
                        a_scales, w4_codes, w4_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles, (int)tiles);            \
   }

@@ -3,8 +3,6 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include <vector>
-
 #include "mx.h"
 
 namespace mx {
@@ -56,9 +54,28 @@ struct SsTargets {
   int n;
 };
 
+// The tensors of a batched launch, read from the caller's descriptor arrays where they lie (nothing is copied):
+// targets[i * n_targets + q] is target q of anchor i.
+struct SsBatch {
+  const mx_packed_t* anchors;
+  const mx_packed_t* targets;
+  int n, n_targets;
+  SsTensor tensor(int i) const {
+    SsTensor t{};
+    t.codes_h = anchors[i].codes;
+    t.scales_h = anchors[i].scales;
+    t.nblocks = anchors[i].outer * anchors[i].nblocks;
+    for (int q = 0; q < n_targets; ++q) {
+      t.codes_l[q] = targets[(size_t)i * n_targets + q].codes;
+      t.scales_l[q] = targets[(size_t)i * n_targets + q].scales;
+    }
+    return t;
+  }
+};
+
 mx_status_t ss_launch_one(int anchor, const SsTargets& tg, bool hw, const SsTensor& t, int block, int tie, hipStream_t stream);
 size_t ss_workspace_bytes(int n, int64_t total_blocks);
-mx_status_t ss_launch_many(int anchor, const SsTargets& tg, bool hw, int n, const SsTensor* h_tensors, int block, void* workspace,
+mx_status_t ss_launch_many(int anchor, const SsTargets& tg, bool hw, const SsBatch& batch, int block, void* workspace,
                            size_t workspace_bytes, int tie, hipStream_t stream);
 
 // Dense <-> packed kernels.  `dense` / `ld` in elements of dtype; outer / nblocks as in mx.h.

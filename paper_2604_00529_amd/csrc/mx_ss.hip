@@ -295,10 +295,7 @@ static mx_status_t launch_ss_batched(const SsSegment* segs, int64_t nseg, int se
   // With three targets the launch writes twice what it reads, and HBM then does better with fewer waves in
   // flight (a narrower front of open pages): unused dynamic LDS holds a CU at about 22 workgroups (measured:
   // 69.9 -> 72.3 % of peak; every launch with fewer targets loses bandwidth under any such cap).
-#ifndef MX_SS_PAD
-#define MX_SS_PAD 5632
-#endif
-  constexpr unsigned occupancy_pad = sizeof...(TARGETS) >= 3 ? MX_SS_PAD : 0;
+  constexpr unsigned occupancy_pad = sizeof...(TARGETS) >= 3 ? 5632 : 0;
   hipLaunchKernelGGL((ss_batched_kernel<ANCHOR, HW, TARGETS...>), dim3((unsigned)(nseg << seg_shift)), dim3(kSsLanes), occupancy_pad, stream,
                      segs, (int)nseg, seg_shift, ahead, tie);
   return launch_status("a Slice-and-Scale kernel");
@@ -363,11 +360,11 @@ static inline void ss_segments_of(int64_t nblocks, int block, int cpl, int seg_s
   *scale_segs = ceil_div(ceil_div(nblocks, 16), items);
 }
 
-static int64_t ss_count_segments(int n, const SsTensor* t, int block, int cpl, int seg_shift) {
+static int64_t ss_count_segments(const SsBatch& batch, int block, int cpl, int seg_shift) {
   int64_t nseg = 0;
-  for (int i = 0; i < n; ++i) {
+  for (int i = 0; i < batch.n; ++i) {
     int64_t cs, ss;
-    ss_segments_of(t[i].nblocks, block, cpl, seg_shift, &cs, &ss);
+    ss_segments_of(batch.anchors[i].outer * batch.anchors[i].nblocks, block, cpl, seg_shift, &cs, &ss);
     nseg += cs + ss;
   }
   return nseg;
@@ -382,17 +379,17 @@ size_t ss_workspace_bytes(int n, int64_t total_blocks) {
   return sizeof(SsSegment) * (size_t)segs;
 }
 
-mx_status_t ss_launch_many(int anchor, const SsTargets& tg, bool hw, int n, const SsTensor* h_tensors, int block, void* workspace,
+mx_status_t ss_launch_many(int anchor, const SsTargets& tg, bool hw, const SsBatch& batch, int block, void* workspace,
                            size_t workspace_bytes, int tie, hipStream_t stream) {
-  const int cpl = ss_cpl(tg);
+  const int cpl = ss_cpl(tg), n = batch.n;
   for (int i = 0; i < n; ++i)
-    if ((h_tensors[i].nblocks * block) % cpl) return MX_ERR_UNSUPPORTED;   // odd widths convert whole runs of 32 codes
+    if ((batch.anchors[i].outer * batch.anchors[i].nblocks * block) % cpl) return MX_ERR_UNSUPPORTED;   // odd widths convert whole runs of 32 codes
   // pass 1 on the host: segment ranges; nothing is launched before the sizes are known to fit.  Large segments
   // unless their padding (workgroups that find nothing to do) would exceed 1/32 of the launch.
   int seg_shift = kSsSegShiftLarge;
-  int64_t nseg = ss_count_segments(n, h_tensors, block, cpl, seg_shift);
+  int64_t nseg = ss_count_segments(batch, block, cpl, seg_shift);
   {
-    int64_t small = ss_count_segments(n, h_tensors, block, cpl, kSsSegShiftSmall);
+    int64_t small = ss_count_segments(batch, block, cpl, kSsSegShiftSmall);
     if ((nseg << kSsSegShiftLarge) - (small << kSsSegShiftSmall) > (small << kSsSegShiftSmall) / 32) {
       seg_shift = kSsSegShiftSmall;
       nseg = small;
@@ -420,7 +417,7 @@ mx_status_t ss_launch_many(int anchor, const SsTargets& tg, bool hw, int n, cons
     chunk.seg0 = seg0;
     int64_t acc = 0;
     for (int i = 0; i < chunk.count; ++i) {
-      const SsTensor& t = h_tensors[base + i];
+      const SsTensor t = batch.tensor(base + i);
       int64_t cs, ss;
       ss_segments_of(t.nblocks, block, cpl, seg_shift, &cs, &ss);
       int64_t* w = chunk.w + i * stride;

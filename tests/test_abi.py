@@ -142,6 +142,13 @@ def test_validation_returns_codes_without_launching(mx):
     assert L.mx_fake_quant(ref(mx.make_format("int4")), None, ref(s2), ref(B.MxDense(P, B.MX_F32, 32, 32, 32)), None) == 3
     assert L.mx_fake_quant(ref(mx.make_format("int4")), None, ref(s2), ref(B.MxDense(P, B.MX_BF16, 32, 64, 64)), None) == 5
     assert L.mx_fake_quant(ref(mx.make_format("int4", axis=0)), ref(mx.make_format("int8", axis=1)), ref(s2), ref(d2), None) == 2
+    # blocks of 16 with an odd number of blocks: codes are packed in runs of 32, so widths that share dwords across
+    # lanes are refused (quantize and dequant alike); 8- and 4-bit elements pass validation (0 rows here: no launch)
+    for elem, want in (("int7", 5), ("int6", 5), ("int5", 5), ("int3", 5), ("int2", 5), ("e3m3", 5), ("e3m2", 5), ("e2m2", 5)):
+        fk = mx.make_format(elem, block=16)
+        for dt in (B.MX_F32, B.MX_BF16):
+            assert L.mx_quantize(ref(fk), ref(B.MxDense(P, dt, 3, 48, 48)), ref(B.MxPacked(P, P, 3, 3)), None) == want, elem
+            assert L.mx_dequant(ref(fk), ref(B.MxPacked(P, P, 1, 1)), ref(B.MxDense(P, dt, 1, 16, 16)), None) == want, elem
     # dequant
     assert L.mx_dequant(ref(f), ref(B.MxPacked(P, P, 32, 3)), ref(s2), None) == 3
     assert L.mx_dequant(ref(f), None, ref(s2), None) == 1

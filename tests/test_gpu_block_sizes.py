@@ -84,6 +84,43 @@ def test_odd_width_needs_whole_runs_of_32_codes(mx):
     assert e.value.status == 5
 
 
+@pytest.mark.parametrize("rows,cols", [(1, 16), (3, 48), (5, 80)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_blocks_of_16_ending_in_half_a_run_of_32_codes(mx, oracle, rows, cols, dtype):
+    # an odd number of blocks of 16: the last run of 32 codes is half empty.  8- and 4-bit elements are converted (and
+    # nothing is written past the end of the codes: guard bytes behind them stay untouched), the other widths refused
+    import torch
+    rng = np.random.default_rng(rows * 100 + cols)
+    m = (rng.standard_normal((rows, cols)) * 3).astype(np.float32)
+    if dtype == "bf16":
+        m = synth.f32_to_bf16_bits(m)
+    g = to_gpu(m)
+    nb = rows * cols // 16
+    for fmt in ("int8", "e4m3", "int4", "e2m1"):
+        f = mx.make_format(fmt, block=16)
+        bb = 16 * oracle.elem_bits(fmt) // 8
+        codes = torch.full((nb * bb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+        scales = torch.full((nb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+        mx.mx_quantize(g, f, codes[:nb * bb].view(rows, cols // 16, bb), scales[:nb].view(rows, cols // 16))
+        torch.cuda.synchronize()
+        want_c, want_s = oracle.quantize(m, fmt, k=16)
+        assert np.array_equal(to_host(codes[:nb * bb]).reshape(want_c.shape), want_c), fmt
+        assert np.array_equal(to_host(scales[:nb]).reshape(want_s.shape), want_s), fmt
+        assert bool((codes[nb * bb:] == 0xA5).all()) and bool((scales[nb:] == 0xA5).all()), fmt
+        out = "f32" if dtype == "f32" else "bf16"
+        got_d = mx.mx_dequant(codes[:nb * bb].view(rows, cols // 16, bb), scales[:nb].view(rows, cols // 16), f, rows, cols,
+                              dtype=torch.float32 if out == "f32" else torch.bfloat16)
+        assert_same_values(to_host(got_d), oracle.dequant(want_c, want_s, fmt, rows, cols, k=16, out=out))
+        assert_same_values(to_host(mx.mx_fake_quant(g, f)), oracle.fake_quant(m, fmt, k=16))
+    for fmt in ("int7", "int6", "int5", "int3", "int2", "e3m3", "e3m2", "e2m3", "e2m2"):
+        f = mx.make_format(fmt, block=16)
+        with pytest.raises(mx.MxError) as e:
+            mx.mx_quantize(g, f)
+        assert e.value.status == 5, fmt
+        # fake-quant touches no codes and takes every width
+        assert_same_values(to_host(mx.mx_fake_quant(g, f)), oracle.fake_quant(m, fmt, k=16))
+
+
 def test_column_blocks_are_32_only(mx):
     import torch
     w = torch.zeros((128, 64), dtype=torch.float32, device="cuda")
