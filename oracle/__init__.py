@@ -178,8 +178,10 @@ def unpack(codes, fmt, k=32):
     bits = elem_bits(fmt)
     flat = np.ascontiguousarray(codes, dtype=np.uint8).reshape(-1, codes.shape[-1])
     out = np.zeros((flat.shape[0], k), dtype=np.uint8)
+    L, bb = lib(), flat.shape[1]
+    src, dst = flat.ctypes.data, out.ctypes.data
     for t in range(flat.shape[0]):
-        lib().mxo_unpack_block(flat[t].ctypes.data, k, bits, out[t].ctypes.data)
+        L.mxo_unpack_block(src + t * bb, k, bits, dst + t * k)
     return out.reshape(codes.shape[:-1] + (k,))
 
 
@@ -265,17 +267,37 @@ def fake_quant(x, target, anchor=None, axis=1, k=32, tie=TIE_DEFAULT, out=None):
     return dst
 
 
-def gemm_ss_reference(a_codes, a_scales, w_codes, w_scales, target="e2m1", k=32, with_abs=False):
+def dequant_f64(codes, scales, fmt, k=32):
+    """V^ = X * P (Sec. 3.3 notation) as float64, element by element from the two scalar definitions
+    mxo_decode(code) and mxo_scale_value(byte): no float32 in between, so every scale byte 0..254 keeps its exact
+    value (2^-127 .. 2^127 times a minifloat is exact in float64) and byte 255 gives NaN.  codes[..., nblocks,
+    bytes_per_block], scales[..., nblocks] -> [..., nblocks * k]."""
+    L = lib()
+    vals = np.array([L.mxo_decode(*_fmt(fmt), c) for c in range(1 << elem_bits(fmt))], dtype=np.float64)
+    xs = np.array([L.mxo_scale_value(b) for b in range(256)], dtype=np.float64)
+    el = unpack(codes, fmt, k)                                    # [..., nblocks, k] element codes
+    with np.errstate(invalid="ignore"):
+        out = vals[el] * xs[np.asarray(scales, dtype=np.uint8)][..., None]
+    return out.reshape(el.shape[:-2] + (el.shape[-2] * k,))
+
+
+def gemm_ss_reference(a_codes, a_scales, w_codes, w_scales, target="e2m1", k=32, with_abs=False, wide=False):
     """fp64 product of the dequantized operands of the fused consumer GEMM:
     C = DQ(A) @ DQ(Q_{A->t}(W_A)).T with A in MXFP8 E4M3 [M, K/k blocks] and W_A the E4M3 anchor [N, K/k blocks]
     (Eq. (6) for the conversion, Sec. 3.3 notation for the reconstruction; numpy's matmul is the library step).
-    with_abs also returns sum_k |a||w|, the scale of the rounding error of any finite-precision accumulation."""
+    with_abs also returns sum_k |a||w|, the scale of the rounding error of any finite-precision accumulation.
+    wide: reconstruct the operands straight in float64 (dequant_f64) instead of through the float32 dequantizer, so
+    that scale bytes near 0 and 254 keep their exact values and byte 255 propagates as NaN."""
     M, KB = a_scales.shape
     N = w_scales.shape[0]
     K = KB * k
-    a = dequant(a_codes, a_scales, "e4m3", M, K, axis=1, k=k).astype(np.float64)
     tc, ts = slice_and_scale(w_codes, w_scales, "e4m3", target, k=k)
-    w = dequant(tc, ts, target, N, K, axis=1, k=k).astype(np.float64)
+    if wide:
+        a = dequant_f64(a_codes, a_scales, "e4m3", k=k)
+        w = dequant_f64(tc, ts, target, k=k)
+    else:
+        a = dequant(a_codes, a_scales, "e4m3", M, K, axis=1, k=k).astype(np.float64)
+        w = dequant(tc, ts, target, N, K, axis=1, k=k).astype(np.float64)
     if with_abs:
         return a @ w.T, np.abs(a) @ np.abs(w).T
     return a @ w.T

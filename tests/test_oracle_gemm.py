@@ -115,3 +115,59 @@ def test_gemm_reference_closed_forms(oracle):
     a_codes[:, :, 1::2] ^= 0x80
     a_scales[:, 2] += 1
     assert (oracle.gemm_ss_reference(a_codes, a_scales, w_codes, w_scales) == (KB + 1) * 32 * 6.0 * 4.0).all()
+
+
+def test_wide_reconstruction_against_exact_rationals_at_extreme_scale_bytes(oracle):
+    """dequant_f64 / gemm_ss_reference(wide=True): scale bytes 0..5 and 248..254 keep their exact values (where the
+    float32 dequantizer underflows or overflows), the sliced byte saturates at 254 (Eq. (6) scale step inside the E8M0
+    range), and byte 255 makes the block -- and with it every output that touches it -- NaN."""
+    e4m3, e2m1 = _tables()
+    rng = np.random.default_rng(20260405)
+    # element by element against the tables, every code x the extreme bytes
+    codes = np.arange(256, dtype=np.uint8).reshape(8, 1, 32)
+    for byte in (0, 1, 5, 126, 127, 250, 254):
+        scales = np.full((8, 1), byte, dtype=np.uint8)
+        got = oracle.dequant_f64(codes, scales, "e4m3")
+        for c in range(256):
+            want = e4m3.get(c)
+            if want is None:                                  # the two NaN codes (not in the table of finite values)
+                assert np.isnan(got[c // 32, c % 32])
+            else:
+                assert Fraction(float(got[c // 32, c % 32])) == Fraction(2) ** (byte - 127) * want, (byte, c)
+    assert np.isnan(oracle.dequant_f64(codes, np.full((8, 1), 255, dtype=np.uint8), "e4m3")).all()
+    # wherever the float32 dequantizer is exact (moderate bytes), the two reconstructions agree
+    sc = rng.integers(100, 150, size=(8, 1), dtype=np.uint8)
+    f32 = oracle.dequant(codes, sc, "e4m3", 8, 32).astype(np.float64)
+    f64 = oracle.dequant_f64(codes, sc, "e4m3")
+    assert np.array_equal(np.isnan(f32), np.isnan(f64)) and np.array_equal(np.nan_to_num(f32), np.nan_to_num(f64))
+    # the product: low bytes on W against ordinary A, high bytes on W against small A, exact rationals
+    for w_lo, w_hi, a_lo, a_hi in ((0, 6, 120, 134), (248, 255, 90, 101)):
+        a_codes, _, w_codes, _ = _random_operands(rng, 3, 4, 2)
+        w_codes[:, :, ::2] |= 0x60
+        w_codes[(w_codes & 0x7F) == 0x7F] = 0x7E
+        a_scales = rng.integers(a_lo, a_hi, size=(3, 2), dtype=np.uint8)
+        w_scales = rng.integers(w_lo, w_hi, size=(4, 2), dtype=np.uint8)
+        if w_hi == 255:
+            w_scales[0, 0] = 254                              # saturating: 254 + De stays 254
+            w_scales[1, 1] = 250                              # 250 + 6 = 256 -> 254
+        got, got_abs = oracle.gemm_ss_reference(a_codes, a_scales, w_codes, w_scales, with_abs=True, wide=True)
+        for m in range(3):
+            for n in range(4):
+                acc = Fraction(0)
+                for b in range(2):
+                    xa = Fraction(2) ** (int(a_scales[m, b]) - 127)
+                    xw = Fraction(2) ** (min(int(w_scales[n, b]) + DE, 254) - 127)
+                    for j in range(32):
+                        wv = e4m3[int(w_codes[n, b, j])]
+                        wt = e2m1[defs.nearest_code("e2m1", wv / 2 ** DE, negative_zero=bool(w_codes[n, b, j] & 0x80))]
+                        acc += (xa * e4m3[int(a_codes[m, b, j])]) * (xw * wt)
+                assert abs(Fraction(float(got[m, n])) - acc) <= Fraction(float(got_abs[m, n])) * Fraction(1, 2 ** 45), (m, n)
+    # byte 255 on one block of W / of A: NaN in exactly that column / row
+    a_codes, a_scales, w_codes, w_scales = _random_operands(rng, 3, 4, 2)
+    w_scales[2, 1] = 255
+    a_scales[1, 0] = 255
+    got = oracle.gemm_ss_reference(a_codes, a_scales, w_codes, w_scales, wide=True)
+    want_nan = np.zeros((3, 4), dtype=bool)
+    want_nan[:, 2] = True
+    want_nan[1, :] = True
+    assert np.array_equal(np.isnan(got), want_nan)
