@@ -1,10 +1,11 @@
 """Parity at the benchmark's full sizes, in the launch configuration bench.py times.
 
-Config 3 (Llama-8B-shaped checkpoint, 224 tensors, one batched launch): every output byte of the
-4-bit conversions is checked against a 256-entry table that the oracle computes one code at a
-time (the element map of Eq. (4) / Eq. (6) is a pure function of one anchor byte), every scale
-byte against the oracle's scale step, and windows of the 6-bit conversions and of the anchor
-quantization against the oracle proper.  Config 4 (fake-quant of 32768 x 4096 activations and of a
+Config 3 (Llama-8B-shaped checkpoint, 224 tensors, one batched launch): every output byte of every
+conversion (4-bit and 6-bit targets) is checked against tables that the oracle computes -- the element map of
+Eq. (4) / Eq. (6) is a pure function of one anchor byte (256 calls of the oracle's slice_code), the place of every
+code bit inside a packed block is read off the oracle's pack_block on one-bit patterns, and torch on the GPU only
+gathers through those tables -- every scale byte against the oracle's scale step, and windows of the 6-bit
+conversions and of the anchor quantization against the oracle proper as well.  Config 4 (fake-quant of 32768 x 4096 activations and of a
 4096 x 14336 weight down its columns): sampled rows / columns against the oracle.
 """
 import os
@@ -32,6 +33,45 @@ def env():
 def _bf16_to_host(t):
     import torch
     return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def _packing_runs(oracle, bits):
+    """Where the oracle puts every code bit of a block of 32: for each output byte, the runs (element, first code bit,
+    first byte bit, length) that make it up, found from pack_block on patterns with a single bit set."""
+    nbytes = 32 * bits // 8
+    src = {}                                                  # output bit position -> (element, code bit)
+    for e in range(32):
+        for b in range(bits):
+            codes = np.zeros(32, dtype=np.uint8)
+            codes[e] = 1 << b
+            packed = oracle.pack_block(codes, bits)
+            assert packed.size == nbytes
+            pos = [8 * j + t for j in range(nbytes) for t in range(8) if (packed[j] >> t) & 1]
+            assert len(pos) == 1
+            src[pos[0]] = (e, b)
+    assert len(src) == 32 * bits                              # a bijection: nothing overlaps, nothing is dropped
+    runs = []
+    for j in range(nbytes):
+        byte_runs, t = [], 0
+        while t < 8:
+            e, b = src[8 * j + t]
+            n = 1
+            while t + n < 8 and src[8 * j + t + n] == (e, b + n):
+                n += 1
+            byte_runs.append((e, b, t, n))
+            t += n
+        runs.append(byte_runs)
+    return runs
+
+
+def _expected_packed(m, runs):
+    """m: [n, 32] element codes (one per byte, on the GPU) -> the packed blocks [n, bytes] by the oracle's bit layout."""
+    import torch
+    out = torch.zeros((m.shape[0], len(runs)), dtype=torch.uint8, device=m.device)
+    for j, byte_runs in enumerate(runs):
+        for e, b, t, n in byte_runs:
+            out[:, j] |= ((m[:, e] >> b) & ((1 << n) - 1)) << t
+    return out
 
 
 def _windows(rng, nblocks, width, count):
@@ -73,21 +113,31 @@ def test_config3_checkpoint(env, oracle, anchor, target4, targets6):
     lut = torch.tensor([oracle.slice_code(anchor, target4, c) for c in range(256)], dtype=torch.uint8, device="cuda")
     slut = torch.tensor([oracle.slice_byte(anchor, target4, b) for b in range(256)], dtype=torch.uint8, device="cuda")
     assert torch.equal(slut[a_scales.long()], t_scales), "scale bytes"
+    runs4 = _packing_runs(oracle, 4)
     step = 1 << 21                                   # blocks per comparison slab (64 Mi codes)
     for b0 in range(0, a_scales.numel(), step):
         a = a_codes[b0:b0 + step]                    # [n, 32] anchor codes
         m = lut[a.long()]                            # expected 4-bit codes, one per byte
-        want = m[:, 0::2] | (m[:, 1::2] << 4)        # element 2j in the low nibble of byte j
-        assert torch.equal(want, t_codes[b0:b0 + step]), "codes in blocks %d.." % b0
-        del a, m, want
+        assert torch.equal(_expected_packed(m, runs4), t_codes[b0:b0 + step]), "codes in blocks %d.." % b0
+        del a, m
     del t_codes, t_scales, t_views
 
-    # --- 6-bit targets: windows against the oracle proper (first / last blocks of tensors, random interior)
+    # --- 6-bit targets: every byte of the whole checkpoint through the oracle's tables, then windows against the oracle
+    # proper (first / last blocks of tensors, random interior)
+    runs6 = _packing_runs(oracle, 6)
     for tgt in targets6:
         c6, s6, v6 = bench.alloc_targets(torch, mx, a_views, tgt)
         c6.fill_(0xA5)
+        s6.fill_(0xA5)
         mx.SsBatch(a_views, fa, mx.make_format(tgt), v6, wsp).run()
         torch.cuda.synchronize()
+        lut6 = torch.tensor([oracle.slice_code(anchor, tgt, c) for c in range(256)], dtype=torch.uint8, device="cuda")
+        slut6 = torch.tensor([oracle.slice_byte(anchor, tgt, b) for b in range(256)], dtype=torch.uint8, device="cuda")
+        assert torch.equal(slut6[a_scales.long()], s6), "scale bytes (%s)" % tgt
+        for b0 in range(0, a_scales.numel(), step):
+            m = lut6[a_codes[b0:b0 + step].long()]
+            assert torch.equal(_expected_packed(m, runs6), c6[b0:b0 + step]), "%s codes in blocks %d.." % (tgt, b0)
+            del m
         for ti in (0, 1, 2, 5, 100, 222, 223):
             nb = a_views[ti][1].numel()
             ac = a_views[ti][0].reshape(nb, 32)
@@ -118,12 +168,20 @@ def test_config3_random_byte_anchor_full_size(env, oracle):
         slut = torch.tensor([oracle.slice_byte(anchor, target, b) for b in range(256)], dtype=torch.uint8, device="cuda")
         assert torch.equal(slut[scales.long()], os_)
         step = 1 << 21
+        runs4 = _packing_runs(oracle, 4)
         for b0 in range(0, nb, step):
             m = lut[codes[b0:b0 + step].long()]
-            assert torch.equal(m[:, 0::2] | (m[:, 1::2] << 4), oc[b0:b0 + step])
+            assert torch.equal(_expected_packed(m, runs4), oc[b0:b0 + step])
         del oc, os_
+    runs6 = _packing_runs(oracle, 6)
     for anchor, target in (("e4m3", "e3m2"), ("e4m3", "e2m3"), ("int8", "int6")):
         oc, os_ = mx.mx_slice_and_scale(codes, scales, mx.make_format(anchor), mx.make_format(target))
+        lut = torch.tensor([oracle.slice_code(anchor, target, c) for c in range(256)], dtype=torch.uint8, device="cuda")
+        slut = torch.tensor([oracle.slice_byte(anchor, target, b) for b in range(256)], dtype=torch.uint8, device="cuda")
+        assert torch.equal(slut[scales.long()], os_)
+        for b0 in range(0, nb, 1 << 21):
+            m = lut[codes[b0:b0 + (1 << 21)].long()]
+            assert torch.equal(_expected_packed(m, runs6), oc[b0:b0 + (1 << 21)])
         for s in (0, nb - 2048, 12345678, 99999999):
             wc, wsc = oracle.slice_and_scale(codes[s:s + 2048].cpu().numpy(), scales[s:s + 2048].cpu().numpy(), anchor, target)
             assert np.array_equal(os_[s:s + 2048].cpu().numpy(), wsc) and np.array_equal(oc[s:s + 2048].cpu().numpy(), wc)
