@@ -130,6 +130,20 @@ mx_status_t mx_slice_and_scale_batched(const mx_format_t* fa, const mx_format_t*
                                        const mx_packed_t* anchors, const mx_packed_t* targets,
                                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid it): mx_slice_and_scale_batched with the launch tables in a fixed array inside the library instead of
+ * a workspace.  It calls no allocator of any kind, on the host or on the device.  The array holds
+ * MX_SS_NOALLOC_MAX_SEGMENTS descriptors of 64 bytes (1 MiB of device memory on every GPU the library runs on,
+ * held until the process ends); one descriptor covers up to 2^16 pieces of 16 anchor codes (2^13 when the tensors
+ * are small), and every tensor rounds up to whole descriptors for its codes and for its scale bytes: a whole
+ * 8B-parameter checkpoint (224 tensors, 7 G elements) takes about 7 000.  MX_ERR_WORKSPACE, with nothing enqueued,
+ * when a call needs more.  Results are those of mx_slice_and_scale_batched bit for bit.
+ * All calls on one GPU share that GPU's array, which is rewritten by every call: two such calls must not overlap in
+ * time on one GPU (same stream, or ordered by events); calls on different GPUs are independent. */
+#define MX_SS_NOALLOC_MAX_SEGMENTS 16384
+mx_status_t mx_slice_and_scale_batched_noalloc(const mx_format_t* fa, const mx_format_t* ft, int32_t n,
+                                               const mx_packed_t* anchors, const mx_packed_t* targets, void* stream);
+
 /* Several targets from one pass over the anchor (the "convert the anchor to every lower format" workload of
  * Sec. 3.5 "Inference"): the anchor codes and scales are read once and n_targets (1..3) packed tensors are written,
  * each exactly what mx_slice_and_scale gives for its format.  fts / targets: host arrays of n_targets entries, the

@@ -10,7 +10,8 @@ import ctypes
 from . import binding
 from .binding import ELEMS, MxError, make_format
 
-__all__ = ["mx_quantize", "mx_slice_and_scale", "mx_slice_and_scale_batched", "mx_slice_and_scale_multi", "mx_fake_quant", "mx_dequant",
+__all__ = ["mx_quantize", "mx_slice_and_scale", "mx_slice_and_scale_batched", "mx_slice_and_scale_batched_noalloc",
+           "mx_slice_and_scale_multi", "mx_fake_quant", "mx_dequant",
            "mx_gemm_ss_fp4", "mx_packed_bytes", "mx_elem_bits", "mx_elem_emax", "MxFakeQuantSTE", "ELEMS", "MxError", "make_format",
            "packed_shape", "SsBatch"]
 
@@ -166,6 +167,19 @@ def mx_slice_and_scale_batched(anchors, fa, ft, targets=None, workspace=None):
     binding.check(L.mx_slice_and_scale_batched(ctypes.byref(fa), ctypes.byref(ft), n, A, T,
                                                ctypes.c_void_p(workspace.data_ptr()), workspace.numel(),
                                                _stream(anchors[0][0])), "mx_slice_and_scale_batched")
+    return targets
+
+
+def mx_slice_and_scale_batched_noalloc(anchors, fa, ft, targets):
+    """mx_slice_and_scale_batched with the launch tables in the library's own fixed device array: the call allocates
+    nothing (the targets are the caller's).  Calls on one GPU must not overlap in time."""
+    n = len(anchors)
+    if n == 0:
+        return targets
+    A = (binding.MxPacked * n)(*[_packed(c, s, 1, s.numel()) for c, s in anchors])
+    T = (binding.MxPacked * n)(*[_packed(c, s, 1, s.numel()) for c, s in targets])
+    binding.check(binding.lib().mx_slice_and_scale_batched_noalloc(ctypes.byref(fa), ctypes.byref(ft), n, A, T,
+                                                                   _stream(anchors[0][0])), "mx_slice_and_scale_batched_noalloc")
     return targets
 
 

@@ -71,6 +71,8 @@ def lib():
         L.mx_slice_and_scale_batched.argtypes = [P(MxFormat), P(MxFormat), ctypes.c_int32, P(MxPacked), P(MxPacked), vp,
                                                  ctypes.c_size_t, vp]
         L.mx_slice_and_scale_batched.restype = st
+        L.mx_slice_and_scale_batched_noalloc.argtypes = [P(MxFormat), P(MxFormat), ctypes.c_int32, P(MxPacked), P(MxPacked), vp]
+        L.mx_slice_and_scale_batched_noalloc.restype = st
         L.mx_slice_and_scale_multi.argtypes = [P(MxFormat), P(MxPacked), ctypes.c_int32, P(MxFormat), P(MxPacked), vp]
         L.mx_slice_and_scale_multi.restype = st
         L.mx_slice_and_scale_multi_batched.argtypes = [P(MxFormat), ctypes.c_int32, P(MxFormat), ctypes.c_int32, P(MxPacked),

@@ -239,6 +239,26 @@ mx_status_t mx_slice_and_scale_batched(const mx_format_t* fa, const mx_format_t*
   return mx_slice_and_scale_multi_batched(fa, 1, ft, n, anchors, targets, workspace, workspace_bytes, stream);
 }
 
+mx_status_t mx_slice_and_scale_batched_noalloc(const mx_format_t* fa, const mx_format_t* ft, int32_t n, const mx_packed_t* anchors,
+                                               const mx_packed_t* targets, void* stream) {
+  if (!ft) return MX_ERR_NULL;
+  mx::SsTargets tg;
+  bool hw;
+  mx_status_t st = check_ss_targets(fa, 1, ft, &tg, &hw);
+  if (st != MX_OK) return st;
+  if (n < 0) return MX_ERR_SHAPE;
+  if (n == 0) return MX_OK;
+  if (!anchors || !targets) return MX_ERR_NULL;
+  if ((st = check_ss_batch(1, n, anchors, targets)) != MX_OK) return st;
+  drop_stale_error();
+  void* table = nullptr;
+  size_t table_bytes = 0;
+  if ((st = mx::ss_static_workspace(&table, &table_bytes)) != MX_OK) return st;
+  // (a launch that needs more segments than the table holds comes back as MX_ERR_WORKSPACE before anything is enqueued)
+  return mx::ss_launch_many((int)fa->elem, tg, hw, mx::SsBatch{anchors, targets, n, 1}, fa->block, table, table_bytes, (int)ft->round,
+                            static_cast<hipStream_t>(stream));
+}
+
 mx_status_t mx_fake_quant(const mx_format_t* target, const mx_format_t* anchor, const mx_dense_t* src, const mx_dense_t* dst,
                           void* stream) {
   ElemInfo it, ia;

@@ -73,6 +73,11 @@ struct SsBatch {
   }
 };
 
+// Segment descriptors of the library's own table (64 bytes each: 1 MiB per GPU): see mx_slice_and_scale_batched_noalloc.
+constexpr int kSsStaticSegments = 16384;
+// Address and size, on the current device, of that table.
+mx_status_t ss_static_workspace(void** ptr, size_t* bytes);
+
 mx_status_t ss_launch_one(int anchor, const SsTargets& tg, bool hw, const SsTensor& t, int block, int tie, hipStream_t stream);
 size_t ss_workspace_bytes(int n, int64_t total_blocks);
 mx_status_t ss_launch_many(int anchor, const SsTargets& tg, bool hw, const SsBatch& batch, int block, void* workspace,

@@ -12,6 +12,8 @@
 #include "mx_device.h"
 #include "mx_launch.h"
 
+#include <atomic>
+
 namespace mx {
 
 // ---- one piece: CPL anchor codes (CPL/4 dwords) -> CPL * bits / 32 dwords
@@ -439,6 +441,30 @@ mx_status_t ss_launch_many(int anchor, const SsTargets& tg, bool hw, const SsBat
     seg0 += acc;
   }
   return ss_dispatch(anchor, tg, hw, SsMany{segs, nseg, seg_shift, tie, stream});
+}
+
+// ---- a segment table that lives in the library, for callers that cannot allocate or lend device memory
+// `scratch` is a file-scope device array: every GPU the library runs on holds its own copy, at its own address, until
+// the process ends.  In host code the array's name is only a handle for the runtime, never an address to pass to a
+// kernel: the address on the current device comes from hipGetSymbolAddress, is asked for once per device and kept.
+static_assert(sizeof(SsSegment) == 64 && kSsStaticSegments == MX_SS_NOALLOC_MAX_SEGMENTS, "the size mx.h states");
+static __device__ __align__(256) unsigned char scratch[kSsStaticSegments * sizeof(SsSegment)];
+
+mx_status_t ss_static_workspace(void** ptr, size_t* bytes) {
+  static std::atomic<void*> address[64];   // per device; a second thread asking at the same time gets the same answer
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MX_ERR_LAUNCH;
+  void* p = address[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return MX_ERR_LAUNCH;
+    }
+    address[dev].store(p, std::memory_order_release);
+  }
+  *ptr = p;
+  *bytes = sizeof(scratch);
+  return MX_OK;
 }
 
 }  // namespace mx
