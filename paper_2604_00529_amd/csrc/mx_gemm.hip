@@ -33,18 +33,25 @@ constexpr int kMidmMaxM = 48;     // 16 < M <= 48: the streaming kernel with fra
 // with MFMA fragment loads (the 64 lanes of a load on 16 rows, 16 bytes each) the matrix alone takes 12.3 us, read with
 // loads whose lanes take consecutive 16 bytes of one row 9.7 us.  So every load of W here is one contiguous 1 KB -- lane l
 // takes bytes 16 l .. 16 l + 15 of a row's 1 KB K-chunk, half a block -- and the way into the operand layout goes through
-// a wave-private LDS tile, the anchor sliced to E2M1 (Eq. (6)) on the way in, row by row in the order in which the rows
-// were requested, each as soon as it has arrived.  The A chunk takes the same way, unsliced and without passing through
-// registers (loads with LDS as their destination).  One workgroup of 4 waves per 16 NT output columns; K is cut into
-// chunks of 8 K-steps (a K-step is 128 elements = 4 blocks, one per lane group; a chunk is 1024 elements) dealt
-// round-robin to the waves, and the four partial sums are added in a fixed order through LDS (deterministic).
+// a wave-private LDS tile, the anchor sliced to E2M1 (Eq. (6)) on the way in.  One workgroup of 4 waves per 16 NT output
+// columns; K is cut into chunks of 8 K-steps (a K-step is 128 elements = 4 blocks, one per lane group; a chunk is 1024
+// elements) dealt round-robin to the waves, and the four partial sums are added in a fixed order through LDS
+// (deterministic).
 //
-// LDS tile of a wave, used twice per chunk.  First the A chunk: 16 rows of 64 slots of 16 bytes, rows padded by one slot
-// so that the 16 lanes that read one slot of 16 consecutive rows hit 16 different bank groups.  Then, per column tile,
-// 16 rows of 32 slots (one row = the 512 bytes of a column's sliced chunk) with slot s of row r at slot s ^ (r & 15), for
-// the same reason; a row is still written as one contiguous (permuted) run.
+// The rows of a chunk pass through a ring of kDecodeRing register sets: a wave slices row r as soon as it has landed
+// and only then requests row r + kDecodeRing.  (With all 16 NT loads of a chunk issued up front a wave sat behind its
+// own load instructions -- the memory pipe takes them only as fast as it drains -- while rows it could have sliced had
+// long arrived, and all the slicing piled up behind the stream: 15.7 us against 13.1 us for the 58.7 MB matrix.  Rings
+// of 5 to 8 rows measure the same; 12 and more are slower again.)  The MFMAs of a column tile follow its sixteenth row.
+//
+// LDS tile of a wave, used twice per chunk.  First the A chunk, which goes straight from global memory into LDS (no
+// registers in between) and from there into the wave's fragment registers: 16 rows of 64 slots of 16 bytes, rows padded
+// by one slot so that the 16 lanes that read one slot of 16 consecutive rows hit 16 different bank groups.  Then, per
+// column tile, 16 rows of 32 slots (one row = the 512 bytes of a column's sliced chunk) with slot s of row r at slot
+// s ^ (r & 15), for the same reason; a row is still written as one contiguous (permuted) run.
 constexpr int kDecodeARow = 1024 + 16;          // A rows are padded by one slot: row r, slot s -> bank group (r + s) % 16
-constexpr int kDecodeTile = 16 * kDecodeARow;   // (>= the 16 KB of two sliced W tiles)
+constexpr int kDecodeTile = 16 * kDecodeARow;   // (>= the 8 KB of a sliced W tile)
+constexpr int kDecodeRing = 6;                  // rows of W in flight per wave
 constexpr int decode_smem_bytes(int nt) { return 4 * kDecodeTile + 3 * nt * 4 * 64 * (int)sizeof(float); }
 
 // 16 E4M3 anchor codes (4 dwords) -> 16 E2M1 codes (2 dwords): the Slice-and-Scale element step on half a block
@@ -88,9 +95,9 @@ __device__ __forceinline__ void pack_lane_scales(const u32x4& lo, const u32x4& h
              ((w[4 * h + 3] >> sh) << 24);
 }
 
-// s_waitcnt vmcnt(32) on gfx9: vmcnt is split over bits 3:0 and 15:14 of the immediate; the other counters stay at
+// s_waitcnt vmcnt(n) alone on gfx9: vmcnt is split over bits 3:0 and 15:14 of the immediate; the other counters stay at
 // their maxima (expcnt 7 in bits 6:4, lgkmcnt 15 in bits 11:8)
-constexpr int kWaitVmcnt32 = (32 & 15) | (7 << 4) | (15 << 8) | ((32 >> 4) << 14);
+constexpr int wait_vmcnt(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
 
 // Orders the LDS traffic of one wave for the compiler (the hardware executes a wave's LDS instructions in order, so
 // what other lanes wrote is there when the read executes) without making it wait for the global loads in flight.
@@ -107,13 +114,14 @@ __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_decode_kernel(const uint8_
                                                                  const uint8_t* __restrict__ w_codes,
                                                                  const uint8_t* __restrict__ w_scales, float* __restrict__ c,
                                                                  int M, int N, int K, int64_t ldc) {
-  static_assert(NT * 8 * 1024 <= kDecodeTile, "one 8 KB tile of sliced codes per column tile");
+  constexpr int R = 16 * NT, D = kDecodeRing;   // rows of W per chunk; rows in flight
+  static_assert(D <= 16 && 8 * 1024 <= kDecodeTile, "the ring is refilled across column tiles; one 8 KB tile of sliced codes");
   extern __shared__ __attribute__((aligned(16))) uint8_t decode_smem[];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int i = lane & 15, g = lane >> 4;
   const int KB = K / 32, ksteps = K / 128, chunks = (ksteps + 7) / 8;
   uint8_t* tile = decode_smem + wave * kDecodeTile;
-  float(*red)[NT][4][64] = reinterpret_cast<float(*)[NT][4][64]>(decode_smem + 4 * kDecodeTile);   // [3][NT][4][64]
+  f32x4* red = reinterpret_cast<f32x4*>(decode_smem + 4 * kDecodeTile);   // [3][NT][64] partial sums of 4 outputs
   f32x4 acc[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -122,21 +130,24 @@ __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_decode_kernel(const uint8_
   int ncol[NT];   // columns past the edge are computed from column N - 1 and never stored
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) ncol[nt] = col0 + nt * 16 + i;
-  // Buffer loads: the 48 loads of a chunk share one offset register per operand (the row is a scalar offset); with one
-  // 64-bit address per load the kernel does not fit two waves per SIMD.  The host has checked that both matrices are
-  // smaller than 4 GiB.  Reads past the end of a buffer return zero.
+  // Buffer loads: the loads of a chunk share one offset register per operand (the row is a scalar offset).  The host
+  // has checked that both matrices are smaller than 4 GiB.  Reads past the end of a buffer return zero.
   const __amdgpu_buffer_rsrc_t a_rsrc = make_buffer(a_codes, (uint32_t)M * (uint32_t)K);
   const __amdgpu_buffer_rsrc_t w_rsrc = make_buffer(w_codes, (uint32_t)N * (uint32_t)K);
   const __amdgpu_buffer_rsrc_t as_rsrc = make_buffer(a_scales, (uint32_t)M * (uint32_t)KB);
   const __amdgpu_buffer_rsrc_t ws_rsrc = make_buffer(w_scales, (uint32_t)N * (uint32_t)KB);
   for (int chunk = wave; chunk < chunks; chunk += 4) {
     // Lane l covers K-step l / 8 of the chunk.  In a ragged last chunk the lanes of K-steps that do not exist load the
-    // chunk's first 16 bytes instead (every access stays inside the matrices); what they load is sliced like the rest and
-    // never multiplied: the MFMA loop stops at the last K-step.  Rows of A past M read row M - 1; their products land in
-    // output rows that are not stored.
+    // chunk's first 16 bytes instead (every access stays inside the matrices); what they load is sliced like the rest
+    // and multiplied with zero A fragments.  Rows of A past M read row M - 1; their products land in output rows that
+    // are not stored.
     const int steps = ksteps - chunk * 8 < 8 ? ksteps - chunk * 8 : 8;
     const uint32_t lane_off = (lane >> 3) < steps ? 16u * (uint32_t)lane : 0u;
     const uint32_t chunk_off = (uint32_t)chunk * 1024u;
+    auto load_row = [&](int r) {   // row r of the chunk: column col0 + r, one contiguous 1 KB
+      const int n = col0 + r < N ? col0 + r : N - 1;
+      return buffer_load_x4<true>(w_rsrc, lane_off, (uint32_t)n * (uint32_t)K + chunk_off);
+    };
     // A: the chunk of each row (1 KB, lane l <-> 16 bytes) goes straight from global memory into the wave's LDS tile, no
     // registers in between; the hardware puts lane l's 16 bytes at slot l of the row.  These loads are requested before
     // everything else and are the oldest in flight.
@@ -147,9 +158,9 @@ __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_decode_kernel(const uint8_
                                                16, (int)lane_off, (int)(row * (uint32_t)K + chunk_off), 0, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
-    // The 32 scale bytes of the chunk per row / column, requested ahead of W (loads return in order) and unpacked after
-    // W has been requested.  In a ragged last chunk the 32 bytes run past the row's end: into the next row, or past the
-    // end of the array, where a buffer load returns zeros; those bytes belong to K-steps that are not multiplied.
+    // The 32 scale bytes of the chunk per row / column.  In a ragged last chunk the 32 bytes run past the row's end: into
+    // the next row, or past the end of the array, where a buffer load returns zeros; those bytes belong to K-steps that
+    // do not exist and are replaced below.
     u32x4 aslo, ashi, wslo[NT], wshi[NT];
     {
       const uint32_t ao = (uint32_t)(i < M ? i : M - 1) * (uint32_t)KB + (uint32_t)chunk * 32u;
@@ -163,26 +174,22 @@ __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_decode_kernel(const uint8_
       }
     }
     __builtin_amdgcn_sched_barrier(0);
-    u32x4 wraw[NT][16];
+    u32x4 ring[D];
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const int n = col0 + nt * 16 + j < N ? col0 + nt * 16 + j : N - 1;
-        wraw[nt][j] = buffer_load_x4<true>(w_rsrc, lane_off, (uint32_t)n * (uint32_t)K + chunk_off);
-      }
+    for (int r = 0; r < D; ++r) ring[r] = load_row(r);
     __builtin_amdgcn_sched_barrier(0);
-    // The 32 loads of W have been requested after those of A: once no more than 32 loads are outstanding, A is in the
-    // tile (and the scale bytes are in their registers).
-    __builtin_amdgcn_s_waitcnt(kWaitVmcnt32);
+    // the first D rows of W have been requested after A and the scale bytes: once no more than D loads are outstanding,
+    // A is in the tile and the scale bytes are in their registers
+    __builtin_amdgcn_s_waitcnt(wait_vmcnt(D));
     wave_lds_order();
-    // the 8 x 2 fragment runs of lane (i, g): slots 8 p + g and 8 p + 4 + g of row i
+    // the 8 x 2 fragment runs of lane (i, g): slots 8 p + g and 8 p + 4 + g of row i; zeros for K-steps that do not exist
     i32x8 af[8];
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
       u32x4 t0 = *reinterpret_cast<const u32x4*>(tile + i * kDecodeARow + 16 * (8 * p + g));
       u32x4 t1 = *reinterpret_cast<const u32x4*>(tile + i * kDecodeARow + 16 * (8 * p + 4 + g));
       af[p] = i32x8{(int)t0.x, (int)t0.y, (int)t0.z, (int)t0.w, (int)t1.x, (int)t1.y, (int)t1.z, (int)t1.w};
+      if (p >= steps) af[p] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
     }
     // the 8 scale bytes this lane feeds to the MFMAs of the chunk (K-block g of each K-step), packed 4 to a register;
     // those of W sliced (Eq. (6) scale step)
@@ -194,50 +201,70 @@ __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_decode_kernel(const uint8_
       wsc[nt][0] = scale_add_x4(wsc[nt][0], kDeltaE_E4M3_E2M1);
       wsc[nt][1] = scale_add_x4(wsc[nt][1], kDeltaE_E4M3_E2M1);
     }
-    wave_lds_order();   // the tile is free again (the reads above execute before the writes below)
-    // W: lane l holds half l % 2 of block l / 2 of each column's chunk; sliced, it is 8 bytes of the column's row
+    if (steps < 8) {   // a K-step that does not exist is multiplied all the same, as zeros under the scale 2^0 (a stray
+                       // byte 255 there would turn the exact zero into NaN)
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
+      for (int p = 0; p < 8; ++p) {
+        if (p >= steps) {
+          const uint32_t m = 0xFFu << (8 * (p & 3)), one = 127u << (8 * (p & 3));
+          asc[p >> 2] = (asc[p >> 2] & ~m) | one;
 #pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        uint32_t half[2];
-        slice_half_block_e2m1(wraw[nt][j], half);   // Eq. (6) element step
-        *reinterpret_cast<u32x2*>(tile + nt * 8192 + j * 512 + 16 * ((lane >> 1) ^ j) + 8 * (lane & 1)) = u32x2{half[0], half[1]};
-      }
-    wave_lds_order();
-#pragma unroll
-    for (int p = 0; p < 8; ++p) {
-      if (p < steps) {
-        const int ascale = (int)(asc[p >> 2] >> (8 * (p & 3)));   // the instruction reads the low byte
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          // block 4 p + g of column i
-          u32x4 t = *reinterpret_cast<const u32x4*>(tile + nt * 8192 + i * 512 + 16 * ((4 * p + g) ^ i));
-          i32x8 b = {(int)t.x, (int)t.y, (int)t.z, (int)t.w, 0, 0, 0, 0};
-          const int bscale = (int)(wsc[nt][p >> 2] >> (8 * (p & 3)));
-          acc[nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af[p], b, acc[nt], 0 /* A: E4M3 */, 4 /* B: E2M1 */, 0,
-                                                                     ascale, 0, bscale);
+          for (int nt = 0; nt < NT; ++nt) wsc[nt][p >> 2] = (wsc[nt][p >> 2] & ~m) | one;
         }
       }
     }
-    wave_lds_order();   // the next chunk overwrites the tile
+    wave_lds_order();   // the tile is free again (the reads above execute before the writes below)
+    // lane parts of the LDS addresses; the per-row / per-K-step parts are XORed in where they are used (kept opaque so
+    // that the compiler does not hold 24 precomputed addresses in registers)
+    uint32_t wr_lane = 8u * (uint32_t)lane, rd_lane = 16u * (uint32_t)(g ^ i) + 512u * (uint32_t)i;
+    asm volatile("" : "+v"(wr_lane), "+v"(rd_lane));
+    static_for<0, NT>([&](auto ntc) {
+      constexpr int nt = decltype(ntc)::value;
+      // W: lane l holds half l % 2 of block l / 2 of the column's chunk; sliced, it is 8 bytes of the column's row of the
+      // tile: slot (l / 2) ^ j, half l % 2
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int r = nt * 16 + j;
+        uint32_t half[2];
+        slice_half_block_e2m1(ring[r % D], half);   // Eq. (6) element step
+        *reinterpret_cast<u32x2*>(tile + j * 512 + (wr_lane ^ (16u * j))) = u32x2{half[0], half[1]};
+        if (r + D < R) ring[r % D] = load_row(r + D);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      wave_lds_order();
+      // block 4 p + g of column i: slot (4 p + g) ^ i of row i; four K-steps' fragments are read ahead of their MFMAs
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        u32x4 bfr[4];
+#pragma unroll
+        for (int pp = 0; pp < 4; ++pp) bfr[pp] = *reinterpret_cast<const u32x4*>(tile + (rd_lane ^ (64u * (4 * h + pp))));
+#pragma unroll
+        for (int pp = 0; pp < 4; ++pp) {
+          const i32x8 b = {(int)bfr[pp].x, (int)bfr[pp].y, (int)bfr[pp].z, (int)bfr[pp].w, 0, 0, 0, 0};
+          // (the instruction reads the low byte of its scale operands)
+          acc[nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(af[4 * h + pp], b, acc[nt], 0 /* A: E4M3 */, 4 /* B: E2M1 */, 0,
+                                                                     (int)(asc[h] >> (8 * pp)), 0, (int)(wsc[nt][h] >> (8 * pp)));
+        }
+      }
+      wave_lds_order();   // the next column tile, or the next chunk's A, overwrites the tile
+    });
   }
   if (wave > 0) {
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) red[wave - 1][nt][j][lane] = acc[nt][j];
+    for (int nt = 0; nt < NT; ++nt) red[((wave - 1) * NT + nt) * 64 + lane] = acc[nt];
   }
   __syncthreads();
   if (wave == 0) {
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
+    for (int nt = 0; nt < NT; ++nt) {
+      const f32x4 r0 = red[(0 * NT + nt) * 64 + lane], r1 = red[(1 * NT + nt) * 64 + lane], r2 = red[(2 * NT + nt) * 64 + lane];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        float s = ((acc[nt][j] + red[0][nt][j][lane]) + red[1][nt][j][lane]) + red[2][nt][j][lane];
+        const float s = ((acc[nt][j] + r0[j]) + r1[j]) + r2[j];
         const int m = 4 * g + j;
         if (m < M && ncol[nt] < N) c[(int64_t)m * ldc + ncol[nt]] = s;
       }
+    }
   }
 }
 
