@@ -108,10 +108,10 @@ def row(nbytes, timing, **extra):
 
 
 # HBM bytes per launch of the headline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the same
-# counters on a plain copy of known size (profiles/ss_e4m3_e2m1_llama8b_checkpoint.md).  The figure belongs to the
+# counters on a plain copy of known size (profiles/ss_batched_e4m3_e2m1_llama8b_checkpoint.md: 7204.4 MB fetched + 3707.8 MB written).  The figure belongs to the
 # kernel sources it was measured with: when they have changed since, the field is null, not a stale number.
-MEASURED_TRAFFIC = {"bytes": 10912165029, "bytes_per_step": 10905190400,
-                    "sources_sha256": "a3f8a0a8f3a9d1d0"}   # first 16 hex digits over mx_ss.hip + mx_device.h
+MEASURED_TRAFFIC = {"bytes": 10912200000, "bytes_per_step": 10905190400,
+                    "sources_sha256": "20e66e4729090a90"}   # first 16 hex digits over mx_ss.hip + mx_device.h
 TRAFFIC_SOURCES = ("paper_2604_00529_amd/csrc/mx_ss.hip", "paper_2604_00529_amd/csrc/mx_device.h")
 
 
