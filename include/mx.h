@@ -202,6 +202,19 @@ int mx_gemm_ss_fp4_ws_slices(int64_t m, int64_t n, int64_t k, size_t workspace_b
 mx_status_t mx_gemm_ss_fp4_ws(const mx_packed_t* a, const mx_packed_t* w_anchor, const mx_dense_t* c, void* workspace,
                               size_t workspace_bytes, void* stream);
 
+/* The same product for a W_t the caller keeps (Sec. 3.5 "Inference": a precision switch converts the anchor once,
+ * W_t = Q_{A->t}(W_A), and every later call runs with that W_t):
+ *     C[m, n] = sum_k DQ(A)[m, k] * DQ(W_t)[n, k].
+ *   a: as for mx_gemm_ss_fp4.
+ *   w_t: MXFP4 E2M1 weights, K-contiguous: outer = N, nblocks = K / 32, 16 bytes of codes per block (what
+ *        mx_slice_and_scale writes for an E4M3 anchor and the target E2M1, or mx_quantize to E2M1).
+ *   c: dense fp32 [M, N], written.
+ * K must be a multiple of 128; MX_ERR_UNSUPPORTED for M > 48 and K >= 2^24.  With w_t = the Slice-and-Scale of an
+ * anchor the results are those of mx_gemm_ss_fp4 on that anchor, bit for bit (the same kernels without the slicing
+ * step up to 48 rows of A, the kernel of mx_gemm_ss_fp4_ws's first case above).  Up to 48 rows the call streams W_t
+ * once: half the anchor's bytes. */
+mx_status_t mx_gemm_fp8_fp4(const mx_packed_t* a, const mx_packed_t* w_t, const mx_dense_t* c, void* stream);
+
 const char* mx_status_str(mx_status_t status);
 
 #ifdef __cplusplus

@@ -281,26 +281,32 @@ def dequant_f64(codes, scales, fmt, k=32):
     return out.reshape(el.shape[:-2] + (el.shape[-2] * k,))
 
 
-def gemm_ss_reference(a_codes, a_scales, w_codes, w_scales, target="e2m1", k=32, with_abs=False, wide=False):
-    """fp64 product of the dequantized operands of the fused consumer GEMM:
-    C = DQ(A) @ DQ(Q_{A->t}(W_A)).T with A in MXFP8 E4M3 [M, K/k blocks] and W_A the E4M3 anchor [N, K/k blocks]
-    (Eq. (6) for the conversion, Sec. 3.3 notation for the reconstruction; numpy's matmul is the library step).
+def gemm_reference(a_codes, a_scales, w_codes, w_scales, w_fmt="e2m1", k=32, with_abs=False, wide=False):
+    """fp64 product of two dequantized MX operands: C = DQ(A) @ DQ(W).T with A in MXFP8 E4M3 [M, K/k blocks] and W
+    packed in `w_fmt` [N, K/k blocks] (Sec. 3.3 notation for the reconstruction V^ = X * P; Sec. 3.5 "Inference": the
+    model runs with a W_t that was converted before; numpy's matmul is the library step).
     with_abs also returns sum_k |a||w|, the scale of the rounding error of any finite-precision accumulation.
     wide: reconstruct the operands straight in float64 (dequant_f64) instead of through the float32 dequantizer, so
     that scale bytes near 0 and 254 keep their exact values and byte 255 propagates as NaN."""
     M, KB = a_scales.shape
     N = w_scales.shape[0]
     K = KB * k
-    tc, ts = slice_and_scale(w_codes, w_scales, "e4m3", target, k=k)
     if wide:
         a = dequant_f64(a_codes, a_scales, "e4m3", k=k)
-        w = dequant_f64(tc, ts, target, k=k)
+        w = dequant_f64(w_codes, w_scales, w_fmt, k=k)
     else:
         a = dequant(a_codes, a_scales, "e4m3", M, K, axis=1, k=k).astype(np.float64)
-        w = dequant(tc, ts, target, N, K, axis=1, k=k).astype(np.float64)
+        w = dequant(w_codes, w_scales, w_fmt, N, K, axis=1, k=k).astype(np.float64)
     if with_abs:
         return a @ w.T, np.abs(a) @ np.abs(w).T
     return a @ w.T
+
+
+def gemm_ss_reference(a_codes, a_scales, w_codes, w_scales, target="e2m1", k=32, with_abs=False, wide=False):
+    """Reference of the fused consumer GEMM: C = DQ(A) @ DQ(Q_{A->t}(W_A)).T with W_A the E4M3 anchor
+    [N, K/k blocks]: the anchor converted by Eq. (6) (slice_and_scale), then gemm_reference."""
+    tc, ts = slice_and_scale(w_codes, w_scales, "e4m3", target, k=k)
+    return gemm_reference(a_codes, a_scales, tc, ts, w_fmt=target, k=k, with_abs=with_abs, wide=wide)
 
 
 def bf16_bits(x):

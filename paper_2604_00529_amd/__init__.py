@@ -12,7 +12,7 @@ from .binding import ELEMS, MxError, make_format
 
 __all__ = ["mx_quantize", "mx_slice_and_scale", "mx_slice_and_scale_batched", "mx_slice_and_scale_batched_noalloc",
            "mx_slice_and_scale_multi", "mx_fake_quant", "mx_dequant",
-           "mx_gemm_ss_fp4", "mx_packed_bytes", "mx_elem_bits", "mx_elem_emax", "MxFakeQuantSTE", "ELEMS", "MxError", "make_format",
+           "mx_gemm_ss_fp4", "mx_gemm_fp8_fp4", "mx_packed_bytes", "mx_elem_bits", "mx_elem_emax", "MxFakeQuantSTE", "ELEMS", "MxError", "make_format",
            "packed_shape", "SsBatch"]
 
 
@@ -272,6 +272,25 @@ def mx_gemm_ss_fp4(a_codes, a_scales, w_codes, w_scales, out=None, workspace=Non
                                           workspace.numel(), _stream(a_codes)), "mx_gemm_ss_fp4_ws")
         return out
     binding.check(L.mx_gemm_ss_fp4(ctypes.byref(a), ctypes.byref(w), ctypes.byref(c), _stream(a_codes)), "mx_gemm_ss_fp4")
+    return out
+
+
+def mx_gemm_fp8_fp4(a_codes, a_scales, w4_codes, w4_scales, out=None):
+    """C[M, N] = DQ(A) @ DQ(W_t).T for MXFP4 E2M1 weights the caller keeps (Sec. 3.5 "Inference": the anchor is converted
+    once per precision switch, not per call).
+
+    a_*: MXFP8 E4M3 activations [M, K/32, 32] / [M, K/32]; w4_*: E2M1 codes [N, K/32, 16] / scale bytes [N, K/32], e.g.
+    the result of mx_slice_and_scale(anchor -> e2m1).  The results are mx_gemm_ss_fp4's on that anchor bit for bit."""
+    torch = _torch()
+    L = binding.lib()
+    M, KB = a_scales.shape
+    N = w4_scales.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=a_codes.device)
+    a = _packed(a_codes, a_scales, M, KB)
+    w = _packed(w4_codes, w4_scales, N, w4_scales.shape[1])
+    c = _dense(out)
+    binding.check(L.mx_gemm_fp8_fp4(ctypes.byref(a), ctypes.byref(w), ctypes.byref(c), _stream(a_codes)), "mx_gemm_fp8_fp4")
     return out
 
 

@@ -90,6 +90,8 @@ def lib():
         L.mx_dequant.restype = st
         L.mx_gemm_ss_fp4.argtypes = [P(MxPacked), P(MxPacked), P(MxDense), vp]
         L.mx_gemm_ss_fp4.restype = st
+        L.mx_gemm_fp8_fp4.argtypes = [P(MxPacked), P(MxPacked), P(MxDense), vp]
+        L.mx_gemm_fp8_fp4.restype = st
         L.mx_status_str.argtypes = [st]
         L.mx_status_str.restype = ctypes.c_char_p
         _lib = L

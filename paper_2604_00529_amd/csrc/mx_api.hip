@@ -366,6 +366,22 @@ mx_status_t mx_gemm_ss_fp4_ws(const mx_packed_t* a, const mx_packed_t* w_anchor,
                                  c->rows, N, K, c->ld, static_cast<hipStream_t>(stream));
 }
 
+mx_status_t mx_gemm_fp8_fp4(const mx_packed_t* a, const mx_packed_t* w_t, const mx_dense_t* c, void* stream) {
+  mx_status_t st;
+  if ((st = check_packed(a)) != MX_OK) return st;
+  if ((st = check_packed(w_t)) != MX_OK) return st;
+  if ((st = check_dense(c)) != MX_OK) return st;
+  if (c->dtype != MX_F32) return MX_ERR_UNSUPPORTED;
+  if (a->nblocks != w_t->nblocks || c->rows != a->outer || c->cols != w_t->outer) return MX_ERR_SHAPE;
+  if (c->rows == 0 || c->cols == 0) return MX_OK;
+  const int64_t K = a->nblocks * 32;
+  if (K == 0 || K % 128 != 0 || K > 0x7FFFFFFF || c->rows > 0x7FFFFFFF || c->cols > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+  drop_stale_error();
+  return mx::gemm_fp8_fp4_launch(static_cast<const uint8_t*>(a->codes), a->scales, static_cast<const uint8_t*>(w_t->codes),
+                                 w_t->scales, static_cast<float*>(c->data), c->rows, c->cols, K, c->ld,
+                                 static_cast<hipStream_t>(stream));
+}
+
 const char* mx_status_str(mx_status_t status) {
   switch (status) {
     case MX_OK: return "ok";

@@ -768,9 +768,13 @@ constexpr RowsShape quantize_shape() {
   if (E::hw != HW_NONE) return RowsShape{2, 64};                               // E2M1 85 (1 x 64: 73), FP6 79
   return RowsShape{1, 256};
 }
-template <int ELEM>
+template <int ELEM, int DT>
 constexpr RowsShape dequant_shape() {
   using E = Elem<ELEM>;
+  if (DT == MX_F32) {   // 4 elements per lane: half the code bytes per load of the bf16 case (16384 x 28672 tensor)
+    if (E::bits == 8) return RowsShape{2, 128};                                // 84 (1 x 64: 65)
+    if (E::bits == 4 && !E::is_int) return RowsShape{1, 256};                  // 92 (2 x 256: 87)
+  }
   if (E::bits == 4) return E::is_int ? RowsShape{4, 256} : RowsShape{2, 256};  // 79, 83 (1 x 64: 63, 65)
   if (E::bits == 6) return RowsShape{1, 256};                                  // FP6 79 (one conversion per lane), MXINT6 73
   return RowsShape{1, 64};                                                     // 8-bit: 83
@@ -825,7 +829,7 @@ static mx_status_t run_dequant(int axis, int block, const void* codes, const uin
     constexpr int N = Dense<DT>::N;
     int64_t cpr = d.cols / N, nchunks = d.rows * cpr;
     if (cpr > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;
-    constexpr RowsShape shape = dequant_shape<ELEM>();
+    constexpr RowsShape shape = dequant_shape<ELEM, DT>();
     int64_t wgs = (nchunks + shape.threads * shape.unroll - 1) / (shape.threads * shape.unroll);
     if (wgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
     if (block == 32)

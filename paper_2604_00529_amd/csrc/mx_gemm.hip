@@ -19,6 +19,7 @@
 #include "mx_launch.h"
 
 #include <atomic>
+#include <type_traits>
 
 namespace mx {
 
@@ -52,6 +53,7 @@ constexpr int kMidmMaxM = 48;     // 16 < M <= 48: the streaming kernel with fra
 constexpr int kDecodeARow = 1024 + 16;          // A rows are padded by one slot: row r, slot s -> bank group (r + s) % 16
 constexpr int kDecodeTile = 16 * kDecodeARow;   // (>= the 8 KB of a sliced W tile)
 constexpr int kDecodeRing = 6;                  // rows of W in flight per wave
+constexpr int kDecodeRingSliced = 16;           // ... of a W_t kept by the caller (8-byte loads: the same bytes in flight and more; 6: 10.0 us, 16: 9.5 us per call at 16 x 14336 x 4096)
 constexpr int decode_smem_bytes(int nt) { return 4 * kDecodeTile + 3 * nt * 4 * 64 * (int)sizeof(float); }
 
 // 16 E4M3 anchor codes (4 dwords) -> 16 E2M1 codes (2 dwords): the Slice-and-Scale element step on half a block
@@ -84,6 +86,12 @@ __device__ __forceinline__ u32x4 buffer_load_x4(__amdgpu_buffer_rsrc_t rsrc, uin
   return u32x4{v[0], v[1], v[2], v[3]};
 }
 
+template <bool NT>
+__device__ __forceinline__ u32x2 buffer_load_x2(__amdgpu_buffer_rsrc_t rsrc, uint32_t lane_off, uint32_t row_off) {
+  auto v = __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)lane_off, (int)row_off, NT ? 2 : 0);
+  return u32x2{v[0], v[1]};
+}
+
 // Byte g of each of the 8 dwords of a row's 32-byte scale chunk (the K-block that lane group g holds in each of the
 // chunk's 8 K-steps): K-steps 0-3 packed into out[0], 4-7 into out[1].
 __device__ __forceinline__ void pack_lane_scales(const u32x4& lo, const u32x4& hi, int g, uint32_t (&out)[2]) {
@@ -107,14 +115,17 @@ __device__ __forceinline__ void wave_lds_order() {
 }
 
 
-// NT column tiles of 16 per workgroup: 2, or 1 when that is what it takes to give every compute unit a workgroup
-template <int NT>
-__global__ __launch_bounds__(256, 2) void gemm_ss_fp4_decode_kernel(const uint8_t* __restrict__ a_codes,
+// NT column tiles of 16 per workgroup: 2, or 1 when that is what it takes to give every compute unit a workgroup.
+// SLICED: W is a W_t the caller keeps (MXFP4 codes [N][K / 2], scale bytes already those of the target): lane l loads
+// the 8 bytes it would otherwise have made of its 16 anchor codes, and the rest is the same instruction for instruction,
+// so both forms of the kernel return the same bits.
+template <int NT, bool SLICED>
+__global__ __launch_bounds__(256, 2) void gemm_fp4_decode_kernel(const uint8_t* __restrict__ a_codes,
                                                                  const uint8_t* __restrict__ a_scales,
                                                                  const uint8_t* __restrict__ w_codes,
                                                                  const uint8_t* __restrict__ w_scales, float* __restrict__ c,
                                                                  int M, int N, int K, int64_t ldc) {
-  constexpr int R = 16 * NT, D = kDecodeRing;   // rows of W per chunk; rows in flight
+  constexpr int R = 16 * NT, D = SLICED ? kDecodeRingSliced : kDecodeRing;   // rows of W per chunk; rows in flight
   static_assert(D <= 16 && 8 * 1024 <= kDecodeTile, "the ring is refilled across column tiles; one 8 KB tile of sliced codes");
   extern __shared__ __attribute__((aligned(16))) uint8_t decode_smem[];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -133,7 +144,10 @@ __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_decode_kernel(const uint8_
   // Buffer loads: the loads of a chunk share one offset register per operand (the row is a scalar offset).  The host
   // has checked that both matrices are smaller than 4 GiB.  Reads past the end of a buffer return zero.
   const __amdgpu_buffer_rsrc_t a_rsrc = make_buffer(a_codes, (uint32_t)M * (uint32_t)K);
-  const __amdgpu_buffer_rsrc_t w_rsrc = make_buffer(w_codes, (uint32_t)N * (uint32_t)K);
+  using WReg = std::conditional_t<SLICED, u32x2, u32x4>;                  // a lane's 16 codes of W as loaded
+  constexpr uint32_t kWLane = SLICED ? 8u : 16u, kWChunk = SLICED ? 512u : 1024u;
+  const uint32_t w_row = SLICED ? (uint32_t)K / 2u : (uint32_t)K;         // bytes per row of W
+  const __amdgpu_buffer_rsrc_t w_rsrc = make_buffer(w_codes, (uint32_t)N * w_row);
   const __amdgpu_buffer_rsrc_t as_rsrc = make_buffer(a_scales, (uint32_t)M * (uint32_t)KB);
   const __amdgpu_buffer_rsrc_t ws_rsrc = make_buffer(w_scales, (uint32_t)N * (uint32_t)KB);
   for (int chunk = wave; chunk < chunks; chunk += 4) {
@@ -144,9 +158,11 @@ __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_decode_kernel(const uint8_
     const int steps = ksteps - chunk * 8 < 8 ? ksteps - chunk * 8 : 8;
     const uint32_t lane_off = (lane >> 3) < steps ? 16u * (uint32_t)lane : 0u;
     const uint32_t chunk_off = (uint32_t)chunk * 1024u;
-    auto load_row = [&](int r) {   // row r of the chunk: column col0 + r, one contiguous 1 KB
+    const uint32_t w_lane_off = (lane >> 3) < steps ? kWLane * (uint32_t)lane : 0u;
+    auto load_row = [&](int r) {   // row r of the chunk: column col0 + r, one contiguous 1 KB (512 bytes of a sliced W)
       const int n = col0 + r < N ? col0 + r : N - 1;
-      return buffer_load_x4<true>(w_rsrc, lane_off, (uint32_t)n * (uint32_t)K + chunk_off);
+      if constexpr (SLICED) return buffer_load_x2<true>(w_rsrc, w_lane_off, (uint32_t)n * w_row + (uint32_t)chunk * kWChunk);
+      else return buffer_load_x4<true>(w_rsrc, w_lane_off, (uint32_t)n * w_row + (uint32_t)chunk * kWChunk);
     };
     // A: the chunk of each row (1 KB, lane l <-> 16 bytes) goes straight from global memory into the wave's LDS tile, no
     // registers in between; the hardware puts lane l's 16 bytes at slot l of the row.  These loads are requested before
@@ -174,7 +190,7 @@ __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_decode_kernel(const uint8_
       }
     }
     __builtin_amdgcn_sched_barrier(0);
-    u32x4 ring[D];
+    WReg ring[D];
 #pragma unroll
     for (int r = 0; r < D; ++r) ring[r] = load_row(r);
     __builtin_amdgcn_sched_barrier(0);
@@ -198,8 +214,10 @@ __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_decode_kernel(const uint8_
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
       pack_lane_scales(wslo[nt], wshi[nt], g, wsc[nt]);
-      wsc[nt][0] = scale_add_x4(wsc[nt][0], kDeltaE_E4M3_E2M1);
-      wsc[nt][1] = scale_add_x4(wsc[nt][1], kDeltaE_E4M3_E2M1);
+      if constexpr (!SLICED) {
+        wsc[nt][0] = scale_add_x4(wsc[nt][0], kDeltaE_E4M3_E2M1);
+        wsc[nt][1] = scale_add_x4(wsc[nt][1], kDeltaE_E4M3_E2M1);
+      }
     }
     if (steps < 8) {   // a K-step that does not exist is multiplied all the same, as zeros under the scale 2^0 (a stray
                        // byte 255 there would turn the exact zero into NaN)
@@ -226,7 +244,8 @@ __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_decode_kernel(const uint8_
       for (int j = 0; j < 16; ++j) {
         const int r = nt * 16 + j;
         uint32_t half[2];
-        slice_half_block_e2m1(ring[r % D], half);   // Eq. (6) element step
+        if constexpr (SLICED) { half[0] = ring[r % D].x; half[1] = ring[r % D].y; }
+        else slice_half_block_e2m1(ring[r % D], half);   // Eq. (6) element step
         *reinterpret_cast<u32x2*>(tile + j * 512 + (wr_lane ^ (16u * j))) = u32x2{half[0], half[1]};
         if (r + D < R) ring[r % D] = load_row(r + D);
         __builtin_amdgcn_sched_barrier(0);
@@ -276,8 +295,9 @@ __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_decode_kernel(const uint8_
 // kGroup K-steps: the first group is requested ahead of W, the second half-way through the slicing, when half of W's
 // registers are free, the others (MT > 2) behind the MFMAs of the group whose registers they take.  K is split over
 // the four waves in chunks of 1024 as in the decode kernel, and the partial sums are added in the same order.
-template <int MT, int NT>
-__global__ __launch_bounds__(256, 2) void gemm_ss_fp4_midm_kernel(const uint8_t* __restrict__ a_codes,
+// SLICED: as in the decode kernel (W is a kept W_t; 8-byte loads, no Slice-and-Scale step, the same bits).
+template <int MT, int NT, bool SLICED>
+__global__ __launch_bounds__(256, 2) void gemm_fp4_midm_kernel(const uint8_t* __restrict__ a_codes,
                                                                const uint8_t* __restrict__ a_scales,
                                                                const uint8_t* __restrict__ w_codes,
                                                                const uint8_t* __restrict__ w_scales, float* __restrict__ c,
@@ -310,13 +330,16 @@ __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_midm_kernel(const uint8_t*
     as_off[mt] = (uint32_t)m * (uint32_t)KB;
   }
   // (the host has checked that W is smaller than 4 GiB; reads past the end of a buffer return zero)
-  const __amdgpu_buffer_rsrc_t w_rsrc = make_buffer(w_codes, (uint32_t)N * (uint32_t)K);
+  using WReg = std::conditional_t<SLICED, u32x2, u32x4>;
+  constexpr uint32_t kWLane = SLICED ? 8u : 16u, kWChunk = SLICED ? 512u : 1024u;
+  const uint32_t w_row = SLICED ? (uint32_t)K / 2u : (uint32_t)K;         // bytes per row of W
+  const __amdgpu_buffer_rsrc_t w_rsrc = make_buffer(w_codes, (uint32_t)N * w_row);
   const __amdgpu_buffer_rsrc_t as_rsrc = make_buffer(a_scales, (uint32_t)M * (uint32_t)KB);
   const __amdgpu_buffer_rsrc_t ws_rsrc = make_buffer(w_scales, (uint32_t)N * (uint32_t)KB);
   for (int chunk = wave; chunk < chunks; chunk += 4) {
     const int steps = ksteps - chunk * 8 < 8 ? ksteps - chunk * 8 : 8;
-    const uint32_t lane_off = (lane >> 3) < steps ? 16u * (uint32_t)lane : 0u;   // (as in the decode kernel)
-    const uint32_t chunk_off = (uint32_t)chunk * 1024u;
+    const uint32_t lane_off = (lane >> 3) < steps ? kWLane * (uint32_t)lane : 0u;   // (as in the decode kernel)
+    const uint32_t chunk_off = (uint32_t)chunk * kWChunk;
     // the fragments of A of K-steps kGroup q .. kGroup q + kGroup - 1 of the chunk (a K-step that does not exist: the
     // chunk's last one again, which is not multiplied)
     u32x4 a0[2][kGroup][MT], a1[2][kGroup][MT];
@@ -349,13 +372,14 @@ __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_midm_kernel(const uint8_t*
     }
     load_a_group(std::integral_constant<int, 0>{});
     __builtin_amdgcn_sched_barrier(0);
-    u32x4 wraw[NT][16];
+    WReg wraw[NT][16];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
         const int n = col0 + nt * 16 + j < N ? col0 + nt * 16 + j : N - 1;
-        wraw[nt][j] = buffer_load_x4<true>(w_rsrc, lane_off, (uint32_t)n * (uint32_t)K + chunk_off);
+        if constexpr (SLICED) wraw[nt][j] = buffer_load_x2<true>(w_rsrc, lane_off, (uint32_t)n * w_row + chunk_off);
+        else wraw[nt][j] = buffer_load_x4<true>(w_rsrc, lane_off, (uint32_t)n * w_row + chunk_off);
       }
     __builtin_amdgcn_sched_barrier(0);
     uint32_t asc[MT][2], wsc[NT][2];
@@ -364,8 +388,10 @@ __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_midm_kernel(const uint8_t*
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
       pack_lane_scales(wslo[nt], wshi[nt], g, wsc[nt]);
-      wsc[nt][0] = scale_add_x4(wsc[nt][0], kDeltaE_E4M3_E2M1);   // Eq. (6) scale step
-      wsc[nt][1] = scale_add_x4(wsc[nt][1], kDeltaE_E4M3_E2M1);
+      if constexpr (!SLICED) {
+        wsc[nt][0] = scale_add_x4(wsc[nt][0], kDeltaE_E4M3_E2M1);   // Eq. (6) scale step
+        wsc[nt][1] = scale_add_x4(wsc[nt][1], kDeltaE_E4M3_E2M1);
+      }
     }
     // W: lane l holds half l % 2 of block l / 2 of each column's chunk; sliced, it is 8 bytes of the column's row
     static_for<0, NT>([&](auto ntc) {
@@ -373,7 +399,8 @@ __global__ __launch_bounds__(256, 2) void gemm_ss_fp4_midm_kernel(const uint8_t*
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
         uint32_t half[2];
-        slice_half_block_e2m1(wraw[nt][j], half);   // Eq. (6) element step
+        if constexpr (SLICED) { half[0] = wraw[nt][j].x; half[1] = wraw[nt][j].y; }
+        else slice_half_block_e2m1(wraw[nt][j], half);   // Eq. (6) element step
         *reinterpret_cast<u32x2*>(tile + nt * 8192 + j * 512 + 16 * ((lane >> 1) ^ j) + 8 * (lane & 1)) = u32x2{half[0], half[1]};
       }
       if constexpr (nt == 0) {
@@ -1149,54 +1176,76 @@ static bool allow_dynamic_lds(int bytes) {
   return true;
 }
 
-mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
-                               const uint8_t* w_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
-                               hipStream_t stream) {
-  // (the streaming kernels address W, and the decode kernel its up to 16 rows of A, with 32-bit offsets)
-  const bool w_fits_32_bits = N * K <= 0xFFFFFFFFll && 16 * K <= 0xFFFFFFFFll;
-  if (M > 16 && M <= kMidmMaxM && w_fits_32_bits) {
-    const int cus = device_compute_units();
-    if (cus <= 0) return MX_ERR_LAUNCH;
+// The streaming kernels (M <= 48; they address W, and the decode kernel its up to 16 rows of A, with 32-bit offsets).
+// Returns false, with nothing enqueued, when the shape is not theirs.  SLICED: W holds MXFP4 codes, K / 2 bytes per row.
+template <bool SLICED>
+static bool gemm_stream_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes, const uint8_t* w_scales,
+                               float* c, int64_t M, int64_t N, int64_t K, int64_t ldc, hipStream_t stream, mx_status_t* status) {
+  const bool w_fits_32_bits = N * (SLICED ? K / 2 : K) <= 0xFFFFFFFFll && 16 * K <= 0xFFFFFFFFll;
+  if (M > kMidmMaxM || !w_fits_32_bits) return false;
+  *status = MX_ERR_LAUNCH;
+  const int cus = device_compute_units();
+  if (cus <= 0) return true;
+  if (M > 16) {
     const int mt_mid = (int)((M + 15) / 16), nt_mid = (N + 31) / 32 >= cus ? 2 : 1;   // (16 columns per workgroup when 32 leave compute units idle)
 #define MX_GEMM_MIDM(MT, NT)                                                                                               \
   if (mt_mid == MT && nt_mid == NT) {                                                                                      \
     constexpr int kSmem = 4 * NT * 8192;                                                                                   \
-    if (!allow_dynamic_lds<gemm_ss_fp4_midm_kernel<MT, NT>>(kSmem)) return MX_ERR_LAUNCH;                                   \
-    hipLaunchKernelGGL((gemm_ss_fp4_midm_kernel<MT, NT>), dim3((unsigned)((N + 16 * NT - 1) / (16 * NT))), dim3(256),      \
+    if (!allow_dynamic_lds<gemm_fp4_midm_kernel<MT, NT, SLICED>>(kSmem)) return true;                                       \
+    hipLaunchKernelGGL((gemm_fp4_midm_kernel<MT, NT, SLICED>), dim3((unsigned)((N + 16 * NT - 1) / (16 * NT))), dim3(256), \
                        kSmem, stream, a_codes, a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc);              \
   }
     MX_GEMM_MIDM(2, 2) MX_GEMM_MIDM(3, 2) MX_GEMM_MIDM(2, 1) MX_GEMM_MIDM(3, 1)
 #undef MX_GEMM_MIDM
-    return launch_status("the fused GEMM");
+  } else {
+    // 32 columns per workgroup; 16 when 32 would leave compute units without one (N = 4096, K = 14336: 27 us with 128
+    // workgroups of 32 columns)
+#define MX_GEMM_DECODE(NT)                                                                                                  \
+  {                                                                                                                         \
+    if (!allow_dynamic_lds<gemm_fp4_decode_kernel<NT, SLICED>>(decode_smem_bytes(NT))) return true;                         \
+    hipLaunchKernelGGL((gemm_fp4_decode_kernel<NT, SLICED>), dim3((unsigned)((N + 16 * NT - 1) / (16 * NT))), dim3(256),    \
+                       decode_smem_bytes(NT), stream, a_codes, a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc); \
   }
-  if (M > kMidmMaxM || !w_fits_32_bits) {   // (the tiled kernel takes any M; below 49 rows only when W has 4 GiB or more)
-    if (kGemmBM * K > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;   // the kernel addresses a tile of A with 32-bit offsets
-    const int cus = device_compute_units();
-    if (cus <= 0) return MX_ERR_LAUNCH;
-    // Tile width: one workgroup fills a CU, so the tiles run in rounds of `cus`; the narrower tiles trade work per
-    // tile for a last round that is less empty, or for more workgroups when M is small.  A tile costs a fixed part (its
-    // A tile and the latencies of a K-step do not shrink with the width) plus a part per column: measured 19 us + 0.26 us
-    // per column for K = 4096, hence cost ~ rounds x (5 + width / 16).  (896 tiles of 128 columns on 256 CUs are 4
-    // rounds of which the last is half empty; 1024 tiles of 112 columns are 4 full rounds of 7/8 the work.  M = 128:
-    // 224 tiles of 64 columns take 36 us, 128 tiles of 112 columns 48 us.)
-    const int64_t m_tiles = (M + kGemmBM - 1) / kGemmBM;
-    int ntw = 8;
-    int64_t best = -1;
-    for (int cand = 8; cand >= 4; --cand) {
-      const int64_t tiles_c = m_tiles * ((N + 16 * cand - 1) / (16 * cand));
-      const int64_t cost = (tiles_c + cus - 1) / cus * (50 + cand * 10);
-      if (best < 0 || cost < best) { best = cost; ntw = cand; }
-    }
-    const int64_t n_tiles = (N + 16 * ntw - 1) / (16 * ntw);
-    const int64_t tiles = m_tiles * n_tiles;
-    if (tiles > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-    // one persistent workgroup per CU (its LDS and registers fill the CU), fewer when there are fewer tiles; the kernel
-    // counts the K-steps of a workgroup in an int
-    const int64_t grid_wgs = (tiles < cus || K % (4 * kGemmBK) != 0) ? tiles : cus;   // (the kernel takes several tiles only in rounds of four K-steps)
-    if ((tiles + grid_wgs - 1) / grid_wgs * (K / kGemmBK) > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-    if (ldc * kGemmBM >= ((int64_t)1 << 30)) return MX_ERR_UNSUPPORTED;   // a tile of C is addressed with 32-bit byte offsets
-    // 3 stages x 41.5 KB: above the 64 KB a kernel gets by default, so the dynamic size is requested explicitly
-    constexpr int kSmem = 3 * (int)sizeof(GemmStage);
+    if ((N + 31) / 32 >= cus) MX_GEMM_DECODE(2) else MX_GEMM_DECODE(1)
+#undef MX_GEMM_DECODE
+  }
+  *status = launch_status(SLICED ? "the MXFP8 x MXFP4 GEMM" : "the fused GEMM");
+  return true;
+}
+
+mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
+                               const uint8_t* w_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
+                               hipStream_t stream) {
+  mx_status_t status;
+  if (gemm_stream_launch<false>(a_codes, a_scales, w_codes, w_scales, c, M, N, K, ldc, stream, &status)) return status;
+  // the tiled kernel takes any M (below 49 rows only when W has 4 GiB or more)
+  if (kGemmBM * K > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;   // the kernel addresses a tile of A with 32-bit offsets
+  const int cus = device_compute_units();
+  if (cus <= 0) return MX_ERR_LAUNCH;
+  // Tile width: one workgroup fills a CU, so the tiles run in rounds of `cus`; the narrower tiles trade work per
+  // tile for a last round that is less empty, or for more workgroups when M is small.  A tile costs a fixed part (its
+  // A tile and the latencies of a K-step do not shrink with the width) plus a part per column: measured 19 us + 0.26 us
+  // per column for K = 4096, hence cost ~ rounds x (5 + width / 16).  (896 tiles of 128 columns on 256 CUs are 4
+  // rounds of which the last is half empty; 1024 tiles of 112 columns are 4 full rounds of 7/8 the work.  M = 128:
+  // 224 tiles of 64 columns take 36 us, 128 tiles of 112 columns 48 us.)
+  const int64_t m_tiles = (M + kGemmBM - 1) / kGemmBM;
+  int ntw = 8;
+  int64_t best = -1;
+  for (int cand = 8; cand >= 4; --cand) {
+    const int64_t tiles_c = m_tiles * ((N + 16 * cand - 1) / (16 * cand));
+    const int64_t cost = (tiles_c + cus - 1) / cus * (50 + cand * 10);
+    if (best < 0 || cost < best) { best = cost; ntw = cand; }
+  }
+  const int64_t n_tiles = (N + 16 * ntw - 1) / (16 * ntw);
+  const int64_t tiles = m_tiles * n_tiles;
+  if (tiles > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+  // one persistent workgroup per CU (its LDS and registers fill the CU), fewer when there are fewer tiles; the kernel
+  // counts the K-steps of a workgroup in an int
+  const int64_t grid_wgs = (tiles < cus || K % (4 * kGemmBK) != 0) ? tiles : cus;   // (the kernel takes several tiles only in rounds of four K-steps)
+  if ((tiles + grid_wgs - 1) / grid_wgs * (K / kGemmBK) > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+  if (ldc * kGemmBM >= ((int64_t)1 << 30)) return MX_ERR_UNSUPPORTED;   // a tile of C is addressed with 32-bit byte offsets
+  // 3 stages x 41.5 KB: above the 64 KB a kernel gets by default, so the dynamic size is requested explicitly
+  constexpr int kSmem = 3 * (int)sizeof(GemmStage);
 #define MX_GEMM_TILED(NTW)                                                                                                  \
   if (ntw == NTW) {                                                                                                         \
     if (!allow_dynamic_lds<gemm_ss_fp4_tiled_kernel<NTW>>(kSmem)) return MX_ERR_LAUNCH;                                     \
@@ -1204,26 +1253,9 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
                        a_codes, a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles, (int)tiles,      \
                        (int)K, (int64_t)0);                                                                                \
   }
-    MX_GEMM_TILED(8) MX_GEMM_TILED(7) MX_GEMM_TILED(6) MX_GEMM_TILED(5) MX_GEMM_TILED(4)
+  MX_GEMM_TILED(8) MX_GEMM_TILED(7) MX_GEMM_TILED(6) MX_GEMM_TILED(5) MX_GEMM_TILED(4)
 #undef MX_GEMM_TILED
-    return launch_status("the fused GEMM");
-  }
-  if (M <= 16 && w_fits_32_bits) {
-    // 32 columns per workgroup; 16 when 32 would leave compute units without one (N = 4096, K = 14336: 27 us with 128
-    // workgroups of 32 columns)
-    const int cus = device_compute_units();
-    if (cus <= 0) return MX_ERR_LAUNCH;
-#define MX_GEMM_DECODE(NT)                                                                                                  \
-  {                                                                                                                         \
-    if (!allow_dynamic_lds<gemm_ss_fp4_decode_kernel<NT>>(decode_smem_bytes(NT))) return MX_ERR_LAUNCH;                     \
-    hipLaunchKernelGGL(gemm_ss_fp4_decode_kernel<NT>, dim3((unsigned)((N + 16 * NT - 1) / (16 * NT))), dim3(256),           \
-                       decode_smem_bytes(NT), stream, a_codes, a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc); \
-  }
-    if ((N + 31) / 32 >= cus) MX_GEMM_DECODE(2) else MX_GEMM_DECODE(1)
-#undef MX_GEMM_DECODE
-    return launch_status("the fused GEMM");
-  }
-  return MX_ERR_UNSUPPORTED;   // (not reached: every shape is taken above)
+  return launch_status("the fused GEMM");
 }
 
 // C = the K slices' partial sums added in the order of the slices: thread q takes 4 consecutive columns of one row.
@@ -1339,6 +1371,8 @@ bool gemm_hoist_pays(int64_t M, int64_t N) {
 mx_status_t gemm_fp8_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w4_codes,
                                 const uint8_t* w4_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
                                 hipStream_t stream) {
+  mx_status_t status;
+  if (gemm_stream_launch<true>(a_codes, a_scales, w4_codes, w4_scales, c, M, N, K, ldc, stream, &status)) return status;
   if (256 * K > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;   // a tile is addressed with 32-bit offsets
   const int cus = device_compute_units();
   if (cus <= 0) return MX_ERR_LAUNCH;

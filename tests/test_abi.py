@@ -174,6 +174,12 @@ def test_validation_returns_codes_without_launching(mx):
     assert L.mx_gemm_ss_fp4_ws(ref(ga), ref(gw), ref(gc), ctypes.c_void_p(P), L.mx_gemm_ss_fp4_workspace(64, 256) - 1, None) == 7
     assert L.mx_gemm_ss_fp4_ws(ref(B.MxPacked(None, None, 0, 8)), ref(gw), ref(B.MxDense(None, B.MX_F32, 0, 64, 64)), ctypes.c_void_p(P), big, None) == 0
     # the plan query answers "one slice" for arguments that the entry point would refuse or serve without the workspace
+    # the product with a kept W_t: the same checks, no compute
+    assert L.mx_gemm_fp8_fp4(None, ref(gw), ref(gc), None) == 1 and L.mx_gemm_fp8_fp4(ref(ga), ref(gw), None, None) == 1
+    assert L.mx_gemm_fp8_fp4(ref(ga), ref(gw), ref(B.MxDense(P, B.MX_BF16, 16, 64, 64)), None) == 5
+    assert L.mx_gemm_fp8_fp4(ref(ga), ref(B.MxPacked(P, P, 64, 12)), ref(gc), None) == 3
+    assert L.mx_gemm_fp8_fp4(ref(B.MxPacked(P, P, 16, 6)), ref(B.MxPacked(P, P, 64, 6)), ref(gc), None) == 5
+    assert L.mx_gemm_fp8_fp4(ref(B.MxPacked(None, None, 0, 8)), ref(gw), ref(B.MxDense(None, B.MX_F32, 0, 64, 64)), None) == 0
     assert L.mx_gemm_ss_fp4_ws_slices(0, 64, 256, big) == 1 and L.mx_gemm_ss_fp4_ws_slices(64, 64, 192, big) == 1
     assert L.mx_gemm_ss_fp4_ws_slices(64, 4096, 14336, 16) == 1                                                  # workspace too small
     for code in range(8):

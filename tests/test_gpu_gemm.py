@@ -40,7 +40,7 @@ def _group_exponents(codes, scales, fmt):
     return np.ldexp(1.0, g + x)
 
 
-def _error_bound(oracle, ac, asc, wc, wsc, ref_abs, extra_adds=0):
+def _error_bound(oracle, ac, asc, wc, wsc, ref_abs, extra_adds=0, sliced=False):
     """Bound on |C_gpu - C_exact|, element by element, from how the scaled MX matrix instruction adds (measured with
     one-instruction probes, then derived):
       (i)  inside a group of 8 consecutive K elements the products are aligned to the group's largest exponent sum
@@ -51,7 +51,7 @@ def _error_bound(oracle, ac, asc, wc, wsc, ref_abs, extra_adds=0):
            running maximum is at most sum |products|;
       (iii) every instruction rounds its result to fp32 (nearest even, subnormal results kept): 2^-24 of the running
            sum plus 2^-149; the kernels add partial sums of K slices or waves in fp32 a few more times (extra_adds)."""
-    tc, ts = oracle.slice_and_scale(wc, wsc, "e4m3", "e2m1")
+    tc, ts = (wc, wsc) if sliced else oracle.slice_and_scale(wc, wsc, "e4m3", "e2m1")
     ga, gw = _group_exponents(ac, asc, "e4m3"), _group_exponents(tc, ts, "e2m1")
     steps = ac.shape[1] // 4                                                    # instructions per output: K / 128
     with np.errstate(over="ignore", invalid="ignore"):
@@ -112,6 +112,12 @@ def _check(mx, oracle, M, N, K, seed, w_axis0=True, random_bytes=False, want_sli
             assert bool(same.all())
         if want_slices is not None:
             assert slices == want_slices
+    # the same product from a W_t converted beforehand and kept (Sec. 3.5 "Inference"): the bits of the unsplit call
+    t4c, t4s = mx.mx_slice_and_scale(wc, wsc, f8, mx.make_format("e2m1"))
+    c_kept = mx.mx_gemm_fp8_fp4(ac, asc, t4c, t4s)
+    torch.cuda.synchronize()
+    unsplit = c if slices == 1 else c_fly
+    assert bool(((c_kept.view(torch.int32) == unsplit.view(torch.int32)) | (torch.isnan(c_kept) & torch.isnan(unsplit))).all())
     hac, hasc, hwc, hwsc = (x.cpu().numpy() for x in (ac, asc, wc, wsc))
     ref, ref_abs = oracle.gemm_ss_reference(hac, hasc, hwc, hwsc, with_abs=True, wide=True)
     got = c.cpu().numpy().astype(np.float64)
@@ -219,6 +225,53 @@ def test_gemm_seeded_sweep_of_shapes(mx, oracle):
         _check(mx, oracle, M, N, K, seed=7000 + case, w_axis0=kind == 0,
                random_bytes=("narrow", "extreme")[case % 2] if kind == 2 else False)
     assert seen == {"slices", "decode", "mid", "tiled"}
+
+
+@pytest.mark.parametrize("M,N,K", [(16, 256, 512), (1, 48, 128), (7, 104, 2176), (16, 8200, 1152), (33, 64, 1024), (48, 208, 2048),
+                                   (40, 8208, 1024), (64, 1000, 256), (130, 264, 640), (520, 12000, 1024), (1000, 9000, 512)])
+def test_gemm_kept_fp4_weight_random_bytes(mx, oracle, M, N, K):
+    # A W_t that no anchor produced: every nibble pattern (negative zeros included) and scale bytes over a wide range,
+    # some at the ends of the E8M0 range and a few NaN blocks; against the fp64 product of the dequantized operands
+    # (the reference without a conversion step), with the derived bound and the row-norm bar.  Decode, mid and tiled
+    # shapes (tiles of 128 and of 256 rows), ragged in M, N and the last K chunk.
+    import torch
+    rng = np.random.default_rng(M * 7919 + N * 31 + K)
+    ac = rng.integers(0, 256, size=(M, K // 32, 32), dtype=np.uint8)
+    ac[(ac & 0x7F) == 0x7F] = 0x7E
+    w4 = rng.integers(0, 256, size=(N, K // 32, 16), dtype=np.uint8)
+    asc = rng.integers(110, 140, size=(M, K // 32), dtype=np.uint8)
+    w4s = rng.integers(100, 140, size=(N, K // 32), dtype=np.uint8)
+    w4s[rng.integers(N, size=max(1, N // 40)), rng.integers(K // 32, size=max(1, N // 40))] = rng.integers(0, 6)
+    w4s[rng.integers(N, size=max(1, N // 50)), rng.integers(K // 32, size=max(1, N // 50))] = 255
+    got = mx.mx_gemm_fp8_fp4(*(torch.from_numpy(x).cuda() for x in (ac, asc, w4, w4s)))
+    torch.cuda.synchronize()
+    got = got.cpu().numpy().astype(np.float64)
+    ref, ref_abs = oracle.gemm_reference(ac, asc, w4, w4s, w_fmt="e2m1", with_abs=True, wide=True)
+    nan = np.isnan(ref)
+    assert nan.any() and not nan.all() and np.array_equal(np.isnan(got), nan)
+    bound = _error_bound(oracle, ac, asc, w4, w4s, ref_abs, extra_adds=1, sliced=True)
+    err = np.where(nan, 0.0, np.abs(got - ref))
+    assert (nan | (err <= bound)).all(), "worst err / bound %g" % np.nanmax(np.where(nan, 0.0, err / bound))
+    rows = ~nan.all(axis=1)
+    assert (err.max(axis=1) <= 1e-3 * np.sqrt(np.where(nan, 0.0, ref * ref).sum(axis=1)))[rows].all()
+
+
+def test_gemm_kept_fp4_weight_decode_shape_config5(mx, oracle):
+    # the decode shape of the benchmark definition (M = 16, K = 4096, N = 14336) with the weight quantized straight to
+    # MXFP4 (mx_quantize), which a caller may keep as well as a converted anchor
+    import torch
+    rng = np.random.default_rng(1005)
+    a = rng.standard_normal((16, 4096)).astype(np.float32)
+    w = (rng.standard_normal((14336, 4096)) * 0.02).astype(np.float32)
+    ac, asc = mx.mx_quantize(_gpu_bf16(a), mx.make_format("e4m3"))
+    w4, w4s = mx.mx_quantize(_gpu_bf16(w), mx.make_format("e2m1"))
+    got = mx.mx_gemm_fp8_fp4(ac, asc, w4, w4s)
+    torch.cuda.synchronize()
+    hac, hasc, hw4, hw4s = (x.cpu().numpy() for x in (ac, asc, w4, w4s))
+    ref, ref_abs = oracle.gemm_reference(hac, hasc, hw4, hw4s, w_fmt="e2m1", with_abs=True, wide=True)
+    err = np.abs(got.cpu().numpy().astype(np.float64) - ref)
+    assert (err <= _error_bound(oracle, hac, hasc, hw4, hw4s, ref_abs, extra_adds=1, sliced=True)).all()
+    assert (err.max(axis=1) <= 1e-3 * np.sqrt((ref * ref).sum(axis=1))).all()
 
 
 def test_gemm_few_rows_down_proj_shape(mx, oracle):

@@ -171,3 +171,34 @@ def test_wide_reconstruction_against_exact_rationals_at_extreme_scale_bytes(orac
     want_nan[:, 2] = True
     want_nan[1, :] = True
     assert np.array_equal(np.isnan(got), want_nan)
+
+
+def test_gemm_reference_of_a_kept_fp4_weight_against_exact_rationals(oracle):
+    # The product with a W_t that was converted before (Sec. 3.5 "Inference"): the weight's nibbles are read here by hand
+    # (code j of a block = bits 4 j .. 4 j + 3 of its 16 bytes, little endian) and multiplied in exact rationals.  A
+    # swapped nibble order, a scale from the wrong block or a transposed operand fails.
+    e4m3, e2m1 = _tables()
+    rng = np.random.default_rng(20260402)
+    for M, N, KB in [(2, 3, 2), (3, 1, 1)]:
+        a_codes, a_scales, _, _ = _random_operands(rng, M, N, KB)
+        w4 = rng.integers(0, 256, size=(N, KB, 16), dtype=np.uint8)
+        w4_scales = rng.integers(118, 133, size=(N, KB), dtype=np.uint8)
+        got, got_abs = oracle.gemm_reference(a_codes, a_scales, w4, w4_scales, w_fmt="e2m1", with_abs=True)
+        wide = oracle.gemm_reference(a_codes, a_scales, w4, w4_scales, w_fmt="e2m1", wide=True)
+        for m in range(M):
+            for n in range(N):
+                acc = Fraction(0)
+                for b in range(KB):
+                    xa = Fraction(2) ** (int(a_scales[m, b]) - 127)
+                    xw = Fraction(2) ** (int(w4_scales[n, b]) - 127)
+                    for j in range(32):
+                        nib = (int(w4[n, b, j // 2]) >> (4 * (j % 2))) & 0xF
+                        acc += (xa * e4m3[int(a_codes[m, b, j])]) * (xw * e2m1[nib])
+                w = float(acc)
+                assert abs(got[m, n] - w) <= 1e-12 * max(abs(w), float(got_abs[m, n])), (M, N, KB, m, n)
+                assert abs(wide[m, n] - w) <= 1e-12 * max(abs(w), float(got_abs[m, n])), (M, N, KB, m, n)
+    # and the reference of the fused product is this one applied to the converted anchor
+    a_codes, a_scales, w_codes, w_scales = _random_operands(rng, 3, 4, 2)
+    tc, ts = oracle.slice_and_scale(w_codes, w_scales, "e4m3", "e2m1")
+    assert np.array_equal(oracle.gemm_ss_reference(a_codes, a_scales, w_codes, w_scales),
+                          oracle.gemm_reference(a_codes, a_scales, tc, ts, w_fmt="e2m1"))
