@@ -424,6 +424,8 @@ def gemm_rows(torch, mx, synth, rows):
         f4 = mx.make_format("e2m1")
         w4 = [mx.mx_slice_and_scale(c, sc, f8, f4) for c, sc in wv + wv]   # 16 buffers (500 MB): beyond the 256 MB cache, like the anchors
         kept_bytes = Ng * Kg // 2 + Ng * Kg // 32 + Mg * Kg + Mg * Kg // 32 + Mg * Ng * 4
+        kept_need = L.mx_gemm_fp8_fp4_workspace(Mg, Ng, Kg)                      # > 0: the library splits K for this shape
+        kept_ws = torch.empty(kept_need, dtype=torch.uint8, device="cuda") if kept_need else False
         paths = [("", False, base_bytes)] if Mg < mx.GEMM_WORKSPACE_MIN_ROWS else \
                 [("_fused", False, base_bytes), ("_hoisted" if Mg >= mx.GEMM_HOIST_MIN_ROWS else "_k_slices", wsp,
                   base_bytes + (2 * need if Mg >= mx.GEMM_HOIST_MIN_ROWS else 0))]
@@ -434,7 +436,7 @@ def gemm_rows(torch, mx, synth, rows):
             def gemm():
                 i = st["i"] = (st["i"] + 1) % 16
                 if workspace == "kept":
-                    mx.mx_gemm_fp8_fp4(ac, asc, w4[i][0], w4[i][1], cbuf)
+                    mx.mx_gemm_fp8_fp4(ac, asc, w4[i][0], w4[i][1], cbuf, workspace=kept_ws)
                 else:
                     mx.mx_gemm_ss_fp4(ac, asc, wv[i % 8][0], wv[i % 8][1], cbuf, workspace=workspace)
 
@@ -462,7 +464,7 @@ def gemm_rows(torch, mx, synth, rows):
             t = time_region(torch, graph.replay, 12, 4, WARM_MS)
             rows[name + suffix + "_graph"] = gemm_row(tuple(x / 8 for x in t), calls_per_replay=8)
             del graph
-        del a, ac, asc, cbuf, wv, wsp, w4
+        del a, ac, asc, cbuf, wv, wsp, w4, kept_ws
     del wlist
     torch.cuda.empty_cache()
 

@@ -209,11 +209,23 @@ mx_status_t mx_gemm_ss_fp4_ws(const mx_packed_t* a, const mx_packed_t* w_anchor,
  *   w_t: MXFP4 E2M1 weights, K-contiguous: outer = N, nblocks = K / 32, 16 bytes of codes per block (what
  *        mx_slice_and_scale writes for an E4M3 anchor and the target E2M1, or mx_quantize to E2M1).
  *   c: dense fp32 [M, N], written.
- * K must be a multiple of 128; MX_ERR_UNSUPPORTED for M > 48 and K >= 2^24.  With w_t = the Slice-and-Scale of an
- * anchor the results are those of mx_gemm_ss_fp4 on that anchor, bit for bit (the same kernels without the slicing
- * step up to 48 rows of A, the kernel of mx_gemm_ss_fp4_ws's first case above).  Up to 48 rows the call streams W_t
- * once: half the anchor's bytes. */
+ * K must be a multiple of 128; MX_ERR_UNSUPPORTED for M > 48 and K >= 2^24 or a row stride of c of 2^22 elements or
+ * more.  With w_t = the Slice-and-Scale of an anchor the results are those of mx_gemm_ss_fp4 on that anchor, bit for bit
+ * (the same kernels without the slicing step; above 48 rows the kernel with tiles of 256 or 128 rows x 256 columns where
+ * such tiles fill the GPU).  Up to 48 rows the call streams W_t once: half the anchor's bytes. */
 mx_status_t mx_gemm_fp8_fp4(const mx_packed_t* a, const mx_packed_t* w_t, const mx_dense_t* c, void* stream);
+
+/* The same for callers that can lend a workspace (device memory, 16-byte aligned, borrowed for the duration of the
+ * enqueued work; MX_ERR_ALIGN when misaligned): from 49 rows of A on, when the tiles of C leave most compute units
+ * without one, K is split over 2 to 8 workgroups per tile whose partial sums go through the workspace and are added in
+ * the order of the slices -- a fixed order, but not mx_gemm_fp8_fp4's, so the two results differ by fp32 rounding.
+ * mx_gemm_fp8_fp4_workspace(m, n, k) is what the split the library would choose on the current device needs (0: it
+ * would not split); mx_gemm_fp8_fp4_ws_slices the number of slices for a workspace of a given size (1: the result is
+ * mx_gemm_fp8_fp4's bit for bit).  With workspace == NULL, or one too small for any split, this is mx_gemm_fp8_fp4. */
+size_t mx_gemm_fp8_fp4_workspace(int64_t m, int64_t n, int64_t k);
+int mx_gemm_fp8_fp4_ws_slices(int64_t m, int64_t n, int64_t k, size_t workspace_bytes);
+mx_status_t mx_gemm_fp8_fp4_ws(const mx_packed_t* a, const mx_packed_t* w_t, const mx_dense_t* c, void* workspace,
+                               size_t workspace_bytes, void* stream);
 
 const char* mx_status_str(mx_status_t status);
 

@@ -275,12 +275,15 @@ def mx_gemm_ss_fp4(a_codes, a_scales, w_codes, w_scales, out=None, workspace=Non
     return out
 
 
-def mx_gemm_fp8_fp4(a_codes, a_scales, w4_codes, w4_scales, out=None):
+def mx_gemm_fp8_fp4(a_codes, a_scales, w4_codes, w4_scales, out=None, workspace=None):
     """C[M, N] = DQ(A) @ DQ(W_t).T for MXFP4 E2M1 weights the caller keeps (Sec. 3.5 "Inference": the anchor is converted
     once per precision switch, not per call).
 
     a_*: MXFP8 E4M3 activations [M, K/32, 32] / [M, K/32]; w4_*: E2M1 codes [N, K/32, 16] / scale bytes [N, K/32], e.g.
-    the result of mx_slice_and_scale(anchor -> e2m1).  The results are mx_gemm_ss_fp4's on that anchor bit for bit."""
+    the result of mx_slice_and_scale(anchor -> e2m1).  The results are mx_gemm_ss_fp4's on that anchor bit for bit --
+    unless the shape has few tiles and a long K: then, from 49 rows on, K is split over several workgroups per tile
+    through `workspace` (uint8; mx_gemm_fp8_fp4_workspace(M, N, K) bytes, allocated here when not given) and the partial
+    sums are added in a fixed order of their own.  workspace=False never splits."""
     torch = _torch()
     L = binding.lib()
     M, KB = a_scales.shape
@@ -290,6 +293,14 @@ def mx_gemm_fp8_fp4(a_codes, a_scales, w4_codes, w4_scales, out=None):
     a = _packed(a_codes, a_scales, M, KB)
     w = _packed(w4_codes, w4_scales, N, w4_scales.shape[1])
     c = _dense(out)
+    if M >= GEMM_WORKSPACE_MIN_ROWS and workspace is not False:
+        need = L.mx_gemm_fp8_fp4_workspace(M, N, KB * 32)
+        if need:
+            if workspace is None:
+                workspace = torch.empty(need, dtype=torch.uint8, device=a_codes.device)
+            binding.check(L.mx_gemm_fp8_fp4_ws(ctypes.byref(a), ctypes.byref(w), ctypes.byref(c), ctypes.c_void_p(workspace.data_ptr()),
+                                               workspace.numel(), _stream(a_codes)), "mx_gemm_fp8_fp4_ws")
+            return out
     binding.check(L.mx_gemm_fp8_fp4(ctypes.byref(a), ctypes.byref(w), ctypes.byref(c), _stream(a_codes)), "mx_gemm_fp8_fp4")
     return out
 

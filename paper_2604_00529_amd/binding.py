@@ -92,6 +92,12 @@ def lib():
         L.mx_gemm_ss_fp4.restype = st
         L.mx_gemm_fp8_fp4.argtypes = [P(MxPacked), P(MxPacked), P(MxDense), vp]
         L.mx_gemm_fp8_fp4.restype = st
+        L.mx_gemm_fp8_fp4_workspace.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]
+        L.mx_gemm_fp8_fp4_workspace.restype = ctypes.c_size_t
+        L.mx_gemm_fp8_fp4_ws_slices.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_size_t]
+        L.mx_gemm_fp8_fp4_ws_slices.restype = ctypes.c_int
+        L.mx_gemm_fp8_fp4_ws.argtypes = [P(MxPacked), P(MxPacked), P(MxDense), vp, ctypes.c_size_t, vp]
+        L.mx_gemm_fp8_fp4_ws.restype = st
         L.mx_status_str.argtypes = [st]
         L.mx_status_str.restype = ctypes.c_char_p
         _lib = L

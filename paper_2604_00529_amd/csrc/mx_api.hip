@@ -366,8 +366,10 @@ mx_status_t mx_gemm_ss_fp4_ws(const mx_packed_t* a, const mx_packed_t* w_anchor,
                                  c->rows, N, K, c->ld, static_cast<hipStream_t>(stream));
 }
 
-mx_status_t mx_gemm_fp8_fp4(const mx_packed_t* a, const mx_packed_t* w_t, const mx_dense_t* c, void* stream) {
+// shared checks of the two entry points that multiply by a kept W_t; *k_out = K; MX_OK with *k_out = 0: nothing to do
+static mx_status_t check_gemm_kept(const mx_packed_t* a, const mx_packed_t* w_t, const mx_dense_t* c, int64_t* k_out) {
   mx_status_t st;
+  *k_out = 0;
   if ((st = check_packed(a)) != MX_OK) return st;
   if ((st = check_packed(w_t)) != MX_OK) return st;
   if ((st = check_dense(c)) != MX_OK) return st;
@@ -376,10 +378,48 @@ mx_status_t mx_gemm_fp8_fp4(const mx_packed_t* a, const mx_packed_t* w_t, const 
   if (c->rows == 0 || c->cols == 0) return MX_OK;
   const int64_t K = a->nblocks * 32;
   if (K == 0 || K % 128 != 0 || K > 0x7FFFFFFF || c->rows > 0x7FFFFFFF || c->cols > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+  *k_out = K;
+  return MX_OK;
+}
+
+mx_status_t mx_gemm_fp8_fp4(const mx_packed_t* a, const mx_packed_t* w_t, const mx_dense_t* c, void* stream) {
+  int64_t K;
+  mx_status_t st = check_gemm_kept(a, w_t, c, &K);
+  if (st != MX_OK || K == 0) return st;
   drop_stale_error();
   return mx::gemm_fp8_fp4_launch(static_cast<const uint8_t*>(a->codes), a->scales, static_cast<const uint8_t*>(w_t->codes),
                                  w_t->scales, static_cast<float*>(c->data), c->rows, c->cols, K, c->ld,
                                  static_cast<hipStream_t>(stream));
+}
+
+static bool gemm_kept_shape_ok(int64_t m, int64_t n, int64_t k) {
+  return m > 0 && n > 0 && k > 0 && k % 128 == 0 && k <= 0x7FFFFFFF && m <= 0x7FFFFFFF && n <= 0x7FFFFFFF;
+}
+
+int mx_gemm_fp8_fp4_ws_slices(int64_t m, int64_t n, int64_t k, size_t workspace_bytes) {
+  if (!gemm_kept_shape_ok(m, n, k) || mx::gemm_big_tiles_pay(m, n)) return 1;
+  return mx::gemm_splitk_slices(m, n, k, workspace_bytes, nullptr);
+}
+
+size_t mx_gemm_fp8_fp4_workspace(int64_t m, int64_t n, int64_t k) {
+  const int slices = mx_gemm_fp8_fp4_ws_slices(m, n, k, ~(size_t)0);
+  if (slices <= 1) return 0;
+  return (size_t)slices * (size_t)m * (size_t)((n + 3) & ~(int64_t)3) * sizeof(float);   // the partial sums of the K slices
+}
+
+mx_status_t mx_gemm_fp8_fp4_ws(const mx_packed_t* a, const mx_packed_t* w_t, const mx_dense_t* c, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+  int64_t K;
+  mx_status_t st = check_gemm_kept(a, w_t, c, &K);
+  if (st != MX_OK || K == 0) return st;
+  if (!workspace || workspace_bytes == 0 || mx::gemm_big_tiles_pay(c->rows, c->cols)) return mx_gemm_fp8_fp4(a, w_t, c, stream);
+  if (!aligned16(workspace)) return MX_ERR_ALIGN;
+  drop_stale_error();
+  if (mx::gemm_fp8_fp4_splitk(static_cast<const uint8_t*>(a->codes), a->scales, static_cast<const uint8_t*>(w_t->codes),
+                              w_t->scales, static_cast<float*>(c->data), c->rows, c->cols, K, c->ld, workspace, workspace_bytes,
+                              static_cast<hipStream_t>(stream), &st))
+    return st;
+  return mx_gemm_fp8_fp4(a, w_t, c, stream);
 }
 
 const char* mx_status_str(mx_status_t status) {

@@ -535,8 +535,10 @@ __device__ __forceinline__ void gemm_advance(GemmCursor& cur, int ksteps, const 
   else if (cur.tiles_left > 1) gemm_next_tile(cur, sh);
 }
 
-template <int NTW>
-__global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const uint8_t* __restrict__ a_codes,
+// SLICED: W is a W_t the caller keeps (MXFP4 codes, K / 2 bytes per row): the producers load 8 bytes where they would
+// have made 8 of 16, and store them as they are; everything else is the same kernel.
+template <int NTW, bool SLICED>
+__global__ __launch_bounds__(kGemmThreads) void gemm_fp4_tiled_kernel(const uint8_t* __restrict__ a_codes,
                                                                          const uint8_t* __restrict__ a_scales,
                                                                          const uint8_t* __restrict__ w_codes,
                                                                          const uint8_t* __restrict__ w_scales,
@@ -550,7 +552,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
   // c + y c_slice.  One slice (k_len = K) is the whole product.
   const uint32_t k_skip = (uint32_t)blockIdx.y * (uint32_t)k_len;
   a_codes += k_skip;
-  w_codes += k_skip;
+  w_codes += SLICED ? k_skip / 2 : k_skip;
   a_scales += k_skip / 32;
   w_scales += k_skip / 32;
   c += (int64_t)blockIdx.y * c_slice;
@@ -668,22 +670,24 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
     for (int j = 0; j < WP; ++j) {
       const int q = pt + PT * j;
       w_col[j] = (q >> 3) < BN ? (q >> 3) : BN - 1;   // the spare threads of the last piece repeat the tile's last column
-      w_piece[j] = 16 * (q & 7);
+      w_piece[j] = (SLICED ? 8 : 16) * (q & 7);
     }
     const int scol = pt < BN ? pt : BN - 1;
-    u32x4 rb[R][WP];
+    using WReg = std::conditional_t<SLICED, u32x2, u32x4>;   // 16 codes of W as loaded
+    const int64_t w_row = SLICED ? K / 2 : K;              // bytes per row of W
+    WReg rb[R][WP];
     uint32_t rsa[R], rsw[R];
     GemmCursor ld = first;   // the K-step that the next call of load_step requests
     auto load_step = [&](auto slot_c) __attribute__((always_inline)) {
       constexpr int S = decltype(slot_c)::value;
       const int m0 = ld.tm * kGemmBM, n0 = ld.tn * BN;
-      const int k0 = ld.k * kGemmBK;
+      const int k0 = ld.k * (SLICED ? kGemmBK / 2 : kGemmBK);
 #pragma unroll
       for (int j = 0; j < WP; ++j) {
         // plain loads: the workgroups that share this W tile run at about the same time, partly on different XCDs,
         // and non-temporal loads made each of them fetch it from HBM (269 us against 196 us for the kernel)
         const int n = n0 + w_col[j] < N ? n0 + w_col[j] : N - 1;
-        rb[S][j] = *reinterpret_cast<const u32x4*>(w_codes + (int64_t)n * K + k0 + w_piece[j]);
+        rb[S][j] = *reinterpret_cast<const WReg*>(w_codes + (int64_t)n * w_row + k0 + w_piece[j]);
       }
       if constexpr (!kLoader) {   // (with a loader wave the scale bytes of A come with its codes)
         const int ms = m0 + pt < M ? m0 + pt : M - 1;
@@ -699,12 +703,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_ss_fp4_tiled_kernel(const u
       for (int j = 0; j < WP; ++j) {
         const int q = pt + PT * j, col = q >> 3, kb = (q & 7) >> 1, half = q & 1;
         uint32_t b2[2];
-        slice_half_block_e2m1(rb[S][j], b2);   // Eq. (6) element step, once per workgroup and K-step
+        if constexpr (SLICED) { b2[0] = rb[S][j].x; b2[1] = rb[S][j].y; }
+        else slice_half_block_e2m1(rb[S][j], b2);   // Eq. (6) element step, once per workgroup and K-step
         // (the spare threads of the last piece, which loaded the tile's last column again, store nothing)
         if (col < BN) *reinterpret_cast<u32x2*>(&st.b[col * kGemmLdB + 16 * (kb ^ ((col >> 2) & 3)) + 8 * half]) = u32x2{b2[0], b2[1]};
       }
       if constexpr (!kLoader) st.as[pt] = rsa[S];
-      if (pt < BN) st.bs[pt] = scale_add_x4(rsw[S], kDeltaE_E4M3_E2M1);   // Eq. (6) scale step
+      if (pt < BN) st.bs[pt] = SLICED ? rsw[S] : scale_add_x4(rsw[S], kDeltaE_E4M3_E2M1);   // Eq. (6) scale step
     };
     // prologue: steps 0 .. R - 1 requested, step 0 staged
     static_for<0, R>([&](auto d) { load_step(d); });
@@ -1213,12 +1218,11 @@ static bool gemm_stream_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
   return true;
 }
 
-mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
-                               const uint8_t* w_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
-                               hipStream_t stream) {
-  mx_status_t status;
-  if (gemm_stream_launch<false>(a_codes, a_scales, w_codes, w_scales, c, M, N, K, ldc, stream, &status)) return status;
-  // the tiled kernel takes any M (below 49 rows only when W has 4 GiB or more)
+// The tiled kernel: any M (below 49 rows only when W has 4 GiB or more).
+template <bool SLICED>
+static mx_status_t gemm_tiled_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
+                                     const uint8_t* w_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
+                                     hipStream_t stream) {
   if (kGemmBM * K > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;   // the kernel addresses a tile of A with 32-bit offsets
   const int cus = device_compute_units();
   if (cus <= 0) return MX_ERR_LAUNCH;
@@ -1248,14 +1252,22 @@ mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, 
   constexpr int kSmem = 3 * (int)sizeof(GemmStage);
 #define MX_GEMM_TILED(NTW)                                                                                                  \
   if (ntw == NTW) {                                                                                                         \
-    if (!allow_dynamic_lds<gemm_ss_fp4_tiled_kernel<NTW>>(kSmem)) return MX_ERR_LAUNCH;                                     \
-    hipLaunchKernelGGL((gemm_ss_fp4_tiled_kernel<NTW>), dim3((unsigned)grid_wgs), dim3(kGemmThreads), kSmem, stream,     \
+    if (!allow_dynamic_lds<gemm_fp4_tiled_kernel<NTW, SLICED>>(kSmem)) return MX_ERR_LAUNCH;                                \
+    hipLaunchKernelGGL((gemm_fp4_tiled_kernel<NTW, SLICED>), dim3((unsigned)grid_wgs), dim3(kGemmThreads), kSmem, stream, \
                        a_codes, a_scales, w_codes, w_scales, c, (int)M, (int)N, (int)K, ldc, (int)m_tiles, (int)tiles,      \
                        (int)K, (int64_t)0);                                                                                \
   }
   MX_GEMM_TILED(8) MX_GEMM_TILED(7) MX_GEMM_TILED(6) MX_GEMM_TILED(5) MX_GEMM_TILED(4)
 #undef MX_GEMM_TILED
-  return launch_status("the fused GEMM");
+  return launch_status(SLICED ? "the MXFP8 x MXFP4 GEMM" : "the fused GEMM");
+}
+
+mx_status_t gemm_ss_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
+                               const uint8_t* w_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
+                               hipStream_t stream) {
+  mx_status_t status;
+  if (gemm_stream_launch<false>(a_codes, a_scales, w_codes, w_scales, c, M, N, K, ldc, stream, &status)) return status;
+  return gemm_tiled_launch<false>(a_codes, a_scales, w_codes, w_scales, c, M, N, K, ldc, stream);
 }
 
 // C = the K slices' partial sums added in the order of the slices: thread q takes 4 consecutive columns of one row.
@@ -1322,9 +1334,10 @@ int gemm_splitk_slices(int64_t M, int64_t N, int64_t K, size_t workspace_bytes, 
   return best_s;
 }
 
-bool gemm_ss_fp4_splitk(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes, const uint8_t* w_scales,
-                        float* c, int64_t M, int64_t N, int64_t K, int64_t ldc, void* workspace, size_t workspace_bytes,
-                        hipStream_t stream, mx_status_t* status) {
+template <bool SLICED>
+static bool gemm_splitk_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes, const uint8_t* w_scales,
+                               float* c, int64_t M, int64_t N, int64_t K, int64_t ldc, void* workspace, size_t workspace_bytes,
+                               hipStream_t stream, mx_status_t* status) {
   int ntw = 0;
   const int S = gemm_splitk_slices(M, N, K, workspace_bytes, &ntw);
   if (S == 1) return false;
@@ -1336,8 +1349,8 @@ bool gemm_ss_fp4_splitk(const uint8_t* a_codes, const uint8_t* a_scales, const u
   *status = MX_ERR_LAUNCH;
 #define MX_GEMM_TILED_SPLIT(NTW)                                                                                            \
   if (ntw == NTW) {                                                                                                         \
-    if (!allow_dynamic_lds<gemm_ss_fp4_tiled_kernel<NTW>>(kSmem)) return true;                                              \
-    hipLaunchKernelGGL((gemm_ss_fp4_tiled_kernel<NTW>), dim3((unsigned)tiles, (unsigned)S), dim3(kGemmThreads), kSmem,   \
+    if (!allow_dynamic_lds<gemm_fp4_tiled_kernel<NTW, SLICED>>(kSmem)) return true;                                         \
+    hipLaunchKernelGGL((gemm_fp4_tiled_kernel<NTW, SLICED>), dim3((unsigned)tiles, (unsigned)S), dim3(kGemmThreads), kSmem, \
                        stream, a_codes, a_scales, w_codes, w_scales, partial, (int)M, (int)N, (int)K, ldp, (int)m_tiles,    \
                        (int)tiles, (int)k_len, slice);                                                                      \
   }
@@ -1349,6 +1362,17 @@ bool gemm_ss_fp4_splitk(const uint8_t* a_codes, const uint8_t* a_scales, const u
                      (int)N, (int)ldp, ldc, slice, S);
   *status = launch_status("the sum of the fused GEMM's K slices");
   return true;
+}
+
+bool gemm_ss_fp4_splitk(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes, const uint8_t* w_scales,
+                        float* c, int64_t M, int64_t N, int64_t K, int64_t ldc, void* workspace, size_t workspace_bytes,
+                        hipStream_t stream, mx_status_t* status) {
+  return gemm_splitk_launch<false>(a_codes, a_scales, w_codes, w_scales, c, M, N, K, ldc, workspace, workspace_bytes, stream, status);
+}
+bool gemm_fp8_fp4_splitk(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w4_codes, const uint8_t* w4_scales,
+                         float* c, int64_t M, int64_t N, int64_t K, int64_t ldc, void* workspace, size_t workspace_bytes,
+                         hipStream_t stream, mx_status_t* status) {
+  return gemm_splitk_launch<true>(a_codes, a_scales, w4_codes, w4_scales, c, M, N, K, ldc, workspace, workspace_bytes, stream, status);
 }
 
 // Do tiles of 256 rows (256 columns wide) give at least 3/4 of the compute units a workgroup?
@@ -1367,12 +1391,22 @@ bool gemm_hoist_pays(int64_t M, int64_t N) {
   return gemm_tall_tiles_fill(M, N, cus) || (M >= 1024 && 4 * (((M + 127) / 128) * ((N + 255) / 256)) >= 3 * (int64_t)cus);
 }
 
-// The product with W already sliced (E2M1 codes [N][K / 2] and scale bytes [N][K / 32] in a workspace).
+// With W already MXFP4 in memory there is no conversion pass to weigh against: the four-wave kernel with tiles of 256
+// (or 128) rows x 256 columns takes the product as soon as such tiles give 3/4 of the compute units a workgroup;
+// below that the eight-wave kernel with its narrower tiles (and several tiles per workgroup) does.
+bool gemm_big_tiles_pay(int64_t M, int64_t N) {
+  const int cus = device_compute_units();
+  if (cus <= 0) return false;
+  return gemm_tall_tiles_fill(M, N, cus) || 4 * (((M + 127) / 128) * ((N + 255) / 256)) >= 3 * (int64_t)cus;
+}
+
+// The product with W already sliced (E2M1 codes [N][K / 2] and scale bytes [N][K / 32], a workspace's or the caller's).
 mx_status_t gemm_fp8_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w4_codes,
                                 const uint8_t* w4_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
                                 hipStream_t stream) {
   mx_status_t status;
   if (gemm_stream_launch<true>(a_codes, a_scales, w4_codes, w4_scales, c, M, N, K, ldc, stream, &status)) return status;
+  if (!gemm_big_tiles_pay(M, N)) return gemm_tiled_launch<true>(a_codes, a_scales, w4_codes, w4_scales, c, M, N, K, ldc, stream);
   if (256 * K > 0xFFFFFFFFll) return MX_ERR_UNSUPPORTED;   // a tile is addressed with 32-bit offsets
   const int cus = device_compute_units();
   if (cus <= 0) return MX_ERR_LAUNCH;

@@ -104,6 +104,10 @@ int gemm_splitk_slices(int64_t M, int64_t N, int64_t K, size_t workspace_bytes, 
 bool gemm_ss_fp4_splitk(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes, const uint8_t* w_scales,
                         float* c, int64_t M, int64_t N, int64_t K, int64_t ldc, void* workspace, size_t workspace_bytes,
                         hipStream_t stream, mx_status_t* status);
+bool gemm_fp8_fp4_splitk(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w4_codes, const uint8_t* w4_scales,
+                         float* c, int64_t M, int64_t N, int64_t K, int64_t ldc, void* workspace, size_t workspace_bytes,
+                         hipStream_t stream, mx_status_t* status);
+bool gemm_big_tiles_pay(int64_t M, int64_t N);
 mx_status_t gemm_fp8_fp4_launch(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w4_codes,
                                 const uint8_t* w4_scales, float* c, int64_t M, int64_t N, int64_t K, int64_t ldc,
                                 hipStream_t stream);

@@ -180,6 +180,11 @@ def test_validation_returns_codes_without_launching(mx):
     assert L.mx_gemm_fp8_fp4(ref(ga), ref(B.MxPacked(P, P, 64, 12)), ref(gc), None) == 3
     assert L.mx_gemm_fp8_fp4(ref(B.MxPacked(P, P, 16, 6)), ref(B.MxPacked(P, P, 64, 6)), ref(gc), None) == 5
     assert L.mx_gemm_fp8_fp4(ref(B.MxPacked(None, None, 0, 8)), ref(gw), ref(B.MxDense(None, B.MX_F32, 0, 64, 64)), None) == 0
+    assert L.mx_gemm_fp8_fp4_ws(None, ref(gw), ref(gc), ctypes.c_void_p(P), big, None) == 1
+    assert L.mx_gemm_fp8_fp4_ws(ref(ga), ref(B.MxPacked(P, P, 64, 12)), ref(gc), ctypes.c_void_p(P), big, None) == 3
+    assert L.mx_gemm_fp8_fp4_ws(ref(B.MxPacked(None, None, 0, 8)), ref(gw), ref(B.MxDense(None, B.MX_F32, 0, 64, 64)), ctypes.c_void_p(P), big, None) == 0
+    assert L.mx_gemm_fp8_fp4_workspace(0, 64, 256) == 0 and L.mx_gemm_fp8_fp4_workspace(64, 64, 192) == 0
+    assert L.mx_gemm_fp8_fp4_ws_slices(64, 64, 192, big) == 1 and L.mx_gemm_fp8_fp4_ws_slices(16, 4096, 14336, big) == 1
     assert L.mx_gemm_ss_fp4_ws_slices(0, 64, 256, big) == 1 and L.mx_gemm_ss_fp4_ws_slices(64, 64, 192, big) == 1
     assert L.mx_gemm_ss_fp4_ws_slices(64, 4096, 14336, 16) == 1                                                  # workspace too small
     for code in range(8):

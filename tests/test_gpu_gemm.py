@@ -114,10 +114,18 @@ def _check(mx, oracle, M, N, K, seed, w_axis0=True, random_bytes=False, want_sli
             assert slices == want_slices
     # the same product from a W_t converted beforehand and kept (Sec. 3.5 "Inference"): the bits of the unsplit call
     t4c, t4s = mx.mx_slice_and_scale(wc, wsc, f8, mx.make_format("e2m1"))
-    c_kept = mx.mx_gemm_fp8_fp4(ac, asc, t4c, t4s)
+    c_kept = mx.mx_gemm_fp8_fp4(ac, asc, t4c, t4s, workspace=False)
+    c_kept_ws = mx.mx_gemm_fp8_fp4(ac, asc, t4c, t4s)         # lends a workspace when the library would split K
     torch.cuda.synchronize()
     unsplit = c if slices == 1 else c_fly
     assert bool(((c_kept.view(torch.int32) == unsplit.view(torch.int32)) | (torch.isnan(c_kept) & torch.isnan(unsplit))).all())
+    Lk = mx.binding.lib()
+    kept_slices = Lk.mx_gemm_fp8_fp4_ws_slices(M, N, K, Lk.mx_gemm_fp8_fp4_workspace(M, N, K)) if M >= mx.GEMM_WORKSPACE_MIN_ROWS else 1
+    if kept_slices == 1:
+        assert bool(((c_kept_ws.view(torch.int32) == c_kept.view(torch.int32)) | (torch.isnan(c_kept_ws) & torch.isnan(c_kept))).all())
+    if want_slices is not None:
+        # (the anchor-fed call's workspace is sized for W_t and can cap its slices; this one's is sized for the plan)
+        assert (kept_slices > 1) == (want_slices > 1) and kept_slices >= want_slices
     hac, hasc, hwc, hwsc = (x.cpu().numpy() for x in (ac, asc, wc, wsc))
     ref, ref_abs = oracle.gemm_ss_reference(hac, hasc, hwc, hwsc, with_abs=True, wide=True)
     got = c.cpu().numpy().astype(np.float64)
@@ -140,6 +148,12 @@ def _check(mx, oracle, M, N, K, seed, w_axis0=True, random_bytes=False, want_sli
         # K slices: the same products grouped differently -- within the same bound of each other
         d = np.where(nan, 0.0, np.abs(got - c_fly.cpu().numpy().astype(np.float64)))
         assert (d <= 2 * bound)[~nan].all()
+    if kept_slices > 1:
+        # the kept W_t through K slices: against the reference with the bound of that many more additions
+        gk = c_kept_ws.cpu().numpy().astype(np.float64)
+        assert np.array_equal(np.isnan(gk), nan)
+        bk = _error_bound(oracle, hac, hasc, hwc, hwsc, ref_abs, extra_adds=kept_slices)
+        assert (nan | (np.abs(np.where(nan, 0.0, gk - ref)) <= bk)).all()
     # the benchmark definition's bar on every operand class: max |err| <= 1e-3 * ||row||_2 per output row (over the
     # row's finite outputs)
     rows = ~nan.all(axis=1)
