@@ -8,7 +8,11 @@
 // split K over several workgroups whose partial sums pass through it.
 //
 // Kernels by shape: M <= 16 decode (streams W once), 16 < M <= 48 the same stream against two or three row
-// tiles of A, M > 48 the LDS-tiled persistent kernel with producer and consumer waves.
+// tiles of A, M > 48 the LDS-tiled persistent kernel with producer and consumer waves.  Each of them also exists in a
+// form for a W_t that the caller keeps (MXFP4 codes in memory, converted once per precision switch): 8-byte loads where
+// 16 anchor bytes were loaded, no slicing and no scale step, the same instruction stream otherwise -- every output's
+// sum over K runs in the same order in all kernels, so all ways through this file return the same bits (a K split
+// aside).
 //
 // Operand layout of that instruction, established by one-hot probes on the GPU:
 //   lane l = (i = l % 16, g = l / 16).  An FP4 operand lane holds the 32 codes of K-block g of row /
