@@ -73,7 +73,8 @@ typedef enum { MX_ROUND_DEFAULT = 0, MX_ROUND_HALF_AWAY = 1, MX_ROUND_HALF_EVEN 
 typedef struct {
   mx_elem_t elem;
   mx_scale_t scale;
-  int32_t block;   /* k: 16, 32, 64 or 128 along a row (axis 1); 32 down a column (axis 0) and in the GEMM */
+  int32_t block;   /* k: 16, 32, 64 or 128 (down a column, axis 0: the row count must be a multiple of 32 also for
+                      k = 16); 32 in the GEMM */
   int32_t axis;    /* 1: along rows (last axis); 0: down columns */
   mx_round_t round;
 } mx_format_t;

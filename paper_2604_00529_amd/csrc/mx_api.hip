@@ -141,7 +141,6 @@ mx_status_t mx_quantize(const mx_format_t* f, const mx_dense_t* src, const mx_pa
   if ((st = blocked_shape(f, src->rows, src->cols, &outer, &nblocks)) != MX_OK) return st;
   if (outer != dst->outer || nblocks != dst->nblocks) return MX_ERR_SHAPE;
   if (outer == 0 || nblocks == 0) return MX_OK;
-  if (f->axis == 0 && f->block != 32) return MX_ERR_UNSUPPORTED;   // column blocks: 32 rows only
   if (partial_window_unsupported(f, info, src->rows, src->cols)) return MX_ERR_UNSUPPORTED;
   mx::DenseArg s{src->data, (int)src->dtype, src->rows, src->cols, src->ld};
   drop_stale_error();
@@ -280,7 +279,6 @@ mx_status_t mx_fake_quant(const mx_format_t* target, const mx_format_t* anchor, 
   int64_t outer, nblocks;
   if ((st = blocked_shape(target, src->rows, src->cols, &outer, &nblocks)) != MX_OK) return st;
   if (outer == 0 || nblocks == 0) return MX_OK;
-  if (target->axis == 0 && target->block != 32) return MX_ERR_UNSUPPORTED;   // column blocks: 32 rows only
   mx::DenseArg s{src->data, (int)src->dtype, src->rows, src->cols, src->ld};
   mx::DenseArg d{dst->data, (int)dst->dtype, dst->rows, dst->cols, dst->ld};
   drop_stale_error();
@@ -298,7 +296,6 @@ mx_status_t mx_dequant(const mx_format_t* f, const mx_packed_t* src, const mx_de
   if ((st = blocked_shape(f, dst->rows, dst->cols, &outer, &nblocks)) != MX_OK) return st;
   if (outer != src->outer || nblocks != src->nblocks) return MX_ERR_SHAPE;
   if (outer == 0 || nblocks == 0) return MX_OK;
-  if (f->axis == 0 && f->block != 32) return MX_ERR_UNSUPPORTED;   // column blocks: 32 rows only
   if (partial_window_unsupported(f, info, dst->rows, dst->cols)) return MX_ERR_UNSUPPORTED;
   mx::DenseArg d{dst->data, (int)dst->dtype, dst->rows, dst->cols, dst->ld};
   drop_stale_error();

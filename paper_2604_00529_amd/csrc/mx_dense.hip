@@ -755,6 +755,251 @@ __global__ __launch_bounds__(TPB) void fake_quant_cols_kernel(const void* __rest
   for (int r = 0; r < 32; ++r) store_quad<DT>(dst, offd + r * ld_dst, v[r]);
 }
 
+// ------------------------------------------------------------------ axis 0, blocks of 16, 64 or 128 rows
+// The codes of a column are one bit string whatever the block size, so the packed tensor has the layout of k = 32 and
+// these kernels keep its 32-row windows: a workgroup of 4 waves takes 4 consecutive windows x 256 columns (wave w =
+// window w, lane l = columns 4l..4l+3).  What changes is which rows share a maximum and where the scale byte lives:
+// k = 16: two scale bytes per window (rows 0-15 and 16-31); k = 64 / 128: the 2 / 4 windows of a block join their
+// maxima through LDS (a block never straddles a workgroup: tiles start at multiples of 4 windows).  Scale bytes go
+// straight to / come straight from global memory.  Plain kernels (rows widened to fp32, no packed-row variants): the
+// benchmark's block is 32.
+struct ColBlockGeom {
+  int g;          // windows per block (k = 64: 2, k = 128: 4; k = 16: 1, with two blocks per window)
+  int halves;     // blocks per window (k = 16: 2, else 1)
+  int64_t nsb;    // scale bytes per column
+};
+__device__ __forceinline__ ColBlockGeom col_block_geom(int block, int64_t nrb) {
+  if (block == 16) return ColBlockGeom{1, 2, 2 * nrb};
+  const int g = block / 32;
+  return ColBlockGeom{g, 1, nrb / g};
+}
+// scale-byte index of half h (rows 16 h ..) of window rb of a column
+__device__ __forceinline__ int64_t col_block_scale_index(const ColBlockGeom& geo, int64_t rb, int h) {
+  return geo.halves == 2 ? 2 * rb + h : rb / geo.g;
+}
+
+// largest |V| (fp32 bits) of each of the lane's 4 columns over the two halves of its window
+__device__ __forceinline__ void column_half_amax(const float (&v)[32][4], uint32_t (&m)[4][2]) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      uint32_t a = 0;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { uint32_t b = abs_bits(v[16 * h + r][j]); a = a > b ? a : b; }
+      m[j][h] = a;
+    }
+}
+
+// The scale bytes of the lane's 4 columns, per half of its window, from the half maxima: the blocks of 64 / 128 rows
+// join the maxima of their windows through `xch` ([4 windows][256 columns]).  Every wave of the workgroup must call it.
+template <int FIRST_EMAX>
+__device__ __forceinline__ void column_block_bytes(const uint32_t (&m)[4][2], uint32_t (&byte)[4][2], const ColBlockGeom& geo,
+                                                   uint32_t (*xch)[kColTileCols], int wave, int lane) {
+  if (geo.halves == 2) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) byte[j][h] = scale_byte_from_amax<FIRST_EMAX>(m[j][h]);
+    return;
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) xch[wave][4 * lane + j] = m[j][0] > m[j][1] ? m[j][0] : m[j][1];
+  __syncthreads();
+  const int base = wave & ~(geo.g - 1);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    uint32_t a = 0;
+    for (int q = 0; q < geo.g; ++q) { uint32_t b = xch[base + q][4 * lane + j]; a = a > b ? a : b; }
+    byte[j][0] = byte[j][1] = scale_byte_from_amax<FIRST_EMAX>(a);
+  }
+}
+
+template <int ELEM, bool HW, int DT>
+__global__ __launch_bounds__(256) void quantize_cols_kblock_kernel(const void* __restrict__ src, uint32_t* __restrict__ codes,
+                                                                   uint8_t* __restrict__ scales, int64_t cols, uint32_t col_groups,
+                                                                   int64_t ld, int64_t nrb, int tie, int block) {
+  using E = Elem<ELEM>;
+  constexpr int W = E::bits, CD = ColChunk<W>::cd, PER_COL = ColChunk<W>::per_col;
+  __shared__ __attribute__((aligned(16))) uint32_t tile[kColTileRbs * W * kColTileCols];
+  __shared__ uint32_t xch[kColTileRbs][kColTileCols];
+  int tid = threadIdx.x;
+  if constexpr (HW && E::hw == HW_FP8) tid = set_fp8_saturation(tid);
+  const int wave = tid >> 6, lane = tid & 63;
+  const ColTile t = col_tile(col_groups);
+  const ColBlockGeom geo = col_block_geom(block, nrb);
+  const int64_t rb = t.rb0 + wave, col = t.c0 + 4 * lane;
+  const bool active = rb < nrb && col < cols;
+  float v[32][4];
+  if (active) {
+    const int64_t off = rb * 32 * ld + col;
+#pragma unroll
+    for (int r = 0; r < 32; ++r) load_quad<DT>(src, off + r * ld, v[r]);
+  } else {
+#pragma unroll
+    for (int r = 0; r < 32; ++r)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[r][j] = 0.0f;
+  }
+  uint32_t m[4][2], byte[4][2];
+  column_half_amax(v, m);
+  column_block_bytes<E::emax>(m, byte, geo, xch, wave, lane);
+  if (active) {
+    uint32_t out[4][W];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+#pragma unroll
+      for (int i = 0; i < W; ++i) out[j][i] = 0;
+      static_for<0, 4>([&](auto cc) {
+        constexpr int C = decltype(cc)::value;
+        float x[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) x[r] = v[8 * C + r][j];
+        const uint32_t b = byte[j][C >> 1];
+        uint64_t bits = b == 255u ? 0ull : encode_chunk<ELEM, HW, 8, DT == MX_BF16>(x, b, tie);
+        insert_bits<W, C * 8 * W, 8 * W>(out[j], bits);
+      });
+      uint8_t* sc = scales + (col + j) * geo.nsb;
+      if (geo.halves == 2) {
+        sc[2 * rb] = (uint8_t)byte[j][0];
+        sc[2 * rb + 1] = (uint8_t)byte[j][1];
+      } else if ((wave & (geo.g - 1)) == 0) {
+        sc[rb / geo.g] = (uint8_t)byte[j][0];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < W; ++i)
+      *reinterpret_cast<u32x4*>(&tile[(wave * W + i) * kColTileCols + 4 * lane]) = u32x4{out[0][i], out[1][i], out[2][i], out[3][i]};
+  }
+  __syncthreads();
+  const int64_t valid_rb = nrb - t.rb0 < kColTileRbs ? nrb - t.rb0 : kColTileRbs;
+  const int valid_dw = (int)valid_rb * W;
+#pragma unroll
+  for (int it = 0; it < PER_COL; ++it) {
+    int k = it * 256 + tid;
+    int c = k / PER_COL, part = k - c * PER_COL;
+    int d0 = part * CD;
+    if (t.c0 + c < cols && d0 < valid_dw) {
+      uint32_t w[CD];
+#pragma unroll
+      for (int q = 0; q < CD; ++q) w[q] = tile[(d0 + q) * kColTileCols + c];
+      uint32_t* g = codes + ((t.c0 + c) * nrb + t.rb0) * W + d0;
+      if (d0 + CD <= valid_dw) {
+        store_dwords<CD>(g, w);
+      } else {
+#pragma unroll
+        for (int q = 0; q < CD; ++q)
+          if (d0 + q < valid_dw) g[q] = w[q];
+      }
+    }
+  }
+}
+
+template <int ELEM, int DT>
+__global__ __launch_bounds__(256) void dequant_cols_kblock_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restrict__ scales,
+                                                                  void* __restrict__ dst, int64_t cols, uint32_t col_groups,
+                                                                  int64_t ld, int64_t nrb, int block) {
+  using E = Elem<ELEM>;
+  constexpr int W = E::bits, CD = ColChunk<W>::cd, PER_COL = ColChunk<W>::per_col;
+  constexpr bool HW = E::hw != HW_NONE;
+  __shared__ __attribute__((aligned(16))) uint32_t tile[kColTileRbs * W * kColTileCols];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const ColTile t = col_tile(col_groups);
+  const ColBlockGeom geo = col_block_geom(block, nrb);
+  const int64_t valid_rb = nrb - t.rb0 < kColTileRbs ? nrb - t.rb0 : kColTileRbs;
+  const int valid_dw = (int)valid_rb * W;
+#pragma unroll
+  for (int it = 0; it < PER_COL; ++it) {
+    int k = it * 256 + tid;
+    int c = k / PER_COL, part = k - c * PER_COL;
+    int d0 = part * CD;
+    if (t.c0 + c < cols && d0 < valid_dw) {
+      const uint32_t* g = codes + ((t.c0 + c) * nrb + t.rb0) * W + d0;
+      uint32_t w[CD];
+      if (d0 + CD <= valid_dw) {
+        load_dwords<CD>(g, w);
+      } else {
+#pragma unroll
+        for (int q = 0; q < CD; ++q) w[q] = d0 + q < valid_dw ? g[q] : 0u;
+      }
+#pragma unroll
+      for (int q = 0; q < CD; ++q) tile[(d0 + q) * kColTileCols + c] = w[q];
+    }
+  }
+  __syncthreads();
+  const int64_t rb = t.rb0 + wave, col = t.c0 + 4 * lane;
+  if (rb < nrb && col < cols) {
+    float v[32][4];
+    uint32_t in[4][W];
+#pragma unroll
+    for (int i = 0; i < W; ++i) {
+      u32x4 q = *reinterpret_cast<const u32x4*>(&tile[(wave * W + i) * kColTileCols + 4 * lane]);
+      in[0][i] = q.x; in[1][i] = q.y; in[2][i] = q.z; in[3][i] = q.w;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint8_t* sc = scales + (col + j) * geo.nsb;
+      const uint32_t b0 = sc[col_block_scale_index(geo, rb, 0)], b1 = sc[col_block_scale_index(geo, rb, 1)];
+      static_for<0, 4>([&](auto cc) {
+        constexpr int C = decltype(cc)::value;
+        const uint32_t byte = (C >> 1) ? b1 : b0;
+        float x[8];
+        decode_chunk<ELEM, HW, 8>(extract_bits<W, C * 8 * W, 8 * W>(in[j]), byte, x);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) v[8 * C + r][j] = byte == 255u ? __uint_as_float(0x7FC00000u) : x[r];
+      });
+    }
+    int64_t off = rb * 32 * ld + col;
+#pragma unroll
+    for (int r = 0; r < 32; ++r) store_quad<DT>(dst, off + r * ld, v[r]);
+  }
+}
+
+template <int TARGET, int ANCHOR, bool HW, int DT>
+__global__ __launch_bounds__(256) void fake_quant_cols_kblock_kernel(const void* __restrict__ src, void* __restrict__ dst,
+                                                                     int64_t cols, uint32_t col_groups, int64_t ld_src,
+                                                                     int64_t ld_dst, int64_t nrb, int tie, int block) {
+  constexpr int FIRST = FirstFormat<TARGET, ANCHOR>::elem;
+  __shared__ uint32_t xch[kColTileRbs][kColTileCols];
+  int tid = threadIdx.x;
+  if constexpr (HW && Elem<FIRST>::hw == HW_FP8) tid = set_fp8_saturation(tid);
+  const int wave = tid >> 6, lane = tid & 63;
+  const ColTile t = col_tile(col_groups);
+  const ColBlockGeom geo = col_block_geom(block, nrb);
+  const int64_t rb = t.rb0 + wave, col = t.c0 + 4 * lane;
+  const bool active = rb < nrb && col < cols;
+  float v[32][4];
+  if (active) {
+    const int64_t off = rb * 32 * ld_src + col;
+#pragma unroll
+    for (int r = 0; r < 32; ++r) load_quad<DT>(src, off + r * ld_src, v[r]);
+  } else {
+#pragma unroll
+    for (int r = 0; r < 32; ++r)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[r][j] = 0.0f;
+  }
+  uint32_t m[4][2], byte[4][2];
+  column_half_amax(v, m);
+  column_block_bytes<Elem<FIRST>::emax>(m, byte, geo, xch, wave, lane);
+  if (!active) return;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      float x[8];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) x[r] = v[8 * c + r][j];
+      fake_quant_chunk<TARGET, ANCHOR, HW, 8, DT == MX_BF16>(x, byte[j][c >> 1], tie);
+#pragma unroll
+      for (int r = 0; r < 8; ++r) v[8 * c + r][j] = x[r];
+    }
+  }
+  const int64_t offd = rb * 32 * ld_dst + col;
+#pragma unroll
+  for (int r = 0; r < 32; ++r) store_quad<DT>(dst, offd + r * ld_dst, v[r]);
+}
+
 // ------------------------------------------------------------------ host launchers
 // Launch shape of the row-axis kernels: chunks per lane and lanes per workgroup.  Which shape streams best
 // depends on the read : write mix and on the arithmetic per element, so it is chosen per element format
@@ -806,6 +1051,12 @@ static mx_status_t run_quantize(int axis, int block, int tie, const DenseArg& s,
       hipLaunchKernelGGL((quantize_rows_kernel<ELEM, HW, DT, shape.unroll, shape.threads, true>), dim3((unsigned)wgs), dim3(shape.threads), 0, st,
                          s.data, static_cast<uint32_t*>(codes), scales, nchunks, (uint32_t)cpr, s.ld, (int)(s.ld == s.cols), tie,
                          log2_lanes_of(block, N));
+  } else if (block != 32) {
+    if (s.cols % 4 || s.rows % 32) return MX_ERR_UNSUPPORTED;
+    const int64_t nrb = s.rows / 32, cgs = (s.cols + kColTileCols - 1) / kColTileCols, rbgs = (nrb + kColTileRbs - 1) / kColTileRbs;
+    if (cgs * rbgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((quantize_cols_kblock_kernel<ELEM, HW, DT>), dim3((unsigned)(cgs * rbgs)), dim3(256), 0, st, s.data,
+                       static_cast<uint32_t*>(codes), scales, s.cols, (uint32_t)cgs, s.ld, nrb, tie, block);
   } else {
     if (s.cols % 4) return MX_ERR_UNSUPPORTED;
     int64_t nrb = s.rows / 32;
@@ -839,6 +1090,12 @@ static mx_status_t run_dequant(int axis, int block, const void* codes, const uin
       hipLaunchKernelGGL((dequant_rows_kernel<ELEM, DT, shape.unroll, shape.threads, true>), dim3((unsigned)wgs), dim3(shape.threads), 0, st,
                          static_cast<const uint32_t*>(codes), scales, d.data, nchunks, (uint32_t)cpr, d.ld, (int)(d.ld == d.cols),
                          log2_lanes_of(block, N));
+  } else if (block != 32) {
+    if (d.cols % 4 || d.rows % 32) return MX_ERR_UNSUPPORTED;
+    const int64_t nrb = d.rows / 32, cgs = (d.cols + kColTileCols - 1) / kColTileCols, rbgs = (nrb + kColTileRbs - 1) / kColTileRbs;
+    if (cgs * rbgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((dequant_cols_kblock_kernel<ELEM, DT>), dim3((unsigned)(cgs * rbgs)), dim3(256), 0, st,
+                       static_cast<const uint32_t*>(codes), scales, d.data, d.cols, (uint32_t)cgs, d.ld, nrb, block);
   } else {
     if (d.cols % 4) return MX_ERR_UNSUPPORTED;
     int64_t nrb = d.rows / 32;
@@ -872,6 +1129,12 @@ static mx_status_t run_fake_quant(int axis, int block, int tie, const DenseArg& 
       hipLaunchKernelGGL((fake_quant_rows_kernel<TARGET, ANCHOR, HW, DT, kFqUnroll, kFqThreads, true>), dim3((unsigned)wgs), dim3(kFqThreads), 0,
                          st, s.data, d.data, nchunks, (uint32_t)cpr, s.ld, d.ld, (int)(s.ld == s.cols), (int)(d.ld == d.cols), tie,
                          log2_lanes_of(block, N));
+  } else if (block != 32) {
+    if (s.cols % 4 || s.rows % 32) return MX_ERR_UNSUPPORTED;
+    const int64_t nrb = s.rows / 32, cgs = (s.cols + kColTileCols - 1) / kColTileCols, rbgs = (nrb + kColTileRbs - 1) / kColTileRbs;
+    if (cgs * rbgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((fake_quant_cols_kblock_kernel<TARGET, ANCHOR, HW, DT>), dim3((unsigned)(cgs * rbgs)), dim3(256), 0, st, s.data,
+                       d.data, s.cols, (uint32_t)cgs, s.ld, d.ld, nrb, tie, block);
   } else {
     if (s.cols % 4) return MX_ERR_UNSUPPORTED;
     int64_t qpr = s.cols / 4, nrb = s.rows / 32, nitems = qpr * nrb;

@@ -1,4 +1,4 @@
-"""Block sizes other than 32 on the GPU (blocks along a row): 16, 64 and 128 -- the sizes of the paper's
+"""Block sizes other than 32 on the GPU (blocks along a row, and down a column): 16, 64 and 128 -- the sizes of the paper's
 block-size sweep (Sec. 4.3, App. C; its bit sweep uses 64).  Every entry point against the oracle, bit for bit,
 and the paper's own study shape: 100 random (1, 1024) tensors, quantized directly and through Slice-and-Scale."""
 import numpy as np
@@ -121,11 +121,62 @@ def test_blocks_of_16_ending_in_half_a_run_of_32_codes(mx, oracle, rows, cols, d
         assert_same_values(to_host(mx.mx_fake_quant(g, f)), oracle.fake_quant(m, fmt, k=16))
 
 
-def test_column_blocks_are_32_only(mx):
+def _column_inputs(dtype):
+    # rows a multiple of 128 (every block size divides them): 1, 3 and 5 tiles of 4 windows, the last one ragged
+    # (12 and 20 windows); more than 256 columns and a ragged column tile
+    w1 = synth.config1_weight(seed=1201, rows=128, cols=520)
+    w2 = synth.config1_weight(seed=1202, rows=384, cols=72)
+    w3 = np.ascontiguousarray(np.concatenate([synth.edge_case_matrix(seed=29, rows=40, cols=256)] * 16, axis=0)[:640])
+    w4 = np.concatenate([synth.special_matrix(cols=128)] * 32, axis=0)[:128]
+    mats = [w1, w2, w3, w4]
+    if dtype == "bf16":
+        mats = [synth.f32_to_bf16_bits(m) for m in mats]
+    return mats
+
+
+@pytest.mark.parametrize("k", BLOCKS)
+@pytest.mark.parametrize("fmt", FORMATS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_column_blocks_quantize_dequant_fake_quant(mx, oracle, k, fmt, dtype):
+    # blocks of 16, 64 and 128 rows down the columns (axis 0): every entry point against the oracle, bit for bit
     import torch
-    w = torch.zeros((128, 64), dtype=torch.float32, device="cuda")
+    for tie in ("default", "away"):
+        f = mx.make_format(fmt, axis=0, block=k, round=tie)
+        for m in _column_inputs(dtype):
+            want_c, want_s = oracle.quantize(m, fmt, axis=0, k=k, tie=TIES[tie])
+            got_c, got_s = mx.mx_quantize(to_gpu(m), f)
+            assert np.array_equal(to_host(got_s), want_s), (tie, m.shape)
+            assert np.array_equal(to_host(got_c), want_c), (tie, m.shape)
+            want_f = oracle.fake_quant(m, fmt, axis=0, k=k, tie=TIES[tie])
+            assert_same_values(to_host(mx.mx_fake_quant(to_gpu(m), f)), want_f)
+            out = "f32" if dtype == "f32" else "bf16"
+            want_d = oracle.dequant(want_c, want_s, fmt, m.shape[0], m.shape[1], axis=0, k=k, out=out)
+            got_d = mx.mx_dequant(got_c, got_s, f, m.shape[0], m.shape[1],
+                                  dtype=torch.float32 if out == "f32" else torch.bfloat16)
+            assert_same_values(to_host(got_d), want_d)
+
+
+@pytest.mark.parametrize("k", BLOCKS)
+@pytest.mark.parametrize("anchor,target", [("int8", "int4"), ("e4m3", "e2m1"), ("e4m3", "e3m2")])
+def test_column_blocks_via_anchor(mx, oracle, k, anchor, target):
+    # Eq. (7) with column blocks of every size, and the stored-anchor route (quantize, Slice-and-Scale, dequantize)
+    # that it must equal
+    import torch
+    fa, ft = mx.make_format(anchor, axis=0, block=k), mx.make_format(target, axis=0, block=k)
+    for m in _column_inputs("bf16")[:2]:
+        want = oracle.fake_quant(m, target, anchor=anchor, axis=0, k=k)
+        assert_same_values(to_host(mx.mx_fake_quant(to_gpu(m), ft, anchor=fa)), want)
+        c8, s8 = mx.mx_quantize(to_gpu(m), fa)
+        ct, st = mx.mx_slice_and_scale(c8, s8, fa, ft)
+        got = mx.mx_dequant(ct, st, ft, m.shape[0], m.shape[1], dtype=torch.bfloat16)
+        assert_same_values(to_host(got), want)
+
+
+def test_column_blocks_of_16_need_whole_windows_of_32_rows(mx):
+    import torch
+    w = torch.zeros((48, 64), dtype=torch.float32, device="cuda")       # 3 blocks of 16 rows: half a window is left over
     with pytest.raises(mx.MxError) as e:
-        mx.mx_fake_quant(w, mx.make_format("int4", axis=0, block=64))
+        mx.mx_fake_quant(w, mx.make_format("int4", axis=0, block=16))
     assert e.value.status == 5
 
 

@@ -39,7 +39,7 @@ def _shape(rng, axis, k):
         cols = k * int(rng.choice([1, 2, 3, 5, 8, 13, 24, 40]))
         cols = (cols + 7) // 8 * 8 if k < 8 else cols
     else:
-        rows = 32 * int(rng.choice([1, 2, 3, 5, 9]))
+        rows = max(k, 32) * int(rng.choice([1, 2, 3, 5, 9]))                 # whole blocks, and whole windows of 32 rows
         cols = 8 * int(rng.choice([1, 2, 3, 7, 16, 33, 65, 130]))
     return rows, cols
 
@@ -49,7 +49,7 @@ def test_dense_entry_points_random_case(mx, oracle, seed):
     import torch
     rng = np.random.default_rng(7000 + seed)
     axis = int(rng.integers(0, 2))
-    k = 32 if axis == 0 else int(rng.choice([16, 32, 64, 128]))
+    k = int(rng.choice([32, 32, 16, 64, 128])) if axis == 0 else int(rng.choice([16, 32, 64, 128]))
     fmt = str(rng.choice(CORE + EXTRA))
     dtype = str(rng.choice(["f32", "bf16"]))
     tie = str(rng.choice(["default", "away", "even"]))
