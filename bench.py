@@ -25,7 +25,7 @@ FP8_MFMA_PEAK = 5.0e15
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-GROUPS = ("ss", "dense", "fq", "cols", "gemm")
+GROUPS = ("ss", "dense", "fq", "cols", "blocks", "gemm")
 
 
 def log(*a):
@@ -240,6 +240,8 @@ def run_groups(torch, mx, synth, rows, groups, args, ckpt):
         fake_quant_rows(torch, mx, synth, rows)
     if "cols" in groups:
         column_rows(torch, mx, synth, rows)
+    if "blocks" in groups:
+        block_size_rows(torch, mx, synth, rows)
     if "gemm" in groups:
         gemm_rows(torch, mx, synth, rows)
 
@@ -387,6 +389,34 @@ def column_rows(torch, mx, synth, rows):
     pc, ps = mx.mx_quantize(w2, f8)
     rows["quantize_config2_4096x4096_e4m3_axis0"] = row(w2.numel() * 2 + w2.numel() // 32 * 33, time_region(torch, lambda: mx.mx_quantize(w2, f8, pc, ps), 20, 5, WARM_MS), cache_resident=True)
     del w2, pc, ps
+    torch.cuda.empty_cache()
+
+
+def block_size_rows(torch, mx, synth, rows):
+    """Block sizes other than the benchmark's 32 (the paper evaluates 64 and sweeps 16 .. 128, Sec. 4.3): quantize,
+    Slice-and-Scale and fake-quant with blocks along rows on four stacked copies of the largest decoder weight (470 MB as
+    bf16), and quantize / fake-quant with blocks of 64 rows down the columns of configs[3]'s activations."""
+    r, c = 4 * 14336, 4096
+    w = torch.cat([synth.torch_config3_weight(1000 + i, 14336, c) for i in range(4)], dim=0)
+    out = torch.empty_like(w)
+    for k in (64, 16, 128):
+        f8, f4 = mx.make_format("e4m3", block=k), mx.make_format("e2m1", block=k)
+        pc, ps = mx.mx_quantize(w, f8)
+        nb = r * c // k
+        rows["quantize_bf16_e4m3_block%d" % k] = row(r * c * 2 + r * c + nb, time_region(torch, lambda: mx.mx_quantize(w, f8, pc, ps), 10, 3, WARM_MS))
+        tc, ts = mx.mx_slice_and_scale(pc, ps, f8, f4)
+        rows["ss_e4m3_e2m1_block%d" % k] = row(r * c + r * c // 2 + 2 * nb, time_region(torch, lambda: mx.mx_slice_and_scale(pc, ps, f8, f4, tc, ts), 10, 3, WARM_MS))
+        rows["fake_quant_bf16_e2m1_via_e4m3_block%d" % k] = row(r * c * 4, time_region(torch, lambda: mx.mx_fake_quant(w, f4, f8, out), 10, 3, WARM_MS))
+        del pc, ps, tc, ts
+    del w, out
+    torch.cuda.empty_cache()
+    act = synth.torch_config4_activations()
+    out = torch.empty_like(act)
+    f8c, f4c = mx.make_format("e4m3", axis=0, block=64), mx.make_format("e2m1", axis=0, block=64)
+    pc, ps = mx.mx_quantize(act, f8c)
+    rows["quantize_bf16_e4m3_axis0_block64"] = row(act.numel() * 3 + act.numel() // 64, time_region(torch, lambda: mx.mx_quantize(act, f8c, pc, ps), 10, 3, WARM_MS))
+    rows["fake_quant_bf16_e2m1_axis0_block64"] = row(act.numel() * 4, time_region(torch, lambda: mx.mx_fake_quant(act, f4c, None, out), 10, 3, WARM_MS))
+    del act, out, pc, ps
     torch.cuda.empty_cache()
 
 
