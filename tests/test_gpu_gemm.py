@@ -288,6 +288,33 @@ def test_gemm_kept_fp4_weight_decode_shape_config5(mx, oracle):
     assert (err.max(axis=1) <= 1e-3 * np.sqrt((ref * ref).sum(axis=1))).all()
 
 
+def test_gemm_kept_fp4_weight_smaller_workspace_fewer_slices(mx, oracle):
+    # 64 x 4096 x 14336 with a kept W_t: the plan wants 8 slices of K (8 x 64 x 4096 x 4 bytes of partial sums); lent a
+    # workspace for two, the call splits K in two; lent 1 KB, it does not split and returns mx_gemm_fp8_fp4's bits
+    import ctypes
+    import torch
+    M, N, K = 64, 4096, 14336
+    rng = np.random.default_rng(4096)
+    a = rng.standard_normal((M, K)).astype(np.float32)
+    w = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    ac, asc = mx.mx_quantize(_gpu_bf16(a), mx.make_format("e4m3"))
+    w4, w4s = mx.mx_quantize(_gpu_bf16(w), mx.make_format("e2m1"))
+    L = mx.binding.lib()
+    assert L.mx_gemm_fp8_fp4_workspace(M, N, K) == 8 * M * N * 4
+    two = 2 * M * N * 4
+    assert L.mx_gemm_fp8_fp4_ws_slices(M, N, K, two) == 2 and L.mx_gemm_fp8_fp4_ws_slices(M, N, K, 1024) == 1
+    plain = mx.mx_gemm_fp8_fp4(ac, asc, w4, w4s, workspace=False)
+    c2 = mx.mx_gemm_fp8_fp4(ac, asc, w4, w4s, workspace=torch.empty(two, dtype=torch.uint8, device="cuda"))
+    c1 = mx.mx_gemm_fp8_fp4(ac, asc, w4, w4s, workspace=torch.empty(1024, dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
+    assert torch.equal(c1, plain)
+    hac, hasc, hw4, hw4s = (x.cpu().numpy() for x in (ac, asc, w4, w4s))
+    ref, ref_abs = oracle.gemm_reference(hac, hasc, hw4, hw4s, w_fmt="e2m1", with_abs=True, wide=True)
+    bound = _error_bound(oracle, hac, hasc, hw4, hw4s, ref_abs, extra_adds=2, sliced=True)
+    for got in (plain, c2):
+        assert (np.abs(got.cpu().numpy().astype(np.float64) - ref) <= bound).all()
+
+
 def test_gemm_few_rows_down_proj_shape(mx, oracle):
     # M = 64, N = 4096, K = 14336: the few-tiles row of the bench, in the configuration it times (eight slices of K on
     # 256 compute units, default call with a workspace)
