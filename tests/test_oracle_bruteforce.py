@@ -105,18 +105,38 @@ def test_quantize_small_tensors_bruteforce(oracle, fmt, dtype):
                     assert list(un[r, j]) == want, (r, j)
 
 
+@pytest.mark.parametrize("k", [16, 64, 128])
+@pytest.mark.parametrize("fmt", ["int8", "int4", "e4m3", "e2m1"])
+def test_quantize_other_block_sizes_bruteforce(oracle, fmt, k):
+    # Eq. (1) / (2) block by block for the block sizes of the paper's sweep (Sec. 4.3): the scale byte comes from the
+    # maximum over exactly k consecutive elements and element j of block b sits at position j of that block's codes
+    w = synth.config1_weight(seed=6, rows=3, cols=256)
+    w[1, 70] = 37.5                                   # an outlier that must move one block's scale only
+    codes, scales = oracle.quantize(w, fmt, axis=1, k=k)
+    un = oracle.unpack(codes, fmt, k)
+    assert scales.shape == (3, 256 // k)
+    for r in range(3):
+        for j in range(256 // k):
+            byte, want = defs.quantize_block(fmt, [float(v) for v in w[r, j * k:(j + 1) * k]], "default")
+            assert scales[r, j] == byte, (r, j)
+            assert list(un[r, j]) == want, (r, j)
+
+
 def test_quantize_axis0_is_transpose_of_axis1(oracle):
     # blocks along axis 0 of M are blocks along axis 1 of M^T, packed with outer = cols
-    m = synth.config1_weight(seed=9, rows=64, cols=48)
-    for fmt in ("int8", "e4m3", "e2m1", "e3m2"):
-        c0, s0 = oracle.quantize(m, fmt, axis=0)
-        c1, s1 = oracle.quantize(np.ascontiguousarray(m.T), fmt, axis=1)
-        assert np.array_equal(c0, c1) and np.array_equal(s0, s1)
-        d0 = oracle.dequant(c0, s0, fmt, 64, 48, axis=0)
-        d1 = oracle.dequant(c1, s1, fmt, 48, 64, axis=1)
-        assert np.array_equal(d0, d1.T)
-        f0 = oracle.fake_quant(m, fmt, axis=0)
-        assert np.array_equal(f0, d0)
+    # (for every block size; the block-by-block brute force pins axis 1 for blocks of 32 above and of 16 / 64 / 128 below)
+    m = synth.config1_weight(seed=9, rows=128, cols=48)
+    for k in (32, 16, 64, 128):
+        for fmt in ("int8", "e4m3", "e2m1", "e3m2"):
+            c0, s0 = oracle.quantize(m, fmt, axis=0, k=k)
+            c1, s1 = oracle.quantize(np.ascontiguousarray(m.T), fmt, axis=1, k=k)
+            assert np.array_equal(c0, c1) and np.array_equal(s0, s1)
+            assert s0.shape == (48, 128 // k)
+            d0 = oracle.dequant(c0, s0, fmt, 128, 48, axis=0, k=k)
+            d1 = oracle.dequant(c1, s1, fmt, 48, 128, axis=1, k=k)
+            assert np.array_equal(d0, d1.T)
+            f0 = oracle.fake_quant(m, fmt, axis=0, k=k)
+            assert np.array_equal(f0, d0)
 
 
 def _read_examples():
