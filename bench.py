@@ -207,6 +207,17 @@ def main():
     }
     del batch, t_codes, t_scales, t_views
 
+    # ---------------------------------------------------------------- the measured ceiling of a plain copy beside it
+    # a device-to-device copy of the anchor's codes by the runtime's own copy (read = write: a mix with more writes than
+    # the conversion's 2 : 1), same clock
+    dst = torch.empty_like(a_codes)
+    c_ms, c_med, _, _ = time_region(torch, lambda: dst.copy_(a_codes), 10, 3)
+    copy_gbs = 2 * a_codes.numel() / (c_med * 1e-3) / 1e9
+    del dst
+    torch.cuda.empty_cache()
+    result["config"]["copy_ceiling"] = {"GB/s": round(copy_gbs, 1), "kind": "torch device-to-device copy of the anchor codes (%d B read + written)" % a_codes.numel()}
+    result["config"]["pct_of_copy_ceiling"] = round(100 * value / copy_gbs, 1)
+
     # ---------------------------------------------------------------- CPU oracle beside it (bounded sample)
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(torch, a_views, tensors)
@@ -249,7 +260,7 @@ def run_groups(torch, mx, synth, rows, groups, args, ckpt):
 def ss_rows(torch, mx, synth, rows, args, ckpt):
     """The other Slice-and-Scale conversions of configs[2] on the whole checkpoint (HBM), then configs[0] and [1]
     (single small tensors that stay in the 256 MB last-level cache: flagged, not roofline rows)."""
-    steps2 = max(3, min(args.steps, 10))
+    steps2 = max(3, min(args.steps, 20))
     if ckpt is None:
         ckpt = build_checkpoint(torch, mx, synth, args.layers, "e4m3")
     tensors, a_codes, a_scales, a_views = ckpt
@@ -312,9 +323,9 @@ def dense_rows(torch, mx, synth, rows):
             f = mx.make_format(elem)
             pc, ps = mx.mx_quantize(src, f)
             nbytes = r * c * esz + r * c // 32 * (4 * bits + 1)
-            rows["quantize_%s_%s" % (dt_name, elem)] = row(nbytes, time_region(torch, lambda: mx.mx_quantize(src, f, pc, ps), 10, 3, WARM_MS))
+            rows["quantize_%s_%s" % (dt_name, elem)] = row(nbytes, time_region(torch, lambda: mx.mx_quantize(src, f, pc, ps), 20, 3, WARM_MS))
             deq = torch.empty((r, c), dtype=src.dtype, device="cuda")
-            rows["dequant_%s_%s" % (elem, dt_name)] = row(nbytes, time_region(torch, lambda: mx.mx_dequant(pc, ps, f, r, c, out=deq), 10, 3, WARM_MS))
+            rows["dequant_%s_%s" % (elem, dt_name)] = row(nbytes, time_region(torch, lambda: mx.mx_dequant(pc, ps, f, r, c, out=deq), 20, 3, WARM_MS))
             del pc, ps, deq
         del src
     del wbig
@@ -344,10 +355,10 @@ def fake_quant_rows(torch, mx, synth, rows):
             rows["fake_quant_%s_mixed_formats" % dt_name + ("_via_anchor" if via else "")] = row(nby, time_region(torch, fq, 64, 6, WARM_MS))
         for elem in ("int8", "int4", "e4m3", "e3m2", "e2m1"):
             f = mx.make_format(elem)
-            rows["fake_quant_%s_%s" % (dt_name, elem)] = row(nby, time_region(torch, lambda: mx.mx_fake_quant(act, f, None, out), 10, 3, WARM_MS))
+            rows["fake_quant_%s_%s" % (dt_name, elem)] = row(nby, time_region(torch, lambda: mx.mx_fake_quant(act, f, None, out), 20, 3, WARM_MS))
         # for scale: the framework's own device-to-device copy of the same tensor (same bytes read and written per
         # element as fake-quant; not a kernel of this library)
-        rows["reference_torch_copy_%s" % dt_name] = row(nby, time_region(torch, lambda: out.copy_(act), 10, 3, WARM_MS))
+        rows["reference_torch_copy_%s" % dt_name] = row(nby, time_region(torch, lambda: out.copy_(act), 20, 3, WARM_MS))
         del out, act
     del act16
     torch.cuda.empty_cache()
@@ -363,11 +374,11 @@ def column_rows(torch, mx, synth, rows):
     nby = act.numel() * 4
     for elem, bits in (("e2m1", 4), ("int4", 4), ("e4m3", 8)):
         f0 = mx.make_format(elem, axis=0)
-        rows["fake_quant_bf16_%s_axis0" % elem] = row(nby, time_region(torch, lambda: mx.mx_fake_quant(act, f0, None, out), 10, 3, WARM_MS))
+        rows["fake_quant_bf16_%s_axis0" % elem] = row(nby, time_region(torch, lambda: mx.mx_fake_quant(act, f0, None, out), 20, 3, WARM_MS))
         pc, ps = mx.mx_quantize(act, f0)
         nbytes = act.numel() * 2 + act.numel() // 32 * (4 * bits + 1)
-        rows["quantize_bf16_%s_axis0" % elem] = row(nbytes, time_region(torch, lambda: mx.mx_quantize(act, f0, pc, ps), 10, 3, WARM_MS))
-        rows["dequant_%s_bf16_axis0" % elem] = row(nbytes, time_region(torch, lambda: mx.mx_dequant(pc, ps, f0, act.shape[0], act.shape[1], out=out), 10, 3, WARM_MS))
+        rows["quantize_bf16_%s_axis0" % elem] = row(nbytes, time_region(torch, lambda: mx.mx_quantize(act, f0, pc, ps), 20, 3, WARM_MS))
+        rows["dequant_%s_bf16_axis0" % elem] = row(nbytes, time_region(torch, lambda: mx.mx_dequant(pc, ps, f0, act.shape[0], act.shape[1], out=out), 20, 3, WARM_MS))
         del pc, ps
     del act, out
     torch.cuda.empty_cache()
@@ -383,7 +394,7 @@ def column_rows(torch, mx, synth, rows):
     rows["fake_quant_bf16_config4_weight_4096x14336_axis0_mixed_formats"] = row(w.numel() * 4, time_region(torch, fqw, 64, 6, WARM_MS), cache_resident=True)
     f8 = mx.make_format("e4m3", axis=0)
     pc, ps = mx.mx_quantize(w, f8)
-    rows["quantize_bf16_config4_weight_4096x14336_e4m3_axis0"] = row(w.numel() * 2 + w.numel() // 32 * 33, time_region(torch, lambda: mx.mx_quantize(w, f8, pc, ps), 10, 3, WARM_MS), cache_resident=True)
+    rows["quantize_bf16_config4_weight_4096x14336_e4m3_axis0"] = row(w.numel() * 2 + w.numel() // 32 * 33, time_region(torch, lambda: mx.mx_quantize(w, f8, pc, ps), 20, 3, WARM_MS), cache_resident=True)
     del w, wo, pc, ps
     w2 = torch.from_numpy(synth.config2_weight().view(np.int16)).view(torch.bfloat16).cuda()
     pc, ps = mx.mx_quantize(w2, f8)
@@ -403,10 +414,10 @@ def block_size_rows(torch, mx, synth, rows):
         f8, f4 = mx.make_format("e4m3", block=k), mx.make_format("e2m1", block=k)
         pc, ps = mx.mx_quantize(w, f8)
         nb = r * c // k
-        rows["quantize_bf16_e4m3_block%d" % k] = row(r * c * 2 + r * c + nb, time_region(torch, lambda: mx.mx_quantize(w, f8, pc, ps), 10, 3, WARM_MS))
+        rows["quantize_bf16_e4m3_block%d" % k] = row(r * c * 2 + r * c + nb, time_region(torch, lambda: mx.mx_quantize(w, f8, pc, ps), 20, 3, WARM_MS))
         tc, ts = mx.mx_slice_and_scale(pc, ps, f8, f4)
-        rows["ss_e4m3_e2m1_block%d" % k] = row(r * c + r * c // 2 + 2 * nb, time_region(torch, lambda: mx.mx_slice_and_scale(pc, ps, f8, f4, tc, ts), 10, 3, WARM_MS))
-        rows["fake_quant_bf16_e2m1_via_e4m3_block%d" % k] = row(r * c * 4, time_region(torch, lambda: mx.mx_fake_quant(w, f4, f8, out), 10, 3, WARM_MS))
+        rows["ss_e4m3_e2m1_block%d" % k] = row(r * c + r * c // 2 + 2 * nb, time_region(torch, lambda: mx.mx_slice_and_scale(pc, ps, f8, f4, tc, ts), 20, 3, WARM_MS))
+        rows["fake_quant_bf16_e2m1_via_e4m3_block%d" % k] = row(r * c * 4, time_region(torch, lambda: mx.mx_fake_quant(w, f4, f8, out), 20, 3, WARM_MS))
         del pc, ps, tc, ts
     del w, out
     torch.cuda.empty_cache()
@@ -414,8 +425,8 @@ def block_size_rows(torch, mx, synth, rows):
     out = torch.empty_like(act)
     f8c, f4c = mx.make_format("e4m3", axis=0, block=64), mx.make_format("e2m1", axis=0, block=64)
     pc, ps = mx.mx_quantize(act, f8c)
-    rows["quantize_bf16_e4m3_axis0_block64"] = row(act.numel() * 3 + act.numel() // 64, time_region(torch, lambda: mx.mx_quantize(act, f8c, pc, ps), 10, 3, WARM_MS))
-    rows["fake_quant_bf16_e2m1_axis0_block64"] = row(act.numel() * 4, time_region(torch, lambda: mx.mx_fake_quant(act, f4c, None, out), 10, 3, WARM_MS))
+    rows["quantize_bf16_e4m3_axis0_block64"] = row(act.numel() * 3 + act.numel() // 64, time_region(torch, lambda: mx.mx_quantize(act, f8c, pc, ps), 20, 3, WARM_MS))
+    rows["fake_quant_bf16_e2m1_axis0_block64"] = row(act.numel() * 4, time_region(torch, lambda: mx.mx_fake_quant(act, f4c, None, out), 20, 3, WARM_MS))
     del act, out, pc, ps
     torch.cuda.empty_cache()
 
@@ -491,7 +502,7 @@ def gemm_rows(torch, mx, synth, rows):
             with torch.cuda.graph(graph):
                 for _ in range(8):
                     gemm()
-            t = time_region(torch, graph.replay, 12, 4, WARM_MS)
+            t = time_region(torch, graph.replay, 20, 4, WARM_MS)
             rows[name + suffix + "_graph"] = gemm_row(tuple(x / 8 for x in t), calls_per_replay=8)
             del graph
         del a, ac, asc, cbuf, wv, wsp, w4, kept_ws
