@@ -439,6 +439,8 @@ def gemm_rows(torch, mx, synth, rows):
     in registers inside the product kernel (W_t never exists in memory); `_hoisted` writes W_t into a workspace with the
     Slice-and-Scale kernel and multiplies it with a second kernel (its bytes count the workspace's write and re-read).
     `_kept_w_t` rows multiply by a W_t converted beforehand (mx_gemm_fp8_fp4; the conversion is not timed).
+    `_with_activation_quantize_graph` rows time the whole consumer call as a model makes it: mx_quantize of the bf16
+    activations to MXFP8 along K, then the anchor-fed product on its default path.
     Rows time the Python call (events per call); `_graph` rows replay a captured HIP graph of 8 calls, which takes the
     host's call overhead (3-5 us, a fifth of the decode kernel's time) out of the figure."""
     f8 = mx.make_format("e4m3")
@@ -505,6 +507,30 @@ def gemm_rows(torch, mx, synth, rows):
             t = time_region(torch, graph.replay, 20, 4, WARM_MS)
             rows[name + suffix + "_graph"] = gemm_row(tuple(x / 8 for x in t), calls_per_replay=8)
             del graph
+        # the whole consumer call as a model makes it: bf16 activations quantized to MXFP8 along K (mx_quantize) and the
+        # product, anchor-fed by the default path; 8 such pairs per graph replay
+        st2 = {"i": 0}
+        ws_default = wsp if Mg >= mx.GEMM_WORKSPACE_MIN_ROWS else False
+
+        def quant_gemm():
+            i = st2["i"] = (st2["i"] + 1) % 8
+            mx.mx_quantize(a, f8, ac, asc)
+            mx.mx_gemm_ss_fp4(ac, asc, wv[i][0], wv[i][1], cbuf, workspace=ws_default)
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for _ in range(8):
+                quant_gemm()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph):
+            for _ in range(8):
+                quant_gemm()
+        t = time_region(torch, graph.replay, 20, 4, WARM_MS)
+        nbytes_g = base_bytes + Mg * Kg * 2 + (2 * need if Mg >= mx.GEMM_HOIST_MIN_ROWS else 0)   # (read by gemm_row) + the bf16 activations
+        rows[name + "_with_activation_quantize_graph"] = gemm_row(tuple(x / 8 for x in t), calls_per_replay=8)
+        del graph
         del a, ac, asc, cbuf, wv, wsp, w4, kept_ws
     del wlist
     torch.cuda.empty_cache()
