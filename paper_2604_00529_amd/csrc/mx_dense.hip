@@ -504,6 +504,57 @@ __device__ __forceinline__ ColTile col_tile(uint32_t col_groups) {
   return ColTile{(int64_t)rbg * RBS, (int64_t)(blockIdx.x - rbg * col_groups) * kColTileCols};
 }
 
+// The LDS tile <-> the transposed packed tensor: chunk k = (column k / PER_COL, part k % PER_COL) is CD consecutive
+// dwords of that column's run of RBS * W dwords.  Plain accesses: a column's run is completed by several lanes, and L2
+// merges them.  `valid_dw`: the dwords of the run that lie inside the tensor (a ragged last tile).
+template <int W, int RBS, int TPB>
+__device__ __forceinline__ void cols_tile_to_codes(const uint32_t* tile, uint32_t* __restrict__ codes, const ColTile& t, int64_t cols,
+                                                   int64_t nrb, int valid_dw, int tid) {
+  constexpr int CD = ColChunk<W, RBS>::cd, PER_COL = ColChunk<W, RBS>::per_col;
+#pragma unroll
+  for (int it = 0; it < kColTileCols * PER_COL / TPB; ++it) {
+    int k = it * TPB + tid;
+    int c = k / PER_COL, part = k - c * PER_COL;
+    int d0 = part * CD;
+    if (t.c0 + c < cols && d0 < valid_dw) {
+      uint32_t w[CD];
+#pragma unroll
+      for (int q = 0; q < CD; ++q) w[q] = tile[(d0 + q) * kColTileCols + c];
+      uint32_t* g = codes + ((t.c0 + c) * nrb + t.rb0) * W + d0;
+      if (d0 + CD <= valid_dw) {
+        store_dwords<CD>(g, w);
+      } else {
+#pragma unroll
+        for (int q = 0; q < CD; ++q)
+          if (d0 + q < valid_dw) g[q] = w[q];
+      }
+    }
+  }
+}
+template <int W, int RBS, int TPB>
+__device__ __forceinline__ void cols_codes_to_tile(uint32_t* tile, const uint32_t* __restrict__ codes, const ColTile& t, int64_t cols,
+                                                   int64_t nrb, int valid_dw, int tid) {
+  constexpr int CD = ColChunk<W, RBS>::cd, PER_COL = ColChunk<W, RBS>::per_col;
+#pragma unroll
+  for (int it = 0; it < kColTileCols * PER_COL / TPB; ++it) {
+    int k = it * TPB + tid;
+    int c = k / PER_COL, part = k - c * PER_COL;
+    int d0 = part * CD;
+    if (t.c0 + c < cols && d0 < valid_dw) {
+      const uint32_t* g = codes + ((t.c0 + c) * nrb + t.rb0) * W + d0;
+      uint32_t w[CD];
+      if (d0 + CD <= valid_dw) {
+        load_dwords<CD>(g, w);
+      } else {
+#pragma unroll
+        for (int q = 0; q < CD; ++q) w[q] = d0 + q < valid_dw ? g[q] : 0u;
+      }
+#pragma unroll
+      for (int q = 0; q < CD; ++q) tile[(d0 + q) * kColTileCols + c] = w[q];
+    }
+  }
+}
+
 // bf16 rows held as loaded (two columns per dword): largest |V| of each of the lane's 4 columns over its 32 rows, as
 // fp32 bit patterns, from packed 16-bit maxima
 typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
@@ -529,7 +580,7 @@ __global__ __launch_bounds__(64 * RBS) void quantize_cols_kernel(const void* __r
                                                                  int64_t ld, int64_t nrb, int tie) {
   using E = Elem<ELEM>;
   static_assert(!RAW || DT == MX_BF16, "rows are kept as loaded only for bf16");
-  constexpr int W = E::bits, CD = ColChunk<W, RBS>::cd, PER_COL = ColChunk<W, RBS>::per_col, TPB = 64 * RBS;
+  constexpr int W = E::bits, TPB = 64 * RBS;
   __shared__ __attribute__((aligned(16))) uint32_t tile[RBS * W * kColTileCols];
   __shared__ __attribute__((aligned(8))) uint8_t tile_scales[kColTileCols * RBS];
   int tid = threadIdx.x;
@@ -591,26 +642,7 @@ __global__ __launch_bounds__(64 * RBS) void quantize_cols_kernel(const void* __r
   __syncthreads();
   const int64_t valid_rb = nrb - t.rb0 < RBS ? nrb - t.rb0 : RBS;
   const int valid_dw = (int)valid_rb * W;
-  // codes: chunk k = (column k / PER_COL, part k % PER_COL) -> CD consecutive dwords of that column's run
-#pragma unroll
-  for (int it = 0; it < kColTileCols * PER_COL / TPB; ++it) {
-    int k = it * TPB + tid;
-    int c = k / PER_COL, part = k - c * PER_COL;
-    int d0 = part * CD;
-    if (t.c0 + c < cols && d0 < valid_dw) {
-      uint32_t w[CD];
-#pragma unroll
-      for (int q = 0; q < CD; ++q) w[q] = tile[(d0 + q) * kColTileCols + c];
-      uint32_t* g = codes + ((t.c0 + c) * nrb + t.rb0) * W + d0;
-      if (d0 + CD <= valid_dw) {
-        store_dwords<CD>(g, w);   // plain stores: a column's run is completed by several lanes, and L2 merges them
-      } else {
-#pragma unroll
-        for (int q = 0; q < CD; ++q)
-          if (d0 + q < valid_dw) g[q] = w[q];
-      }
-    }
-  }
+  cols_tile_to_codes<W, RBS, TPB>(tile, codes, t, cols, nrb, valid_dw, tid);
   // scales: one column per thread, its (up to) RBS consecutive bytes
   if (tid < kColTileCols && t.c0 + tid < cols) {
     uint8_t* g = scales + (t.c0 + tid) * nrb + t.rb0;
@@ -628,7 +660,7 @@ __global__ __launch_bounds__(256) void dequant_cols_kernel(const uint32_t* __res
                                                            void* __restrict__ dst, int64_t cols, uint32_t col_groups,
                                                            int64_t ld, int64_t nrb) {
   using E = Elem<ELEM>;
-  constexpr int W = E::bits, CD = ColChunk<W>::cd, PER_COL = ColChunk<W>::per_col;
+  constexpr int W = E::bits;
   constexpr bool HW = E::hw != HW_NONE;
   __shared__ __attribute__((aligned(16))) uint32_t tile[kColTileRbs * W * kColTileCols];
   __shared__ __attribute__((aligned(4))) uint8_t tile_scales[kColTileCols * kColTileRbs];
@@ -636,24 +668,7 @@ __global__ __launch_bounds__(256) void dequant_cols_kernel(const uint32_t* __res
   const ColTile t = col_tile(col_groups);
   const int64_t valid_rb = nrb - t.rb0 < kColTileRbs ? nrb - t.rb0 : kColTileRbs;
   const int valid_dw = (int)valid_rb * W;
-#pragma unroll
-  for (int it = 0; it < PER_COL; ++it) {
-    int k = it * 256 + tid;
-    int c = k / PER_COL, part = k - c * PER_COL;
-    int d0 = part * CD;
-    if (t.c0 + c < cols && d0 < valid_dw) {
-      const uint32_t* g = codes + ((t.c0 + c) * nrb + t.rb0) * W + d0;
-      uint32_t w[CD];
-      if (d0 + CD <= valid_dw) {
-        load_dwords<CD>(g, w);
-      } else {
-#pragma unroll
-        for (int q = 0; q < CD; ++q) w[q] = d0 + q < valid_dw ? g[q] : 0u;
-      }
-#pragma unroll
-      for (int q = 0; q < CD; ++q) tile[(d0 + q) * kColTileCols + c] = w[q];
-    }
-  }
+  cols_codes_to_tile<W, kColTileRbs, 256>(tile, codes, t, cols, nrb, valid_dw, tid);
   if (t.c0 + tid < cols) {
     const uint8_t* g = scales + (t.c0 + tid) * nrb + t.rb0;
     for (int q = 0; q < (int)valid_rb; ++q) tile_scales[tid * kColTileRbs + q] = g[q];
@@ -820,7 +835,7 @@ __global__ __launch_bounds__(256) void quantize_cols_kblock_kernel(const void* _
                                                                    uint8_t* __restrict__ scales, int64_t cols, uint32_t col_groups,
                                                                    int64_t ld, int64_t nrb, int tie, int block) {
   using E = Elem<ELEM>;
-  constexpr int W = E::bits, CD = ColChunk<W>::cd, PER_COL = ColChunk<W>::per_col;
+  constexpr int W = E::bits;
   __shared__ __attribute__((aligned(16))) uint32_t tile[kColTileRbs * W * kColTileCols];
   __shared__ uint32_t xch[kColTileRbs][kColTileCols];
   int tid = threadIdx.x;
@@ -874,25 +889,7 @@ __global__ __launch_bounds__(256) void quantize_cols_kblock_kernel(const void* _
   __syncthreads();
   const int64_t valid_rb = nrb - t.rb0 < kColTileRbs ? nrb - t.rb0 : kColTileRbs;
   const int valid_dw = (int)valid_rb * W;
-#pragma unroll
-  for (int it = 0; it < PER_COL; ++it) {
-    int k = it * 256 + tid;
-    int c = k / PER_COL, part = k - c * PER_COL;
-    int d0 = part * CD;
-    if (t.c0 + c < cols && d0 < valid_dw) {
-      uint32_t w[CD];
-#pragma unroll
-      for (int q = 0; q < CD; ++q) w[q] = tile[(d0 + q) * kColTileCols + c];
-      uint32_t* g = codes + ((t.c0 + c) * nrb + t.rb0) * W + d0;
-      if (d0 + CD <= valid_dw) {
-        store_dwords<CD>(g, w);
-      } else {
-#pragma unroll
-        for (int q = 0; q < CD; ++q)
-          if (d0 + q < valid_dw) g[q] = w[q];
-      }
-    }
-  }
+  cols_tile_to_codes<W, kColTileRbs, 256>(tile, codes, t, cols, nrb, valid_dw, tid);
 }
 
 template <int ELEM, int DT>
@@ -900,7 +897,7 @@ __global__ __launch_bounds__(256) void dequant_cols_kblock_kernel(const uint32_t
                                                                   void* __restrict__ dst, int64_t cols, uint32_t col_groups,
                                                                   int64_t ld, int64_t nrb, int block) {
   using E = Elem<ELEM>;
-  constexpr int W = E::bits, CD = ColChunk<W>::cd, PER_COL = ColChunk<W>::per_col;
+  constexpr int W = E::bits;
   constexpr bool HW = E::hw != HW_NONE;
   __shared__ __attribute__((aligned(16))) uint32_t tile[kColTileRbs * W * kColTileCols];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -908,24 +905,7 @@ __global__ __launch_bounds__(256) void dequant_cols_kblock_kernel(const uint32_t
   const ColBlockGeom geo = col_block_geom(block, nrb);
   const int64_t valid_rb = nrb - t.rb0 < kColTileRbs ? nrb - t.rb0 : kColTileRbs;
   const int valid_dw = (int)valid_rb * W;
-#pragma unroll
-  for (int it = 0; it < PER_COL; ++it) {
-    int k = it * 256 + tid;
-    int c = k / PER_COL, part = k - c * PER_COL;
-    int d0 = part * CD;
-    if (t.c0 + c < cols && d0 < valid_dw) {
-      const uint32_t* g = codes + ((t.c0 + c) * nrb + t.rb0) * W + d0;
-      uint32_t w[CD];
-      if (d0 + CD <= valid_dw) {
-        load_dwords<CD>(g, w);
-      } else {
-#pragma unroll
-        for (int q = 0; q < CD; ++q) w[q] = d0 + q < valid_dw ? g[q] : 0u;
-      }
-#pragma unroll
-      for (int q = 0; q < CD; ++q) tile[(d0 + q) * kColTileCols + c] = w[q];
-    }
-  }
+  cols_codes_to_tile<W, kColTileRbs, 256>(tile, codes, t, cols, nrb, valid_dw, tid);
   __syncthreads();
   const int64_t rb = t.rb0 + wave, col = t.c0 + 4 * lane;
   if (rb < nrb && col < cols) {
