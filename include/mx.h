@@ -15,9 +15,10 @@
  *   - Nothing is allocated, freed or synchronized by the library, on the device or on the host.
  *     Work is enqueued on the HIP stream passed as `stream` (a hipStream_t cast to void*; NULL =
  *     the default stream) and is complete when that stream reaches the end of the enqueued work.
- *   - The library keeps no state between calls apart from two facts it memoizes per device on
- *     first use (its number of compute units; that a kernel has been granted its LDS size there);
- *     calls from several threads are safe.
+ *   - The library keeps no state between calls apart from facts it memoizes per device on first
+ *     use (its number of compute units; that a kernel has been granted its LDS size there; the
+ *     device address of the descriptor array of mx_slice_and_scale_batched_noalloc); calls from
+ *     several threads are safe (for that one entry point: as long as they do not overlap on a GPU).
  *   - All arguments are validated on the host before anything is launched: a call that returns
  *     an error has had no effect on device memory.  Errors are reported by return code only.
  *   - Dense tensors are row-major [rows, cols] with leading dimension `ld` (elements, >= cols).
