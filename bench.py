@@ -60,6 +60,25 @@ def time_region(torch, fn, steps, warmup, warm_ms=0.0):
     return ev[0].elapsed_time(ev[steps]) / steps, statistics.median(per), min(per), wall_ms / steps
 
 
+def time_graph(torch, fn, calls, steps=20, warmup=4):
+    """Milliseconds per call of fn when `calls` of them are replayed as one captured HIP graph (the kernels without the
+    host between the launches): time_region's tuple, divided by `calls`."""
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for _ in range(calls):
+            fn()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        for _ in range(calls):
+            fn()
+    t = time_region(torch, graph.replay, steps, warmup, WARM_MS)
+    del graph
+    return tuple(x / calls for x in t)
+
+
 def build_checkpoint(torch, mx, synth, layers, anchor_elem):
     """Quantize the synthetic decoder weights to one packed anchor arena; returns per-tensor views."""
     tensors = synth.llama8b_tensor_list(layers)
@@ -302,11 +321,16 @@ def ss_rows(torch, mx, synth, rows, args, ckpt):
         nb = ps.numel()
         t = time_region(torch, lambda: mx.mx_quantize(w, f, pc, ps), 20, 5, WARM_MS)
         rows["quantize_%s_%s" % (name, anchor)] = row(w.numel() * w.element_size() + nb * 33, t, cache_resident=True)
+        # launches this short are timed by the host's pace; 16 of them replayed as one graph give the kernel's own time
+        t = time_graph(torch, lambda: mx.mx_quantize(w, f, pc, ps), 16)
+        rows["quantize_%s_%s_graph" % (name, anchor)] = row(w.numel() * w.element_size() + nb * 33, t, cache_resident=True, calls_per_replay=16)
         for tg in targets:
             ftg = mx.make_format(tg)
             oc, os_ = mx.mx_slice_and_scale(pc, ps, f, ftg)
             t = time_region(torch, lambda: mx.mx_slice_and_scale(pc, ps, f, ftg, oc, os_), 20, 5, WARM_MS)
             rows["ss_%s_%s_%s" % (name, anchor, tg)] = row(ss_bytes(nb, 8, mx.mx_elem_bits(tg)), t, cache_resident=True)
+            t = time_graph(torch, lambda: mx.mx_slice_and_scale(pc, ps, f, ftg, oc, os_), 16)
+            rows["ss_%s_%s_%s_graph" % (name, anchor, tg)] = row(ss_bytes(nb, 8, mx.mx_elem_bits(tg)), t, cache_resident=True, calls_per_replay=16)
         del pc, ps, w
 
 
@@ -493,20 +517,7 @@ def gemm_rows(torch, mx, synth, rows):
                 return out
             rows[name + suffix] = gemm_row(time_region(torch, gemm, 24, 8, WARM_MS))
             # the same 8 calls as one captured graph: per-call time without the host between the launches
-            graph = torch.cuda.CUDAGraph()
-            side = torch.cuda.Stream()
-            side.wait_stream(torch.cuda.current_stream())
-            with torch.cuda.stream(side):
-                for _ in range(8):
-                    gemm()
-            torch.cuda.current_stream().wait_stream(side)
-            torch.cuda.synchronize()
-            with torch.cuda.graph(graph):
-                for _ in range(8):
-                    gemm()
-            t = time_region(torch, graph.replay, 20, 4, WARM_MS)
-            rows[name + suffix + "_graph"] = gemm_row(tuple(x / 8 for x in t), calls_per_replay=8)
-            del graph
+            rows[name + suffix + "_graph"] = gemm_row(time_graph(torch, gemm, 8), calls_per_replay=8)
         # the whole consumer call as a model makes it: bf16 activations quantized to MXFP8 along K (mx_quantize) and the
         # product, anchor-fed by the default path; 8 such pairs per graph replay
         st2 = {"i": 0}
@@ -516,21 +527,9 @@ def gemm_rows(torch, mx, synth, rows):
             i = st2["i"] = (st2["i"] + 1) % 8
             mx.mx_quantize(a, f8, ac, asc)
             mx.mx_gemm_ss_fp4(ac, asc, wv[i][0], wv[i][1], cbuf, workspace=ws_default)
-        graph = torch.cuda.CUDAGraph()
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            for _ in range(8):
-                quant_gemm()
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-        with torch.cuda.graph(graph):
-            for _ in range(8):
-                quant_gemm()
-        t = time_region(torch, graph.replay, 20, 4, WARM_MS)
+        t = time_graph(torch, quant_gemm, 8)
         nbytes_g = base_bytes + Mg * Kg * 2 + (2 * need if Mg >= mx.GEMM_HOIST_MIN_ROWS else 0)   # (read by gemm_row) + the bf16 activations
-        rows[name + "_with_activation_quantize_graph"] = gemm_row(tuple(x / 8 for x in t), calls_per_replay=8)
-        del graph
+        rows[name + "_with_activation_quantize_graph"] = gemm_row(t, calls_per_replay=8)
         del a, ac, asc, cbuf, wv, wsp, w4, kept_ws
     del wlist
     torch.cuda.empty_cache()
