@@ -770,6 +770,139 @@ __global__ __launch_bounds__(TPB) void fake_quant_cols_kernel(const void* __rest
   for (int r = 0; r < 32; ++r) store_quad<DT>(dst, offd + r * ld_dst, v[r]);
 }
 
+// DQ(Q(.)) of a lane's R x N values (column j under scale byte `byte[j]`) for the 6-bit minifloats, whose hardware
+// conversion takes 32 values under ONE scale: the values are first divided by their own column's scale (ldexp: exact,
+// or so far below the smallest code that they round to zero either way) -- or, with an E4M3 anchor, replaced by their
+// anchor elements P_h, which all share the scale 2^De of Eq. (6) -- then converted 32 at a time under one scale, and
+// every code is read back under its column's scale (X P: exact, at most 4 significant bits).
+template <int TARGET, int ANCHOR, int R, int N>
+__device__ __forceinline__ void fake_quant_fp6_columns(float (&v)[R][N], const uint32_t (&byte)[N], int tie) {
+  using E = Elem<TARGET>;
+  constexpr int TOTAL = R * N, BATCHES = (TOTAL + 31) / 32;
+  uint32_t byte_out[N];
+  float s;
+  if constexpr (ANCHOR < 0) {
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+      byte_out[j] = byte[j];
+#pragma unroll
+      for (int r = 0; r < R; ++r) v[r][j] = ldexpf(v[r][j], 127 - (int)byte[j]);
+    }
+    s = scale_operand(127u);
+  } else {
+    constexpr int DE = Elem<ANCHOR>::emax - E::emax, PIECE = R < 8 ? R : 8;
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+      byte_out[j] = byte[j] + DE > 254u ? 254u : byte[j] + DE;
+#pragma unroll
+      for (int c = 0; c < R / PIECE; ++c) {
+        float x[PIECE];
+#pragma unroll
+        for (int r = 0; r < PIECE; ++r) x[r] = v[PIECE * c + r][j];
+        uint64_t ch = encode_chunk<ANCHOR, true, PIECE>(x, byte[j], tie);
+        decode_chunk<ANCHOR, true, PIECE>(ch, 127u, x);               // the anchor elements P_h as numbers
+#pragma unroll
+        for (int r = 0; r < PIECE; ++r) v[PIECE * c + r][j] = x[r];
+      }
+    }
+    s = scale_operand(127u + DE);
+  }
+  static_for<0, BATCHES>([&](auto bc) {
+    constexpr int B = decltype(bc)::value;
+    f32x16 ev = {}, od = {};   // value e of the batch = flat element 32 B + e = v[(32 B + e) / N][(32 B + e) % N]
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int e0 = 32 * B + 2 * i, e1 = e0 + 1;
+      if (e0 < TOTAL) ev[i] = v[e0 / N][e0 % N];
+      if (e1 < TOTAL) od[i] = v[e1 / N][e1 % N];
+    }
+    const u32x6 p = cvt_2xpk16_fp6_f32<E::hw == HW_BF6>(ev, od, s);   // element 2i = ev[i], 2i + 1 = od[i]
+    static_for<0, 32>([&](auto ec) {
+      constexpr int EI = decltype(ec)::value, FLAT = 32 * B + EI;
+      if constexpr (FLAT < TOTAL) {
+        constexpr int POS = 6 * EI, W = POS / 32, SH = POS % 32;
+        uint32_t c = p[W] >> SH;
+        if constexpr (SH > 26) c |= p[W + 1] << (32 - SH);
+        const uint32_t f = ((c & 0x1Fu) << (23 - E::mu)) | ((c & 0x20u) << 26);
+        constexpr int J = FLAT % N;
+        // (a minifloat without Inf / NaN in the top of an fp32's fields reads as its value times 2^(bias - 127))
+        v[FLAT / N][J] = byte[J] == 255u ? __uint_as_float(0x7FC00000u)
+                                         : ldexpf(__uint_as_float(f), (int)byte_out[J] - 127 + (127 - E::bias));
+      }
+    });
+  });
+}
+
+// The same map with the rows of a block dealt to the waves of a workgroup (k = 32: eight waves of 4 rows; 64 and 128:
+// eight waves of 8 and 16 rows; 16: four waves of 4): a wave loads its rows as 64 chunks of 16 bytes (1 KB per row),
+// the waves exchange their columns' partial maxima through LDS (planes of dwords), and every wave converts and stores
+// its own rows.  Four loads in flight per lane instead of 32 and a third of the registers: many small waves per compute
+// unit, which is what a launch of well under 100 us needs to ramp up and drain quickly (32768 x 4096 bf16, k = 32: 0.79
+// of the HBM peak against 0.75-0.76 for the 32-rows-per-lane kernel; on a tensor four times the size both stream at
+// 0.81-0.82).  Needs the column count to be a multiple of the chunk (8 bf16 / 4 fp32 columns).
+template <int TARGET, int ANCHOR, bool HW, int DT, int WAVES, int RPW>
+__global__ __launch_bounds__(64 * WAVES) void fake_quant_cols_split_kernel(const void* __restrict__ src, void* __restrict__ dst,
+                                                                           uint32_t chunks_per_row, uint32_t col_groups,
+                                                                           int64_t ld_src, int64_t ld_dst, int tie) {
+  constexpr int FIRST = FirstFormat<TARGET, ANCHOR>::elem;
+  constexpr int N = Dense<DT>::N, PIECE = RPW < 8 ? RPW : 8;   // rows converted per call
+  static_assert(RPW % PIECE == 0, "rows per wave");
+  __shared__ uint32_t part[WAVES][N][64];
+  int tid = threadIdx.x;
+  if constexpr (HW && Elem<FIRST>::hw == HW_FP8) tid = set_fp8_saturation(tid);
+  const int lane = tid & 63, wave = tid >> 6;
+  const int64_t blk = (int64_t)(blockIdx.x / col_groups);
+  const uint32_t chunk = (blockIdx.x % col_groups) * 64u + (uint32_t)lane;
+  const bool live = chunk < chunks_per_row;   // (a lane past the row's end takes part in the barrier only)
+  float v[RPW][N];
+  const int64_t row0 = blk * (WAVES * RPW) + wave * RPW;
+  if (live) {
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) load_chunk<DT>(src, (row0 + r) * ld_src + (int64_t)chunk * N, v[r]);
+  } else {
+#pragma unroll
+    for (int r = 0; r < RPW; ++r)
+#pragma unroll
+      for (int j = 0; j < N; ++j) v[r][j] = 0.f;
+  }
+#pragma unroll
+  for (int j = 0; j < N; ++j) {
+    uint32_t m = 0;
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) { uint32_t a = abs_bits(v[r][j]); m = m > a ? m : a; }
+    part[wave][j][lane] = m;
+  }
+  __syncthreads();
+  uint32_t byte[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) {
+    uint32_t m = part[0][j][lane];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) { uint32_t a = part[w][j][lane]; m = m > a ? m : a; }
+    byte[j] = scale_byte_from_amax<Elem<FIRST>::emax>(m);
+  }
+  if constexpr (HW && (Elem<TARGET>::hw == HW_FP6 || Elem<TARGET>::hw == HW_BF6)) {
+    fake_quant_fp6_columns<TARGET, ANCHOR, RPW, N>(v, byte, tie);
+  } else {
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+#pragma unroll
+      for (int c = 0; c < RPW / PIECE; ++c) {
+        float x[PIECE];
+#pragma unroll
+        for (int r = 0; r < PIECE; ++r) x[r] = v[PIECE * c + r][j];
+        fake_quant_chunk<TARGET, ANCHOR, HW, PIECE, DT == MX_BF16>(x, byte[j], tie);
+#pragma unroll
+        for (int r = 0; r < PIECE; ++r) v[PIECE * c + r][j] = x[r];
+      }
+    }
+  }
+  if (live) {
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) store_chunk<DT>(dst, (row0 + r) * ld_dst + (int64_t)chunk * N, v[r]);
+  }
+}
+
 // ------------------------------------------------------------------ axis 0, blocks of 16, 64 or 128 rows
 // The codes of a column are one bit string whatever the block size, so the packed tensor has the layout of k = 32 and
 // these kernels keep its 32-row windows: a workgroup of 4 waves takes 4 consecutive windows x 256 columns (wave w =
@@ -1109,6 +1242,19 @@ static mx_status_t run_fake_quant(int axis, int block, int tie, const DenseArg& 
       hipLaunchKernelGGL((fake_quant_rows_kernel<TARGET, ANCHOR, HW, DT, kFqUnroll, kFqThreads, true>), dim3((unsigned)wgs), dim3(kFqThreads), 0,
                          st, s.data, d.data, nchunks, (uint32_t)cpr, s.ld, d.ld, (int)(s.ld == s.cols), (int)(d.ld == d.cols), tie,
                          log2_lanes_of(block, N));
+  } else if (s.cols % Dense<DT>::N == 0 && s.cols / Dense<DT>::N <= 0xFFFFFFFFll && s.rows % 32 == 0 &&
+             (s.rows / block) * ((s.cols / Dense<DT>::N + 63) / 64) <= 0x7FFFFFFF) {
+    // (the axis extent is a multiple of the block: checked at the boundary; and of 32 also for blocks of 16, as for the
+    // packed tensors, so that one rule holds for all three operations whatever the column count)
+    const int64_t cpr = s.cols / Dense<DT>::N, cgs = (cpr + 63) / 64, nblk = s.rows / block;
+#define MX_FQ_SPLIT(WAVES, RPW)                                                                                          \
+    hipLaunchKernelGGL((fake_quant_cols_split_kernel<TARGET, ANCHOR, HW, DT, WAVES, RPW>), dim3((unsigned)(nblk * cgs)), \
+                       dim3(64 * WAVES), 0, st, s.data, d.data, (uint32_t)cpr, (uint32_t)cgs, s.ld, d.ld, tie)
+    if (block == 32) MX_FQ_SPLIT(8, 4);
+    else if (block == 64) MX_FQ_SPLIT(8, 8);
+    else if (block == 128) MX_FQ_SPLIT(8, 16);
+    else MX_FQ_SPLIT(4, 4);
+#undef MX_FQ_SPLIT
   } else if (block != 32) {
     if (s.cols % 4 || s.rows % 32) return MX_ERR_UNSUPPORTED;
     const int64_t nrb = s.rows / 32, cgs = (s.cols + kColTileCols - 1) / kColTileCols, rbgs = (nrb + kColTileRbs - 1) / kColTileRbs;

@@ -267,6 +267,33 @@ def test_fake_quant_via_anchor(mx, oracle, anchor, target, dtype, axis):
             assert_same_values(to_host(got), want)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("k", [32, 16, 64, 128])
+def test_fake_quant_down_columns_column_counts_of_4_mod_8(mx, oracle, dtype, k):
+    """Down the columns the fake-quant kernel takes 16-byte chunks of a row (8 bf16 / 4 fp32 columns) when the column
+    count allows it; bf16 tensors whose column count is 4 mod 8 take the kernels with 4 columns per lane.  Both kinds
+    on neighbouring column counts, for every block size, with a padded leading dimension whose padding must stay
+    untouched."""
+    import torch
+    rng = np.random.default_rng(77 + k)
+    for cols in (4, 12, 100, 104, 516, 520):
+        rows = 256
+        ld = (cols + 7) // 8 * 8 + 8
+        m = (rng.standard_normal((rows, cols)) * np.exp(rng.uniform(-3, 3, size=(rows, cols)))).astype(np.float32)
+        host = synth.f32_to_bf16_bits(m) if dtype == "bf16" else m
+        wide = np.zeros((rows, ld), dtype=host.dtype)
+        wide[:, :cols] = host
+        src = to_gpu(wide)[:, :cols]
+        for fmt, anchor in (("e2m1", None), ("e2m1", "e4m3"), ("int4", "int8"), ("e3m2", None), ("int7", None)):
+            f = mx.make_format(fmt, axis=0, block=k)
+            fa = mx.make_format(anchor, axis=0, block=k) if anchor else None
+            out_wide = torch.zeros((rows, ld), dtype=src.dtype, device="cuda")
+            mx.mx_fake_quant(src, f, fa, out_wide[:, :cols])
+            want = oracle.fake_quant(host, fmt, anchor=anchor, axis=0, k=k)
+            assert_same_values(to_host(out_wide[:, :cols].contiguous()), want)
+            assert not bool(out_wide[:, cols:].any()), (cols, fmt, anchor)
+
+
 def test_fake_quant_in_place_and_ste(mx, oracle):
     import torch
     m = synth.config1_weight(seed=8, rows=64, cols=256)
