@@ -389,37 +389,65 @@ def fake_quant_rows(torch, mx, synth, rows):
 
 
 def column_rows(torch, mx, synth, rows):
-    """Blocks down the columns (axis 0): the 256 MiB activation tensor of configs[3] (HBM), the weight leg of
-    configs[3] -- bf16 4096 x 14336, blocks along K, 112 MiB dense: inside the 256 MB last-level cache, flagged -- and
-    configs[1]'s column-axis quantization (32 MiB, cache resident)."""
+    """Blocks down the columns (axis 0): the 256 MiB activation tensor of configs[3], the weight leg of configs[3] --
+    bf16 4096 x 14336, blocks along K, 112 MiB dense -- and configs[1]'s column-axis quantization (32 MiB, cache
+    resident, flagged).  Every call of a row works on the next of several buffer sets (4 for the activations, 6 for the
+    weight), so that neither the dense nor the packed side of a call is still in the 256 MB last-level cache from the
+    call before: with one set the packed tensor (67-134 MB) stays there and quantize / dequantize read 7 / 25-35 points
+    better than they stream from HBM."""
     import numpy as np
-    act = synth.torch_config4_activations()
-    out = torch.empty_like(act)
-    nby = act.numel() * 4
-    for elem, bits in (("e2m1", 4), ("int4", 4), ("e4m3", 8)):
-        f0 = mx.make_format(elem, axis=0)
-        rows["fake_quant_bf16_%s_axis0" % elem] = row(nby, time_region(torch, lambda: mx.mx_fake_quant(act, f0, None, out), 20, 3, WARM_MS))
-        pc, ps = mx.mx_quantize(act, f0)
-        nbytes = act.numel() * 2 + act.numel() // 32 * (4 * bits + 1)
-        rows["quantize_bf16_%s_axis0" % elem] = row(nbytes, time_region(torch, lambda: mx.mx_quantize(act, f0, pc, ps), 20, 3, WARM_MS))
-        rows["dequant_%s_bf16_axis0" % elem] = row(nbytes, time_region(torch, lambda: mx.mx_dequant(pc, ps, f0, act.shape[0], act.shape[1], out=out), 20, 3, WARM_MS))
-        del pc, ps
-    del act, out
-    torch.cuda.empty_cache()
-    w = synth.torch_config3_weight(2000, 4096, 14336)                # [K, N]: the weight of x @ W, blocks down its columns
-    wo = torch.empty_like(w)
-    sched = synth.config4_format_schedule(steps=64)
+    NA, NW = 4, 6
+    act0 = synth.torch_config4_activations()
+    acts = [act0] + [act0.clone() for _ in range(NA - 1)]
+    outs = [torch.empty_like(act0) for _ in range(NA)]
+    nby = act0.numel() * 4
     st = {"k": 0}
 
+    def nxt(n):
+        st["k"] = (st["k"] + 1) % n
+        return st["k"]
+    for elem, bits in (("e2m1", 4), ("int4", 4), ("e4m3", 8)):
+        f0 = mx.make_format(elem, axis=0)
+
+        def fq():
+            i = nxt(NA)
+            mx.mx_fake_quant(acts[i], f0, None, outs[i])
+        rows["fake_quant_bf16_%s_axis0" % elem] = row(nby, time_region(torch, fq, 20, 4, WARM_MS))
+        packs = [mx.mx_quantize(a, f0) for a in acts]
+        nbytes = act0.numel() * 2 + act0.numel() // 32 * (4 * bits + 1)
+
+        def qz():
+            i = nxt(NA)
+            mx.mx_quantize(acts[i], f0, packs[i][0], packs[i][1])
+
+        def dq():
+            i = nxt(NA)
+            mx.mx_dequant(packs[i][0], packs[i][1], f0, act0.shape[0], act0.shape[1], out=outs[i])
+        rows["quantize_bf16_%s_axis0" % elem] = row(nbytes, time_region(torch, qz, 20, 4, WARM_MS))
+        rows["dequant_%s_bf16_axis0" % elem] = row(nbytes, time_region(torch, dq, 20, 4, WARM_MS))
+        del packs
+    del act0, acts, outs
+    torch.cuda.empty_cache()
+    w0 = synth.torch_config3_weight(2000, 4096, 14336)               # [K, N]: the weight of x @ W, blocks down its columns
+    ws = [w0] + [w0.clone() for _ in range(NW - 1)]
+    wos = [torch.empty_like(w0) for _ in range(NW)]
+    sched = synth.config4_format_schedule(steps=64)
+    sk = {"k": 0}
+
     def fqw():
-        elem = sched[st["k"] % len(sched)]
-        st["k"] += 1
-        mx.mx_fake_quant(w, mx.make_format(elem, axis=0), None, wo)
-    rows["fake_quant_bf16_config4_weight_4096x14336_axis0_mixed_formats"] = row(w.numel() * 4, time_region(torch, fqw, 64, 6, WARM_MS), cache_resident=True)
+        elem = sched[sk["k"] % len(sched)]
+        sk["k"] += 1
+        i = nxt(NW)
+        mx.mx_fake_quant(ws[i], mx.make_format(elem, axis=0), None, wos[i])
+    rows["fake_quant_bf16_config4_weight_4096x14336_axis0_mixed_formats"] = row(w0.numel() * 4, time_region(torch, fqw, 64, 6, WARM_MS))
     f8 = mx.make_format("e4m3", axis=0)
-    pc, ps = mx.mx_quantize(w, f8)
-    rows["quantize_bf16_config4_weight_4096x14336_e4m3_axis0"] = row(w.numel() * 2 + w.numel() // 32 * 33, time_region(torch, lambda: mx.mx_quantize(w, f8, pc, ps), 20, 3, WARM_MS), cache_resident=True)
-    del w, wo, pc, ps
+    wpacks = [mx.mx_quantize(w, f8) for w in ws]
+
+    def qw():
+        i = nxt(NW)
+        mx.mx_quantize(ws[i], f8, wpacks[i][0], wpacks[i][1])
+    rows["quantize_bf16_config4_weight_4096x14336_e4m3_axis0"] = row(w0.numel() * 2 + w0.numel() // 32 * 33, time_region(torch, qw, 24, 6, WARM_MS))
+    del w0, ws, wos, wpacks
     w2 = torch.from_numpy(synth.config2_weight().view(np.int16)).view(torch.bfloat16).cuda()
     pc, ps = mx.mx_quantize(w2, f8)
     rows["quantize_config2_4096x4096_e4m3_axis0"] = row(w2.numel() * 2 + w2.numel() // 32 * 33, time_region(torch, lambda: mx.mx_quantize(w2, f8, pc, ps), 20, 5, WARM_MS), cache_resident=True)
@@ -445,13 +473,24 @@ def block_size_rows(torch, mx, synth, rows):
         del pc, ps, tc, ts
     del w, out
     torch.cuda.empty_cache()
-    act = synth.torch_config4_activations()
-    out = torch.empty_like(act)
+    # down the columns of config 4's activations, four buffer sets in turn (see column_rows)
+    act0 = synth.torch_config4_activations()
+    acts = [act0] + [act0.clone() for _ in range(3)]
+    outs = [torch.empty_like(act0) for _ in range(4)]
     f8c, f4c = mx.make_format("e4m3", axis=0, block=64), mx.make_format("e2m1", axis=0, block=64)
-    pc, ps = mx.mx_quantize(act, f8c)
-    rows["quantize_bf16_e4m3_axis0_block64"] = row(act.numel() * 3 + act.numel() // 64, time_region(torch, lambda: mx.mx_quantize(act, f8c, pc, ps), 20, 3, WARM_MS))
-    rows["fake_quant_bf16_e2m1_axis0_block64"] = row(act.numel() * 4, time_region(torch, lambda: mx.mx_fake_quant(act, f4c, None, out), 20, 3, WARM_MS))
-    del act, out, pc, ps
+    packs = [mx.mx_quantize(a, f8c) for a in acts]
+    st = {"k": 0}
+
+    def qz():
+        i = st["k"] = (st["k"] + 1) % 4
+        mx.mx_quantize(acts[i], f8c, packs[i][0], packs[i][1])
+
+    def fq():
+        i = st["k"] = (st["k"] + 1) % 4
+        mx.mx_fake_quant(acts[i], f4c, None, outs[i])
+    rows["quantize_bf16_e4m3_axis0_block64"] = row(act0.numel() * 3 + act0.numel() // 64, time_region(torch, qz, 20, 4, WARM_MS))
+    rows["fake_quant_bf16_e2m1_axis0_block64"] = row(act0.numel() * 4, time_region(torch, fq, 20, 4, WARM_MS))
+    del act0, acts, outs, packs
     torch.cuda.empty_cache()
 
 
