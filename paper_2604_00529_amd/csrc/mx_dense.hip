@@ -655,23 +655,27 @@ __global__ __launch_bounds__(64 * RBS) void quantize_cols_kernel(const void* __r
   }
 }
 
-template <int ELEM, int DT>
-__global__ __launch_bounds__(256) void dequant_cols_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restrict__ scales,
+// RBS row blocks per workgroup (one per wave): 4, or 8 for codes of 4 bits and fewer, whose runs per column would
+// otherwise be 64 bytes and shorter.  (A kernel in which every lane fetched the 16 bytes of a 4-bit block itself, without
+// the LDS pass, was faster while the packed tensor sat in the last-level cache -- 0.80 against 0.73 -- and slower when it
+// came from HBM, 0.44 against 0.54: not kept.)
+template <int ELEM, int DT, int RBS>
+__global__ __launch_bounds__(64 * RBS) void dequant_cols_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restrict__ scales,
                                                            void* __restrict__ dst, int64_t cols, uint32_t col_groups,
                                                            int64_t ld, int64_t nrb) {
   using E = Elem<ELEM>;
   constexpr int W = E::bits;
   constexpr bool HW = E::hw != HW_NONE;
-  __shared__ __attribute__((aligned(16))) uint32_t tile[kColTileRbs * W * kColTileCols];
-  __shared__ __attribute__((aligned(4))) uint8_t tile_scales[kColTileCols * kColTileRbs];
+  __shared__ __attribute__((aligned(16))) uint32_t tile[RBS * W * kColTileCols];
+  __shared__ __attribute__((aligned(4))) uint8_t tile_scales[kColTileCols * RBS];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const ColTile t = col_tile(col_groups);
-  const int64_t valid_rb = nrb - t.rb0 < kColTileRbs ? nrb - t.rb0 : kColTileRbs;
+  const ColTile t = col_tile<RBS>(col_groups);
+  const int64_t valid_rb = nrb - t.rb0 < RBS ? nrb - t.rb0 : RBS;
   const int valid_dw = (int)valid_rb * W;
-  cols_codes_to_tile<W, kColTileRbs, 256>(tile, codes, t, cols, nrb, valid_dw, tid);
-  if (t.c0 + tid < cols) {
+  cols_codes_to_tile<W, RBS, 64 * RBS>(tile, codes, t, cols, nrb, valid_dw, tid);
+  if (tid < kColTileCols && t.c0 + tid < cols) {
     const uint8_t* g = scales + (t.c0 + tid) * nrb + t.rb0;
-    for (int q = 0; q < (int)valid_rb; ++q) tile_scales[tid * kColTileRbs + q] = g[q];
+    for (int q = 0; q < (int)valid_rb; ++q) tile_scales[tid * RBS + q] = g[q];
   }
   __syncthreads();
   const int64_t rb = t.rb0 + wave, col = t.c0 + 4 * lane;
@@ -685,7 +689,7 @@ __global__ __launch_bounds__(256) void dequant_cols_kernel(const uint32_t* __res
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      uint32_t byte = tile_scales[(4 * lane + j) * kColTileRbs + wave];
+      uint32_t byte = tile_scales[(4 * lane + j) * RBS + wave];
       static_for<0, 4>([&](auto cc) {
         constexpr int C = decltype(cc)::value;
         float x[8];
@@ -698,43 +702,6 @@ __global__ __launch_bounds__(256) void dequant_cols_kernel(const uint32_t* __res
 #pragma unroll
     for (int r = 0; r < 32; ++r) store_quad<DT>(dst, off + r * ld, v[r]);
   }
-}
-
-// 4-bit codes to bf16 without the LDS pass: a workgroup of one wave takes one row block x 256 columns, every lane
-// reads the 16 bytes of codes and the scale byte of each of its 4 columns itself (neighbouring row blocks, in flight
-// at the same time, share the 32-byte sectors) and stores its 32 rows.  Eight points of HBM bandwidth above the
-// tiled kernel for these formats; for wider codes the tiled kernel is as fast or faster.
-template <int ELEM>
-__global__ __launch_bounds__(64) void dequant_cols_direct_kernel(const uint32_t* __restrict__ codes, const uint8_t* __restrict__ scales,
-                                                                 void* __restrict__ dst, int64_t cols, uint32_t col_groups,
-                                                                 int64_t ld, int64_t nrb) {
-  using E = Elem<ELEM>;
-  static_assert(E::bits == 4, "one 128-bit load per column and row block");
-  constexpr bool HW = E::hw != HW_NONE;
-  const int lane = threadIdx.x;
-  const uint32_t rbu = blockIdx.x / col_groups;
-  const int64_t rb = rbu, col = (int64_t)(blockIdx.x - rbu * col_groups) * kColTileCols + 4 * lane;
-  if (col >= cols) return;
-  uint32_t in[4][4], byte[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    load_dwords<4>(codes + ((col + j) * nrb + rb) * 4, in[j]);
-    byte[j] = scales[(col + j) * nrb + rb];
-  }
-  float v[32][4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    static_for<0, 4>([&](auto cc) {
-      constexpr int C = decltype(cc)::value;
-      float x[8];
-      decode_chunk<ELEM, HW, 8>((uint64_t)in[j][C], byte[j], x);
-#pragma unroll
-      for (int r = 0; r < 8; ++r) v[8 * C + r][j] = byte[j] == 255u ? __uint_as_float(0x7FC00000u) : x[r];
-    });
-  }
-  const int64_t off = rb * 32 * ld + col;
-#pragma unroll
-  for (int r = 0; r < 32; ++r) store_quad<MX_BF16>(dst, off + r * ld, v[r]);
 }
 
 template <int TARGET, int ANCHOR, bool HW, int DT, int TPB>
@@ -1212,17 +1179,11 @@ static mx_status_t run_dequant(int axis, int block, const void* codes, const uin
   } else {
     if (d.cols % 4) return MX_ERR_UNSUPPORTED;
     int64_t nrb = d.rows / 32;
-    int64_t cgs = (d.cols + kColTileCols - 1) / kColTileCols, rbgs = (nrb + kColTileRbs - 1) / kColTileRbs;
-    if constexpr (Elem<ELEM>::bits == 4 && DT == MX_BF16) {
-      if (cgs * nrb > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-      if (nrb > 0)
-        hipLaunchKernelGGL((dequant_cols_direct_kernel<ELEM>), dim3((unsigned)(cgs * nrb)), dim3(64), 0, st,
-                           static_cast<const uint32_t*>(codes), scales, d.data, d.cols, (uint32_t)cgs, d.ld, nrb);
-    } else {
-      if (cgs * rbgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
-      hipLaunchKernelGGL((dequant_cols_kernel<ELEM, DT>), dim3((unsigned)(cgs * rbgs)), dim3(256), 0, st,
-                         static_cast<const uint32_t*>(codes), scales, d.data, d.cols, (uint32_t)cgs, d.ld, nrb);
-    }
+    constexpr int RBS = Elem<ELEM>::bits <= 4 ? 8 : kColTileRbs;
+    int64_t cgs = (d.cols + kColTileCols - 1) / kColTileCols, rbgs = (nrb + RBS - 1) / RBS;
+    if (cgs * rbgs > 0x7FFFFFFF) return MX_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((dequant_cols_kernel<ELEM, DT, RBS>), dim3((unsigned)(cgs * rbgs)), dim3(64 * RBS), 0, st,
+                       static_cast<const uint32_t*>(codes), scales, d.data, d.cols, (uint32_t)cgs, d.ld, nrb);
   }
   return launch_status("a dense kernel");
 }
